@@ -1,0 +1,132 @@
+/*
+ * lvx.h -- C ABI of the MI355X (gfx950) cross-attention path of LV-XAttn.
+ *
+ * One worker of LV-XAttn keeps its large key/value block in local HBM and is
+ * visited by small query blocks (Algorithm 1 of the paper).  Per visit it runs
+ *   FlashAttention(Q_j, K_i, V_i) -> (dO partial, dL partial)   lvx_xattn_fwd
+ *   Rescale(O_j, L_j, dO, dL)                                    lvx_xattn_merge
+ * and, in the backward pass, recomputes the attention probabilities from the
+ * saved statistic L instead of storing them (Section 3.2)       lvx_xattn_bwd.
+ *
+ * General rules for every entry point
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The library
+ *     never allocates, frees or synchronises; all work is enqueued on the HIP
+ *     stream the caller passes (a hipStream_t cast to void*, NULL = default).
+ *   - Scratch memory is a caller-provided workspace whose size comes from
+ *     lvx_xattn_workspace_bytes; it must be 256-byte aligned.
+ *   - lvx_problem / lvx_mask structs and the pointer arrays of lvx_xattn_merge
+ *     live in HOST memory and are read before the call returns.
+ *   - Errors are returned as negative lvx_status values; argument errors are
+ *     detected on the host before anything is launched.  No exceptions, no aborts.
+ *   - No global state; calls on different streams may run concurrently as long
+ *     as their buffers do not overlap.
+ *
+ * Tensor layout (all strides in ELEMENTS, innermost dimension D contiguous)
+ *   Q, O, dO, dQ : [B, Hq,  Sq,  D]   strides q_sb, q_sh, q_ss
+ *   K, V, dK, dV : [B, Hkv, Skv, D]   strides kv_sb, kv_sh, kv_ss
+ *     (strides let a K/V *block* be a view into a larger tensor)
+ *   L (LSE), delta : [B, Hq, Sq] float32, contiguous, natural logarithm,
+ *     -inf for a query row that sees no key.
+ *   Grouped-query attention: query head hq reads K/V head hq / (Hq / Hkv)
+ *     (contiguous groups); dK/dV sum over the heads of a group.
+ *   Supported head dims D: 64, 128.  Sq, Skv >= 1, no multiple-of-tile rule.
+ */
+#ifndef LVX_H
+#define LVX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LVX_OK = 0,
+  LVX_ERR_NULL = -1,        /* a required pointer is NULL */
+  LVX_ERR_SHAPE = -2,       /* non-positive size, Hq % Hkv != 0, too many parts/splits */
+  LVX_ERR_DTYPE = -3,       /* unknown or unsupported dtype combination */
+  LVX_ERR_STRIDE = -4,      /* stride too small for the shape, or misaligned for vector access */
+  LVX_ERR_MASK = -5,        /* mask geometry does not cover Sq x Skv */
+  LVX_ERR_WORKSPACE = -6,   /* workspace NULL, misaligned or smaller than required */
+  LVX_ERR_UNSUPPORTED = -7, /* head dim other than 64 / 128 */
+  LVX_ERR_HIP = -8          /* a kernel launch failed (hipGetLastError) */
+} lvx_status;
+
+typedef enum { LVX_F32 = 0, LVX_BF16 = 1 } lvx_dtype;
+
+/* The attention problem of Section 2: O = softmax(Q K^T * softmax_scale) V per (batch, head). */
+typedef struct {
+  int32_t B, Hq, Hkv, Sq, Skv, D;
+  int64_t q_sb, q_sh, q_ss;      /* batch / head / row strides of Q, O, dO, dQ */
+  int64_t kv_sb, kv_sh, kv_ss;   /* batch / head / row strides of K, V, dK, dV */
+  float softmax_scale;           /* <= 0 selects the paper's 1/sqrt(D) */
+} lvx_problem;
+
+/* Optional media mask (not in the paper; part of this library's problem statement):
+ * query row i may attend key row j iff
+ *   allow[b * stride_b + (i / q_chunk) * stride_q + (j / kv_block)] != 0.
+ * A masked score is -infinity.  Pass NULL for dense attention.  To mask a K/V block that is a
+ * window [j0, j0+Skv) of a longer sequence (j0 a multiple of kv_block), offset `allow` by
+ * j0 / kv_block columns. */
+typedef struct {
+  const uint8_t* allow;          /* device pointer */
+  int32_t q_chunk, kv_block;     /* text tokens per chunk, visual tokens per block (>= 1) */
+  int32_t n_q_chunks, n_kv_blocks; /* must satisfy n_q_chunks*q_chunk >= Sq, n_kv_blocks*kv_block >= Skv */
+  int64_t stride_b, stride_q;    /* element strides; stride_b = 0 shares the bitmap across batch */
+} lvx_mask;
+
+enum { LVX_WS_FWD = 0, LVX_WS_BWD = 1 };
+enum { LVX_MAX_PARTS = 64 };
+
+/* Bytes of workspace lvx_xattn_fwd (which = LVX_WS_FWD) or lvx_xattn_bwd (LVX_WS_BWD) needs for
+ * this problem and dtype.  Returns 0 on invalid arguments. */
+size_t lvx_xattn_workspace_bytes(const lvx_problem* p, lvx_dtype dtype, int which);
+
+/* Forward pass of one visit (Algorithm 1, the FlashAttention call; Section 2 defines the result):
+ *   O[b,h,i,:] = sum_j softmax_j(scale * <Q_i, K_j>) V_j,   L[b,h,i] = ln sum_j exp(scale * <Q_i, K_j>)
+ * over the Skv keys passed.  q/k/v have type `dtype`; o has type `o_dtype`, which is either `dtype`
+ * or LVX_F32 (use LVX_F32 for partial results that will be merged).  o uses Q's strides.
+ * A row with no visible key gets O = 0, L = -inf.  Overwrites o and lse. */
+lvx_status lvx_xattn_fwd(const lvx_problem* p, lvx_dtype dtype, const void* q, const void* k,
+                         const void* v, const lvx_mask* mask, void* o, lvx_dtype o_dtype,
+                         float* lse, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Rescale of Algorithm 1, for n_parts >= 1 partial results of the same query block:
+ *   L' = ln sum_k exp(L_k),   O' = sum_k exp(L_k - L') O_k        (all L_k = -inf -> O' = 0, L' = -inf)
+ * o_parts[k] is a contiguous [B,Hq,Sq,D] device tensor of type part_dtype, lse_parts[k] a contiguous
+ * [B,Hq,Sq] float32 device tensor; the two pointer arrays themselves are host arrays of n_parts
+ * entries (n_parts <= LVX_MAX_PARTS).  o_out (contiguous, out_dtype) may alias o_parts[0] when the
+ * two dtypes have the same size, and lse_out may alias lse_parts[0]: the running (O_j, L_j) of
+ * Algorithm 1 is updated in place with n_parts = 2.  The identity element is (O, L) = (0, -inf). */
+lvx_status lvx_xattn_merge(int32_t B, int32_t Hq, int32_t Sq, int32_t D, int32_t n_parts,
+                           const void* const* o_parts, const float* const* lse_parts,
+                           lvx_dtype part_dtype, void* o_out, lvx_dtype out_dtype, float* lse_out,
+                           void* hip_stream);
+
+/* Backward pass of one visit: gradients of loss = sum(O * dO) for the K/V block passed, with the
+ * attention probabilities recomputed as p_ij = exp(scale * <Q_i, K_j> - L_i) from the saved L
+ * (Section 3.2 saves only x, O and L; Table 1 counts the five matrix products).
+ *   o, lse : the FINAL output and statistic of the whole key range (after all merges), even when
+ *            k/v are only one block of it.  o and d_o have type `dtype` and use Q's strides.
+ *   dk, dv : type `dtype`, K's strides, OVERWRITTEN with this block's gradients (they are final:
+ *            no other block contributes to them).
+ *   dq_accum : float32, contiguous [B,Hq,Sq,D], ACCUMULATED into (+=).  The caller zeroes it before
+ *            the first block and converts with lvx_xattn_dq_finalize after the last.
+ * No gradient flows through L.  Rows with L = -inf get zero gradients. */
+lvx_status lvx_xattn_bwd(const lvx_problem* p, lvx_dtype dtype, const void* q, const void* k,
+                         const void* v, const void* o, const float* lse, const void* d_o,
+                         const lvx_mask* mask, float* dq_accum, void* dk, void* dv,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* dq (type `dtype`, Q's strides) = dq_accum (float32, contiguous) rounded to `dtype`. */
+lvx_status lvx_xattn_dq_finalize(const lvx_problem* p, const float* dq_accum, void* dq,
+                                 lvx_dtype dtype, void* hip_stream);
+
+/* Human-readable name of a status code (static storage). */
+const char* lvx_strerror(lvx_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LVX_H */

@@ -1,0 +1,181 @@
+"""Thin ctypes binding of liblvx.so (include/lvx.h).  Argument marshalling only.
+
+PyTorch is used for device memory and streams; every step of the attention path runs in the
+HIP kernels behind the C ABI.  There is no CPU fallback: if the library is missing or no GPU
+is present the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblvx.so")
+
+LVX_F32, LVX_BF16 = 0, 1
+LVX_WS_FWD, LVX_WS_BWD = 0, 1
+LVX_MAX_PARTS = 64
+
+EXPORTS = ("lvx_xattn_workspace_bytes", "lvx_xattn_fwd", "lvx_xattn_merge", "lvx_xattn_bwd",
+           "lvx_xattn_dq_finalize", "lvx_strerror")
+
+
+class LvxError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} (status {code})")
+
+
+class lvx_problem(C.Structure):
+    _fields_ = [("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("Sq", C.c_int32),
+                ("Skv", C.c_int32), ("D", C.c_int32),
+                ("q_sb", C.c_int64), ("q_sh", C.c_int64), ("q_ss", C.c_int64),
+                ("kv_sb", C.c_int64), ("kv_sh", C.c_int64), ("kv_ss", C.c_int64),
+                ("softmax_scale", C.c_float)]
+
+
+class lvx_mask(C.Structure):
+    _fields_ = [("allow", C.c_void_p), ("q_chunk", C.c_int32), ("kv_block", C.c_int32),
+                ("n_q_chunks", C.c_int32), ("n_kv_blocks", C.c_int32),
+                ("stride_b", C.c_int64), ("stride_q", C.c_int64)]
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Load liblvx.so (built by paper_2502_02406_amd.build); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} not found: build it with `python -m paper_2502_02406_amd.build`")
+        lib = C.CDLL(LIB_PATH)
+        lib.lvx_xattn_workspace_bytes.restype = C.c_size_t
+        lib.lvx_xattn_workspace_bytes.argtypes = [C.POINTER(lvx_problem), C.c_int, C.c_int]
+        lib.lvx_xattn_fwd.restype = C.c_int
+        lib.lvx_xattn_fwd.argtypes = [C.POINTER(lvx_problem), C.c_int, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.POINTER(lvx_mask), C.c_void_p, C.c_int,
+                                      C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.lvx_xattn_merge.restype = C.c_int
+        lib.lvx_xattn_merge.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                        C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int,
+                                        C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+        lib.lvx_xattn_bwd.restype = C.c_int
+        lib.lvx_xattn_bwd.argtypes = [C.POINTER(lvx_problem), C.c_int, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.POINTER(lvx_mask), C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.lvx_xattn_dq_finalize.restype = C.c_int
+        lib.lvx_xattn_dq_finalize.argtypes = [C.POINTER(lvx_problem), C.c_void_p, C.c_void_p,
+                                              C.c_int, C.c_void_p]
+        lib.lvx_strerror.restype = C.c_char_p
+        lib.lvx_strerror.argtypes = [C.c_int]
+        _lib = lib
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return load().lvx_strerror(int(code)).decode()
+
+
+def dtype_code(dt: torch.dtype) -> int:
+    if dt == torch.float32:
+        return LVX_F32
+    if dt == torch.bfloat16:
+        return LVX_BF16
+    raise TypeError(f"unsupported dtype {dt}")
+
+
+def _stream() -> int:
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def make_problem(q: torch.Tensor, k: torch.Tensor, softmax_scale: float = 0.0) -> lvx_problem:
+    """Shape and strides of Q [B,Hq,Sq,D] and K [B,Hkv,Skv,D] (K may be a strided view)."""
+    assert q.dim() == 4 and k.dim() == 4 and q.stride(3) == 1 and k.stride(3) == 1
+    p = lvx_problem()
+    p.B, p.Hq, p.Sq, p.D = q.shape
+    p.Hkv, p.Skv = k.shape[1], k.shape[2]
+    p.q_sb, p.q_sh, p.q_ss = q.stride(0), q.stride(1), q.stride(2)
+    p.kv_sb, p.kv_sh, p.kv_ss = k.stride(0), k.stride(1), k.stride(2)
+    p.softmax_scale = float(softmax_scale)
+    return p
+
+
+def make_mask(allow: torch.Tensor, q_chunk: int, kv_block: int, kv_block0: int = 0,
+              n_kv_blocks: Optional[int] = None) -> lvx_mask:
+    """allow: uint8 device tensor [n_q_chunks, n_kv_blocks_total] or [B, ...]; kv_block0 offsets
+    the bitmap columns for a K/V block that starts at key kv_block0 * kv_block."""
+    assert allow.dtype == torch.uint8 and allow.is_cuda and allow.stride(-1) == 1
+    m = lvx_mask()
+    m.allow = allow.data_ptr() + kv_block0
+    m.q_chunk, m.kv_block = int(q_chunk), int(kv_block)
+    m.n_q_chunks = allow.shape[-2]
+    m.n_kv_blocks = (allow.shape[-1] - kv_block0) if n_kv_blocks is None else int(n_kv_blocks)
+    m.stride_q = allow.stride(-2)
+    m.stride_b = allow.stride(0) if allow.dim() == 3 else 0
+    return m
+
+
+def lvx_xattn_workspace_bytes(p: lvx_problem, dtype: int, which: int) -> int:
+    return int(load().lvx_xattn_workspace_bytes(C.byref(p), dtype, which))
+
+
+def _check(code: int, where: str) -> None:
+    if code != 0:
+        raise LvxError(code, where)
+
+
+def lvx_xattn_fwd(p: lvx_problem, q, k, v, mask: Optional[lvx_mask], o, lse, workspace) -> None:
+    """o (dtype of q, or float32) and lse (float32 [B,Hq,Sq]) are overwritten."""
+    if not q.is_cuda:
+        raise RuntimeError("lvx_xattn_fwd needs device tensors")
+    code = load().lvx_xattn_fwd(C.byref(p), dtype_code(q.dtype), q.data_ptr(), k.data_ptr(),
+                                v.data_ptr(), C.byref(mask) if mask is not None else None,
+                                o.data_ptr(), dtype_code(o.dtype), lse.data_ptr(),
+                                workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                _stream())
+    _check(code, "lvx_xattn_fwd")
+
+
+def lvx_xattn_merge(o_parts: Sequence[torch.Tensor], lse_parts: Sequence[torch.Tensor],
+                    o_out: torch.Tensor, lse_out: torch.Tensor) -> None:
+    """Rescale of Algorithm 1 over the given parts (each contiguous [B,Hq,Sq,D] / [B,Hq,Sq])."""
+    n = len(o_parts)
+    B, Hq, Sq, D = o_out.shape
+    if not o_out.is_cuda:
+        raise RuntimeError("lvx_xattn_merge needs device tensors")
+    for t in list(o_parts) + list(lse_parts) + [o_out, lse_out]:
+        assert t.is_contiguous()
+    op = (C.c_void_p * max(n, 1))(*[t.data_ptr() for t in o_parts])
+    lp = (C.c_void_p * max(n, 1))(*[t.data_ptr() for t in lse_parts])
+    code = load().lvx_xattn_merge(B, Hq, Sq, D, n, op, lp, dtype_code(o_parts[0].dtype) if n else 0,
+                                  o_out.data_ptr(), dtype_code(o_out.dtype), lse_out.data_ptr(),
+                                  _stream())
+    _check(code, "lvx_xattn_merge")
+
+
+def lvx_xattn_bwd(p: lvx_problem, q, k, v, o, lse, d_o, mask: Optional[lvx_mask], dq_accum, dk, dv,
+                  workspace) -> None:
+    """dk/dv (views with K's strides) overwritten; dq_accum (float32, contiguous) accumulated."""
+    if not q.is_cuda:
+        raise RuntimeError("lvx_xattn_bwd needs device tensors")
+    assert dq_accum.dtype == torch.float32 and dq_accum.is_contiguous()
+    assert dk.stride() == k.stride() and dv.stride() == k.stride()
+    assert o.stride() == q.stride() and d_o.stride() == q.stride()
+    code = load().lvx_xattn_bwd(C.byref(p), dtype_code(q.dtype), q.data_ptr(), k.data_ptr(),
+                                v.data_ptr(), o.data_ptr(), lse.data_ptr(), d_o.data_ptr(),
+                                C.byref(mask) if mask is not None else None, dq_accum.data_ptr(),
+                                dk.data_ptr(), dv.data_ptr(), workspace.data_ptr(),
+                                workspace.numel() * workspace.element_size(), _stream())
+    _check(code, "lvx_xattn_bwd")
+
+
+def lvx_xattn_dq_finalize(p: lvx_problem, dq_accum, dq) -> None:
+    code = load().lvx_xattn_dq_finalize(C.byref(p), dq_accum.data_ptr(), dq.data_ptr(),
+                                        dtype_code(dq.dtype), _stream())
+    _check(code, "lvx_xattn_dq_finalize")

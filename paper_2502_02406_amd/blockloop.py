@@ -1,0 +1,108 @@
+"""Algorithm 1 of the paper on ONE GPU: the query block visits N key/value blocks in turn.
+
+The distributed schedule keeps each K/V block on its worker and passes (Q_j, O_j, L_j) around a
+ring; each visit is FlashAttention(Q_j, K_i, V_i) followed by Rescale.  Here the send/recv steps
+are dropped and the N blocks are N windows of one GPU's K/V tensors, so the loop is
+
+    (O, L) <- (0, -inf);  for n in blocks:  (dO, dL) <- lvx_xattn_fwd(Q, K[n], V[n]);
+                                             (O, L) <- lvx_xattn_merge((O, L), (dO, dL))
+
+and the backward pass runs lvx_xattn_bwd once per block with the FINAL (O, L): dK/dV of a block
+are complete after its call, dQ accumulates over blocks (no rescaling appears in backward).
+
+This module only sequences C-ABI calls and owns the buffers between them (allocated once, in
+the constructor, so the timed loop allocates nothing); all arithmetic is in the kernels.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Optional, Tuple
+
+import torch
+
+from . import binding as B
+
+
+@dataclass
+class MediaMask:
+    allow: torch.Tensor      # uint8 device tensor [n_q_chunks, n_kv_blocks] (or [B, ., .])
+    q_chunk: int
+    kv_block: int
+
+
+class BlockLoop:
+    def __init__(self, q_shape, kv_shape, dtype: torch.dtype, n_blocks: int = 1,
+                 mask: Optional[MediaMask] = None, softmax_scale: float = 0.0,
+                 device: str = "cuda"):
+        if not torch.cuda.is_available():
+            raise RuntimeError("BlockLoop needs a GPU: there is no CPU fallback")
+        B.load()
+        self.Bsz, self.Hq, self.Sq, self.D = q_shape
+        _, self.Hkv, self.Skv, _ = kv_shape
+        assert self.Skv % n_blocks == 0, "blocks must be equal (the paper's Skv/n)"
+        self.n_blocks = n_blocks
+        self.blk = self.Skv // n_blocks
+        if mask is not None and n_blocks > 1:
+            assert self.blk % mask.kv_block == 0, "block boundaries must fall on mask blocks"
+        self.dtype, self.mask, self.scale, self.dev = dtype, mask, softmax_scale, device
+        f32 = dict(dtype=torch.float32, device=device)
+        rows = (self.Bsz, self.Hq, self.Sq)
+        self.lse = torch.empty(rows, **f32)
+        self.o = torch.empty(q_shape, dtype=dtype, device=device)
+        if n_blocks > 1:
+            self.o_acc = torch.empty(q_shape, **f32)       # running O_j of Algorithm 1
+            self.o_part = torch.empty(q_shape, **f32)      # delta-O of one visit
+            self.lse_part = torch.empty(rows, **f32)
+        self.dq_accum = torch.empty(q_shape, **f32)
+        self.dq = torch.empty(q_shape, dtype=dtype, device=device)
+        # one workspace sized for the larger of the two passes
+        qd = torch.empty(q_shape, dtype=dtype, device="meta")
+        kd = torch.empty((self.Bsz, self.Hkv, self.blk, self.D), dtype=dtype, device="meta")
+        p = B.make_problem(qd, kd, softmax_scale)
+        p.kv_sh = self.Skv * self.D
+        p.kv_sb = self.Hkv * self.Skv * self.D
+        code = B.dtype_code(dtype)
+        nbytes = max(B.lvx_xattn_workspace_bytes(p, code, B.LVX_WS_FWD),
+                     B.lvx_xattn_workspace_bytes(p, code, B.LVX_WS_BWD))
+        if nbytes == 0:
+            raise B.LvxError(-2, "lvx_xattn_workspace_bytes")
+        self.ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+    def _mask_for(self, n: int) -> Optional[B.lvx_mask]:
+        if self.mask is None:
+            return None
+        per = self.blk // self.mask.kv_block if self.n_blocks > 1 else 0
+        nkb = (self.blk + self.mask.kv_block - 1) // self.mask.kv_block
+        return B.make_mask(self.mask.allow, self.mask.q_chunk, self.mask.kv_block, n * per, nkb)
+
+    def forward(self, q, k, v) -> Tuple[torch.Tensor, torch.Tensor]:
+        """Returns (O in the input dtype, L float32); both are buffers owned by this object."""
+        if self.n_blocks == 1:
+            p = B.make_problem(q, k, self.scale)
+            B.lvx_xattn_fwd(p, q, k, v, self._mask_for(0), self.o, self.lse, self.ws)
+            return self.o, self.lse
+        for n in range(self.n_blocks):
+            kb = k[:, :, n * self.blk:(n + 1) * self.blk]
+            vb = v[:, :, n * self.blk:(n + 1) * self.blk]
+            p = B.make_problem(q, kb, self.scale)
+            if n == 0:      # merging with the identity (0, -inf) is a no-op: write the state directly
+                B.lvx_xattn_fwd(p, q, kb, vb, self._mask_for(n), self.o_acc, self.lse, self.ws)
+            else:
+                B.lvx_xattn_fwd(p, q, kb, vb, self._mask_for(n), self.o_part, self.lse_part, self.ws)
+                B.lvx_xattn_merge([self.o_acc, self.o_part], [self.lse, self.lse_part],
+                                  self.o_acc, self.lse)
+        B.lvx_xattn_merge([self.o_acc], [self.lse], self.o, self.lse)    # round to the output dtype
+        return self.o, self.lse
+
+    def backward(self, q, k, v, o, lse, d_o, dk, dv) -> torch.Tensor:
+        """dk/dv (same shape and strides as k) are overwritten; returns dQ in the input dtype."""
+        self.dq_accum.zero_()
+        for n in range(self.n_blocks):
+            sl = slice(n * self.blk, (n + 1) * self.blk)
+            kb, vb = k[:, :, sl], v[:, :, sl]
+            p = B.make_problem(q, kb, self.scale)
+            B.lvx_xattn_bwd(p, q, kb, vb, o, lse, d_o, self._mask_for(n), self.dq_accum,
+                            dk[:, :, sl], dv[:, :, sl], self.ws)
+        p = B.make_problem(q, k, self.scale)
+        B.lvx_xattn_dq_finalize(p, self.dq_accum, self.dq)
+        return self.dq

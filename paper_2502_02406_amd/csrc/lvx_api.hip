@@ -1,0 +1,222 @@
+// C ABI of the library (see include/lvx.h): argument validation on the host, workspace carving,
+// KV-split choice, and kernel launches on the caller's stream.  Nothing here allocates or
+// synchronises.
+#include "../../include/lvx.h"
+#include "lvx_internal.h"
+
+#include <math.h>
+
+using namespace lvx;
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+int device_cu_count() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      n = v;
+    else
+      return 256;
+  }
+  return n;
+}
+
+lvx_status check_problem(const lvx_problem* p, lvx_dtype dtype) {
+  if (!p) return LVX_ERR_NULL;
+  if (dtype != LVX_F32 && dtype != LVX_BF16) return LVX_ERR_DTYPE;
+  if (p->B < 1 || p->Hq < 1 || p->Hkv < 1 || p->Sq < 1 || p->Skv < 1 || p->D < 1) return LVX_ERR_SHAPE;
+  if (p->Hq % p->Hkv != 0) return LVX_ERR_SHAPE;
+  if (p->B > 65535 || p->Hq > 65535) return LVX_ERR_SHAPE;
+  if (p->D != 64 && p->D != 128) return LVX_ERR_UNSUPPORTED;
+  // rows are read with 16-byte vector accesses: strides must keep that alignment
+  const int64_t vec = dtype == LVX_F32 ? 4 : 8;
+  const int64_t qs[3] = {p->q_sb, p->q_sh, p->q_ss}, ks[3] = {p->kv_sb, p->kv_sh, p->kv_ss};
+  for (int i = 0; i < 3; ++i)
+    if (qs[i] % vec != 0 || ks[i] % vec != 0) return LVX_ERR_STRIDE;
+  if (p->q_ss < p->D || p->kv_ss < p->D) return LVX_ERR_STRIDE;
+  if (p->Sq > 1 && p->q_sh < 0) return LVX_ERR_STRIDE;
+  if (p->q_sh < 0 || p->q_sb < 0 || p->kv_sh < 0 || p->kv_sb < 0) return LVX_ERR_STRIDE;
+  if (p->Hq > 1 && p->q_sh < (int64_t)p->D) return LVX_ERR_STRIDE;
+  if (p->Hkv > 1 && p->kv_sh < (int64_t)p->D) return LVX_ERR_STRIDE;
+  if (p->B > 1 && (p->q_sb < (int64_t)p->D || p->kv_sb < (int64_t)p->D)) return LVX_ERR_STRIDE;
+  return LVX_OK;
+}
+
+lvx_status check_mask(const lvx_problem* p, const lvx_mask* m) {
+  if (!m) return LVX_OK;
+  if (!m->allow) return LVX_ERR_NULL;
+  if (m->q_chunk < 1 || m->kv_block < 1 || m->n_q_chunks < 1 || m->n_kv_blocks < 1) return LVX_ERR_MASK;
+  if ((int64_t)m->n_q_chunks * m->q_chunk < p->Sq) return LVX_ERR_MASK;
+  if ((int64_t)m->n_kv_blocks * m->kv_block < p->Skv) return LVX_ERR_MASK;
+  if (m->stride_q < m->n_kv_blocks || m->stride_b < 0) return LVX_ERR_MASK;
+  return LVX_OK;
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+Dims make_dims(const lvx_problem* p) {
+  Dims d;
+  d.B = p->B; d.Hq = p->Hq; d.Hkv = p->Hkv; d.Sq = p->Sq; d.Skv = p->Skv; d.D = p->D;
+  d.q_sb = p->q_sb; d.q_sh = p->q_sh; d.q_ss = p->q_ss;
+  d.kv_sb = p->kv_sb; d.kv_sh = p->kv_sh; d.kv_ss = p->kv_ss;
+  d.scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->D);
+  return d;
+}
+
+MaskDev make_mask(const lvx_mask* m) {
+  MaskDev r;
+  if (!m) { r.allow = nullptr; r.q_chunk = r.kv_block = 1; r.n_q_chunks = r.n_kv_blocks = 0; r.stride_b = r.stride_q = 0; return r; }
+  r.allow = m->allow; r.q_chunk = m->q_chunk; r.kv_block = m->kv_block;
+  r.n_q_chunks = m->n_q_chunks; r.n_kv_blocks = m->n_kv_blocks;
+  r.stride_b = (long)m->stride_b; r.stride_q = (long)m->stride_q;
+  return r;
+}
+
+int fwd_split(const Dims& d, lvx_dtype dtype) {
+  return dtype == LVX_BF16 ? fwd_bf16_pick_split(d, device_cu_count()) : 1;
+}
+int bwd_split(const Dims& d, lvx_dtype dtype) {
+  return dtype == LVX_BF16 ? bwd_bf16_pick_split(d, device_cu_count()) : 1;
+}
+
+size_t fwd_ws(const Dims& d, int n_split) {
+  if (n_split <= 1) return ALIGN;   // never zero, so that a valid workspace pointer is always passed
+  const size_t rows = (size_t)d.B * d.Hq * d.Sq;
+  return align_up(rows * d.D * sizeof(float) * n_split) + align_up(rows * sizeof(float) * n_split);
+}
+size_t bwd_ws(const Dims& d) { return align_up((size_t)d.B * d.Hq * d.Sq * sizeof(float)); }
+
+}  // namespace
+
+extern "C" {
+
+const char* lvx_strerror(lvx_status s) {
+  switch (s) {
+    case LVX_OK: return "ok";
+    case LVX_ERR_NULL: return "required pointer is NULL";
+    case LVX_ERR_SHAPE: return "invalid shape";
+    case LVX_ERR_DTYPE: return "unsupported dtype";
+    case LVX_ERR_STRIDE: return "invalid or misaligned stride / pointer";
+    case LVX_ERR_MASK: return "mask geometry does not cover the problem";
+    case LVX_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case LVX_ERR_UNSUPPORTED: return "unsupported head dimension";
+    case LVX_ERR_HIP: return "HIP launch failed";
+  }
+  return "unknown status";
+}
+
+size_t lvx_xattn_workspace_bytes(const lvx_problem* p, lvx_dtype dtype, int which) {
+  if (check_problem(p, dtype) != LVX_OK) return 0;
+  const Dims d = make_dims(p);
+  if (which == LVX_WS_FWD) return fwd_ws(d, fwd_split(d, dtype));
+  if (which == LVX_WS_BWD) return bwd_ws(d);
+  return 0;
+}
+
+lvx_status lvx_xattn_fwd(const lvx_problem* p, lvx_dtype dtype, const void* q, const void* k,
+                         const void* v, const lvx_mask* mask, void* o, lvx_dtype o_dtype,
+                         float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  lvx_status st = check_problem(p, dtype);
+  if (st != LVX_OK) return st;
+  if (!q || !k || !v || !o || !lse) return LVX_ERR_NULL;
+  if (o_dtype != dtype && o_dtype != LVX_F32) return LVX_ERR_DTYPE;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return LVX_ERR_STRIDE;
+  if ((st = check_mask(p, mask)) != LVX_OK) return st;
+  FwdArgs a;
+  a.d = make_dims(p);
+  a.mask = make_mask(mask);
+  a.q = q; a.k = k; a.v = v; a.o = o; a.o_is_f32 = o_dtype == LVX_F32; a.lse = lse;
+  a.n_split = fwd_split(a.d, dtype);
+  a.o_part = nullptr; a.lse_part = nullptr;
+  const size_t need = fwd_ws(a.d, a.n_split);
+  if (!workspace || ((uintptr_t)workspace % ALIGN) != 0 || workspace_bytes < need) return LVX_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)hip_stream;
+  const size_t rows = (size_t)a.d.B * a.d.Hq * a.d.Sq;
+  if (a.n_split > 1) {
+    a.o_part = (float*)workspace;
+    a.lse_part = (float*)((char*)workspace + align_up(rows * a.d.D * sizeof(float) * a.n_split));
+  }
+  hipError_t e = dtype == LVX_BF16 ? launch_fwd_bf16(a, s) : launch_fwd_f32(a, s);
+  if (e != hipSuccess) return LVX_ERR_HIP;
+  if (a.n_split > 1) {
+    MergeArgs m;
+    m.n_parts = a.n_split;
+    for (int i = 0; i < a.n_split; ++i) {
+      m.o_parts[i] = a.o_part + (size_t)i * rows * a.d.D;
+      m.lse_parts[i] = a.lse_part + (size_t)i * rows;
+    }
+    m.rows = (long)rows; m.D = a.d.D; m.o_out = o; m.lse_out = lse;
+    m.Hq = a.d.Hq; m.Sq = a.d.Sq; m.o_sb = a.d.q_sb; m.o_sh = a.d.q_sh; m.o_ss = a.d.q_ss;
+    e = launch_merge(m, 1, a.o_is_f32, s);
+    if (e != hipSuccess) return LVX_ERR_HIP;
+  }
+  return LVX_OK;
+}
+
+lvx_status lvx_xattn_merge(int32_t B, int32_t Hq, int32_t Sq, int32_t D, int32_t n_parts,
+                           const void* const* o_parts, const float* const* lse_parts,
+                           lvx_dtype part_dtype, void* o_out, lvx_dtype out_dtype, float* lse_out,
+                           void* hip_stream) {
+  if (!o_parts || !lse_parts || !o_out || !lse_out) return LVX_ERR_NULL;
+  if (B < 1 || Hq < 1 || Sq < 1 || n_parts < 1 || n_parts > LVX_MAX_PARTS) return LVX_ERR_SHAPE;
+  if (D != 64 && D != 128) return LVX_ERR_UNSUPPORTED;
+  if ((part_dtype != LVX_F32 && part_dtype != LVX_BF16) || (out_dtype != LVX_F32 && out_dtype != LVX_BF16))
+    return LVX_ERR_DTYPE;
+  if (!aligned16(o_out)) return LVX_ERR_STRIDE;
+  MergeArgs m;
+  for (int i = 0; i < n_parts; ++i) {
+    if (!o_parts[i] || !lse_parts[i]) return LVX_ERR_NULL;
+    if (!aligned16(o_parts[i])) return LVX_ERR_STRIDE;
+    m.o_parts[i] = o_parts[i];
+    m.lse_parts[i] = lse_parts[i];
+  }
+  m.n_parts = n_parts;
+  m.rows = (long)B * Hq * Sq; m.D = D; m.o_out = o_out; m.lse_out = lse_out;
+  m.Hq = Hq; m.Sq = Sq; m.o_ss = D; m.o_sh = (long)Sq * D; m.o_sb = (long)Hq * Sq * D;
+  hipError_t e = launch_merge(m, part_dtype == LVX_F32, out_dtype == LVX_F32, (hipStream_t)hip_stream);
+  return e == hipSuccess ? LVX_OK : LVX_ERR_HIP;
+}
+
+lvx_status lvx_xattn_bwd(const lvx_problem* p, lvx_dtype dtype, const void* q, const void* k,
+                         const void* v, const void* o, const float* lse, const void* d_o,
+                         const lvx_mask* mask, float* dq_accum, void* dk, void* dv,
+                         void* workspace, size_t workspace_bytes, void* hip_stream) {
+  lvx_status st = check_problem(p, dtype);
+  if (st != LVX_OK) return st;
+  if (!q || !k || !v || !o || !lse || !d_o || !dq_accum || !dk || !dv) return LVX_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) ||
+      !aligned16(dq_accum) || !aligned16(dk) || !aligned16(dv))
+    return LVX_ERR_STRIDE;
+  if ((st = check_mask(p, mask)) != LVX_OK) return st;
+  BwdArgs a;
+  a.d = make_dims(p);
+  a.mask = make_mask(mask);
+  const size_t need = bwd_ws(a.d);
+  if (!workspace || ((uintptr_t)workspace % ALIGN) != 0 || workspace_bytes < need) return LVX_ERR_WORKSPACE;
+  a.q = q; a.k = k; a.v = v; a.o = o; a.d_o = d_o; a.lse = lse;
+  a.delta = (float*)workspace;
+  a.dq_accum = dq_accum; a.dk = dk; a.dv = dv;
+  a.n_split_dq = bwd_split(a.d, dtype);
+  hipStream_t s = (hipStream_t)hip_stream;
+  hipError_t e = launch_delta(a.d, o, d_o, dtype == LVX_F32, a.delta, s);
+  if (e != hipSuccess) return LVX_ERR_HIP;
+  e = dtype == LVX_BF16 ? launch_bwd_bf16(a, s) : launch_bwd_f32(a, s);
+  return e == hipSuccess ? LVX_OK : LVX_ERR_HIP;
+}
+
+lvx_status lvx_xattn_dq_finalize(const lvx_problem* p, const float* dq_accum, void* dq,
+                                 lvx_dtype dtype, void* hip_stream) {
+  lvx_status st = check_problem(p, dtype);
+  if (st != LVX_OK) return st;
+  if (!dq_accum || !dq) return LVX_ERR_NULL;
+  if (!aligned16(dq_accum) || !aligned16(dq)) return LVX_ERR_STRIDE;
+  hipError_t e = launch_dq_finalize(make_dims(p), dq_accum, dq, dtype == LVX_F32, (hipStream_t)hip_stream);
+  return e == hipSuccess ? LVX_OK : LVX_ERR_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,176 @@
+// HBM-bound kernels of the path: the Rescale/merge of Algorithm 1 (also used to combine the
+// forward kernel's KV splits), the backward's delta = rowsum(dO * O), and the dQ conversion.
+#include "lvx_internal.h"
+
+namespace lvx {
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
+__device__ __forceinline__ float bf16_lo(unsigned u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(unsigned u) { return __uint_as_float(u & 0xffff0000u); }
+__device__ __forceinline__ unsigned pack_bf16(float a, float b) {
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+  bf16x2 r;
+  r[0] = (__bf16)a;   // round to nearest even
+  r[1] = (__bf16)b;
+  return *(unsigned*)&r;
+}
+
+// One thread owns VEC consecutive elements of one (b,h,i) row: VEC = 4 floats or 8 bf16 (16 bytes).
+// L' = ln sum_k exp(L_k), O' = sum_k exp(L_k - L') O_k.  A row's threads sit in one wavefront, so
+// every lane has read lse_parts[*][row] before lane 0 of the row stores lse_out[row]; this is
+// what makes lse_out == lse_parts[0] (in-place update of the running state) safe.
+template <bool PART_F32, bool OUT_F32>
+__global__ void __launch_bounds__(256) merge_kernel(MergeArgs a) {
+  constexpr int VEC_IN = PART_F32 ? 4 : 8;
+  constexpr int VEC_OUT = OUT_F32 ? 4 : 8;
+  constexpr int VEC = VEC_IN < VEC_OUT ? VEC_IN : VEC_OUT;   // elements per thread
+  const int vpr = a.D / VEC;                                  // threads per row
+  const long t = (long)blockIdx.x * 256 + threadIdx.x;
+  const long row = t / vpr;
+  if (row >= a.rows) return;
+  const int c = (int)(t % vpr) * VEC;
+
+  float M = -INFINITY;
+  for (int k = 0; k < a.n_parts; ++k) M = fmaxf(M, a.lse_parts[k][row]);
+  float acc[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+  float Lout = -INFINITY;
+  if (M != -INFINITY) {
+    float z = 0.f;
+    for (int k = 0; k < a.n_parts; ++k) z += expf(a.lse_parts[k][row] - M);
+    Lout = M + logf(z);
+    for (int k = 0; k < a.n_parts; ++k) {
+      const float lk = a.lse_parts[k][row];
+      if (lk == -INFINITY) continue;
+      const float w = expf(lk - Lout);
+      if (PART_F32) {
+        const float* src = (const float*)a.o_parts[k] + row * a.D + c;
+#pragma unroll
+        for (int e = 0; e < VEC; e += 4) {
+          f32x4 x = *(const f32x4*)(src + e);
+          acc[e] += w * x[0]; acc[e + 1] += w * x[1]; acc[e + 2] += w * x[2]; acc[e + 3] += w * x[3];
+        }
+      } else {
+        const unsigned* src = (const unsigned*)((const uint16_t*)a.o_parts[k] + row * a.D + c);
+        if (VEC == 8) {
+          u32x4 x = *(const u32x4*)src;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { acc[2 * e] += w * bf16_lo(x[e]); acc[2 * e + 1] += w * bf16_hi(x[e]); }
+        } else {
+          unsigned x0 = src[0], x1 = src[1];
+          acc[0] += w * bf16_lo(x0); acc[1] += w * bf16_hi(x0);
+          acc[2] += w * bf16_lo(x1); acc[3] += w * bf16_hi(x1);
+        }
+      }
+    }
+  }
+  const long i = row % a.Sq, h = (row / a.Sq) % a.Hq, b = row / ((long)a.Sq * a.Hq);
+  const long off = b * a.o_sb + h * a.o_sh + i * a.o_ss + c;
+  if (OUT_F32) {
+    float* dst = (float*)a.o_out + off;
+#pragma unroll
+    for (int e = 0; e < VEC; e += 4) {
+      f32x4 y = {acc[e], acc[e + 1], acc[e + 2], acc[e + 3]};
+      *(f32x4*)(dst + e) = y;
+    }
+  } else {
+    unsigned* dst = (unsigned*)((uint16_t*)a.o_out + off);
+    if (VEC == 8) {
+      u32x4 y = {pack_bf16(acc[0], acc[1]), pack_bf16(acc[2], acc[3]), pack_bf16(acc[4], acc[5]),
+                 pack_bf16(acc[6], acc[7])};
+      *(u32x4*)dst = y;
+    } else {
+      dst[0] = pack_bf16(acc[0], acc[1]);
+      dst[1] = pack_bf16(acc[2], acc[3]);
+    }
+  }
+  if (c == 0) a.lse_out[row] = Lout;
+}
+
+hipError_t launch_merge(const MergeArgs& a, int part_is_f32, int out_is_f32, hipStream_t s) {
+  const int vec = (part_is_f32 || out_is_f32) ? 4 : 8;
+  const long threads = a.rows * (a.D / vec);
+  const unsigned blocks = (unsigned)((threads + 255) / 256);
+  if (part_is_f32 && out_is_f32) merge_kernel<true, true><<<blocks, 256, 0, s>>>(a);
+  else if (part_is_f32) merge_kernel<true, false><<<blocks, 256, 0, s>>>(a);
+  else if (out_is_f32) merge_kernel<false, true><<<blocks, 256, 0, s>>>(a);
+  else merge_kernel<false, false><<<blocks, 256, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+// delta[b,h,i] = sum_d dO[b,h,i,d] * O[b,h,i,d].  16 lanes per row.
+template <bool F32>
+__global__ void __launch_bounds__(256) delta_kernel(Dims d, const void* o, const void* d_o,
+                                                    float* delta) {
+  const long rows = (long)d.B * d.Hq * d.Sq;
+  const long row = ((long)blockIdx.x * 256 + threadIdx.x) / 16;
+  const int c = threadIdx.x % 16;
+  float s = 0.f;
+  if (row < rows) {
+    const long i = row % d.Sq, h = (row / d.Sq) % d.Hq, b = row / ((long)d.Sq * d.Hq);
+    const long off = b * d.q_sb + h * d.q_sh + i * d.q_ss;
+    if (F32) {
+      const float* po = (const float*)o + off;
+      const float* pg = (const float*)d_o + off;
+      for (int e = c * 4; e < d.D; e += 64) {
+        f32x4 x = *(const f32x4*)(po + e), y = *(const f32x4*)(pg + e);
+        s += x[0] * y[0] + x[1] * y[1] + x[2] * y[2] + x[3] * y[3];
+      }
+    } else {
+      const uint16_t* po = (const uint16_t*)o + off;
+      const uint16_t* pg = (const uint16_t*)d_o + off;
+      for (int e = c * 8; e < d.D; e += 128) {
+        u32x4 x = *(const u32x4*)(po + e), y = *(const u32x4*)(pg + e);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) s += bf16_lo(x[k]) * bf16_lo(y[k]) + bf16_hi(x[k]) * bf16_hi(y[k]);
+      }
+    }
+  }
+#pragma unroll
+  for (int m = 8; m >= 1; m >>= 1) s += __shfl_xor(s, m, 16);
+  if (row < rows && c == 0) delta[row] = s;
+}
+
+hipError_t launch_delta(const Dims& d, const void* o, const void* d_o, int is_f32, float* delta,
+                        hipStream_t s) {
+  const long rows = (long)d.B * d.Hq * d.Sq;
+  const unsigned blocks = (unsigned)((rows * 16 + 255) / 256);
+  if (is_f32) delta_kernel<true><<<blocks, 256, 0, s>>>(d, o, d_o, delta);
+  else delta_kernel<false><<<blocks, 256, 0, s>>>(d, o, d_o, delta);
+  return hipGetLastError();
+}
+
+// dq (input dtype, Q's strides) = dq_accum (float32, contiguous).  One thread per 8 elements.
+template <bool F32>
+__global__ void __launch_bounds__(256) dq_finalize_kernel(Dims d, const float* acc, void* dq) {
+  const int vpr = d.D / 8;
+  const long t = (long)blockIdx.x * 256 + threadIdx.x;
+  const long row = t / vpr;
+  if (row >= (long)d.B * d.Hq * d.Sq) return;
+  const int c = (int)(t % vpr) * 8;
+  const long i = row % d.Sq, h = (row / d.Sq) % d.Hq, b = row / ((long)d.Sq * d.Hq);
+  const long off = b * d.q_sb + h * d.q_sh + i * d.q_ss + c;
+  const f32x4 x0 = *(const f32x4*)(acc + row * d.D + c), x1 = *(const f32x4*)(acc + row * d.D + c + 4);
+  if (F32) {
+    *(f32x4*)((float*)dq + off) = x0;
+    *(f32x4*)((float*)dq + off + 4) = x1;
+  } else {
+    u32x4 y = {pack_bf16(x0[0], x0[1]), pack_bf16(x0[2], x0[3]), pack_bf16(x1[0], x1[1]),
+               pack_bf16(x1[2], x1[3])};
+    *(u32x4*)((uint16_t*)dq + off) = y;
+  }
+}
+
+hipError_t launch_dq_finalize(const Dims& d, const float* dq_accum, void* dq, int is_f32,
+                              hipStream_t s) {
+  const long threads = (long)d.B * d.Hq * d.Sq * (d.D / 8);
+  const unsigned blocks = (unsigned)((threads + 255) / 256);
+  if (is_f32) dq_finalize_kernel<true><<<blocks, 256, 0, s>>>(d, dq_accum, dq);
+  else dq_finalize_kernel<false><<<blocks, 256, 0, s>>>(d, dq_accum, dq);
+  return hipGetLastError();
+}
+
+}  // namespace lvx

@@ -1,0 +1,75 @@
+// Internal launch interface between the C-ABI host layer (lvx_api.hip) and the kernels.
+// Everything here is private to the library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lvx {
+
+// Media mask as the kernels see it (allow == nullptr means dense attention).
+struct MaskDev {
+  const uint8_t* allow;
+  int q_chunk, kv_block, n_q_chunks, n_kv_blocks;
+  long stride_b, stride_q;
+};
+
+// Shape, strides (in elements) and scale shared by every kernel.
+struct Dims {
+  int B, Hq, Hkv, Sq, Skv, D;
+  long q_sb, q_sh, q_ss;
+  long kv_sb, kv_sh, kv_ss;
+  float scale;          // multiplies Q K^T (natural-log domain)
+};
+
+struct FwdArgs {
+  Dims d;
+  MaskDev mask;
+  const void *q, *k, *v;
+  void* o;              // final output (Q's strides) when n_split == 1
+  int o_is_f32;         // 1: o is float32, 0: o has the input dtype
+  float* lse;           // [B,Hq,Sq]
+  int n_split;          // number of KV splits handled by separate workgroups
+  float* o_part;        // [n_split, B,Hq,Sq,D] float32, contiguous (n_split > 1)
+  float* lse_part;      // [n_split, B,Hq,Sq]
+};
+
+struct BwdArgs {
+  Dims d;
+  MaskDev mask;
+  const void *q, *k, *v, *o, *d_o;
+  const float* lse;     // final statistic, [B,Hq,Sq]
+  float* delta;         // workspace, [B,Hq,Sq]: rowsum(dO * O)
+  float* dq_accum;      // [B,Hq,Sq,D] float32, accumulated into
+  void *dk, *dv;        // K's strides, input dtype, overwritten
+  int n_split_dq;       // KV splits of the dQ kernel (each adds into dq_accum)
+};
+
+struct MergeArgs {
+  const void* o_parts[64];
+  const float* lse_parts[64];
+  int n_parts;
+  long rows;            // B*Hq*Sq
+  int D;
+  void* o_out;
+  float* lse_out;
+  // output addressing: row r = ((b*Hq + h)*Sq + i) -> o_out + b*o_sb + h*o_sh + i*o_ss
+  int Hq, Sq;
+  long o_sb, o_sh, o_ss;
+};
+
+// kernels for float32 tensors (plain FMA, correctness-grade)
+hipError_t launch_fwd_f32(const FwdArgs& a, hipStream_t s);
+hipError_t launch_bwd_f32(const BwdArgs& a, hipStream_t s);
+// kernels for bfloat16 tensors (MFMA)
+hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t s);
+hipError_t launch_bwd_bf16(const BwdArgs& a, hipStream_t s);
+int fwd_bf16_pick_split(const Dims& d, int n_cu);
+int bwd_bf16_pick_split(const Dims& d, int n_cu);
+// memory-bound helpers
+hipError_t launch_merge(const MergeArgs& a, int part_is_f32, int out_is_f32, hipStream_t s);
+hipError_t launch_delta(const Dims& d, const void* o, const void* d_o, int is_f32, float* delta,
+                        hipStream_t s);
+hipError_t launch_dq_finalize(const Dims& d, const float* dq_accum, void* dq, int is_f32,
+                              hipStream_t s);
+
+}  // namespace lvx

@@ -1,0 +1,133 @@
+// Device helpers shared by the bf16 MFMA kernels (gfx950 only).
+//
+// Register layouts of v_mfma_f32_32x32x16_bf16 (wave64), lane l, g = l / 32:
+//   A (32 x 16): row m = l % 32, k = 8 g + e, e = 0..7   (8 bf16 per lane)
+//   B (16 x 32): col n = l % 32, k = 8 g + e
+//   C (32 x 32): col n = l % 32, row m = 8 (v / 4) + 4 g + (v % 4), v = 0..15
+// All kernels compute TRANSPOSED score tiles S^T = K Q^T, so that a lane holds one query column
+// and 16 key rows per 32x32 block: the softmax statistics of a query are per-lane scalars, and
+// the C registers, converted to bf16, already ARE the B operand of the next product over keys
+// (k index = key), with key order  key = 16 t + 8 (e / 4) + 4 g + (e % 4)  for k-step t, slot e.
+// The matching A operand (V^T or K^T) is fetched with the transposing LDS read, two per operand.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lvx {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+
+#define LVX_LDS(ptr, type) ((type __attribute__((address_space(3)))*)(ptr))
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ f32x16 zero16() {
+  f32x16 z;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) z[i] = 0.f;
+  return z;
+}
+
+// Transposing LDS read.  Within each group of 16 lanes, lane j supplies the address of 4
+// consecutive bf16; lane i receives element i of the 4 quads supplied by lanes 4r..4r+3 taken as
+// row r, i.e. result[r] = row_r[i].  With lanes 4r..4r+3 pointing at 16 consecutive columns of
+// row k0 + r of a row-major tile, lane i gets the column (k0..k0+3, n0 + i).
+__device__ __forceinline__ s16x4 lds_read_tr(const void* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (s16x4 __attribute__((address_space(3)))*)(uintptr_t)(p));
+}
+
+// A operand (32 rows n x 16 k) of a product over k taken from a ROW-MAJOR LDS tile X[k][n]
+// (pitch in bytes): rows n0 + l%32, k slots e -> k = kbase + 8 (e / 4) + 4 g + (e % 4).
+__device__ __forceinline__ bf16x8 load_tr_operand(const char* tile, int pitch_b, int kbase, int n0,
+                                                  int lane) {
+  const int j = lane & 15, half = (lane >> 4) & 1, g = lane >> 5;
+  const char* p = tile + (kbase + 4 * g + (j >> 2)) * pitch_b + (n0 + 16 * half + 4 * (j & 3)) * 2;
+  s16x4 lo = lds_read_tr(p);
+  s16x4 hi = lds_read_tr(p + 8 * pitch_b);
+  typedef __attribute__((ext_vector_type(8))) short s16x8;
+  s16x8 r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+// Two floats -> packed bf16 (round to nearest even), low half = a.
+__device__ __forceinline__ unsigned pack2_bf16(float a, float b) {
+  bf16x2 r;
+  r[0] = (__bf16)a;
+  r[1] = (__bf16)b;
+  return __builtin_bit_cast(unsigned, r);
+}
+
+// 8 consecutive C registers (v0..v0+7) of one 32x32 block -> B operand of the next product.
+__device__ __forceinline__ bf16x8 cvt_operand(const f32x16& c, int v0) {
+  u32x4 r = {pack2_bf16(c[v0], c[v0 + 1]), pack2_bf16(c[v0 + 2], c[v0 + 3]),
+             pack2_bf16(c[v0 + 4], c[v0 + 5]), pack2_bf16(c[v0 + 6], c[v0 + 7])};
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+// max / sum across the two half-waves (lanes l and l ^ 32 hold the same query column).
+__device__ __forceinline__ float xhalf_max(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float xhalf_sum(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Media-mask classification of the rectangle query rows [i0, i1] x key rows [j0, j1]:
+// 0 = nothing visible, 1 = everything visible, 2 = mixed.  Wave-uniform arguments.
+__device__ __forceinline__ int mask_rect(const MaskDev& m, int b, int i0, int i1, int j0, int j1) {
+  if (!m.allow) return 1;
+  const uint8_t* base = m.allow + b * m.stride_b;
+  bool any = false, all = true;
+  for (int c = i0 / m.q_chunk; c <= i1 / m.q_chunk; ++c)
+    for (int f = j0 / m.kv_block; f <= j1 / m.kv_block; ++f) {
+      const bool on = base[(long)c * m.stride_q + f] != 0;
+      any |= on;
+      all &= on;
+    }
+  return all ? 1 : (any ? 2 : 0);
+}
+
+__device__ __forceinline__ bool mask_elem(const MaskDev& m, int b, int i, int j) {
+  return m.allow[b * m.stride_b + (long)(i / m.q_chunk) * m.stride_q + (j / m.kv_block)] != 0;
+}
+
+// XCD-aware decode of a 1-D grid.  Workgroup ids are dealt round-robin to the 8 XCDs, each with
+// its own L2.  All work items that share a K/V head are placed on one XCD (or, when there are
+// fewer heads than XCDs, a head is cut into equal parts) so that one HBM fetch of a K/V tile
+// feeds every workgroup that needs it.  Returns false for padding workgroups.
+struct HeadWork { int head; int item; };
+__host__ __device__ inline int xcd_parts(int n_heads) {   // parts a head is cut into
+  int g = n_heads % 8 == 0 ? 8 : (n_heads % 4 == 0 ? 4 : (n_heads % 2 == 0 ? 2 : 1));
+  return 8 / g;
+}
+__host__ __device__ inline long xcd_grid(int n_heads, int items_per_head) {
+  const int S = xcd_parts(n_heads);
+  const int per_vh = (items_per_head + S - 1) / S;
+  const long n_vh = (long)n_heads * S;                    // multiple of 8
+  return n_vh * per_vh;
+}
+__device__ __forceinline__ bool xcd_decode(long pid, int n_heads, int items_per_head, HeadWork* w) {
+  const int S = xcd_parts(n_heads);
+  const int per_vh = (items_per_head + S - 1) / S;
+  const int xcd = (int)(pid % 8);
+  const long slot = pid / 8;
+  const long vh = (slot / per_vh) * 8 + xcd;
+  const int item = (int)(vh % S) * per_vh + (int)(slot % per_vh);
+  w->head = (int)(vh / S);
+  w->item = item;
+  return item < items_per_head;
+}
+
+}  // namespace lvx
