@@ -1,0 +1,168 @@
+#!/usr/bin/env python3
+"""Benchmark of the LV-XAttn cross-attention path on ONE MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input: the forward
+block loop (Algorithm 1 with the send/recv removed: per K/V block lvx_xattn_fwd + lvx_xattn_merge)
+followed by the backward block loop (per block lvx_xattn_bwd, then lvx_xattn_dq_finalize).
+The workload is the long-video share: B=1, Hq=32, Hkv=8, D=128, Sq=2048, Skv=262144 in 8 blocks
+of 32768, bf16.  FLOPs follow the paper's Table 1 convention (forward 4, backward 10 times
+Sq*Skv*h*d).  Inputs are seeded, synthetic and resident in HBM before the timed region.
+
+Prints ONE JSON line.  `roofline` is for the dominant kernel, timed live with HIP events on the
+stream the kernels run on; `cpu_baseline` is the fp64 oracle timed on the host cores on a bounded
+sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(w, seed):
+    """Oracle forward + backward on a slice of the workload: one K/V head (its 4 query heads),
+    the first `sq` query rows and the first `skv` keys."""
+    import numpy as np
+    import oracle
+    from paper_2502_02406_amd import workloads as W
+    sq, skv = 2048, 131072
+    G = w.Hq // w.Hkv
+    small = W.scaled(w, name="cpu_sample", B=1, Hq=G, Hkv=1, Sq=sq, Skv=skv, n_blocks=1)
+    x = W.make_inputs(small, seed)
+    q, k, v, g = (W.as_f32_numpy(x[n]) for n in ("q", "k", "v", "do"))
+    oracle.fwd(q[:, :, :8], k[:, :, :512], v[:, :, :512])          # warm the thread pool
+    t0 = time.perf_counter()
+    oracle.fwd(q, k, v)
+    oracle.bwd(q, k, v, g)
+    dt = time.perf_counter() - t0
+    flops = small.fwd_flops() + small.bwd_flops()
+    return {"value": flops / dt * 1e-12, "unit": "TFLOP/s", "cores": oracle.threads(),
+            "kind": "oracle", "seconds": dt,
+            "sample": f"fp64 oracle fwd+bwd on B=1 Hq={G} Hkv=1 Sq={sq} Skv={skv} D={w.D} "
+                      f"(one K/V head, first {sq} query rows, first {skv} keys of the workload)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c3_longvideo_256k")
+    ap.add_argument("--seed", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures ONE GPU (the kernel on one GPU's K/V share); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2502_02406_amd import binding as B
+    from paper_2502_02406_amd import workloads as W
+    from paper_2502_02406_amd.blockloop import BlockLoop, MediaMask
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+    B.load()
+    w = W.WORKLOADS[args.workload]
+    seed = W.BASE_SEED if args.seed is None else args.seed
+    x = W.make_inputs(w, seed)
+    dev = {n: t.cuda() for n, t in x.items()}
+    del x
+    mask = MediaMask(dev["allow"], w.q_chunk, w.kv_block) if w.masked else None
+    dt = W.torch_dtype(w.dtype)
+    loop = BlockLoop(tuple(dev["q"].shape), tuple(dev["k"].shape), dt, w.n_blocks, mask)
+    q, k, v, g = dev["q"], dev["k"], dev["v"], dev["do"]
+    dk, dv = torch.empty_like(k), torch.empty_like(v)
+
+    def step():
+        o, lse = loop.forward(q, k, v)
+        loop.backward(q, k, v, o, lse, g, dk, dv)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / args.steps
+    flops = w.fwd_flops() + w.bwd_flops()
+    value = flops / sec * 1e-12
+
+    # ---- per-kernel timing with HIP events on the launch stream (torch's current stream)
+    def timed(fn, reps):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        fn()
+        torch.cuda.synchronize()
+        ev[0].record()
+        for i in range(reps):
+            fn()
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        return sum(ev[i].elapsed_time(ev[i + 1]) for i in range(reps)) / reps   # ms
+
+    o, lse = loop.forward(q, k, v)
+    blk = loop.blk
+    kb, vb = k[:, :, :blk], v[:, :, :blk]
+    p = B.make_problem(q, kb)
+    m0 = loop._mask_for(0)
+    reps = max(3, args.steps)
+    unit = float(w.B * w.Hq * w.D) * (w.visible_pairs() / w.n_blocks)    # Sq*Skv_blk*h*d
+    B.lvx_xattn_bwd(p, q, kb, vb, o, lse, g, m0, loop.dq_accum, dk[:, :, :blk], dv[:, :, :blk],
+                    loop.ws, B.LVX_BWD_DELTA)
+    ms_dkdv = timed(lambda: B.lvx_xattn_bwd(p, q, kb, vb, o, lse, g, m0, loop.dq_accum,
+                                            dk[:, :, :blk], dv[:, :, :blk], loop.ws, B.LVX_BWD_DKDV), reps)
+    ms_dq = timed(lambda: B.lvx_xattn_bwd(p, q, kb, vb, o, lse, g, m0, loop.dq_accum,
+                                          dk[:, :, :blk], dv[:, :, :blk], loop.ws, B.LVX_BWD_DQ), reps)
+    o_part = torch.empty(q.shape, dtype=torch.float32, device="cuda")
+    l_part = torch.empty(q.shape[:3], dtype=torch.float32, device="cuda")
+    ms_fwd = timed(lambda: B.lvx_xattn_fwd(p, q, kb, vb, m0, o_part, l_part, loop.ws), reps)
+    o_acc = torch.zeros_like(o_part)
+    l_acc = torch.zeros_like(l_part)
+    ms_merge = timed(lambda: B.lvx_xattn_merge([o_acc, o_part], [l_acc, l_part], o_acc, l_acc), reps)
+    rows = w.B * w.Hq * w.Sq
+    merge_bytes = 3 * rows * w.D * 4 + 3 * rows * 4
+    kernels = {
+        "bwd_dkdv": {"ms": ms_dkdv, "flops": 8 * unit, "tflops": 8 * unit / ms_dkdv * 1e-9},
+        "bwd_dq": {"ms": ms_dq, "flops": 6 * unit, "tflops": 6 * unit / ms_dq * 1e-9},
+        "fwd": {"ms": ms_fwd, "flops": 4 * unit, "tflops": 4 * unit / ms_fwd * 1e-9},
+        "merge": {"ms": ms_merge, "bytes": merge_bytes, "gbs": merge_bytes / ms_merge * 1e-6,
+                  "frac_hbm": merge_bytes / ms_merge * 1e-6 / PEAK_HBM_GBS},
+    }
+    dom = max(("bwd_dkdv", "bwd_dq", "fwd"), key=lambda n: kernels[n]["ms"])
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": kernels[dom]["tflops"],
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": kernels[dom]["tflops"] / PEAK_BF16_TFLOPS, "traffic": None,
+                "launch_ms": kernels[dom]["ms"],
+                "note": "flops = the matrix products this kernel itself performs per launch "
+                        "(one K/V block of the workload)"}
+
+    out = {
+        "metric": "cross-attn fwd+bwd TFLOP/s, Sq=2048 Skv=256K, 1 GPU",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "Sq": w.Sq,
+                   "Skv": w.Skv, "kv_blocks": w.n_blocks, "masked": w.masked, "seed": seed},
+        "frac_of_bf16_mfma_peak": value / PEAK_BF16_TFLOPS,
+        "flops_per_step": flops,
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, seed)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

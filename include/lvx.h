@@ -119,6 +119,17 @@ lvx_status lvx_xattn_bwd(const lvx_problem* p, lvx_dtype dtype, const void* q, c
                          const lvx_mask* mask, float* dq_accum, void* dk, void* dv,
                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The same call restricted to some of its kernels, for measurement: `stages` is a bit set of
+ * LVX_BWD_DELTA (delta = rowsum(dO * O) into the workspace), LVX_BWD_DKDV (dK and dV) and
+ * LVX_BWD_DQ (dQ accumulation).  DKDV and DQ read the delta a previous DELTA stage left in the
+ * same workspace.  lvx_xattn_bwd is this call with LVX_BWD_ALL. */
+enum { LVX_BWD_DELTA = 1, LVX_BWD_DKDV = 2, LVX_BWD_DQ = 4, LVX_BWD_ALL = 7 };
+lvx_status lvx_xattn_bwd_stages(const lvx_problem* p, lvx_dtype dtype, const void* q, const void* k,
+                                const void* v, const void* o, const float* lse, const void* d_o,
+                                const lvx_mask* mask, float* dq_accum, void* dk, void* dv,
+                                void* workspace, size_t workspace_bytes, void* hip_stream,
+                                unsigned stages);
+
 /* dq (type `dtype`, Q's strides) = dq_accum (float32, contiguous) rounded to `dtype`. */
 lvx_status lvx_xattn_dq_finalize(const lvx_problem* p, const float* dq_accum, void* dq,
                                  lvx_dtype dtype, void* hip_stream);

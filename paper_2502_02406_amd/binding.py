@@ -19,8 +19,10 @@ LVX_F32, LVX_BF16 = 0, 1
 LVX_WS_FWD, LVX_WS_BWD = 0, 1
 LVX_MAX_PARTS = 64
 
+LVX_BWD_DELTA, LVX_BWD_DKDV, LVX_BWD_DQ, LVX_BWD_ALL = 1, 2, 4, 7
+
 EXPORTS = ("lvx_xattn_workspace_bytes", "lvx_xattn_fwd", "lvx_xattn_merge", "lvx_xattn_bwd",
-           "lvx_xattn_dq_finalize", "lvx_strerror")
+           "lvx_xattn_bwd_stages", "lvx_xattn_dq_finalize", "lvx_strerror")
 
 
 class LvxError(RuntimeError):
@@ -69,6 +71,8 @@ def load() -> C.CDLL:
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.POINTER(lvx_mask), C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.lvx_xattn_bwd_stages.restype = C.c_int
+        lib.lvx_xattn_bwd_stages.argtypes = lib.lvx_xattn_bwd.argtypes + [C.c_uint]
         lib.lvx_xattn_dq_finalize.restype = C.c_int
         lib.lvx_xattn_dq_finalize.argtypes = [C.POINTER(lvx_problem), C.c_void_p, C.c_void_p,
                                               C.c_int, C.c_void_p]
@@ -160,19 +164,23 @@ def lvx_xattn_merge(o_parts: Sequence[torch.Tensor], lse_parts: Sequence[torch.T
 
 
 def lvx_xattn_bwd(p: lvx_problem, q, k, v, o, lse, d_o, mask: Optional[lvx_mask], dq_accum, dk, dv,
-                  workspace) -> None:
-    """dk/dv (views with K's strides) overwritten; dq_accum (float32, contiguous) accumulated."""
+                  workspace, stages: int = LVX_BWD_ALL) -> None:
+    """dk/dv (views with K's strides) overwritten; dq_accum (float32, contiguous) accumulated.
+    With stages != LVX_BWD_ALL this is lvx_xattn_bwd_stages (a subset of the kernels)."""
     if not q.is_cuda:
         raise RuntimeError("lvx_xattn_bwd needs device tensors")
     assert dq_accum.dtype == torch.float32 and dq_accum.is_contiguous()
     assert dk.stride() == k.stride() and dv.stride() == k.stride()
     assert o.stride() == q.stride() and d_o.stride() == q.stride()
-    code = load().lvx_xattn_bwd(C.byref(p), dtype_code(q.dtype), q.data_ptr(), k.data_ptr(),
-                                v.data_ptr(), o.data_ptr(), lse.data_ptr(), d_o.data_ptr(),
-                                C.byref(mask) if mask is not None else None, dq_accum.data_ptr(),
-                                dk.data_ptr(), dv.data_ptr(), workspace.data_ptr(),
-                                workspace.numel() * workspace.element_size(), _stream())
-    _check(code, "lvx_xattn_bwd")
+    args = (C.byref(p), dtype_code(q.dtype), q.data_ptr(), k.data_ptr(),
+            v.data_ptr(), o.data_ptr(), lse.data_ptr(), d_o.data_ptr(),
+            C.byref(mask) if mask is not None else None, dq_accum.data_ptr(),
+            dk.data_ptr(), dv.data_ptr(), workspace.data_ptr(),
+            workspace.numel() * workspace.element_size(), _stream())
+    if stages == LVX_BWD_ALL:
+        _check(load().lvx_xattn_bwd(*args), "lvx_xattn_bwd")
+    else:
+        _check(load().lvx_xattn_bwd_stages(*args, stages), "lvx_xattn_bwd_stages")
 
 
 def lvx_xattn_dq_finalize(p: lvx_problem, dq_accum, dq) -> None:

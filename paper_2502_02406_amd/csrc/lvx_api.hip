@@ -186,7 +186,18 @@ lvx_status lvx_xattn_bwd(const lvx_problem* p, lvx_dtype dtype, const void* q, c
                          const void* v, const void* o, const float* lse, const void* d_o,
                          const lvx_mask* mask, float* dq_accum, void* dk, void* dv,
                          void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return lvx_xattn_bwd_stages(p, dtype, q, k, v, o, lse, d_o, mask, dq_accum, dk, dv, workspace,
+                              workspace_bytes, hip_stream, LVX_BWD_ALL);
+}
+
+lvx_status lvx_xattn_bwd_stages(const lvx_problem* p, lvx_dtype dtype, const void* q, const void* k,
+                                const void* v, const void* o, const float* lse, const void* d_o,
+                                const lvx_mask* mask, float* dq_accum, void* dk, void* dv,
+                                void* workspace, size_t workspace_bytes, void* hip_stream,
+                                unsigned stages) {
   lvx_status st = check_problem(p, dtype);
+  if (st != LVX_OK) return st;
+  if (stages == 0 || (stages & ~(unsigned)LVX_BWD_ALL)) return LVX_ERR_SHAPE;
   if (st != LVX_OK) return st;
   if (!q || !k || !v || !o || !lse || !d_o || !dq_accum || !dk || !dv) return LVX_ERR_NULL;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) ||
@@ -203,9 +214,11 @@ lvx_status lvx_xattn_bwd(const lvx_problem* p, lvx_dtype dtype, const void* q, c
   a.dq_accum = dq_accum; a.dk = dk; a.dv = dv;
   a.n_split_dq = bwd_split(a.d, dtype);
   hipStream_t s = (hipStream_t)hip_stream;
-  hipError_t e = launch_delta(a.d, o, d_o, dtype == LVX_F32, a.delta, s);
+  hipError_t e = hipSuccess;
+  if (stages & LVX_BWD_DELTA) e = launch_delta(a.d, o, d_o, dtype == LVX_F32, a.delta, s);
   if (e != hipSuccess) return LVX_ERR_HIP;
-  e = dtype == LVX_BF16 ? launch_bwd_bf16(a, s) : launch_bwd_f32(a, s);
+  if (stages & (LVX_BWD_DKDV | LVX_BWD_DQ))
+    e = dtype == LVX_BF16 ? launch_bwd_bf16(a, stages, s) : launch_bwd_f32(a, stages, s);
   return e == hipSuccess ? LVX_OK : LVX_ERR_HIP;
 }
 

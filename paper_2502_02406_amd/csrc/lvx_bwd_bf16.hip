@@ -439,7 +439,7 @@ int bwd_bf16_pick_split(const Dims& d, int n_cu) {
   return (int)want;
 }
 
-hipError_t launch_bwd_bf16(const BwdArgs& a, hipStream_t s) {
+hipError_t launch_bwd_bf16(const BwdArgs& a, unsigned stages, hipStream_t s) {
   const Dims& d = a.d;
   const int G = d.Hq / d.Hkv;
   const int n_qt = (d.Sq + QM - 1) / QM;
@@ -450,14 +450,14 @@ hipError_t launch_bwd_bf16(const BwdArgs& a, hipStream_t s) {
     static bool once = false, once2 = false;
     if ((e = set_smem_once(bwd_dq_bf16_kernel<64>, DqSmem<64>::TOTAL, &once)) != hipSuccess) return e;
     if ((e = set_smem_once(bwd_dkdv_bf16_kernel<64>, DkvSmem<64>::TOTAL, &once2)) != hipSuccess) return e;
-    bwd_dkdv_bf16_kernel<64><<<(unsigned)grid_k, 256, DkvSmem<64>::TOTAL, s>>>(a);
-    bwd_dq_bf16_kernel<64><<<(unsigned)grid_q, 256, DqSmem<64>::TOTAL, s>>>(a);
+    if (stages & 2) bwd_dkdv_bf16_kernel<64><<<(unsigned)grid_k, 256, DkvSmem<64>::TOTAL, s>>>(a);
+    if (stages & 4) bwd_dq_bf16_kernel<64><<<(unsigned)grid_q, 256, DqSmem<64>::TOTAL, s>>>(a);
   } else {
     static bool once = false, once2 = false;
     if ((e = set_smem_once(bwd_dq_bf16_kernel<128>, DqSmem<128>::TOTAL, &once)) != hipSuccess) return e;
     if ((e = set_smem_once(bwd_dkdv_bf16_kernel<128>, DkvSmem<128>::TOTAL, &once2)) != hipSuccess) return e;
-    bwd_dkdv_bf16_kernel<128><<<(unsigned)grid_k, 256, DkvSmem<128>::TOTAL, s>>>(a);
-    bwd_dq_bf16_kernel<128><<<(unsigned)grid_q, 256, DqSmem<128>::TOTAL, s>>>(a);
+    if (stages & 2) bwd_dkdv_bf16_kernel<128><<<(unsigned)grid_k, 256, DkvSmem<128>::TOTAL, s>>>(a);
+    if (stages & 4) bwd_dq_bf16_kernel<128><<<(unsigned)grid_q, 256, DqSmem<128>::TOTAL, s>>>(a);
   }
   return hipGetLastError();
 }

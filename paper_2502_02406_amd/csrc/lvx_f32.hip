@@ -248,15 +248,15 @@ hipError_t launch_fwd_f32(const FwdArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_bwd_f32(const BwdArgs& a, hipStream_t s) {
+hipError_t launch_bwd_f32(const BwdArgs& a, unsigned stages, hipStream_t s) {
   dim3 gq((a.d.Sq + R - 1) / R, a.d.Hq, a.d.B);
   dim3 gk((a.d.Skv + R - 1) / R, a.d.Hkv, a.d.B);
   if (a.d.D == 64) {
-    bwd_dq_f32_kernel<64><<<gq, 256, 0, s>>>(a);
-    bwd_dkdv_f32_kernel<64><<<gk, 256, 0, s>>>(a);
+    if (stages & 4) bwd_dq_f32_kernel<64><<<gq, 256, 0, s>>>(a);
+    if (stages & 2) bwd_dkdv_f32_kernel<64><<<gk, 256, 0, s>>>(a);
   } else {
-    bwd_dq_f32_kernel<128><<<gq, 256, 0, s>>>(a);
-    bwd_dkdv_f32_kernel<128><<<gk, 256, 0, s>>>(a);
+    if (stages & 4) bwd_dq_f32_kernel<128><<<gq, 256, 0, s>>>(a);
+    if (stages & 2) bwd_dkdv_f32_kernel<128><<<gk, 256, 0, s>>>(a);
   }
   return hipGetLastError();
 }

@@ -59,10 +59,10 @@ struct MergeArgs {
 
 // kernels for float32 tensors (plain FMA, correctness-grade)
 hipError_t launch_fwd_f32(const FwdArgs& a, hipStream_t s);
-hipError_t launch_bwd_f32(const BwdArgs& a, hipStream_t s);
+hipError_t launch_bwd_f32(const BwdArgs& a, unsigned stages, hipStream_t s);   // stages: 2 = dK/dV, 4 = dQ
 // kernels for bfloat16 tensors (MFMA)
 hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t s);
-hipError_t launch_bwd_bf16(const BwdArgs& a, hipStream_t s);
+hipError_t launch_bwd_bf16(const BwdArgs& a, unsigned stages, hipStream_t s);
 int fwd_bf16_pick_split(const Dims& d, int n_cu);
 int bwd_bf16_pick_split(const Dims& d, int n_cu);
 // memory-bound helpers
