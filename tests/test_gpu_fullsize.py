@@ -1,0 +1,90 @@
+"""GPU parity at the full workload sizes, in the launch configuration bench.py times (same block
+loop, same strided K/V block views, same split-KV choice).  The oracle cannot evaluate these sizes
+in full, so it evaluates SAMPLED outputs one by one from the definition (query rows of O, L and dQ;
+key rows of dK and dV), and a checksum that holds at any size is added:
+    sum_j dV[b, hkv, j, :] = sum over the head group and the query rows with a visible key of dO
+(because every such row of P sums to one)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2502_02406_amd import workloads as W
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+TOL = dict(o=1e-2, lse=1e-3, grad=2e-2)
+
+
+def sample_rows(rng, n, B, H, S):
+    return np.stack([rng.integers(0, B, n), rng.integers(0, H, n), rng.integers(0, S, n)], axis=1).astype(np.int32)
+
+
+def rel(x, ref):
+    return float(np.linalg.norm(x - ref) / max(np.linalg.norm(ref), 1e-30)), \
+        float(np.abs(x - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+@pytest.mark.parametrize("name", ["c2_llama_64k", "c3_longvideo_256k", "c4_flamingo_masked",
+                                  "c5_extreme_1m"])
+def test_full_size_sampled_parity(name):
+    from paper_2502_02406_amd.blockloop import BlockLoop, MediaMask
+    w = W.WORKLOADS[name]
+    print(f"[fullsize] {name}: generating inputs", flush=True)
+    x = W.make_inputs(w)
+    dev = {n: t.cuda() for n, t in x.items()}
+    omask = dmask = None
+    if w.masked:
+        omask = oracle.Mask(x["allow"].numpy(), w.q_chunk, w.kv_block)
+        dmask = MediaMask(dev["allow"], w.q_chunk, w.kv_block)
+    loop = BlockLoop(tuple(x["q"].shape), tuple(x["k"].shape), torch.bfloat16, w.n_blocks, dmask)
+    print(f"[fullsize] {name}: GPU forward + backward", flush=True)
+    O, L = loop.forward(dev["q"], dev["k"], dev["v"])
+    dk, dv = torch.empty_like(dev["k"]), torch.empty_like(dev["v"])
+    dq = loop.backward(dev["q"], dev["k"], dev["v"], O, L, dev["do"], dk, dv)
+    torch.cuda.synchronize()
+    O, L, dq = O.float().cpu().numpy(), L.cpu().numpy(), dq.float().cpu().numpy()
+    assert np.isfinite(O).all() and np.isfinite(dq).all()
+
+    qn, kn, vn, gn = (W.as_f32_numpy(x[n]) for n in ("q", "k", "v", "do"))
+    rng = np.random.default_rng(11)
+    # ---- sampled query rows: O, L, dQ
+    qr = sample_rows(rng, 48, w.B, w.Hq, w.Sq)
+    qr[0] = (0, 0, 0)
+    qr[1] = (w.B - 1, w.Hq - 1, w.Sq - 1)
+    print(f"[fullsize] {name}: oracle on {len(qr)} query rows", flush=True)
+    Or, Lr = oracle.fwd_rows(qn, kn, vn, qr, mask=omask)
+    dQr = oracle.bwd_q_rows(qn, kn, vn, gn, qr, mask=omask)
+    Og = np.stack([O[b, h, i] for b, h, i in qr]).astype(np.float64)
+    Lg = np.array([L[b, h, i] for b, h, i in qr], dtype=np.float64)
+    dQg = np.stack([dq[b, h, i] for b, h, i in qr]).astype(np.float64)
+    assert np.isfinite(Lr).all()
+    assert np.abs(Lg - Lr).max() <= TOL["lse"], f"L err {np.abs(Lg - Lr).max()}"
+    assert np.abs(Og - Or).max() <= TOL["o"]
+    assert rel(Og, Or)[0] <= 2e-2, f"O rel err {rel(Og, Or)}"
+    assert max(rel(dQg, dQr)) <= TOL["grad"], f"dQ rel err {rel(dQg, dQr)}"
+
+    # ---- sampled key rows of ONE K/V head: dK, dV (needs the statistics of its whole head group)
+    b0, hk0 = w.B - 1, w.Hkv // 2
+    hi = w.Skv if not w.masked else 32 * w.kv_block          # masked workload: only these keys are visible
+    js = np.unique(np.concatenate([rng.integers(0, hi, 40), [0, hi - 1]]))
+    kr = np.stack([np.full_like(js, b0), np.full_like(js, hk0), js], axis=1).astype(np.int32)
+    print(f"[fullsize] {name}: oracle on {len(kr)} key rows of head ({b0},{hk0})", flush=True)
+    dKr, dVr = oracle.bwd_kv_rows(qn, kn, vn, gn, kr, mask=omask)
+    dkh = dk[b0, hk0].float().cpu().numpy()
+    dvh = dv[b0, hk0].float().cpu().numpy()
+    dKg, dVg = dkh[js].astype(np.float64), dvh[js].astype(np.float64)
+    assert max(rel(dKg, dKr)) <= TOL["grad"], f"dK rel err {rel(dKg, dKr)}"
+    assert max(rel(dVg, dVr)) <= TOL["grad"], f"dV rel err {rel(dVg, dVr)}"
+
+    # ---- checksum over every key row of that head
+    G = w.Hq // w.Hkv
+    g64 = gn[b0, hk0 * G:(hk0 + 1) * G].astype(np.float64)
+    want = g64.sum(axis=(0, 1))          # every query row of these workloads sees at least one key
+    got = dvh.astype(np.float64).sum(axis=0)
+    assert np.abs(got - want).max() <= 2e-2 * np.abs(want).max(), \
+        f"dV checksum off by {np.abs(got - want).max()} (scale {np.abs(want).max()})"
+    assert np.isfinite(dkh).all() and np.isfinite(dvh).all()
+    if w.masked:      # keys nobody may attend get exactly zero gradients
+        assert np.all(dkh[hi:] == 0.0) and np.all(dvh[hi:] == 0.0)
+    print(f"[fullsize] {name}: ok", flush=True)
