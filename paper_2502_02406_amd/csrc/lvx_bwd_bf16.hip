@@ -29,9 +29,10 @@ constexpr int QM = 128;      // query rows per workgroup
 constexpr int QN = 64;       // keys per tile
 
 template <int D> struct DqSmem {
-  static constexpr int P = (D + 8) * 2;        // row pitch (bytes) of the K and V tiles
-  static constexpr int T_BYTES = QN * P;
-  static constexpr int STAGE = 2 * T_BYTES;
+  static constexpr int P = (D + 8) * 2;        // row pitch (bytes) of the V tile (b128 reads only)
+  static constexpr int K_BYTES = ILV_ROWS * P; // K tile: row-interleaved, read both ways
+  static constexpr int V_BYTES = QN * P;
+  static constexpr int STAGE = K_BYTES + V_BYTES;
   static constexpr int TOTAL = 2 * STAGE;
 };
 
@@ -110,11 +111,11 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   };
   auto store_tile = [&](int stage) {
     char* ks = smem + stage * SM::STAGE;
-    char* vs = ks + SM::T_BYTES;
+    char* vs = ks + SM::K_BYTES;
 #pragma unroll
     for (int p = 0; p < NPASS; ++p) {
       const int r = p * RPP + ld_row;
-      *(u32x4*)(ks + r * SM::P + ld_col * 2) = kreg[p];
+      *(u32x4*)(ks + ilv_off<D>(ld_row, p * RPP, ld_col)) = kreg[p];
       *(u32x4*)(vs + r * SM::P + ld_col * 2) = vreg[p];
     }
   };
@@ -131,7 +132,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
     const int nxt = next_tile(cur + 1);
     if (nxt < t_end) load_tile(nxt);
     const char* ks_ = smem + stage * SM::STAGE;
-    const char* vs_ = ks_ + SM::T_BYTES;
+    const char* vs_ = ks_ + SM::K_BYTES;
     const int j0 = cur * QN;
     int cls = 1;
     if (a.mask.allow)
@@ -143,11 +144,10 @@ bwd_dq_bf16_kernel(BwdArgs a) {
       for (int kb = 0; kb < 2; ++kb) {
         sacc[kb] = zero16();
         pacc[kb] = zero16();
-        const char* krow = ks_ + (kb * 32 + ql) * SM::P + g * 16;
         const char* vrow = vs_ + (kb * 32 + ql) * SM::P + g * 16;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-          sacc[kb] = mfma32(*(const bf16x8*)(krow + ks * 32), qf[ks], sacc[kb]);
+          sacc[kb] = mfma32(*(const bf16x8*)(ks_ + ilv_off<D>(ql, kb * 32, 16 * ks + 8 * g)), qf[ks], sacc[kb]);
           pacc[kb] = mfma32(*(const bf16x8*)(vrow + ks * 32), gf[ks], pacc[kb]);
         }
       }
@@ -170,7 +170,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
         const bf16x8 sf = cvt_operand(sacc[t >> 1], 8 * (t & 1));
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-          const bf16x8 kt = load_tr_operand(ks_, SM::P, 16 * t, 32 * db, lane);
+          const bf16x8 kt = load_tr_operand_ilv<D>(ks_, 16 * t, 32 * db, lane);
           dq[db] = mfma32(kt, sf, dq[db]);
         }
       }
@@ -197,10 +197,10 @@ constexpr int KN = 4 * 32 * KVB;       // keys per workgroup (4 waves)
 constexpr int KM = 32;                 // query rows per step
 
 template <int D> struct DkvSmem {
-  static constexpr int P = (D + 8) * 2;        // row pitch (bytes) of the Q and dO tiles
-  static constexpr int T_BYTES = KM * P;
+  static constexpr int P = (D + 8) * 2;        // row pitch (bytes) of the resident V rows
+  static constexpr int T_BYTES = ILV_ROWS * P; // [Q; dO] as ONE 64-row interleaved tile (rows 0..31 Q, 32..63 dO)
   static constexpr int STAT = KM * 4;          // one float per row
-  static constexpr int STAGE = 2 * T_BYTES + 2 * STAT;
+  static constexpr int STAGE = T_BYTES + 2 * STAT;
   static constexpr int V_BYTES = KN * P;       // this workgroup's V rows, resident for the kernel
   static constexpr int TOTAL = 2 * STAGE + V_BYTES;
 };
@@ -299,17 +299,17 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   };
   auto store_step = [&](int stage) {
     char* qs = smem + stage * SM::STAGE;
-    char* gs = qs + SM::T_BYTES;
 #pragma unroll
     for (int p = 0; p < NLD; ++p) {
       const int c = p * 256 + tid;
       if (c < CHUNKS) {
         const int r = c / CPR, col = (c % CPR) * 8;
-        *(u32x4*)(qs + r * SM::P + col * 2) = qreg[p];
-        *(u32x4*)(gs + r * SM::P + col * 2) = greg[p];
+        (void)r;
+        *(u32x4*)(qs + ilv_off<D>(tid / CPR, p * (256 / CPR), col)) = qreg[p];
+        *(u32x4*)(qs + ilv_off<D>(tid / CPR, KM + p * (256 / CPR), col)) = greg[p];
       }
     }
-    if (tid < 2 * KM) *(float*)(gs + SM::T_BYTES + tid * 4) = sreg;
+    if (tid < 2 * KM) *(float*)(qs + SM::T_BYTES + tid * 4) = sreg;
   };
 
   int cur = next_step(0);
@@ -320,8 +320,7 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
     const int nxt = next_step(cur + 1);
     if (nxt < n_steps) load_step(nxt);
     const char* qs_ = smem + stage * SM::STAGE;
-    const char* gs_ = qs_ + SM::T_BYTES;
-    const float* lse_s = (const float*)(gs_ + SM::T_BYTES);
+    const float* lse_s = (const float*)(qs_ + SM::T_BYTES);
     const float* del_s = lse_s + KM;
     const int i0 = (cur % spH) * KM;
     int cls = 1;
@@ -334,12 +333,10 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
       f32x16 sacc[KVB], pacc[KVB];
 #pragma unroll
       for (int kb = 0; kb < KVB; ++kb) { sacc[kb] = zero16(); pacc[kb] = zero16(); }
-      const char* qrow = qs_ + kl * SM::P + g * 16;
-      const char* grow = gs_ + kl * SM::P + g * 16;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 qa = *(const bf16x8*)(qrow + ks * 32);
-        const bf16x8 ga = *(const bf16x8*)(grow + ks * 32);
+        const bf16x8 qa = *(const bf16x8*)(qs_ + ilv_off<D>(kl, 0, 16 * ks + 8 * g));
+        const bf16x8 ga = *(const bf16x8*)(qs_ + ilv_off<D>(kl, KM, 16 * ks + 8 * g));
 #pragma unroll
         for (int kb = 0; kb < KVB; ++kb) {
           sacc[kb] = mfma32(qa, kf[kb][ks], sacc[kb]);
@@ -380,8 +377,8 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
         }
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-          const bf16x8 gt = load_tr_operand(gs_, SM::P, 16 * t, 32 * db, lane);
-          const bf16x8 qtr = load_tr_operand(qs_, SM::P, 16 * t, 32 * db, lane);
+          const bf16x8 gt = load_tr_operand_ilv<D>(qs_, KM + 16 * t, 32 * db, lane);
+          const bf16x8 qtr = load_tr_operand_ilv<D>(qs_, 16 * t, 32 * db, lane);
 #pragma unroll
           for (int kb = 0; kb < KVB; ++kb) {
             dv[kb][db] = mfma32(gt, pf[kb], dv[kb][db]);

@@ -171,7 +171,7 @@ fwd_bf16_kernel(FwdArgs a) {
       tmax = xhalf_max(tmax);
       const float m_new = fmaxf(m_run, tmax);
       const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = exp2f((m_run - m_safe) * c2);     // m_run = -inf -> 0
+      const float alpha = __builtin_amdgcn_exp2f((m_run - m_safe) * c2);     // m_run = -inf -> 0
       const float mc = m_safe * c2;
       m_run = m_new;
       float psum = 0.f;
@@ -179,7 +179,7 @@ fwd_bf16_kernel(FwdArgs a) {
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const float p = exp2f(fmaf(sacc[kb][v], c2, -mc));
+          const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kb][v], c2, -mc));
           sacc[kb][v] = p;
           psum += p;
         }

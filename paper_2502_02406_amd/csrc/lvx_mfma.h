@@ -59,6 +59,32 @@ __device__ __forceinline__ bf16x8 load_tr_operand(const char* tile, int pitch_b,
   return __builtin_bit_cast(bf16x8, r);
 }
 
+// Row-interleaved tile: up to 64 logical rows of D bf16 at pitch (D + 8) * 2 bytes, logical row r
+// stored in physical row (r % 4) * 20 + r / 4.  With D = 128 (pitch 272 = 16 mod 256) BOTH access
+// patterns of a tile are free of LDS bank conflicts and need no address arithmetic beyond an
+// immediate offset: b128 reads of one 16-byte column by 16 consecutive logical rows land in 16
+// distinct 16-byte bank groups, and a transposing read of 4 consecutive logical rows x 64 bytes
+// lands in four disjoint 64-byte groups (20 * 272 = 64 mod 256).
+constexpr int ILV_ROWS = 80;                       // physical rows of a 64-row interleaved tile
+__device__ __forceinline__ int ilv_row(int r) { return (r & 3) * 20 + (r >> 2); }
+// Byte offset of logical row (rc + rl), column col: rc is a compile-time multiple of 4 (so that it
+// becomes an immediate offset), rl the lane-dependent part.
+template <int D> __device__ __forceinline__ int ilv_off(int rl, int rc, int col) {
+  return ilv_row(rl) * ((D + 8) * 2) + (rc >> 2) * ((D + 8) * 2) + col * 2;
+}
+// A operand via transposing reads from an interleaved tile (same contract as load_tr_operand;
+// kbase is the first logical row, a multiple of 16).
+template <int D>
+__device__ __forceinline__ bf16x8 load_tr_operand_ilv(const char* tile, int kbase, int n0, int lane) {
+  const int j = lane & 15, half = (lane >> 4) & 1, g = lane >> 5;
+  const char* p = tile + ilv_off<D>(4 * g + (j >> 2), 0, 16 * half + 4 * (j & 3));   // lane part
+  s16x4 lo = lds_read_tr(p + ilv_off<D>(0, kbase, n0));
+  s16x4 hi = lds_read_tr(p + ilv_off<D>(0, kbase + 8, n0));
+  typedef __attribute__((ext_vector_type(8))) short s16x8;
+  s16x8 r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, r);
+}
+
 // Two floats -> packed bf16 (round to nearest even), low half = a.
 __device__ __forceinline__ unsigned pack2_bf16(float a, float b) {
   bf16x2 r;
