@@ -85,6 +85,23 @@ __device__ __forceinline__ bf16x8 load_tr_operand_ilv(const char* tile, int kbas
   return __builtin_bit_cast(bf16x8, r);
 }
 
+// Direct global -> LDS copy of 16 bytes per lane (no staging registers): lane l's 16 bytes land at
+// lds_dst + 16 l, where lds_dst must be wave-uniform.  Completion is tracked by vmcnt; the
+// compiler does not order later LDS reads against it, so callers wait with wait_vmcnt<N>() and
+// then cross a barrier before reading.
+__device__ __forceinline__ void dma16(const void* gsrc, void* lds_dst) {
+  __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gsrc,
+                                   (void __attribute__((address_space(3)))*)lds_dst, 16, 0, 0);
+}
+// s_waitcnt vmcnt(N) only (expcnt and lgkmcnt left at "no wait").
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+// Workgroup barrier without the memory fences of __syncthreads (which would drain vmcnt and so
+// serialise the DMA pipeline).  LDS traffic of the calling wave must already be waited for.
+__device__ __forceinline__ void wg_barrier() { __builtin_amdgcn_s_barrier(); }
+
 // Two floats -> packed bf16 (round to nearest even), low half = a.
 __device__ __forceinline__ unsigned pack2_bf16(float a, float b) {
   bf16x2 r;
