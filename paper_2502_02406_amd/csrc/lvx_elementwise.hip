@@ -101,16 +101,21 @@ hipError_t launch_merge(const MergeArgs& a, int part_is_f32, int out_is_f32, hip
   return hipGetLastError();
 }
 
-// delta[b,h,i] = sum_d dO[b,h,i,d] * O[b,h,i,d].  16 lanes per row.
+// delta[b,h,i] = sum_d dO[b,h,i,d] * O[b,h,i,d].  16 lanes per row.  The bf16 kernels read the
+// row statistics 32 rows at a time with aligned vector copies, so two padded copies are written
+// as well ([B,Hq,sq_pad], sq_pad a multiple of 32): lse2p = L * log2(e) with +inf for rows
+// without keys and for pad rows (which makes their probabilities exp2(-inf) = 0), and deltap.
 template <bool F32>
 __global__ void __launch_bounds__(256) delta_kernel(Dims d, const void* o, const void* d_o,
-                                                    float* delta) {
-  const long rows = (long)d.B * d.Hq * d.Sq;
-  const long row = ((long)blockIdx.x * 256 + threadIdx.x) / 16;
+                                                    const float* lse, float* delta, float* lse2p,
+                                                    float* deltap, int sq_pad) {
+  const long rows = (long)d.B * d.Hq * sq_pad;
+  const long rowp = ((long)blockIdx.x * 256 + threadIdx.x) / 16;
   const int c = threadIdx.x % 16;
+  if (rowp >= rows) return;                 // whole 16-lane groups leave together
+  const long i = rowp % sq_pad, h = (rowp / sq_pad) % d.Hq, b = rowp / ((long)sq_pad * d.Hq);
   float s = 0.f;
-  if (row < rows) {
-    const long i = row % d.Sq, h = (row / d.Sq) % d.Hq, b = row / ((long)d.Sq * d.Hq);
+  if (i < d.Sq) {
     const long off = b * d.q_sb + h * d.q_sh + i * d.q_ss;
     if (F32) {
       const float* po = (const float*)o + off;
@@ -131,15 +136,24 @@ __global__ void __launch_bounds__(256) delta_kernel(Dims d, const void* o, const
   }
 #pragma unroll
   for (int m = 8; m >= 1; m >>= 1) s += __shfl_xor(s, m, 16);
-  if (row < rows && c == 0) delta[row] = s;
+  if (c != 0) return;
+  float l2 = INFINITY;
+  if (i < d.Sq) {
+    const long row = (b * d.Hq + h) * d.Sq + i;
+    delta[row] = s;
+    const float L = lse[row];
+    if (L != -INFINITY) l2 = L * 1.4426950408889634f;
+  }
+  lse2p[rowp] = l2;
+  deltap[rowp] = s;
 }
 
-hipError_t launch_delta(const Dims& d, const void* o, const void* d_o, int is_f32, float* delta,
-                        hipStream_t s) {
-  const long rows = (long)d.B * d.Hq * d.Sq;
+hipError_t launch_delta(const Dims& d, const void* o, const void* d_o, int is_f32, const float* lse,
+                        float* delta, float* lse2p, float* deltap, int sq_pad, hipStream_t s) {
+  const long rows = (long)d.B * d.Hq * sq_pad;
   const unsigned blocks = (unsigned)((rows * 16 + 255) / 256);
-  if (is_f32) delta_kernel<true><<<blocks, 256, 0, s>>>(d, o, d_o, delta);
-  else delta_kernel<false><<<blocks, 256, 0, s>>>(d, o, d_o, delta);
+  if (is_f32) delta_kernel<true><<<blocks, 256, 0, s>>>(d, o, d_o, lse, delta, lse2p, deltap, sq_pad);
+  else delta_kernel<false><<<blocks, 256, 0, s>>>(d, o, d_o, lse, delta, lse2p, deltap, sq_pad);
   return hipGetLastError();
 }
 

@@ -39,6 +39,9 @@ struct BwdArgs {
   const void *q, *k, *v, *o, *d_o;
   const float* lse;     // final statistic, [B,Hq,Sq]
   float* delta;         // workspace, [B,Hq,Sq]: rowsum(dO * O)
+  float* lse2p;         // workspace, [B,Hq,sq_pad]: L * log2(e), +inf for rows without keys and pad rows
+  float* deltap;        // workspace, [B,Hq,sq_pad]: delta again, 0 in pad rows
+  int sq_pad;           // Sq rounded up to a multiple of 32
   float* dq_accum;      // [B,Hq,Sq,D] float32, accumulated into
   void *dk, *dv;        // K's strides, input dtype, overwritten
   int n_split_dq;       // KV splits of the dQ kernel (each adds into dq_accum)
@@ -63,12 +66,14 @@ hipError_t launch_bwd_f32(const BwdArgs& a, unsigned stages, hipStream_t s);   /
 // kernels for bfloat16 tensors (MFMA)
 hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t s);
 hipError_t launch_bwd_bf16(const BwdArgs& a, unsigned stages, hipStream_t s);
+hipError_t launch_bwd_dkdv_bf16(const BwdArgs& a, hipStream_t s);
+hipError_t launch_bwd_dq_bf16(const BwdArgs& a, hipStream_t s);
 int fwd_bf16_pick_split(const Dims& d, int n_cu);
 int bwd_bf16_pick_split(const Dims& d, int n_cu);
 // memory-bound helpers
 hipError_t launch_merge(const MergeArgs& a, int part_is_f32, int out_is_f32, hipStream_t s);
-hipError_t launch_delta(const Dims& d, const void* o, const void* d_o, int is_f32, float* delta,
-                        hipStream_t s);
+hipError_t launch_delta(const Dims& d, const void* o, const void* d_o, int is_f32, const float* lse,
+                        float* delta, float* lse2p, float* deltap, int sq_pad, hipStream_t s);
 hipError_t launch_dq_finalize(const Dims& d, const float* dq_accum, void* dq, int is_f32,
                               hipStream_t s);
 

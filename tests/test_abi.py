@@ -110,7 +110,7 @@ def test_merge_and_bwd_errors(lib):
 def test_workspace_sizes_and_strerror(lib):
     p = problem(B=1, Hq=32, Hkv=8, Sq=2048, Skv=32768)
     rows = 32 * 2048
-    assert B.lvx_xattn_workspace_bytes(p, B.LVX_BF16, B.LVX_WS_BWD) == rows * 4
+    assert B.lvx_xattn_workspace_bytes(p, B.LVX_BF16, B.LVX_WS_BWD) == 3 * rows * 4   # delta + 2 padded stats
     assert B.lvx_xattn_workspace_bytes(p, B.LVX_BF16, B.LVX_WS_FWD) >= 256
     assert B.lvx_xattn_workspace_bytes(p, B.LVX_F32, B.LVX_WS_FWD) == 256
     assert B.lvx_xattn_workspace_bytes(problem(D=96), B.LVX_BF16, B.LVX_WS_FWD) == 0
