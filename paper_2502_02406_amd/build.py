@@ -26,12 +26,19 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-ato
          "-Wno-unused-command-line-argument"]
 
 
+# Per-file flags.  The key-stationary backward kernel runs one wave per SIMD with the whole
+# register file; there the compiler would by default put every matrix-instruction result into the
+# accumulation registers, including the scores that the vector ALU consumes next.  Its own
+# accumulators are pinned to that file in the source, everything else stays in ordinary registers.
+FILE_FLAGS = {"lvx_bwd_dkdv_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
+
 def _compile(src: str, force: bool, extra) -> str:
     obj = os.path.join(OBJ, os.path.basename(src).replace(".hip", ".o"))
     deps = [src] + glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(HERE, "..", "include", "*.h"))
     if not force and os.path.exists(obj) and all(os.path.getmtime(obj) >= os.path.getmtime(d) for d in deps):
         return obj
-    cmd = [HIPCC] + FLAGS + list(extra) + ["-c", src, "-o", obj]
+    cmd = [HIPCC] + FLAGS + FILE_FLAGS.get(os.path.basename(src), []) + list(extra) + ["-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     msgs = "\n".join(l for l in (r.stdout + r.stderr).splitlines()
                      if "packed-fp32-ops" not in l and l.strip())

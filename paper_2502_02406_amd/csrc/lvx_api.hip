@@ -90,9 +90,9 @@ size_t fwd_ws(const Dims& d, int n_split) {
   return align_up(rows * d.D * sizeof(float) * n_split) + align_up(rows * sizeof(float) * n_split);
 }
 int sq_padded(const Dims& d) { return (d.Sq + 31) / 32 * 32; }
-size_t bwd_ws(const Dims& d) {      // delta [B,Hq,Sq] + two padded statistics arrays [B,Hq,sq_pad]
+size_t bwd_ws(const Dims& d) {      // delta [B,Hq,Sq] + padded statistics [B,Hq,sq_pad/32][2][32]
   return align_up((size_t)d.B * d.Hq * d.Sq * sizeof(float)) +
-         2 * align_up((size_t)d.B * d.Hq * sq_padded(d) * sizeof(float));
+         align_up(2 * (size_t)d.B * d.Hq * sq_padded(d) * sizeof(float));
 }
 
 }  // namespace
@@ -216,14 +216,12 @@ lvx_status lvx_xattn_bwd_stages(const lvx_problem* p, lvx_dtype dtype, const voi
   a.q = q; a.k = k; a.v = v; a.o = o; a.d_o = d_o; a.lse = lse;
   a.delta = (float*)workspace;
   a.sq_pad = sq_padded(a.d);
-  const size_t padded = align_up((size_t)a.d.B * a.d.Hq * a.sq_pad * sizeof(float));
-  a.lse2p = (float*)((char*)workspace + align_up((size_t)a.d.B * a.d.Hq * a.d.Sq * sizeof(float)));
-  a.deltap = (float*)((char*)a.lse2p + padded);
+  a.stats = (float*)((char*)workspace + align_up((size_t)a.d.B * a.d.Hq * a.d.Sq * sizeof(float)));
   a.dq_accum = dq_accum; a.dk = dk; a.dv = dv;
   a.n_split_dq = bwd_split(a.d, dtype);
   hipStream_t s = (hipStream_t)hip_stream;
   hipError_t e = hipSuccess;
-  if (stages & LVX_BWD_DELTA) e = launch_delta(a.d, o, d_o, dtype == LVX_F32, lse, a.delta, a.lse2p, a.deltap, a.sq_pad, s);
+  if (stages & LVX_BWD_DELTA) e = launch_delta(a.d, o, d_o, dtype == LVX_F32, lse, a.delta, a.stats, a.sq_pad, s);
   if (e != hipSuccess) return LVX_ERR_HIP;
   if (stages & (LVX_BWD_DKDV | LVX_BWD_DQ))
     e = dtype == LVX_BF16 ? launch_bwd_bf16(a, stages, s) : launch_bwd_f32(a, stages, s);

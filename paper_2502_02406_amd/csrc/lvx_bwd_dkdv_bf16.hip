@@ -1,41 +1,66 @@
-// bf16 backward, key-stationary kernel: dK and dV of one K/V block (Table 1 of the paper counts
-// the backward as five products; this kernel performs four of them: S, dP, dV, dK).
-// A wave keeps its keys of K in registers (V in LDS) and streams the query rows of every head
-// that shares this K/V head.  S = Q K^T and dP = dO V^T put one KEY per lane, so P and dS (bf16)
-// are the B operands of dV^T += dO^T P and dK^T += Q^T dS, with dO^T / Q^T from transposing reads.
+// bf16 backward, key-stationary kernel: dK and dV of one K/V block.  Table 1 of the paper counts
+// the backward as five matrix products; this kernel performs four of them (S, dP, dV, dK) with
+// the probabilities recomputed from the saved statistic L (Section 3.2 saves only x, O and L):
+//   p_ij = exp(scale <Q_i, K_j> - L_i),   dS_ij = p_ij (<dO_i, V_j> - delta_i).
+//
+// Workgroup = 4 wavefronts = 256 keys of one (batch, K/V head), one wave per SIMD with the whole
+// register file: a wave owns 64 keys (two 32-key blocks), keeps their K operands in registers and
+// their dK^T / dV^T accumulators (2 x 2 x D/32 MFMA blocks = 256 registers at D = 128) in the
+// accumulation registers; V of the workgroup stays in LDS.  Owning two key blocks halves the LDS
+// traffic: every Q / dO operand fetched from LDS feeds two matrix instructions.
+// The query rows of all heads that share this K/V head are streamed 32 at a time: [Q; dO] tiles
+// (plus the 32 row statistics L log2(e) and delta) travel HBM -> LDS by direct global-to-LDS
+// copies into a ring of four stages, issued three steps ahead, one barrier per step.
+// S = Q K^T and dP = dO V^T put one KEY per lane and 16 query rows in a lane's registers, so P and
+// dS, rounded to bf16, are already the B operands of dV^T += dO^T P and dK^T += Q^T dS, with
+// dO^T / Q^T fetched by transposing LDS reads: nothing goes back through LDS or memory.
+// The loop is software pipelined inside each wave: while the matrix core contracts step i
+// (dV, dK), the vector ALU turns the scores of step i+1 into P and dS; then the scores of step
+// i+2 are formed.
 #include "lvx_internal.h"
 #include "lvx_mfma.h"
+
+#include <type_traits>
 
 namespace lvx {
 
 namespace {
 
 constexpr float LOG2E = 1.4426950408889634f;
-
-// ------------------------------------------------------------------------------------------
-// dK/dV kernel
-// ------------------------------------------------------------------------------------------
-constexpr int KVB = 1;                 // 32-key blocks per wave
-constexpr int KN = 4 * 32 * KVB;       // keys per workgroup (4 waves)
+constexpr int KVB = 2;                 // 32-key blocks per wave
+constexpr int NWV = 4;                 // waves per workgroup
+constexpr int KN = NWV * 32 * KVB;     // keys per workgroup
 constexpr int KM = 32;                 // query rows per step
+constexpr int NSTG = 4;                // ring stages
+
+// dK^T / dV^T accumulation: the sixteen 32x32 accumulator blocks of a wave fill the accumulation
+// register file exactly, and only matrix instructions touch them until the epilogue.  The
+// instruction is written out so that the accumulator stays in that file by construction.
+__device__ __forceinline__ void mfma32_acc(f32x16& acc, bf16x8 a, bf16x8 b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
 
 template <int D> struct DkvSmem {
-  static constexpr int P = (D + 8) * 2;        // row pitch (bytes) of the resident V rows
-  static constexpr int T_BYTES = ILV_ROWS * P; // [Q; dO] as ONE 64-row interleaved tile (rows 0..31 Q, 32..63 dO)
-  static constexpr int STAT = KM * 4;          // one float per row
-  static constexpr int STAGE = T_BYTES + 2 * STAT;
-  static constexpr int V_BYTES = KN * P;       // this workgroup's V rows, resident for the kernel
-  static constexpr int TOTAL = 2 * STAGE + V_BYTES;
+  static constexpr int CPR = D / 8;                 // 16-byte chunks of data per row
+  static constexpr int P = (D + 8) * 2;             // row pitch in bytes
+  static constexpr int SPR = P / 16;                // 16-byte slots per row
+  static constexpr int RUN = 8 * SPR;               // slots of one run: 8 consecutive physical rows
+  static constexpr int NCR = (RUN + 63) / 64;       // wave-level copies (64 slots) per run
+  static constexpr int STAT_OFF = ILV_ROWS * P;     // 32 x L log2(e), then 32 x delta
+  static constexpr int STAGE = STAT_OFF + 256;      // [Q; dO] as one 64-row interleaved tile + statistics
+  static constexpr int V_BYTES = KN * P;            // V rows of the workgroup, resident
+  static constexpr int TOTAL = NSTG * STAGE + V_BYTES;
+  static_assert(RUN >= 64, "a run must hold at least one full copy");
 };
 
-template <int D>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+// GENERAL = false: dense attention and Sq a multiple of 32 (no mask code, no ragged query tile, so
+// that the steady-state loop is one basic block); GENERAL = true: everything else.
+template <int D, bool GENERAL>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 bwd_dkdv_bf16_kernel(BwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   using SM = DkvSmem<D>;
-  constexpr int KS = D / 16, DB = D / 32, CPR = D / 8;
-  constexpr int CHUNKS = KM * CPR;                 // 16-byte chunks per Q (or dO) tile
-  constexpr int NLD = (CHUNKS + 255) / 256;        // chunks per thread
+  constexpr int KS = D / 16, DB = D / 32, CPR = SM::CPR, NCR = SM::NCR;
 
   const Dims& d = a.d;
   const int G = d.Hq / d.Hkv;
@@ -43,13 +68,12 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   HeadWork hw;
   if (!xcd_decode(blockIdx.x, d.B * d.Hkv, n_kt, &hw)) return;
   const int b = hw.head / d.Hkv, hk = hw.head % d.Hkv;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, kl = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, kl = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int j_wg0 = hw.item * KN;
   const int j_wave0 = j_wg0 + wave * 32 * KVB;
 
-  // K operands of this wave's keys stay in registers: lane holds key j_wave0 + 32 kb + kl,
-  // columns 16 ks + 8 g ..; the V rows of the workgroup stay in LDS (registers are spent on the
-  // two accumulators).
+  // ---- K operands of this wave's keys: lane holds key j_wave0 + 32 kb + kl, columns 16 ks + 8 g ..
   bf16x8 kf[KVB][KS];
 #pragma unroll
   for (int kb = 0; kb < KVB; ++kb) {
@@ -62,7 +86,8 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
       kf[kb][ks] = __builtin_bit_cast(bf16x8, x);
     }
   }
-  char* const vres = smem + 2 * SM::STAGE;
+  // ---- V rows of the workgroup -> LDS (plain row-major: only read as whole rows)
+  char* const vres = smem + NSTG * SM::STAGE;
   for (int c = tid; c < KN * CPR; c += 256) {
     const int r = c / CPR, col = (c % CPR) * 8, j = j_wg0 + r;
     u32x4 y = {0, 0, 0, 0};
@@ -70,8 +95,78 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
       y = *(const u32x4*)((const uint16_t*)a.v + b * d.kv_sb + hk * d.kv_sh + (long)j * d.kv_ss + col);
     *(u32x4*)(vres + r * SM::P + col * 2) = y;
   }
-  const char* const vwave = vres + (wave * 32 * KVB + kl) * SM::P + g * 16;
+  // Finish these loads before the tile copies start: otherwise their first use inside the loop
+  // would make the compiler drain every copy in flight.
+#pragma unroll
+  for (int kb = 0; kb < KVB; ++kb)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(kf[kb][ks]));
   const float c2 = d.scale * LOG2E;
+
+  // ---- query steps: the G heads of the group, KM rows at a time; fully masked steps are skipped
+  const int spH = (d.Sq + KM - 1) / KM;
+  const int n_all = G * spH;
+  const int j_wg1 = min(d.Skv, j_wg0 + KN) - 1;
+  auto next_step = [&](int s) __attribute__((always_inline)) -> int {
+    if (GENERAL && a.mask.allow)
+      while (s < n_all) {
+        const int i0 = (s % spH) * KM;
+        if (mask_rect(a.mask, b, i0, min(d.Sq, i0 + KM) - 1, j_wg0, j_wg1) != 0) break;
+        ++s;
+      }
+    return min(s, n_all);
+  };
+  int n = n_all;                                   // number of steps this workgroup performs
+  if (GENERAL && a.mask.allow) {
+    n = 0;
+    for (int s = next_step(0); s < n_all; s = next_step(s + 1)) ++n;
+  }
+
+  // ---- tile copies.  In the interleaved tile the logical rows 4 j + w (j = 0..7) of Q occupy the
+  // 8 consecutive physical rows 20 w .. 20 w + 7, and those of dO the next 8: a "run" of 8 SPR
+  // 16-byte slots.  Wave w copies the two runs of group w, each with NCR wave-level copies of 64
+  // slots (the last one re-covers the tail of the previous so that no copy crosses a run); lane l
+  // of a copy starting at slot a fills slot a + l = (row (a + l) / SPR of the run, chunk
+  // (a + l) % SPR; the pad chunk re-reads the last one).  Every copy therefore has a wave-uniform
+  // base and the per-lane offsets are the same for all runs.  The 64 statistics of the step are
+  // one more copy of 4 bytes per lane, issued by every wave.
+  const char* const q0 = (const char*)a.q + (b * d.q_sb) * 2;
+  const char* const g0 = (const char*)a.d_o + (b * d.q_sb) * 2;
+  const char* const l0 = (const char*)a.stats + ((long)b * d.Hq * a.sq_pad) * 8;
+  const unsigned row_bytes = (unsigned)(d.q_ss * 2);
+  auto run_start = [&](int c) __attribute__((always_inline)) -> int { return c + 1 < NCR ? 64 * c : SM::RUN - 64; };
+  unsigned cp_off[NCR];
+#pragma unroll
+  for (int c = 0; c < NCR; ++c) {
+    const int sl = run_start(c) + lane;
+    cp_off[c] = (unsigned)(4 * (sl / SM::SPR)) * row_bytes + (unsigned)min(sl % SM::SPR, CPR - 1) * 16;
+  }
+  auto issue_tile = [&](int s, char* st) __attribute__((always_inline)) {
+    const int hq = hk * G + s / spH, i0 = (s % spH) * KM;
+    const long tile = ((long)hq * d.q_sh + (long)i0 * d.q_ss) * 2;
+    const char* qb = q0 + tile + (long)wave * row_bytes;        // this wave's first row: tile row w
+    const char* gb = g0 + tile + (long)wave * row_bytes;
+    const int rows = min(KM, d.Sq - i0);
+    char* const qdst = st + 20 * wave * SM::P;
+    char* const gdst = qdst + 8 * SM::P;
+    if (!GENERAL || rows == KM) {
+#pragma unroll
+      for (int c = 0; c < NCR; ++c) {
+        dma16s(qb, cp_off[c], qdst + run_start(c) * 16);
+        dma16s(gb, cp_off[c], gdst + run_start(c) * 16);
+      }
+    } else {                                       // ragged last tile of a head: clamp the rows
+#pragma unroll
+      for (int c = 0; c < NCR; ++c) {
+        const int sl = run_start(c) + lane;
+        const unsigned r = (unsigned)min(4 * (sl / SM::SPR) + wave, rows - 1);     // row of the tile
+        const unsigned off = r * row_bytes + (unsigned)min(sl % SM::SPR, CPR - 1) * 16;
+        dma16s(q0 + tile, off, qdst + run_start(c) * 16);
+        dma16s(g0 + tile, off, gdst + run_start(c) * 16);
+      }
+    }
+    dma4s(l0 + ((long)hq * a.sq_pad + i0) * 8, lane * 4, st + SM::STAT_OFF);
+  };
 
   f32x16 dk[KVB][DB], dv[KVB][DB];
 #pragma unroll
@@ -79,144 +174,194 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
 #pragma unroll
     for (int i = 0; i < DB; ++i) { dk[kb][i] = zero16(); dv[kb][i] = zero16(); }
 
-  // query steps: the G heads of the group, KM rows at a time
-  const int spH = (d.Sq + KM - 1) / KM;
-  const int n_steps = G * spH;
-  const int j_wg1 = min(d.Skv, j_wg0 + KN) - 1;
-  auto next_step = [&](int s) -> int {
-    if (a.mask.allow)
-      while (s < n_steps) {
-        const int i0 = (s % spH) * KM;
-        if (mask_rect(a.mask, b, i0, min(d.Sq, i0 + KM) - 1, j_wg0, j_wg1) != 0) break;
-        ++s;
-      }
-    return s;
-  };
-  u32x4 qreg[NLD], greg[NLD];
-  float sreg = 0.f;
-  auto load_step = [&](int s) {
-    const int hq = hk * G + s / spH, i0 = (s % spH) * KM;
-    const long base = b * d.q_sb + hq * d.q_sh;
+  // ---- building blocks ------------------------------------------------------------------------
+  // S = Q K^T and dP = dO V^T of one step: lane = key column, registers = query rows.  The four
+  // LDS operands of a k-step are fetched while the matrix instructions of the previous one run.
+  auto score = [&](const char* __restrict__ t, const char* __restrict__ vw, f32x16 (&s)[KVB],
+                   f32x16 (&p)[KVB]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int p = 0; p < NLD; ++p) {
-      const int c = p * 256 + tid;
-      const int r = c / CPR, col = (c % CPR) * 8;
-      u32x4 x = {0, 0, 0, 0}, y = {0, 0, 0, 0};
-      if (c < CHUNKS && i0 + r < d.Sq) {
-        x = *(const u32x4*)((const uint16_t*)a.q + base + (long)(i0 + r) * d.q_ss + col);
-        y = *(const u32x4*)((const uint16_t*)a.d_o + base + (long)(i0 + r) * d.q_ss + col);
+    for (int kb = 0; kb < KVB; ++kb) { s[kb] = zero16(); p[kb] = zero16(); }
+    const char* qrow = t + ilv_off<D>(kl, 0, 8 * g);
+    const char* grow = t + ilv_off<D>(kl, KM, 8 * g);
+    bf16x8 qa[2], ga[2], va[2][KVB];               // two operand sets, used alternately
+    qa[0] = *(const bf16x8*)qrow;
+    ga[0] = *(const bf16x8*)grow;
+#pragma unroll
+    for (int kb = 0; kb < KVB; ++kb) va[0][kb] = *(const bf16x8*)(vw + kb * 32 * SM::P);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int cu = ks & 1, nx = cu ^ 1;
+      if (ks + 1 < KS) {
+        qa[nx] = *(const bf16x8*)(qrow + (ks + 1) * 32);
+        ga[nx] = *(const bf16x8*)(grow + (ks + 1) * 32);
+#pragma unroll
+        for (int kb = 0; kb < KVB; ++kb) va[nx][kb] = *(const bf16x8*)(vw + kb * 32 * SM::P + (ks + 1) * 32);
       }
-      qreg[p] = x;
-      greg[p] = y;
-    }
-    if (tid < 2 * KM) {                      // threads 0..31: L * log2(e); 32..63: delta
-      const int r = tid % KM;
-      const long row = ((long)b * d.Hq + hq) * d.Sq + i0 + r;
-      float x = tid < KM ? INFINITY : 0.f;
-      if (i0 + r < d.Sq) {
-        if (tid < KM) { const float L = a.lse[row]; if (L != -INFINITY) x = L * LOG2E; }
-        else x = a.delta[row];
-      }
-      sreg = x;
+#pragma unroll
+      for (int kb = 0; kb < KVB; ++kb) s[kb] = mfma32(qa[cu], kf[kb][ks], s[kb]);
+#pragma unroll
+      for (int kb = 0; kb < KVB; ++kb) p[kb] = mfma32(ga[cu], va[cu][kb], p[kb]);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
-  auto store_step = [&](int stage) {
-    char* qs = smem + stage * SM::STAGE;
+  // masked elements of a step's scores -> -inf (wave-uniform decision, rarely taken)
+  auto mask_scores = [&](int st, f32x16 (&s)[KVB]) __attribute__((always_inline)) {
+    if (!GENERAL || !a.mask.allow) return;
+    const int i0 = (st % spH) * KM;
+    const int cls = mask_rect(a.mask, b, i0, min(d.Sq, i0 + KM) - 1, min(j_wave0, d.Skv - 1),
+                              min(d.Skv - 1, j_wave0 + 32 * KVB - 1));
+    if (cls == 1) return;
+    asm volatile("" ::: "memory");
 #pragma unroll
-    for (int p = 0; p < NLD; ++p) {
-      const int c = p * 256 + tid;
-      if (c < CHUNKS) {
-        const int r = c / CPR, col = (c % CPR) * 8;
-        (void)r;
-        *(u32x4*)(qs + ilv_off<D>(tid / CPR, p * (256 / CPR), col)) = qreg[p];
-        *(u32x4*)(qs + ilv_off<D>(tid / CPR, KM + p * (256 / CPR), col)) = greg[p];
+    for (int kb = 0; kb < KVB; ++kb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int j = j_wave0 + 32 * kb + kl, i = i0 + 8 * (v / 4) + 4 * g + (v % 4);
+        const bool ok = j < d.Skv && i < d.Sq && mask_elem(a.mask, b, i, j);
+        if (!ok) s[kb][v] = -INFINITY;
       }
+  };
+  // Conversion of scores into operands, element x of a step (x = 0..31: four query rows q4 = x / 8
+  // of key block kb = (x / 4) % 2, row e = x % 4 of the four): p = exp2(s c2 - L2), dS = p (dP -
+  // delta), packed in pairs as bf16 into word 2 (q4 % 2) + e / 2 of operand q4 / 2 of the key block.
+  struct Conv { f32x4 l4, d4; };
+  struct Carry { float pr, ds; };
+  auto conv_stats = [&](const char* __restrict__ t, int q4, Conv& cv) __attribute__((always_inline)) {
+    cv.l4 = *(const f32x4*)(t + SM::STAT_OFF + (8 * q4 + 4 * g) * 4);
+    cv.d4 = *(const f32x4*)(t + SM::STAT_OFF + 128 + (8 * q4 + 4 * g) * 4);
+  };
+  auto conv_elem = [&](int x, const Conv& cv, Carry& cy, const f32x16 (&s)[KVB], const f32x16 (&p)[KVB],
+                       u32x4 (&pwo)[KVB][2], u32x4 (&swo)[KVB][2]) __attribute__((always_inline)) {
+    const int q4 = x / 8, kb = (x / 4) % 2, e = x % 4, v = 4 * q4 + e;
+    const float pr = __builtin_amdgcn_exp2f(fmaf(s[kb][v], c2, -cv.l4[e]));
+    const float ds = pr * (p[kb][v] - cv.d4[e]);
+    if (e % 2 == 0) { cy.pr = pr; cy.ds = ds; return; }
+    pwo[kb][q4 >> 1][2 * (q4 & 1) + e / 2] = pack2_bf16(cy.pr, pr);
+    swo[kb][q4 >> 1][2 * (q4 & 1) + e / 2] = pack2_bf16(cy.ds, ds);
+  };
+  auto convert = [&](const char* __restrict__ t, const f32x16 (&s)[KVB], const f32x16 (&p)[KVB],
+                     u32x4 (&pwo)[KVB][2], u32x4 (&swo)[KVB][2]) __attribute__((always_inline)) {
+    Conv cv;
+    Carry cy;
+#pragma unroll
+    for (int x = 0; x < 32; ++x) {
+      if (x % 8 == 0) conv_stats(t, x / 8, cv);
+      conv_elem(x, cv, cy, s, p, pwo, swo);
     }
-    if (tid < 2 * KM) *(float*)(qs + SM::T_BYTES + tid * 4) = sreg;
+  };
+  // dV^T += dO^T P and dK^T += Q^T dS of one step (two k-steps of 16 query rows)
+  auto contract = [&](const char* __restrict__ t, const u32x4 (&pwi)[KVB][2], const u32x4 (&swi)[KVB][2]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const bf16x8 gt = load_tr_operand_ilv<D>(t, KM + 16 * t2, 32 * db, lane);
+        const bf16x8 qt = load_tr_operand_ilv<D>(t, 16 * t2, 32 * db, lane);
+#pragma unroll
+        for (int kb = 0; kb < KVB; ++kb) {
+          mfma32_acc(dv[kb][db], gt, __builtin_bit_cast(bf16x8, pwi[kb][t2]));
+          mfma32_acc(dk[kb][db], qt, __builtin_bit_cast(bf16x8, swi[kb][t2]));
+        }
+      }
+  };
+  // contract(step i) on the matrix core together with convert(step i+1) on the vector ALU: every
+  // matrix instruction is followed by the conversion of 32 / (8 DB) elements, and nothing is
+  // scheduled across these units, so the two pipes stay busy together.  The transposed operands of
+  // a group of four matrix instructions are fetched one group ahead.
+  auto contract_convert = [&](const char* __restrict__ t0, const char* __restrict__ t1,
+                              const u32x4 (&pwi)[KVB][2], const u32x4 (&swi)[KVB][2],
+                              const f32x16 (&s)[KVB], const f32x16 (&p)[KVB],
+                              u32x4 (&pwo)[KVB][2], u32x4 (&swo)[KVB][2]) __attribute__((always_inline)) {
+    constexpr int NM = 8 * DB, EPM = 32 / NM;      // matrix instructions, elements per instruction
+    bf16x8 gt[2], qt[2];                           // two operand sets, used alternately
+    gt[0] = load_tr_operand_ilv<D>(t0, KM, 0, lane);
+    qt[0] = load_tr_operand_ilv<D>(t0, 0, 0, lane);
+    Conv cv[2];
+    Carry cy;
+    conv_stats(t1, 0, cv[0]);
+#pragma unroll
+    for (int m = 0; m < NM; ++m) {
+      const int c = m / 4, t2 = c / DB, db = c % DB, j = m % 4, cu = c & 1;
+      if (j == 0 && c + 1 < 2 * DB) {
+        gt[cu ^ 1] = load_tr_operand_ilv<D>(t0, KM + 16 * ((c + 1) / DB), 32 * ((c + 1) % DB), lane);
+        qt[cu ^ 1] = load_tr_operand_ilv<D>(t0, 16 * ((c + 1) / DB), 32 * ((c + 1) % DB), lane);
+      }
+      if (j % 2 == 0) mfma32_acc(dv[j / 2][db], gt[cu], __builtin_bit_cast(bf16x8, pwi[j / 2][t2]));
+      else mfma32_acc(dk[j / 2][db], qt[cu], __builtin_bit_cast(bf16x8, swi[j / 2][t2]));
+#pragma unroll
+      for (int x = m * EPM; x < (m + 1) * EPM; ++x) {
+        const int q4 = x / 8;
+        if (x % 8 == 0 && q4 + 1 < 4) conv_stats(t1, q4 + 1, cv[(q4 + 1) & 1]);   // one q4 ahead
+        conv_elem(x, cv[q4 & 1], cy, s, p, pwo, swo);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
   };
 
-  int cur = next_step(0);
-  if (cur < n_steps) { load_step(cur); store_step(0); }
-  __syncthreads();
-  int stage = 0;
-  while (cur < n_steps) {
-    const int nxt = next_step(cur + 1);
-    if (nxt < n_steps) load_step(nxt);
-    const char* qs_ = smem + stage * SM::STAGE;
-    const float* lse_s = (const float*)(qs_ + SM::T_BYTES);
-    const float* del_s = lse_s + KM;
-    const int i0 = (cur % spH) * KM;
-    int cls = 1;
-    if (a.mask.allow)
-      cls = mask_rect(a.mask, b, i0, min(d.Sq, i0 + KM) - 1, j_wave0,
-                      min(d.Skv - 1, j_wave0 + 32 * KVB - 1));
-    if (j_wave0 >= d.Skv) cls = 0;
-    if (cls != 0) {
-      // ---- S = Q K^T and dP = dO V^T: lane = key column, registers = query rows
-      f32x16 sacc[KVB], pacc[KVB];
+  // ---- pipeline over the needed steps.  Step number q of the sequence lives in ring stage q % 4.
+  int cursor = next_step(0);                       // next step to issue
+  int e[NSTG];                                     // step ids of the next four steps (static indexing only)
 #pragma unroll
-      for (int kb = 0; kb < KVB; ++kb) { sacc[kb] = zero16(); pacc[kb] = zero16(); }
+  for (int q = 0; q < NSTG; ++q) e[q] = n_all;
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 qa = *(const bf16x8*)(qs_ + ilv_off<D>(kl, 0, 16 * ks + 8 * g));
-        const bf16x8 ga = *(const bf16x8*)(qs_ + ilv_off<D>(kl, KM, 16 * ks + 8 * g));
-#pragma unroll
-        for (int kb = 0; kb < KVB; ++kb) {
-          sacc[kb] = mfma32(qa, kf[kb][ks], sacc[kb]);
-          pacc[kb] = mfma32(ga, *(const bf16x8*)(vwave + kb * 32 * SM::P + ks * 32), pacc[kb]);
-        }
-      }
-      // ---- P and dS in place
-      const bool need_mask = (j_wave0 + 32 * KVB > d.Skv) || cls == 2;
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        const f32x4 l4 = *(const f32x4*)(lse_s + 8 * q4 + 4 * g);
-        const f32x4 d4 = *(const f32x4*)(del_s + 8 * q4 + 4 * g);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int v = 4 * q4 + e;
-#pragma unroll
-          for (int kb = 0; kb < KVB; ++kb) {
-            float p = __builtin_amdgcn_exp2f(fmaf(sacc[kb][v], c2, -l4[e]));
-            if (need_mask) {
-              const int j = j_wave0 + 32 * kb + kl, i = i0 + 8 * q4 + 4 * g + e;
-              bool ok = j < d.Skv;
-              if (ok && cls == 2) ok = i < d.Sq && mask_elem(a.mask, b, i, j);
-              if (!ok) p = 0.f;
-            }
-            sacc[kb][v] = p;
-            pacc[kb][v] = p * (pacc[kb][v] - d4[e]);
-          }
-        }
-      }
-      // ---- dV^T += dO^T P,  dK^T += Q^T dS  (two k-steps of 16 query rows)
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        bf16x8 pf[KVB], sf[KVB];
-#pragma unroll
-        for (int kb = 0; kb < KVB; ++kb) {
-          pf[kb] = cvt_operand(sacc[kb], 8 * t);
-          sf[kb] = cvt_operand(pacc[kb], 8 * t);
-        }
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const bf16x8 gt = load_tr_operand_ilv<D>(qs_, KM + 16 * t, 32 * db, lane);
-          const bf16x8 qtr = load_tr_operand_ilv<D>(qs_, 16 * t, 32 * db, lane);
-#pragma unroll
-          for (int kb = 0; kb < KVB; ++kb) {
-            dv[kb][db] = mfma32(gt, pf[kb], dv[kb][db]);
-            dk[kb][db] = mfma32(qtr, sf[kb], dk[kb][db]);
-          }
-        }
-      }
+  for (int q = 0; q < NSTG - 1; ++q) {
+    e[q] = cursor;
+    if (q < n) {
+      issue_tile(cursor, smem + q * SM::STAGE);
+      cursor = next_step(cursor + 1);
     }
-    if (nxt < n_steps) store_step(stage ^ 1);
-    __syncthreads();
-    stage ^= 1;
-    cur = nxt;
+  }
+  wait_vmcnt<0>();
+  __syncthreads();                                 // V rows and the first tiles are in LDS
+  const char* const vw = vres + (wave * 32 * KVB + kl) * SM::P + g * 16;
+
+  f32x16 s[KVB], p[KVB];
+  u32x4 pf0[KVB][2] = {}, sf0[KVB][2] = {}, pf1[KVB][2] = {}, sf1[KVB][2] = {};   // packed P and dS operands
+  if (n > 0) {
+    score(smem, vw, s, p);
+    mask_scores(e[0], s);
+    convert(smem, s, p, pf0, sf0);
+    if (n > 1) { score(smem + SM::STAGE, vw, s, p); mask_scores(e[1], s); }
+  }
+  // iteration i: every wave has finished step i - 1 (barrier), so its stage takes step i + 3;
+  // contract step i, convert step i + 1 (already scored), score step i + 2.
+  auto top = [&](bool issue, char* __restrict__ st_copy) __attribute__((always_inline)) {
+    wait_vmcnt<0>();
+    wg_barrier();
+    if (issue) {
+      e[3] = cursor;
+      issue_tile(cursor, st_copy);
+      cursor = next_step(cursor + 1);
+    }
+  };
+  auto full_iter = [&](int i, char* __restrict__ st_copy, const char* __restrict__ t0,
+                       const char* __restrict__ t1, const char* __restrict__ t2,
+                       const char* __restrict__ vw_, const u32x4 (&pfi)[KVB][2],
+                       const u32x4 (&sfi)[KVB][2], u32x4 (&pfo)[KVB][2], u32x4 (&sfo)[KVB][2]) __attribute__((always_inline)) {
+    top(true, st_copy);
+    contract_convert(t0, t1, pfi, sfi, s, p, pfo, sfo);
+    score(t2, vw_, s, p);
+    mask_scores(e[2], s);
+    e[0] = e[1]; e[1] = e[2]; e[2] = e[3];
+  };
+  auto stage = [&](int q) __attribute__((always_inline)) -> char* { return smem + (q % NSTG) * SM::STAGE; };
+  int i = 0;
+  while (i + 4 < n) {                              // two full iterations per trip, each issuing a tile
+    full_iter(i, stage(i + 3), stage(i), stage(i + 1), stage(i + 2), vw, pf0, sf0, pf1, sf1);
+    full_iter(i + 1, stage(i + 4), stage(i + 1), stage(i + 2), stage(i + 3), vw, pf1, sf1, pf0, sf0);
+    i += 2;
+  }
+  for (; i < n; ++i) {                             // the last (at most four) iterations
+    top(i + 3 < n, stage(i + 3));
+    contract(stage(i), pf0, sf0);
+    if (i + 1 < n) convert(stage(i + 1), s, p, pf0, sf0);
+    if (i + 2 < n) { score(stage(i + 2), vw, s, p); mask_scores(e[2], s); }
+    e[0] = e[1]; e[1] = e[2]; e[2] = e[3];
   }
 
-  // ---- write dK = scale * acc, dV = acc (transposed accumulators: lane = key row)
+  // ---- write dK = scale * acc, dV = acc (transposed accumulators: lane = key row).  The last
+  // matrix instructions must have retired before their registers are read.
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 #pragma unroll
   for (int kb = 0; kb < KVB; ++kb) {
     const int j = j_wave0 + 32 * kb + kl;
@@ -245,22 +390,24 @@ hipError_t set_smem_once(F* fn, int bytes, bool* done) {
   return e;
 }
 
+
+template <int D, bool GENERAL>
+hipError_t launch(const BwdArgs& a, long grid, hipStream_t s) {
+  static bool once = false;
+  hipError_t e = set_smem_once(bwd_dkdv_bf16_kernel<D, GENERAL>, DkvSmem<D>::TOTAL, &once);
+  if (e != hipSuccess) return e;
+  bwd_dkdv_bf16_kernel<D, GENERAL><<<(unsigned)grid, 256, DkvSmem<D>::TOTAL, s>>>(a);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_bwd_dkdv_bf16(const BwdArgs& a, hipStream_t s) {
   const Dims& d = a.d;
-  const long grid_k = xcd_grid(d.B * d.Hkv, (d.Skv + KN - 1) / KN);
-  hipError_t e;
-  if (d.D == 64) {
-    static bool once = false;
-    if ((e = set_smem_once(bwd_dkdv_bf16_kernel<64>, DkvSmem<64>::TOTAL, &once)) != hipSuccess) return e;
-    bwd_dkdv_bf16_kernel<64><<<(unsigned)grid_k, 256, DkvSmem<64>::TOTAL, s>>>(a);
-  } else {
-    static bool once = false;
-    if ((e = set_smem_once(bwd_dkdv_bf16_kernel<128>, DkvSmem<128>::TOTAL, &once)) != hipSuccess) return e;
-    bwd_dkdv_bf16_kernel<128><<<(unsigned)grid_k, 256, DkvSmem<128>::TOTAL, s>>>(a);
-  }
-  return hipGetLastError();
+  const long grid = xcd_grid(d.B * d.Hkv, (d.Skv + KN - 1) / KN);
+  const bool general = a.mask.allow != nullptr || d.Sq % KM != 0;
+  if (d.D == 64) return general ? launch<64, true>(a, grid, s) : launch<64, false>(a, grid, s);
+  return general ? launch<128, true>(a, grid, s) : launch<128, false>(a, grid, s);
 }
 
 }  // namespace lvx

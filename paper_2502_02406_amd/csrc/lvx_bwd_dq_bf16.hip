@@ -80,9 +80,9 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   const long row = ((long)b * d.Hq + hq) * d.Sq + i_lane;
   float lse2 = INFINITY, delta = 0.f;       // +inf makes p = exp2(-inf) = 0 for dead rows
   if (row_ok) {
-    const long rowp = ((long)b * d.Hq + hq) * a.sq_pad + i_lane;
-    lse2 = a.lse2p[rowp];
-    delta = a.deltap[rowp];
+    const long slot = (((long)b * d.Hq + hq) * a.sq_pad + (i_lane & ~31)) * 2 + (i_lane & 31);
+    lse2 = a.stats[slot];
+    delta = a.stats[slot + 32];
   }
   const float c2 = d.scale * LOG2E;
 

@@ -102,13 +102,14 @@ hipError_t launch_merge(const MergeArgs& a, int part_is_f32, int out_is_f32, hip
 }
 
 // delta[b,h,i] = sum_d dO[b,h,i,d] * O[b,h,i,d].  16 lanes per row.  The bf16 kernels read the
-// row statistics 32 rows at a time with aligned vector copies, so two padded copies are written
-// as well ([B,Hq,sq_pad], sq_pad a multiple of 32): lse2p = L * log2(e) with +inf for rows
-// without keys and for pad rows (which makes their probabilities exp2(-inf) = 0), and deltap.
+// row statistics 32 rows at a time with aligned copies, so a padded, grouped copy is written as
+// well: stats[B,Hq,sq_pad/32][2][32] (sq_pad a multiple of 32) holds, per group of 32 rows, 32
+// values of L * log2(e) -- +inf for rows without keys and for pad rows, which makes their
+// probabilities exp2(-inf) = 0 -- followed by the 32 values of delta (0 in pad rows).
 template <bool F32>
 __global__ void __launch_bounds__(256) delta_kernel(Dims d, const void* o, const void* d_o,
-                                                    const float* lse, float* delta, float* lse2p,
-                                                    float* deltap, int sq_pad) {
+                                                    const float* lse, float* delta, float* stats,
+                                                    int sq_pad) {
   const long rows = (long)d.B * d.Hq * sq_pad;
   const long rowp = ((long)blockIdx.x * 256 + threadIdx.x) / 16;
   const int c = threadIdx.x % 16;
@@ -144,16 +145,17 @@ __global__ void __launch_bounds__(256) delta_kernel(Dims d, const void* o, const
     const float L = lse[row];
     if (L != -INFINITY) l2 = L * 1.4426950408889634f;
   }
-  lse2p[rowp] = l2;
-  deltap[rowp] = s;
+  const long slot = (rowp / 32) * 64 + rowp % 32;     // sq_pad is a multiple of 32
+  stats[slot] = l2;
+  stats[slot + 32] = s;
 }
 
 hipError_t launch_delta(const Dims& d, const void* o, const void* d_o, int is_f32, const float* lse,
-                        float* delta, float* lse2p, float* deltap, int sq_pad, hipStream_t s) {
+                        float* delta, float* stats, int sq_pad, hipStream_t s) {
   const long rows = (long)d.B * d.Hq * sq_pad;
   const unsigned blocks = (unsigned)((rows * 16 + 255) / 256);
-  if (is_f32) delta_kernel<true><<<blocks, 256, 0, s>>>(d, o, d_o, lse, delta, lse2p, deltap, sq_pad);
-  else delta_kernel<false><<<blocks, 256, 0, s>>>(d, o, d_o, lse, delta, lse2p, deltap, sq_pad);
+  if (is_f32) delta_kernel<true><<<blocks, 256, 0, s>>>(d, o, d_o, lse, delta, stats, sq_pad);
+  else delta_kernel<false><<<blocks, 256, 0, s>>>(d, o, d_o, lse, delta, stats, sq_pad);
   return hipGetLastError();
 }
 

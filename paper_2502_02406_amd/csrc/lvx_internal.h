@@ -39,8 +39,8 @@ struct BwdArgs {
   const void *q, *k, *v, *o, *d_o;
   const float* lse;     // final statistic, [B,Hq,Sq]
   float* delta;         // workspace, [B,Hq,Sq]: rowsum(dO * O)
-  float* lse2p;         // workspace, [B,Hq,sq_pad]: L * log2(e), +inf for rows without keys and pad rows
-  float* deltap;        // workspace, [B,Hq,sq_pad]: delta again, 0 in pad rows
+  float* stats;         // workspace, [B,Hq,sq_pad/32][2][32]: per group of 32 query rows, 32 values of
+                        // L * log2(e) (+inf for rows without keys and pad rows), then 32 of delta
   int sq_pad;           // Sq rounded up to a multiple of 32
   float* dq_accum;      // [B,Hq,Sq,D] float32, accumulated into
   void *dk, *dv;        // K's strides, input dtype, overwritten
@@ -73,7 +73,7 @@ int bwd_bf16_pick_split(const Dims& d, int n_cu);
 // memory-bound helpers
 hipError_t launch_merge(const MergeArgs& a, int part_is_f32, int out_is_f32, hipStream_t s);
 hipError_t launch_delta(const Dims& d, const void* o, const void* d_o, int is_f32, const float* lse,
-                        float* delta, float* lse2p, float* deltap, int sq_pad, hipStream_t s);
+                        float* delta, float* stats, int sq_pad, hipStream_t s);
 hipError_t launch_dq_finalize(const Dims& d, const float* dq_accum, void* dq, int is_f32,
                               hipStream_t s);
 

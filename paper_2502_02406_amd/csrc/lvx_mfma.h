@@ -93,6 +93,23 @@ __device__ __forceinline__ void dma16(const void* gsrc, void* lds_dst) {
   __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gsrc,
                                    (void __attribute__((address_space(3)))*)lds_dst, 16, 0, 0);
 }
+// The same copy written out as an instruction, with a wave-uniform 64-bit base and a 32-bit byte
+// offset per lane (dma4s: 4 bytes per lane, landing at lds_dst + 4 l).  The compiler does not see
+// a memory instruction here: it neither counts the copy in vmcnt nor lets it force the waits of
+// unrelated LDS reads to zero, which it does for the builtin above while any copy is in flight.
+// The caller orders everything by hand: wait_vmcnt<N>() + barrier before the data is read, a
+// barrier before a stage is overwritten.  m0 (reserved, never live across statements) carries the
+// LDS address; one wait state separates its write from the copy.
+__device__ __forceinline__ void dma16s(const void* base, unsigned voff, void* lds_dst) {
+  const unsigned l = (unsigned)(uintptr_t)LVX_LDS(lds_dst, char);
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(voff), "s"(base), "s"(l) : "memory");
+}
+__device__ __forceinline__ void dma4s(const void* base, unsigned voff, void* lds_dst) {
+  const unsigned l = (unsigned)(uintptr_t)LVX_LDS(lds_dst, char);
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+               :: "v"(voff), "s"(base), "s"(l) : "memory");
+}
 // s_waitcnt vmcnt(N) only (expcnt and lgkmcnt left at "no wait").
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
   static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
