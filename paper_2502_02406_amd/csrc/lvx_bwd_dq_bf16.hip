@@ -82,7 +82,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   if (row_ok) {
     const long slot = (((long)b * d.Hq + hq) * a.sq_pad + (i_lane & ~31)) * 2 + (i_lane & 31);
     lse2 = a.stats[slot];
-    delta = a.stats[slot + 32];
+    delta = -a.stats[slot + 32];
   }
   const float c2 = d.scale * LOG2E;
 

@@ -105,7 +105,7 @@ hipError_t launch_merge(const MergeArgs& a, int part_is_f32, int out_is_f32, hip
 // row statistics 32 rows at a time with aligned copies, so a padded, grouped copy is written as
 // well: stats[B,Hq,sq_pad/32][2][32] (sq_pad a multiple of 32) holds, per group of 32 rows, 32
 // values of L * log2(e) -- +inf for rows without keys and for pad rows, which makes their
-// probabilities exp2(-inf) = 0 -- followed by the 32 values of delta (0 in pad rows).
+// probabilities exp2(-inf) = 0 -- followed by the 32 values of -delta (0 in pad rows).
 template <bool F32>
 __global__ void __launch_bounds__(256) delta_kernel(Dims d, const void* o, const void* d_o,
                                                     const float* lse, float* delta, float* stats,
@@ -147,7 +147,7 @@ __global__ void __launch_bounds__(256) delta_kernel(Dims d, const void* o, const
   }
   const long slot = (rowp / 32) * 64 + rowp % 32;     // sq_pad is a multiple of 32
   stats[slot] = l2;
-  stats[slot + 32] = s;
+  stats[slot + 32] = -s;
 }
 
 hipError_t launch_delta(const Dims& d, const void* o, const void* d_o, int is_f32, const float* lse,

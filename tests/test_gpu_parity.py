@@ -47,11 +47,14 @@ def check_fwd(O, L, Oref, Lref, tol, tag):
         assert np.all(O[inf_ref] == 0.0), f"{tag}: rows without keys must give O = 0"
 
 
-def check_grad(g, ref, tol, tag):
+def check_grad(g, ref, tol, tag, cancel_atol=0.0):
+    """cancel_atol > 0 is for references that vanish only by cancellation (a single key: dS =
+    p (dP - delta) with dP and delta two float32 sums of the same D products taken in different
+    orders); zeros that are structural (masked or dead rows, p = 0) must be exact."""
     g = g.float().cpu().numpy().astype(np.float64)
     assert np.isfinite(g).all(), f"{tag}: non-finite gradient"
     if np.abs(ref).max() == 0.0:
-        assert np.all(g == 0.0), f"{tag}: expected exact zeros"
+        assert np.abs(g).max() <= cancel_atol, f"{tag}: expected zeros, got {np.abs(g).max()}"
         return
     assert rel_fro(g, ref) <= tol["grad"], f"{tag}: Frobenius rel err {rel_fro(g, ref)}"
     assert rel_max(g, ref) <= tol["grad"], f"{tag}: max-abs rel err {rel_max(g, ref)}"
@@ -82,8 +85,11 @@ def run_case(w: W.Workload, seed=W.BASE_SEED, do_bwd=True, v_mean=0.0):
     # the oracle differentiates the exact forward; the GPU was handed its own (rounded) O and L,
     # as a real backward pass would be
     dQr, dKr, dVr = oracle.bwd(qn, kn, vn, gn, mask=omask)
-    check_grad(dq, dQr, tol, w.name + " dQ")
-    check_grad(dk, dKr, tol, w.name + " dK")
+    # One key: O = V and p = 1, so dS, dQ and dK vanish by cancellation of sums of magnitude
+    # D * |dO| * |V| ~ 30, i.e. up to a few float32 ulps (1e-6) times |Q| or |K| times the scale.
+    atol = 1e-5 if w.Skv == 1 else 0.0
+    check_grad(dq, dQr, tol, w.name + " dQ", atol)
+    check_grad(dk, dKr, tol, w.name + " dK", atol)
     check_grad(dv, dVr, tol, w.name + " dV")
 
 
