@@ -1,47 +1,98 @@
-// bf16 backward kernels.  The attention probabilities are recomputed from the saved statistic:
-// p_ij = exp(scale <Q_i, K_j> - L_i) (Section 3.2 of the paper saves only x, O and L), and
-// dS_ij = p_ij (<dO_i, V_j> - delta_i) with delta_i = sum_d dO_id O_id.
+// bf16 backward, query-stationary kernel: dQ of one K/V block.  Table 1 of the paper counts the
+// backward as five matrix products; this kernel performs three of them (S, dP, dQ) with the
+// probabilities recomputed from the saved statistic L (Section 3.2 saves only x, O and L):
+//   p_ij = exp(scale <Q_i, K_j> - L_i),   dS_ij = p_ij (<dO_i, V_j> - delta_i),   dQ_i += scale dS_ij K_j.
+// S and dP are also formed by the key-stationary kernel (7 products for the 5 that Table 1
+// counts); the alternative, one kernel that scatters dQ with float atomics, is bounded by the L2
+// atomic rate (about one float per channel per clock), far below the matrix cores.
 //
-// Two kernels, no atomics in the inner loops and no round trip of P or dS through memory:
-//   dq kernel   -- query-stationary (same structure as the forward kernel): transposed tiles
-//                  S^T = K Q^T and dP^T = V dO^T put one query per lane, dS^T (bf16) is then the
-//                  B operand of dQ^T += K^T dS^T, K^T coming from transposing LDS reads.
-//   dkdv kernel -- key-stationary: a wave keeps its keys of K in registers (V in LDS) and streams the
-//                  query rows of every head that shares this K/V head.  S = Q K^T and
-//                  dP = dO V^T put one KEY per lane, so P and dS (bf16) are the B operands of
-//                  dV^T += dO^T P and dK^T += Q^T dS, with dO^T / Q^T from transposing reads.
-// S and dP are therefore formed twice (7 matrix products for the 5 that Table 1 counts); the
-// alternative, one kernel that scatters dQ with float atomics, is bounded by the L2 atomic rate
-// (about one float per channel per clock), far below the matrix cores for long key ranges.
+// Workgroup = 4 wavefronts = 256 query rows of one (batch, query head), one wave per SIMD with
+// the whole register file.  A wave owns 64 query rows (two 32-row blocks): their Q and dO operands
+// and the dQ^T accumulators live in the accumulation registers for the whole kernel, so every K
+// or V operand fetched from LDS feeds two matrix instructions.  K/V tiles of 64 keys travel
+// HBM -> LDS by direct global-to-LDS copies into a ring of four stages, issued two tiles ahead,
+// one barrier per tile.
+// Transposed tiles S^T = K Q^T and dP^T = V dO^T put one QUERY per lane (its statistics are
+// per-lane scalars) and 16 keys in a lane's registers, so dS^T, rounded to bf16, is already the
+// B operand of dQ^T += K^T dS^T, with K^T fetched by transposing LDS reads.
+// The loop runs over 32-key halves and is software pipelined inside each wave: while the matrix
+// core contracts half h (dQ) and scores half h+2 (S, dP), the vector ALU turns the scores of half
+// h+1 into dS; two sets of score registers alternate.
 #include "lvx_internal.h"
 #include "lvx_mfma.h"
+
+#include <type_traits>
 
 namespace lvx {
 
 namespace {
 
 constexpr float LOG2E = 1.4426950408889634f;
+constexpr int QB = 2;                  // 32-row query blocks per wave
+constexpr int NWV = 4;                 // waves per workgroup
+constexpr int QM = NWV * 32 * QB;      // query rows per workgroup
+constexpr int TN = 64;                 // keys per tile (two halves of 32)
+constexpr int NSTG = 4;                // ring stages
+constexpr int XE = 12;                 // elements of a half converted during the contraction (of 32)
 
-// ------------------------------------------------------------------------------------------
-// dQ kernel
-// ------------------------------------------------------------------------------------------
-constexpr int QM = 128;      // query rows per workgroup
-constexpr int QN = 64;       // keys per tile
-
+// LDS tile of 64 rows x D bf16, rows interleaved: logical row r lives in group r % 4 at row r / 4;
+// a group is 16 rows of pitch (D + 8) * 2 bytes plus 64 bytes, which puts the four groups 64 bytes
+// apart modulo 256.  Both access patterns are then free of bank conflicts: b128 reads of one
+// column chunk by 16 consecutive logical rows, and transposing reads of 4 consecutive logical
+// rows x 64 bytes.
 template <int D> struct DqSmem {
-  static constexpr int P = (D + 8) * 2;        // row pitch (bytes) of the V tile (b128 reads only)
-  static constexpr int K_BYTES = ILV_ROWS * P; // K tile: row-interleaved, read both ways
-  static constexpr int V_BYTES = QN * P;
-  static constexpr int STAGE = K_BYTES + V_BYTES;
-  static constexpr int TOTAL = 2 * STAGE;
+  static constexpr int CPR = D / 8;                 // 16-byte chunks of data per row
+  static constexpr int P = (D + 8) * 2;             // row pitch in bytes
+  static constexpr int SPR = P / 16;                // 16-byte slots per row
+  static constexpr int GS = 16 * P + 64;            // group stride in bytes
+  static constexpr int TILE = 4 * GS;
+  static constexpr int STAGE = 2 * TILE;            // K tile, then V tile
+  static constexpr int TOTAL = NSTG * STAGE;
+  static constexpr int RUN = 16 * SPR;              // slots of one group (contiguous)
+  static constexpr int NCR = (RUN + 63) / 64;       // wave-level copies (64 slots) per group
+  static_assert(GS % 256 == 64, "groups must sit 64 bytes apart modulo 256");
 };
-
+// byte offset of logical row rl + rc (rc a compile-time multiple of 4), byte column colb
+template <int D> __device__ __forceinline__ int tile_off(int rl, int rc, int colb) {
+  return (rl & 3) * DqSmem<D>::GS + ((rl >> 2) + (rc >> 2)) * DqSmem<D>::P + colb;
+}
+// A operand (32 rows n x 16 k) of a product over k from the row-major logical tile X[k][n]:
+// rows n0 + l % 32, k slots e -> logical row kbase + 8 (e / 4) + 4 g + (e % 4)
 template <int D>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+__device__ __forceinline__ bf16x8 tile_tr_operand(const char* tile, int kbase, int n0, int lane) {
+  const int j = lane & 15, half = (lane >> 4) & 1, g = lane >> 5;
+  const char* p = tile + tile_off<D>(4 * g + (j >> 2), 0, (16 * half + 4 * (j & 3)) * 2);
+  s16x4 lo = lds_read_tr(p + tile_off<D>(0, kbase, n0 * 2));
+  s16x4 hi = lds_read_tr(p + tile_off<D>(0, kbase + 8, n0 * 2));
+  typedef __attribute__((ext_vector_type(8))) short s16x8;
+  s16x8 r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+// Matrix instructions written out, so that the operand files are fixed by construction: the
+// stationary B operands (Q, dO) and the dQ accumulators sit in the accumulation registers, scores
+// in ordinary registers where the vector ALU reads them.  The compiler does not know these are
+// matrix instructions; the distances it would otherwise enforce between a matrix result and its
+// first reader are kept by the order of the code (a result is read at least two matrix
+// instructions and a wait after it was issued).
+__device__ __forceinline__ void mfma_first(f32x16& c, bf16x8 a, bf16x8 b_acc) {     // c = a b
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(c) : "v"(a), "a"(b_acc));
+}
+__device__ __forceinline__ void mfma_next(f32x16& c, bf16x8 a, bf16x8 b_acc) {      // c += a b
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "a"(b_acc));
+}
+__device__ __forceinline__ void mfma_acc(f32x16& c_acc, bf16x8 a, bf16x8 b) {       // c += a b, c in acc regs
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c_acc) : "v"(a), "v"(b));
+}
+
+// GENERAL = false: dense attention and Skv a multiple of 64 (no mask code, no ragged tile, so that
+// the steady-state loop is one basic block); GENERAL = true: everything else.
+template <int D, bool GENERAL>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 bwd_dq_bf16_kernel(BwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   using SM = DqSmem<D>;
-  constexpr int KS = D / 16, DB = D / 32, CPR = D / 8, RPP = 256 / CPR, NPASS = QN / RPP;
+  constexpr int KS = D / 16, DB = D / 32, CPR = SM::CPR, NCR = SM::NCR;
 
   const Dims& d = a.d;
   const int G = d.Hq / d.Hkv;
@@ -53,140 +104,309 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   const int hq = hk * G + (hw.item % (G * n_qt)) / n_qt;
   const int qt = hw.item % n_qt;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, ql = lane & 31;
-  const int i_wave0 = qt * QM + wave * 32;
-  const int i_lane = i_wave0 + ql;
-  const bool row_ok = i_lane < d.Sq;
+  const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ql = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int i_wave0 = qt * QM + wave * 32 * QB;     // first query row of this wave
 
-  const int n_tiles = (d.Skv + QN - 1) / QN;
+  // KV range of this split, in tiles
+  const int n_tiles = (d.Skv + TN - 1) / TN;
   const int tps = (n_tiles + a.n_split_dq - 1) / a.n_split_dq;
   const int t_begin = split * tps;
   const int t_end = min(n_tiles, t_begin + tps);
 
-  bf16x8 qf[KS], gf[KS];
-  {
-    const long off = b * d.q_sb + hq * d.q_sh + (long)i_lane * d.q_ss;
+  // ---- stationary operands and statistics of this lane's query rows i_wave0 + 32 qb + ql
+  bf16x8 qf[QB][KS], gf[QB][KS];
+  float l2[QB], nd[QB];                // L log2(e) (+inf: no probability mass) and -delta
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const int i = i_wave0 + 32 * qb + ql;
+    const bool ok = i < d.Sq;
+    const long off = b * d.q_sb + hq * d.q_sh + (long)i * d.q_ss;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       u32x4 x = {0, 0, 0, 0}, y = {0, 0, 0, 0};
-      if (row_ok) {
+      if (ok) {
         x = *(const u32x4*)((const uint16_t*)a.q + off + 16 * ks + 8 * g);
         y = *(const u32x4*)((const uint16_t*)a.d_o + off + 16 * ks + 8 * g);
       }
-      qf[ks] = __builtin_bit_cast(bf16x8, x);
-      gf[ks] = __builtin_bit_cast(bf16x8, y);
+      qf[qb][ks] = __builtin_bit_cast(bf16x8, x);
+      gf[qb][ks] = __builtin_bit_cast(bf16x8, y);
+    }
+    l2[qb] = INFINITY;
+    nd[qb] = 0.f;
+    if (ok) {
+      const long slot = (((long)b * d.Hq + hq) * a.sq_pad + (i & ~31)) * 2 + (i & 31);
+      l2[qb] = a.stats[slot];
+      nd[qb] = a.stats[slot + 32];
     }
   }
-  const long row = ((long)b * d.Hq + hq) * d.Sq + i_lane;
-  float lse2 = INFINITY, delta = 0.f;       // +inf makes p = exp2(-inf) = 0 for dead rows
-  if (row_ok) {
-    const long slot = (((long)b * d.Hq + hq) * a.sq_pad + (i_lane & ~31)) * 2 + (i_lane & 31);
-    lse2 = a.stats[slot];
-    delta = -a.stats[slot + 32];
+  // Finish these loads (and move the operands into the accumulation registers) before the tile
+  // copies start: the copies are not counted by the compiler, so nothing may wait on memory later.
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      asm volatile("" : "+a"(qf[qb][ks]));
+      asm volatile("" : "+a"(gf[qb][ks]));
+    }
+    asm volatile("" : "+v"(l2[qb]), "+v"(nd[qb]));
   }
   const float c2 = d.scale * LOG2E;
 
-  const uint16_t* kbase = (const uint16_t*)a.k + b * d.kv_sb + hk * d.kv_sh;
-  const uint16_t* vbase = (const uint16_t*)a.v + b * d.kv_sb + hk * d.kv_sh;
-  const int ld_row = tid / CPR, ld_col = (tid % CPR) * 8;
+  // ---- tiles this workgroup needs (media mask: tiles visible to none of its rows are skipped)
   const int i_wg0 = qt * QM, i_wg1 = min(d.Sq, i_wg0 + QM) - 1;
-  auto next_tile = [&](int t) -> int {
-    if (a.mask.allow)
-      while (t < t_end && mask_rect(a.mask, b, i_wg0, i_wg1, t * QN, min(d.Skv, t * QN + QN) - 1) == 0) ++t;
-    return t;
+  auto tile_needed = [&](int t) __attribute__((always_inline)) -> bool {
+    if (!GENERAL || !a.mask.allow) return true;
+    return mask_rect(a.mask, b, i_wg0, i_wg1, t * TN, min(d.Skv, t * TN + TN) - 1) != 0;
   };
-  u32x4 kreg[NPASS], vreg[NPASS];
-  auto load_tile = [&](int t) {
-#pragma unroll
-    for (int p = 0; p < NPASS; ++p) {
-      const int j = t * QN + p * RPP + ld_row;
-      u32x4 zk = {0, 0, 0, 0}, zv = {0, 0, 0, 0};
-      if (j < d.Skv) {
-        zk = *(const u32x4*)(kbase + (long)j * d.kv_ss + ld_col);
-        zv = *(const u32x4*)(vbase + (long)j * d.kv_ss + ld_col);
-      }
-      kreg[p] = zk;
-      vreg[p] = zv;
-    }
+  auto next_tile = [&](int t) __attribute__((always_inline)) -> int {
+    while (t < t_end && !tile_needed(t)) ++t;
+    return min(t, t_end);
   };
-  auto store_tile = [&](int stage) {
-    char* ks = smem + stage * SM::STAGE;
-    char* vs = ks + SM::K_BYTES;
-#pragma unroll
-    for (int p = 0; p < NPASS; ++p) {
-      const int r = p * RPP + ld_row;
-      *(u32x4*)(ks + ilv_off<D>(ld_row, p * RPP, ld_col)) = kreg[p];
-      *(u32x4*)(vs + r * SM::P + ld_col * 2) = vreg[p];
-    }
-  };
-
-  f32x16 dq[DB];
-#pragma unroll
-  for (int i = 0; i < DB; ++i) dq[i] = zero16();
-
-  int cur = next_tile(t_begin);
-  if (cur < t_end) { load_tile(cur); store_tile(0); }
-  __syncthreads();
-  int stage = 0;
-  while (cur < t_end) {
-    const int nxt = next_tile(cur + 1);
-    if (nxt < t_end) load_tile(nxt);
-    const char* ks_ = smem + stage * SM::STAGE;
-    const char* vs_ = ks_ + SM::K_BYTES;
-    const int j0 = cur * QN;
-    int cls = 1;
-    if (a.mask.allow)
-      cls = mask_rect(a.mask, b, i_wave0, min(d.Sq - 1, i_wave0 + 31), j0, min(d.Skv, j0 + QN) - 1);
-    if (i_wave0 >= d.Sq) cls = 0;
-    if (cls != 0) {
-      f32x16 sacc[2], pacc[2];
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        sacc[kb] = zero16();
-        pacc[kb] = zero16();
-        const char* vrow = vs_ + (kb * 32 + ql) * SM::P + g * 16;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          sacc[kb] = mfma32(*(const bf16x8*)(ks_ + ilv_off<D>(ql, kb * 32, 16 * ks + 8 * g)), qf[ks], sacc[kb]);
-          pacc[kb] = mfma32(*(const bf16x8*)(vrow + ks * 32), gf[ks], pacc[kb]);
-        }
-      }
-      const bool need_mask = (j0 + QN > d.Skv) || cls == 2;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          float p = __builtin_amdgcn_exp2f(fmaf(sacc[kb][v], c2, -lse2));
-          if (need_mask) {
-            const int j = j0 + kb * 32 + 8 * (v / 4) + 4 * g + (v % 4);
-            bool ok = j < d.Skv;
-            if (ok && cls == 2) ok = row_ok && mask_elem(a.mask, b, i_lane, j);
-            if (!ok) p = 0.f;
-          }
-          sacc[kb][v] = p * (pacc[kb][v] - delta);      // dS^T
-        }
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const bf16x8 sf = cvt_operand(sacc[t >> 1], 8 * (t & 1));
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const bf16x8 kt = load_tr_operand_ilv<D>(ks_, 16 * t, 32 * db, lane);
-          dq[db] = mfma32(kt, sf, dq[db]);
-        }
-      }
-    }
-    if (nxt < t_end) store_tile(stage ^ 1);
-    __syncthreads();
-    stage ^= 1;
-    cur = nxt;
+  int cursor = next_tile(t_begin);                 // next tile to issue
+  int nt = max(t_end - t_begin, 0);                // number of tiles this workgroup performs
+  if (GENERAL && a.mask.allow) {
+    nt = 0;
+    for (int t = cursor; t < t_end; t = next_tile(t + 1)) ++nt;
   }
-  if (!row_ok) return;
-  float* out = a.dq_accum + row * D;
+
+  // ---- tile copies.  Group w of a tile (logical rows 4 j + w, j = 0..15) is contiguous in LDS:
+  // RUN slots of 16 bytes.  Wave w copies group w of the K tile and of the V tile, each with NCR
+  // wave-level copies of 64 slots (the last one re-covers the tail of the previous so that no copy
+  // crosses the group); lane l of a copy starting at slot a fills slot a + l = (row (a + l) / SPR
+  // of the group, chunk (a + l) % SPR; the pad chunk re-reads the last one).
+  const char* const k0 = (const char*)a.k + (b * d.kv_sb + hk * d.kv_sh) * 2;
+  const char* const v0 = (const char*)a.v + (b * d.kv_sb + hk * d.kv_sh) * 2;
+  const unsigned row_bytes = (unsigned)(d.kv_ss * 2);
+  auto run_start = [&](int c) __attribute__((always_inline)) -> int { return c + 1 < NCR ? 64 * c : SM::RUN - 64; };
+  unsigned cp_off[NCR];
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
+  for (int c = 0; c < NCR; ++c) {
+    const int sl = run_start(c) + lane;
+    cp_off[c] = (unsigned)(4 * (sl / SM::SPR)) * row_bytes + (unsigned)min(sl % SM::SPR, CPR - 1) * 16;
+  }
+  auto issue_tile = [&](int t, char* st) __attribute__((always_inline)) {
+    const long tile = (long)t * TN * row_bytes;
+    const int rows = min(TN, d.Skv - t * TN);
+    char* const kdst = st + wave * SM::GS;
+    char* const vdst = kdst + SM::TILE;
+    if (!GENERAL || rows == TN) {
+      const char* kb = k0 + tile + (long)wave * row_bytes;     // this wave's first row: tile row w
+      const char* vb = v0 + tile + (long)wave * row_bytes;
 #pragma unroll
-    for (int v = 0; v < 16; ++v)
-      unsafeAtomicAdd(out + 32 * db + 8 * (v / 4) + 4 * g + (v % 4), dq[db][v] * d.scale);
+      for (int c = 0; c < NCR; ++c) {
+        dma16s(kb, cp_off[c], kdst + run_start(c) * 16);
+        dma16s(vb, cp_off[c], vdst + run_start(c) * 16);
+      }
+    } else {                                       // ragged last tile: clamp the rows
+#pragma unroll
+      for (int c = 0; c < NCR; ++c) {
+        const int sl = run_start(c) + lane;
+        const unsigned r = (unsigned)min(4 * (sl / SM::SPR) + wave, rows - 1);
+        const unsigned off = r * row_bytes + (unsigned)min(sl % SM::SPR, CPR - 1) * 16;
+        dma16s(k0 + tile, off, kdst + run_start(c) * 16);
+        dma16s(v0 + tile, off, vdst + run_start(c) * 16);
+      }
+    }
+  };
+  constexpr int NDMA = 2 * NCR;                    // copies per wave and tile
+
+  f32x16 dq[QB][DB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+    for (int i = 0; i < DB; ++i) { dq[qb][i] = zero16(); asm volatile("" : "+a"(dq[qb][i])); }
+
+  // ---- building blocks, all on one 32-key half hb of the tile at st ---------------------------
+  // S^T = K Q^T and dP^T = V dO^T: lane = query column, registers = keys.  The LDS operands of a
+  // k-step are fetched while the matrix instructions of the previous one run; per_group(ks) is
+  // vector work to be overlapped.
+  auto score = [&](const char* __restrict__ st, int hb, f32x16 (&s)[QB], f32x16 (&p)[QB],
+                   auto&& per_group) __attribute__((always_inline)) {
+    const char* krow = st + tile_off<D>(ql, 32 * hb, 16 * g);
+    const char* vrow = krow + SM::TILE;
+    bf16x8 ka[2], va[2];                           // two operand sets, used alternately
+    ka[0] = *(const bf16x8*)krow;
+    va[0] = *(const bf16x8*)vrow;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int cu = ks & 1, nx = cu ^ 1;
+      if (ks + 1 < KS) {
+        ka[nx] = *(const bf16x8*)(krow + (ks + 1) * 32);
+        va[nx] = *(const bf16x8*)(vrow + (ks + 1) * 32);
+      }
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        if (ks == 0) mfma_first(s[qb], ka[cu], qf[qb][ks]);
+        else mfma_next(s[qb], ka[cu], qf[qb][ks]);
+      }
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        if (ks == 0) mfma_first(p[qb], va[cu], gf[qb][ks]);
+        else mfma_next(p[qb], va[cu], gf[qb][ks]);
+      }
+      per_group(ks);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    asm volatile("s_nop 7" ::: "memory");          // the last results settle before anything reads them
+  };
+  auto nothing = [](int) __attribute__((always_inline)) {};
+  // key tail and masked elements of a half's scores -> -inf (wave-uniform decision, rarely taken)
+  auto mask_scores = [&](int t, int hb, f32x16 (&s)[QB]) __attribute__((always_inline)) {
+    if (!GENERAL) return;
+    const int j0 = t * TN + 32 * hb;
+    int cls = 1;
+    if (a.mask.allow && i_wave0 < d.Sq)
+      cls = mask_rect(a.mask, b, i_wave0, min(d.Sq, i_wave0 + 32 * QB) - 1, min(j0, d.Skv - 1),
+                      min(d.Skv, j0 + 32) - 1);
+    if (cls == 1 && j0 + 32 <= d.Skv) return;
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int j = j0 + 8 * (v / 4) + 4 * g + (v % 4), i = i_wave0 + 32 * qb + ql;
+        bool ok = j < d.Skv;
+        if (ok && cls != 1) ok = i < d.Sq && mask_elem(a.mask, b, i, j);
+        if (!ok) s[qb][v] = -INFINITY;
+      }
+  };
+  // Conversion of scores into the dS operands, element x of a half (x = 0..31: query block
+  // qb = x / 16, register v = x % 16): p = exp2(s c2 - L2), dS = p (dP - delta), packed in pairs
+  // as bf16 into word (v % 8) / 2 of operand v / 8 of the query block.
+  struct Carry { float ds; };
+  auto conv_elem = [&](int x, Carry& cy, const f32x16 (&s)[QB], const f32x16 (&p)[QB],
+                       u32x4 (&dsw)[QB][2]) __attribute__((always_inline)) {
+    const int qb = x / 16, v = x % 16;
+    const float pr = __builtin_amdgcn_exp2f(fmaf(s[qb][v], c2, -l2[qb]));
+    const float ds = pr * (p[qb][v] + nd[qb]);
+    if (v % 2 == 0) { cy.ds = ds; return; }
+    dsw[qb][v / 8][(v % 8) / 2] = pack2_bf16(cy.ds, ds);
+  };
+  auto convert = [&](const f32x16 (&s)[QB], const f32x16 (&p)[QB], u32x4 (&dsw)[QB][2]) __attribute__((always_inline)) {
+    Carry cy;
+#pragma unroll
+    for (int x = 0; x < 32; ++x) conv_elem(x, cy, s, p, dsw);
+  };
+  // dQ^T += K^T dS^T over the 32 keys of a half (two k-steps of 16 keys)
+  auto contract = [&](const char* __restrict__ st, int hb, const u32x4 (&dsw)[QB][2]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const bf16x8 kt = tile_tr_operand<D>(st, 32 * hb + 16 * t2, 32 * db, lane);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) mfma_acc(dq[qb][db], kt, __builtin_bit_cast(bf16x8, dsw[qb][t2]));
+      }
+  };
+  // contract(half h) on the matrix core together with the first XE conversions of half h+1 on
+  // the vector ALU; the transposed operand of a pair of matrix instructions is fetched one pair
+  // ahead, and nothing is scheduled across the units.
+  auto contract_convert = [&](const char* __restrict__ st, int hb, const u32x4 (&dsi)[QB][2],
+                              const f32x16 (&s)[QB], const f32x16 (&p)[QB], u32x4 (&dso)[QB][2],
+                              Carry& cy) __attribute__((always_inline)) {
+    constexpr int NM = 2 * DB * QB;                // matrix instructions
+    bf16x8 kt[2];
+    kt[0] = tile_tr_operand<D>(st, 32 * hb, 0, lane);
+#pragma unroll
+    for (int m = 0; m < NM; ++m) {
+      const int c = m / QB, t2 = c / DB, db = c % DB, qb = m % QB, cu = c & 1;
+      if (qb == 0 && c + 1 < 2 * DB)
+        kt[cu ^ 1] = tile_tr_operand<D>(st, 32 * hb + 16 * ((c + 1) / DB), 32 * ((c + 1) % DB), lane);
+      mfma_acc(dq[qb][db], kt[cu], __builtin_bit_cast(bf16x8, dsi[qb][t2]));
+#pragma unroll
+      for (int x = m * XE / NM; x < (m + 1) * XE / NM; ++x) conv_elem(x, cy, s, p, dso);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  // score(half h+2) together with the remaining conversions of half h+1
+  auto score_convert = [&](const char* __restrict__ st, int hb, f32x16 (&s_new)[QB], f32x16 (&p_new)[QB],
+                           const f32x16 (&s)[QB], const f32x16 (&p)[QB], u32x4 (&dso)[QB][2],
+                           Carry& cy) __attribute__((always_inline)) {
+    score(st, hb, s_new, p_new, [&](int ks) __attribute__((always_inline)) {
+#pragma unroll
+      for (int x = XE + ks * (32 - XE) / KS; x < XE + (ks + 1) * (32 - XE) / KS; ++x) conv_elem(x, cy, s, p, dso);
+    });
+  };
+
+  // ---- pipeline.  Tile number q of the sequence lives in ring stage q % 4.  Per tile T (halves
+  // 2T and 2T+1): contract 2T | convert 2T+1 | score 2T+2, then contract 2T+1 | convert 2T+2, the
+  // one barrier of the tile -- every wave is done with tile T, whose stage takes tile T + 4, and
+  // tile T + 2, issued two tiles ago, has landed -- and score 2T+3.
+  int e[NSTG + 1];                                 // tile ids of tiles T .. T + 4 (static indexing only)
+#pragma unroll
+  for (int q = 0; q <= NSTG; ++q) e[q] = t_end;
+#pragma unroll
+  for (int q = 0; q < NSTG; ++q) {
+    if (q < nt) {
+      e[q] = cursor;
+      issue_tile(cursor, smem + q * SM::STAGE);
+      cursor = next_tile(cursor + 1);
+    }
+  }
+  wait_vmcnt<0>();
+  __syncthreads();
+  auto stage = [&](int q) __attribute__((always_inline)) -> char* { return smem + (q % NSTG) * SM::STAGE; };
+  auto mid = [&](auto all_in_flight, bool issue, char* st_copy) __attribute__((always_inline)) {
+    // all_in_flight: tiles T + 2 and T + 3 were both issued, so leaving one tile's copies
+    // outstanding still guarantees that tile T + 2 has landed
+    if constexpr (decltype(all_in_flight)::value) wait_vmcnt<NDMA>();
+    else wait_vmcnt<0>();
+    wg_barrier();
+    if (issue) {
+      e[4] = cursor;
+      issue_tile(cursor, st_copy);
+      cursor = next_tile(cursor + 1);
+    }
+  };
+
+  f32x16 s0[QB], p0[QB], s1[QB], p1[QB];           // scores of even / odd halves
+  u32x4 ds0[QB][2] = {}, ds1[QB][2] = {};          // packed dS operands of even / odd halves
+  Carry cy;
+  if (nt > 0) {
+    score(smem, 0, s0, p0, nothing);
+    mask_scores(e[0], 0, s0);
+    convert(s0, p0, ds0);
+    score(smem, 1, s1, p1, nothing);
+    mask_scores(e[0], 1, s1);
+  }
+  int T = 0;
+  for (; T + 4 < nt; ++T) {                        // full tiles: tile T + 1 is scored, tile T + 4 issued
+    contract_convert(stage(T), 0, ds0, s1, p1, ds1, cy);
+    score_convert(stage(T + 1), 0, s0, p0, s1, p1, ds1, cy);
+    mask_scores(e[1], 0, s0);
+    contract_convert(stage(T), 1, ds1, s0, p0, ds0, cy);
+    mid(std::true_type{}, true, stage(T));
+    score_convert(stage(T + 1), 1, s1, p1, s0, p0, ds0, cy);
+    mask_scores(e[1], 1, s1);
+    e[0] = e[1]; e[1] = e[2]; e[2] = e[3]; e[3] = e[4];
+  }
+  for (; T < nt; ++T) {                            // the last (at most four) tiles
+    const bool more = T + 1 < nt;
+    contract(stage(T), 0, ds0);
+    convert(s1, p1, ds1);
+    if (more) { score(stage(T + 1), 0, s0, p0, nothing); mask_scores(e[1], 0, s0); }
+    contract(stage(T), 1, ds1);
+    if (more) convert(s0, p0, ds0);
+    mid(std::false_type{}, T + 4 < nt, stage(T));
+    if (more) { score(stage(T + 1), 1, s1, p1, nothing); mask_scores(e[1], 1, s1); }
+    e[0] = e[1]; e[1] = e[2]; e[2] = e[3]; e[3] = e[4];
+  }
+
+  // ---- dQ += scale * acc (transposed accumulators: lane = query row).  The last matrix
+  // instructions must have retired before their registers are read.
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const int i = i_wave0 + 32 * qb + ql;
+    if (i >= d.Sq) continue;
+    float* out = a.dq_accum + (((long)b * d.Hq + hq) * d.Sq + i) * D;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        unsafeAtomicAdd(out + 32 * db + 8 * (v / 4) + 4 * g + (v % 4), dq[qb][db][v] * d.scale);
+  }
 }
 
 template <typename F>
@@ -197,14 +417,24 @@ hipError_t set_smem_once(F* fn, int bytes, bool* done) {
   return e;
 }
 
+template <int D, bool GENERAL>
+hipError_t launch(const BwdArgs& a, long grid, hipStream_t s) {
+  static bool once = false;
+  hipError_t e = set_smem_once(bwd_dq_bf16_kernel<D, GENERAL>, DqSmem<D>::TOTAL, &once);
+  if (e != hipSuccess) return e;
+  bwd_dq_bf16_kernel<D, GENERAL><<<(unsigned)grid, 256, DqSmem<D>::TOTAL, s>>>(a);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 int bwd_bf16_pick_split(const Dims& d, int n_cu) {
+  // one workgroup per CU; split the KV axis until the grid covers the chip
   const long base = (long)d.B * d.Hq * ((d.Sq + QM - 1) / QM);
-  const int n_tiles = (d.Skv + QN - 1) / QN;
-  long want = (2L * n_cu + base - 1) / base;
+  const int n_tiles = (d.Skv + TN - 1) / TN;
+  long want = (n_cu + base - 1) / base;
   if (want < 1) want = 1;
-  long cap = n_tiles / 8;
+  long cap = n_tiles / 16;                // keep at least 16 tiles (1024 keys) per split
   if (cap < 1) cap = 1;
   if (want > cap) want = cap;
   if (want > 64) want = 64;
@@ -215,18 +445,10 @@ hipError_t launch_bwd_dq_bf16(const BwdArgs& a, hipStream_t s) {
   const Dims& d = a.d;
   const int G = d.Hq / d.Hkv;
   const int n_qt = (d.Sq + QM - 1) / QM;
-  const long grid_q = xcd_grid(d.B * d.Hkv, a.n_split_dq * G * n_qt);
-  hipError_t e;
-  if (d.D == 64) {
-    static bool once = false;
-    if ((e = set_smem_once(bwd_dq_bf16_kernel<64>, DqSmem<64>::TOTAL, &once)) != hipSuccess) return e;
-    bwd_dq_bf16_kernel<64><<<(unsigned)grid_q, 256, DqSmem<64>::TOTAL, s>>>(a);
-  } else {
-    static bool once = false;
-    if ((e = set_smem_once(bwd_dq_bf16_kernel<128>, DqSmem<128>::TOTAL, &once)) != hipSuccess) return e;
-    bwd_dq_bf16_kernel<128><<<(unsigned)grid_q, 256, DqSmem<128>::TOTAL, s>>>(a);
-  }
-  return hipGetLastError();
+  const long grid = xcd_grid(d.B * d.Hkv, a.n_split_dq * G * n_qt);
+  const bool general = a.mask.allow != nullptr || d.Skv % TN != 0;
+  if (d.D == 64) return general ? launch<64, true>(a, grid, s) : launch<64, false>(a, grid, s);
+  return general ? launch<128, true>(a, grid, s) : launch<128, false>(a, grid, s);
 }
 
 hipError_t launch_bwd_bf16(const BwdArgs& a, unsigned stages, hipStream_t s) {
