@@ -58,6 +58,9 @@ def main():
     ap.add_argument("--workload", default="c3_longvideo_256k")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (a reference of known HBM traffic "
+                         "for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures ONE GPU (the kernel on one GPU's K/V share); "
@@ -88,6 +91,12 @@ def main():
         o, lse = loop.forward(q, k, v)
         loop.backward(q, k, v, o, lse, g, dk, dv)
 
+    if args.calib_copy:
+        src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

@@ -32,13 +32,8 @@ constexpr int NWV = 4;                 // waves per workgroup
 constexpr int KN = NWV * 32 * KVB;     // keys per workgroup
 constexpr int KM = 32;                 // query rows per step
 constexpr int NSTG = 4;                // ring stages
-#ifndef LVX_XE
-#define LVX_XE 32
-#endif
-#ifndef LVX_ABL
-#define LVX_ABL 0
-#endif
-constexpr int XE = LVX_XE;             // elements of a step converted during the contraction (the rest during scoring)
+constexpr int XE = 32;                 // elements of a step converted during the contraction (the rest, if any,
+                                       // during scoring; measured: no gain from moving them)
 
 // dK^T / dV^T accumulation: the sixteen 32x32 accumulator blocks of a wave fill the accumulation
 // register file exactly, and only matrix instructions touch them until the epilogue.  The
@@ -192,7 +187,7 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   // S = Q K^T and dP = dO V^T of one step: lane = key column, registers = query rows.  The four
   // LDS operands of a k-step are fetched while the matrix instructions of the previous one run.
   auto score = [&](const char* __restrict__ t, const char* __restrict__ vw, f32x16 (&s)[KVB],
-                   f32x16 (&p)[KVB], auto&& per_group) __attribute__((always_inline)) {
+                   f32x16 (&p)[KVB], auto&& per_unit) __attribute__((always_inline)) {
     // dP starts at -delta of its query row (the statistics hold -delta), so that dP - delta needs
     // no vector instruction
 #pragma unroll
@@ -222,11 +217,13 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
         for (int kb = 0; kb < KVB; ++kb) va[nx][kb] = *(const bf16x8*)(vw + kb * 32 * SM::P + (ks + 1) * 32);
       }
 #pragma unroll
-      for (int kb = 0; kb < KVB; ++kb) s[kb] = mfma32(qa[cu], kf[kb][ks], s[kb]);
-#pragma unroll
-      for (int kb = 0; kb < KVB; ++kb) p[kb] = mfma32(ga[cu], va[cu][kb], p[kb]);
-      per_group(ks);
-      __builtin_amdgcn_sched_barrier(0);
+      for (int j = 0; j < 2 * KVB; ++j) {          // S of both key blocks, then dP
+        const int kb = j % KVB;
+        if (j < KVB) s[kb] = mfma32(qa[cu], kf[kb][ks], s[kb]);
+        else p[kb] = mfma32(ga[cu], va[cu][kb], p[kb]);
+        per_unit(ks * 2 * KVB + j);                // vector work in the shadow of this instruction
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
   };
   auto nothing = [](int) __attribute__((always_inline)) {};
@@ -257,7 +254,6 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   };
   auto conv_elem = [&](int x, const Conv& cv, Carry& cy, const f32x16 (&s)[KVB], const f32x16 (&p)[KVB],
                        u32x4 (&pwo)[KVB][2], u32x4 (&swo)[KVB][2]) __attribute__((always_inline)) {
-    if (LVX_ABL & 1) return;
     const int q4 = x / 8, kb = (x / 4) % 2, e = x % 4, v = 4 * q4 + e;
     const float pr = __builtin_amdgcn_exp2f(fmaf(s[kb][v], c2, -cv.l4[e]));
     const float ds = pr * p[kb][v];                 // p already holds dP - delta
@@ -367,48 +363,31 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   };
   // With XE < 32 the remaining elements of step i + 1 are converted while step i + 2 is scored,
   // which needs a second set of score registers (the two sets alternate between iterations).
-#ifdef LVX_TIMING
-  long tx = 0, tm = 0, ty = 0, tn = 0;
-  const long tk0 = __builtin_readcyclecounter();
-#endif
   auto full_iter = [&](char* st_copy, const char* __restrict__ t0,
                        const char* __restrict__ t1, const char* __restrict__ t2,
                        const char* __restrict__ vw_, const u32x4 (&pfi)[KVB][2],
                        const u32x4 (&sfi)[KVB][2], u32x4 (&pfo)[KVB][2], u32x4 (&sfo)[KVB][2],
                        f32x16 (&s_cv)[KVB], f32x16 (&p_cv)[KVB], f32x16 (&s_sc)[KVB],
                        f32x16 (&p_sc)[KVB]) __attribute__((always_inline)) {
-#ifdef LVX_TIMING
-    const long c0 = __builtin_readcyclecounter();
-#endif
     contract_convert(t0, t1, pfi, sfi, s_cv, p_cv, pfo, sfo);
-#ifdef LVX_TIMING
-    const long c1 = __builtin_readcyclecounter();
-#endif
-    if (!(LVX_ABL & 2)) mid(std::true_type{}, true, st_copy);
-#ifdef LVX_TIMING
-    const long c2c = __builtin_readcyclecounter();
-#endif
+    mid(std::true_type{}, true, st_copy);
     if constexpr (XE == 32) {
       score(t2, vw_, s_sc, p_sc, nothing);
     } else {
-      constexpr int EPG = (32 - XE) / KS;          // elements per k-step group
-      static_assert(XE % 8 == 0 && (32 - XE) % KS == 0, "XE must cut at a four-row boundary");
+      constexpr int NU = 2 * KVB * KS;             // matrix instructions of a score phase
+      static_assert(XE % 8 == 0, "XE must cut at a four-row boundary");
       Conv cv[2];
       Carry cy;
       conv_stats(t1, XE / 8, cv[(XE / 8) & 1]);
-      score(t2, vw_, s_sc, p_sc, [&](int ks) __attribute__((always_inline)) {
+      score(t2, vw_, s_sc, p_sc, [&](int m) __attribute__((always_inline)) {
 #pragma unroll
-        for (int x = XE + ks * EPG; x < XE + (ks + 1) * EPG; ++x) {
+        for (int x = XE + m * (32 - XE) / NU; x < XE + (m + 1) * (32 - XE) / NU; ++x) {
           const int q4 = x / 8;
           if (x % 8 == 0 && q4 + 1 < 4) conv_stats(t1, q4 + 1, cv[(q4 + 1) & 1]);
           conv_elem(x, cv[q4 & 1], cy, s_cv, p_cv, pfo, sfo);
         }
       });
     }
-#ifdef LVX_TIMING
-    const long c3 = __builtin_readcyclecounter();
-    tx += c1 - c0; tm += c2c - c1; ty += c3 - c2c; ++tn;
-#endif
     mask_scores(e[2], s_sc);
     e[0] = e[1]; e[1] = e[2]; e[2] = e[3]; e[3] = e[4];
   };
@@ -432,13 +411,6 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
     e[0] = e[1]; e[1] = e[2]; e[2] = e[3]; e[3] = e[4];
   }
 
-#ifdef LVX_TIMING
-  if (blockIdx.x == 8 && tid == 64) {
-    float* o = a.dq_accum;
-    o[0] = (float)tx / tn; o[1] = (float)tm / tn; o[2] = (float)ty / tn; o[3] = (float)tn;
-    o[4] = (float)(__builtin_readcyclecounter() - tk0);
-  }
-#endif
   // ---- write dK = scale * acc, dV = acc (transposed accumulators: lane = key row).  The last
   // matrix instructions must have retired before their registers are read.
   asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");

@@ -33,7 +33,8 @@ constexpr int NWV = 4;                 // waves per workgroup
 constexpr int QM = NWV * 32 * QB;      // query rows per workgroup
 constexpr int TN = 64;                 // keys per tile (two halves of 32)
 constexpr int NSTG = 4;                // ring stages
-constexpr int XE = 12;                 // elements of a half converted during the contraction (of 32)
+constexpr int PF = 1;                  // LDS operand prefetch distance, in k-steps (operand sets = PF + 1)
+constexpr int XE = 8;                  // elements of a half converted during the contraction (of 32)
 
 // LDS tile of 64 rows x D bf16, rows interleaved: logical row r lives in group r % 4 at row r / 4;
 // a group is 16 rows of pitch (D + 8) * 2 bytes plus 64 bytes, which puts the four groups 64 bytes
@@ -219,34 +220,38 @@ bwd_dq_bf16_kernel(BwdArgs a) {
 
   // ---- building blocks, all on one 32-key half hb of the tile at st ---------------------------
   // S^T = K Q^T and dP^T = V dO^T: lane = query column, registers = keys.  The LDS operands of a
-  // k-step are fetched while the matrix instructions of the previous one run; per_group(ks) is
-  // vector work to be overlapped.
+  // k-step are fetched while the matrix instructions of the previous one run; per_unit(m) is
+  // vector work issued right after matrix instruction m (0 .. 4 KS - 1), to run in its shadow.
   auto score = [&](const char* __restrict__ st, int hb, f32x16 (&s)[QB], f32x16 (&p)[QB],
-                   auto&& per_group) __attribute__((always_inline)) {
+                   auto&& per_unit) __attribute__((always_inline)) {
     const char* krow = st + tile_off<D>(ql, 32 * hb, 16 * g);
     const char* vrow = krow + SM::TILE;
-    bf16x8 ka[2], va[2];                           // two operand sets, used alternately
-    ka[0] = *(const bf16x8*)krow;
-    va[0] = *(const bf16x8*)vrow;
+    bf16x8 ka[PF + 1], va[PF + 1];                 // operand sets, used in rotation
+#pragma unroll
+    for (int i = 0; i < PF; ++i) {
+      ka[i] = *(const bf16x8*)(krow + i * 32);
+      va[i] = *(const bf16x8*)(vrow + i * 32);
+    }
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      const int cu = ks & 1, nx = cu ^ 1;
-      if (ks + 1 < KS) {
-        ka[nx] = *(const bf16x8*)(krow + (ks + 1) * 32);
-        va[nx] = *(const bf16x8*)(vrow + (ks + 1) * 32);
+      const int cu = ks % (PF + 1), nx = (ks + PF) % (PF + 1);
+      if (ks + PF < KS) {
+        ka[nx] = *(const bf16x8*)(krow + (ks + PF) * 32);
+        va[nx] = *(const bf16x8*)(vrow + (ks + PF) * 32);
       }
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        if (ks == 0) mfma_first(s[qb], ka[cu], qf[qb][ks]);
-        else mfma_next(s[qb], ka[cu], qf[qb][ks]);
+      for (int j = 0; j < 2 * QB; ++j) {           // S^T of both query blocks, then dP^T
+        const int qb = j % QB;
+        if (j < QB) {
+          if (ks == 0) mfma_first(s[qb], ka[cu], qf[qb][ks]);
+          else mfma_next(s[qb], ka[cu], qf[qb][ks]);
+        } else {
+          if (ks == 0) mfma_first(p[qb], va[cu], gf[qb][ks]);
+          else mfma_next(p[qb], va[cu], gf[qb][ks]);
+        }
+        per_unit(ks * 2 * QB + j);                 // vector work in the shadow of this instruction
+        __builtin_amdgcn_sched_barrier(0);
       }
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        if (ks == 0) mfma_first(p[qb], va[cu], gf[qb][ks]);
-        else mfma_next(p[qb], va[cu], gf[qb][ks]);
-      }
-      per_group(ks);
-      __builtin_amdgcn_sched_barrier(0);
     }
     asm volatile("s_nop 7" ::: "memory");          // the last results settle before anything reads them
   };
@@ -306,13 +311,14 @@ bwd_dq_bf16_kernel(BwdArgs a) {
                               const f32x16 (&s)[QB], const f32x16 (&p)[QB], u32x4 (&dso)[QB][2],
                               Carry& cy) __attribute__((always_inline)) {
     constexpr int NM = 2 * DB * QB;                // matrix instructions
-    bf16x8 kt[2];
-    kt[0] = tile_tr_operand<D>(st, 32 * hb, 0, lane);
+    bf16x8 kt[PF + 1];
+#pragma unroll
+    for (int i = 0; i < PF; ++i) kt[i] = tile_tr_operand<D>(st, 32 * hb + 16 * (i / DB), 32 * (i % DB), lane);
 #pragma unroll
     for (int m = 0; m < NM; ++m) {
-      const int c = m / QB, t2 = c / DB, db = c % DB, qb = m % QB, cu = c & 1;
-      if (qb == 0 && c + 1 < 2 * DB)
-        kt[cu ^ 1] = tile_tr_operand<D>(st, 32 * hb + 16 * ((c + 1) / DB), 32 * ((c + 1) % DB), lane);
+      const int c = m / QB, t2 = c / DB, db = c % DB, qb = m % QB, cu = c % (PF + 1);
+      if (qb == 0 && c + PF < 2 * DB)
+        kt[(c + PF) % (PF + 1)] = tile_tr_operand<D>(st, 32 * hb + 16 * ((c + PF) / DB), 32 * ((c + PF) % DB), lane);
       mfma_acc(dq[qb][db], kt[cu], __builtin_bit_cast(bf16x8, dsi[qb][t2]));
 #pragma unroll
       for (int x = m * XE / NM; x < (m + 1) * XE / NM; ++x) conv_elem(x, cy, s, p, dso);
@@ -323,9 +329,10 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   auto score_convert = [&](const char* __restrict__ st, int hb, f32x16 (&s_new)[QB], f32x16 (&p_new)[QB],
                            const f32x16 (&s)[QB], const f32x16 (&p)[QB], u32x4 (&dso)[QB][2],
                            Carry& cy) __attribute__((always_inline)) {
-    score(st, hb, s_new, p_new, [&](int ks) __attribute__((always_inline)) {
+    constexpr int NU = 2 * QB * KS;                // matrix instructions of a score phase
+    score(st, hb, s_new, p_new, [&](int m) __attribute__((always_inline)) {
 #pragma unroll
-      for (int x = XE + ks * (32 - XE) / KS; x < XE + (ks + 1) * (32 - XE) / KS; ++x) conv_elem(x, cy, s, p, dso);
+      for (int x = XE + m * (32 - XE) / NU; x < XE + (m + 1) * (32 - XE) / NU; ++x) conv_elem(x, cy, s, p, dso);
     });
   };
 

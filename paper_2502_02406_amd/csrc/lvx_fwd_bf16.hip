@@ -125,7 +125,7 @@ fwd_bf16_kernel(FwdArgs a) {
       for (int i = 0; i < L; ++i) {
         int row, col, lds; bool is_k;
         copy_slot(i, row, col, lds, is_k);           // lds, is_k: wave-uniform
-        dma16((is_k ? kt : vt) + cp_off[i], st + lds);
+        dma16s(is_k ? kt : vt, cp_off[i], st + lds);
       }
     } else {                                          // ragged last tile: re-read its last row
       asm volatile("" ::: "memory");
@@ -133,7 +133,7 @@ fwd_bf16_kernel(FwdArgs a) {
       for (int i = 0; i < L; ++i) {
         int row, col, lds; bool is_k;
         copy_slot(i, row, col, lds, is_k);
-        dma16((is_k ? kt : vt) + (unsigned)(min(row, rows - 1) * row_bytes + col), st + lds);
+        dma16s(is_k ? kt : vt, (unsigned)(min(row, rows - 1) * row_bytes + col), st + lds);
       }
     }
   };
