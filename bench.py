@@ -25,6 +25,12 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per launch (read + written) of the three matrix kernels on one K/V block of the bench
+# workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file scaled by what the same
+# counters read for a plain copy of known size (profiles/bench_c3_longvideo_256k_hbm_traffic.md).
+# Counters cannot be read from inside this process, so the figures are carried here.
+MEASURED_HBM_BYTES = {"bwd_dkdv": int((262.4 + 193.9) * 2**20), "bwd_dq": int((160.8 + 128.0) * 2**20),
+                      "fwd": int((144.5 + 32.3) * 2**20)}
 
 
 def cpu_baseline(w, seed):
@@ -151,7 +157,8 @@ def main():
     dom = max(("bwd_dkdv", "bwd_dq", "fwd"), key=lambda n: kernels[n]["ms"])
     roofline = {"bound": "mfma", "kernel": dom, "achieved": kernels[dom]["tflops"],
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": kernels[dom]["tflops"] / PEAK_BF16_TFLOPS, "traffic": None,
+                "frac": kernels[dom]["tflops"] / PEAK_BF16_TFLOPS,
+                "traffic": MEASURED_HBM_BYTES[dom] if args.workload == "c3_longvideo_256k" else None,
                 "launch_ms": kernels[dom]["ms"],
                 "note": "flops = the matrix products this kernel itself performs per launch "
                         "(one K/V block of the workload)"}

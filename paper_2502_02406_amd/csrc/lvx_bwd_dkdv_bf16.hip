@@ -51,7 +51,10 @@ template <int D> struct DkvSmem {
   static constexpr int STAT_OFF = ILV_ROWS * P;     // 32 x L log2(e), then 32 x delta
   static constexpr int STAGE = STAT_OFF + 256;      // [Q; dO] as one 64-row interleaved tile + statistics
   static constexpr int V_BYTES = KN * P;            // V rows of the workgroup, resident
-  static constexpr int TOTAL = NSTG * STAGE + V_BYTES;
+  static constexpr int RING = NSTG * STAGE + V_BYTES;
+  static constexpr int BITS_BYTES = 2048;           // visibility bits of up to 16320 steps (media mask only)
+  static constexpr int WIN_BYTES = 2048;            // window of the mask bitmap (media mask only)
+  static constexpr int TOTAL = RING + BITS_BYTES + WIN_BYTES;
   static_assert(RUN >= 64, "a run must hold at least one full copy");
 };
 
@@ -74,6 +77,81 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int j_wg0 = hw.item * KN;
   const int j_wave0 = j_wg0 + wave * 32 * KVB;
+
+  // ---- query steps: the G heads of the group, KM rows at a time.  With a media mask, steps whose
+  // rows see none of this workgroup's keys are skipped: the window of the bitmap that the
+  // workgroup can touch is copied to LDS and the visibility of the spH row tiles (the same for
+  // every head) is worked out by all threads at once into a bit array.
+  const int spH = (d.Sq + KM - 1) / KM;
+  const int n_all = G * spH;
+  const int j_wg1 = min(d.Skv, j_wg0 + KN) - 1;
+  MaskDev mk = a.mask;
+  unsigned* const bits = (unsigned*)(smem + SM::RING);
+  bool have_bits = false;
+  int per_head = spH;
+  if (GENERAL && mk.allow) {
+    mk = mask_to_lds(a.mask, b, 0, (d.Sq - 1) / mk.q_chunk, j_wg0 / mk.kv_block, j_wg1 / mk.kv_block,
+                     (uint8_t*)smem + SM::RING + SM::BITS_BYTES, SM::WIN_BYTES, tid, 256);
+    if (spH <= (SM::BITS_BYTES - 16) * 8) {
+      have_bits = true;
+      per_head = build_bits(bits, spH, tid, 256, [&](int t) {
+        return mask_rect(mk, b, t * KM, min(d.Sq, t * KM + KM) - 1, j_wg0, j_wg1) != 0;
+      });
+    }
+  }
+  // cursor over the steps in issue order: step id s = head * spH + tile, kept with its head and
+  // first row so that no division is needed per step
+  struct Cursor { int s, h, i0; };
+  auto step_needed = [&](const Cursor& c) __attribute__((always_inline)) -> bool {
+    if (!GENERAL || !mk.allow) return true;
+    return mask_rect(mk, b, c.i0, min(d.Sq, c.i0 + KM) - 1, j_wg0, j_wg1) != 0;
+  };
+  auto advance = [&](Cursor& c) __attribute__((always_inline)) {      // to the next needed step (or the end)
+    if (GENERAL && have_bits) {
+      int t = next_bit(bits, c.i0 / KM + 1, spH);
+      if (t >= spH) { ++c.h; t = next_bit(bits, 0, spH); }
+      c.i0 = t * KM;
+      c.s = (c.h < G && t < spH) ? c.h * spH + t : n_all;
+      return;
+    }
+    do {
+      ++c.s;
+      c.i0 += KM;
+      if (c.i0 >= d.Sq) { c.i0 = 0; ++c.h; }
+    } while (c.s < n_all && !step_needed(c));
+    if (GENERAL) {                                 // wave-uniform (the bitmap is read through the vector path)
+      c.s = __builtin_amdgcn_readfirstlane(c.s);
+      c.h = __builtin_amdgcn_readfirstlane(c.h);
+      c.i0 = __builtin_amdgcn_readfirstlane(c.i0);
+    }
+  };
+  Cursor cursor = {0, 0, 0};
+  if (GENERAL && have_bits) {
+    const int t = next_bit(bits, 0, spH);
+    cursor.i0 = t * KM;
+    cursor.s = t < spH ? t : n_all;
+  } else if (!step_needed(cursor)) {
+    advance(cursor);
+  }
+  int n = n_all;                                   // number of steps this workgroup performs
+  if (GENERAL && mk.allow) {
+    n = G * per_head;
+    if (!have_bits) {
+      n = 0;
+      for (Cursor c = cursor; c.s < n_all; advance(c)) ++n;
+    }
+  }
+  if (GENERAL && n == 0) {                         // keys that no query sees: dK = dV = 0, nothing to read
+    const u32x4 z = {0, 0, 0, 0};
+    for (int c = tid; c < KN * CPR; c += 256) {
+      const int j = j_wg0 + c / CPR, col = (c % CPR) * 8;
+      if (j >= d.Skv) continue;
+      const long off = b * d.kv_sb + hk * d.kv_sh + (long)j * d.kv_ss + col;
+      *(u32x4*)((uint16_t*)a.dk + off) = z;
+      *(u32x4*)((uint16_t*)a.dv + off) = z;
+    }
+    return;
+  }
 
   // ---- K operands of this wave's keys: lane holds key j_wave0 + 32 kb + kl, columns 16 ks + 8 g ..
   bf16x8 kf[KVB][KS];
@@ -105,32 +183,6 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(kf[kb][ks]));
   const float c2 = d.scale * LOG2E;
 
-  // ---- query steps: the G heads of the group, KM rows at a time; fully masked steps are skipped
-  const int spH = (d.Sq + KM - 1) / KM;
-  const int n_all = G * spH;
-  const int j_wg1 = min(d.Skv, j_wg0 + KN) - 1;
-  // cursor over the steps in issue order: step id s = head * spH + tile, kept with its head and
-  // first row so that no division is needed per step
-  struct Cursor { int s, h, i0; };
-  auto step_needed = [&](const Cursor& c) __attribute__((always_inline)) -> bool {
-    if (!GENERAL || !a.mask.allow) return true;
-    return mask_rect(a.mask, b, c.i0, min(d.Sq, c.i0 + KM) - 1, j_wg0, j_wg1) != 0;
-  };
-  auto advance = [&](Cursor& c) __attribute__((always_inline)) {      // to the next needed step (or the end)
-    do {
-      ++c.s;
-      c.i0 += KM;
-      if (c.i0 >= d.Sq) { c.i0 = 0; ++c.h; }
-    } while (c.s < n_all && !step_needed(c));
-  };
-  Cursor cursor = {0, 0, 0};
-  if (!step_needed(cursor)) advance(cursor);
-  int n = n_all;                                   // number of steps this workgroup performs
-  if (GENERAL && a.mask.allow) {
-    n = 0;
-    for (Cursor c = cursor; c.s < n_all; advance(c)) ++n;
-  }
-
   // ---- tile copies.  In the interleaved tile the logical rows 4 j + w (j = 0..7) of Q occupy the
   // 8 consecutive physical rows 20 w .. 20 w + 7, and those of dO the next 8: a "run" of 8 SPR
   // 16-byte slots.  Wave w copies the two runs of group w, each with NCR wave-level copies of 64
@@ -151,7 +203,9 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
     cp_off[c] = (unsigned)(4 * (sl / SM::SPR)) * row_bytes + (unsigned)min(sl % SM::SPR, CPR - 1) * 16;
   }
   auto issue_tile = [&](const Cursor& c, char* st) __attribute__((always_inline)) {
-    const int hq = hk * G + c.h, i0 = c.i0;
+    // (wave-uniform by construction; said explicitly because with a media mask the cursor derives
+    // from bitmap words read through the vector path)
+    const int hq = __builtin_amdgcn_readfirstlane(hk * G + c.h), i0 = __builtin_amdgcn_readfirstlane(c.i0);
     const long tile = ((long)hq * d.q_sh + (long)i0 * d.q_ss) * 2;
     const char* qb = q0 + tile + (long)wave * row_bytes;        // this wave's first row: tile row w
     const char* gb = g0 + tile + (long)wave * row_bytes;
@@ -229,9 +283,9 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   auto nothing = [](int) __attribute__((always_inline)) {};
   // masked elements of a step's scores -> -inf (wave-uniform decision, rarely taken)
   auto mask_scores = [&](int st, f32x16 (&s)[KVB]) __attribute__((always_inline)) {
-    if (!GENERAL || !a.mask.allow) return;
+    if (!GENERAL || !mk.allow) return;
     const int i0 = (st % spH) * KM;
-    const int cls = mask_rect(a.mask, b, i0, min(d.Sq, i0 + KM) - 1, min(j_wave0, d.Skv - 1),
+    const int cls = mask_rect(mk, b, i0, min(d.Sq, i0 + KM) - 1, min(j_wave0, d.Skv - 1),
                               min(d.Skv - 1, j_wave0 + 32 * KVB - 1));
     if (cls == 1) return;
     asm volatile("" ::: "memory");
@@ -240,7 +294,7 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int j = j_wave0 + 32 * kb + kl, i = i0 + 8 * (v / 4) + 4 * g + (v % 4);
-        const bool ok = j < d.Skv && i < d.Sq && mask_elem(a.mask, b, i, j);
+        const bool ok = j < d.Skv && i < d.Sq && mask_elem(mk, b, i, j);
         if (!ok) s[kb][v] = -INFINITY;
       }
   };

@@ -48,7 +48,10 @@ template <int D> struct DqSmem {
   static constexpr int GS = 16 * P + 64;            // group stride in bytes
   static constexpr int TILE = 4 * GS;
   static constexpr int STAGE = 2 * TILE;            // K tile, then V tile
-  static constexpr int TOTAL = NSTG * STAGE;
+  static constexpr int RING = NSTG * STAGE;
+  static constexpr int BITS_BYTES = 4096;           // visibility bits of up to 32704 tiles (media mask only)
+  static constexpr int WIN_BYTES = 16384;           // window of the mask bitmap (media mask only)
+  static constexpr int TOTAL = RING + BITS_BYTES + WIN_BYTES;
   static constexpr int RUN = 16 * SPR;              // slots of one group (contiguous)
   static constexpr int NCR = (RUN + 63) / 64;       // wave-level copies (64 slots) per group
   static_assert(GS % 256 == 64, "groups must sit 64 bytes apart modulo 256");
@@ -154,19 +157,38 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   }
   const float c2 = d.scale * LOG2E;
 
-  // ---- tiles this workgroup needs (media mask: tiles visible to none of its rows are skipped)
+  // ---- tiles this workgroup needs (media mask: tiles visible to none of its rows are skipped).
+  // The window of the bitmap that its rows and key range can touch is copied to LDS, and the
+  // visibility of every tile is worked out by all threads at once into a bit array, so that the
+  // loop never waits on the bitmap.
   const int i_wg0 = qt * QM, i_wg1 = min(d.Sq, i_wg0 + QM) - 1;
+  MaskDev mk = a.mask;
+  unsigned* const bits = (unsigned*)(smem + SM::RING);
+  bool have_bits = false;
+  int nt = max(t_end - t_begin, 0);                // number of tiles this workgroup performs
+  if (GENERAL && mk.allow && t_begin < t_end) {
+    mk = mask_to_lds(a.mask, b, i_wg0 / mk.q_chunk, i_wg1 / mk.q_chunk, (t_begin * TN) / mk.kv_block,
+                     (min(d.Skv, t_end * TN) - 1) / mk.kv_block, (uint8_t*)smem + SM::RING + SM::BITS_BYTES,
+                     SM::WIN_BYTES, tid, 256);
+    if (t_end - t_begin <= (SM::BITS_BYTES - 16) * 8) {
+      have_bits = true;
+      nt = build_bits(bits, t_end - t_begin, tid, 256, [&](int i) {
+        const int t = t_begin + i;
+        return mask_rect(mk, b, i_wg0, i_wg1, t * TN, min(d.Skv, t * TN + TN) - 1) != 0;
+      });
+    }
+  }
   auto tile_needed = [&](int t) __attribute__((always_inline)) -> bool {
-    if (!GENERAL || !a.mask.allow) return true;
-    return mask_rect(a.mask, b, i_wg0, i_wg1, t * TN, min(d.Skv, t * TN + TN) - 1) != 0;
+    if (!GENERAL || !mk.allow) return true;
+    return mask_rect(mk, b, i_wg0, i_wg1, t * TN, min(d.Skv, t * TN + TN) - 1) != 0;
   };
   auto next_tile = [&](int t) __attribute__((always_inline)) -> int {
+    if (GENERAL && have_bits) return t_begin + next_bit(bits, t - t_begin, t_end - t_begin);
     while (t < t_end && !tile_needed(t)) ++t;
-    return min(t, t_end);
+    return __builtin_amdgcn_readfirstlane(min(t, t_end));      // wave-uniform (the bitmap is read through the vector path)
   };
   int cursor = next_tile(t_begin);                 // next tile to issue
-  int nt = max(t_end - t_begin, 0);                // number of tiles this workgroup performs
-  if (GENERAL && a.mask.allow) {
+  if (GENERAL && mk.allow && !have_bits) {
     nt = 0;
     for (int t = cursor; t < t_end; t = next_tile(t + 1)) ++nt;
   }
@@ -261,8 +283,8 @@ bwd_dq_bf16_kernel(BwdArgs a) {
     if (!GENERAL) return;
     const int j0 = t * TN + 32 * hb;
     int cls = 1;
-    if (a.mask.allow && i_wave0 < d.Sq)
-      cls = mask_rect(a.mask, b, i_wave0, min(d.Sq, i_wave0 + 32 * QB) - 1, min(j0, d.Skv - 1),
+    if (mk.allow && i_wave0 < d.Sq)
+      cls = mask_rect(mk, b, i_wave0, min(d.Sq, i_wave0 + 32 * QB) - 1, min(j0, d.Skv - 1),
                       min(d.Skv, j0 + 32) - 1);
     if (cls == 1 && j0 + 32 <= d.Skv) return;
     asm volatile("" ::: "memory");
@@ -272,7 +294,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
       for (int v = 0; v < 16; ++v) {
         const int j = j0 + 8 * (v / 4) + 4 * g + (v % 4), i = i_wave0 + 32 * qb + ql;
         bool ok = j < d.Skv;
-        if (ok && cls != 1) ok = i < d.Sq && mask_elem(a.mask, b, i, j);
+        if (ok && cls != 1) ok = i < d.Sq && mask_elem(mk, b, i, j);
         if (!ok) s[qb][v] = -INFINITY;
       }
   };

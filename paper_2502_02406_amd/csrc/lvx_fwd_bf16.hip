@@ -43,7 +43,10 @@ template <int D> struct FwdSmem {
   static constexpr int STAGE = K_BYTES + V_BYTES;
   static constexpr int NCOPY = KCH + VCH;      // wave-level copies per tile
   static constexpr int L = (NCOPY + NW - 1) / NW;   // copies issued by every wave per tile
-  static constexpr int TOTAL = NS * STAGE;
+  static constexpr int RING = NS * STAGE;
+  static constexpr int BITS_BYTES = 4096;      // visibility bits of up to 32704 tiles (media mask only)
+  static constexpr int WIN_BYTES = 8192;       // window of the mask bitmap (media mask only)
+  static constexpr int TOTAL = RING + BITS_BYTES + WIN_BYTES;
 };
 
 template <int D>
@@ -138,17 +141,36 @@ fwd_bf16_kernel(FwdArgs a) {
     }
   };
 
-  // which tiles does this workgroup need at all (media mask)?
+  // which tiles does this workgroup need at all (media mask)?  The window of the bitmap that its
+  // rows and key range can touch is copied to LDS, and the visibility of every tile is worked out
+  // by all threads at once into a bit array, so that the loop never waits on the bitmap.
   const int i_wg0 = qt * BM, i_wg1 = min(d.Sq, i_wg0 + BM) - 1;
+  MaskDev mk = a.mask;
+  unsigned* const bits = (unsigned*)(smem + SM::RING);
+  bool have_bits = false;
+  if (mk.allow && t_begin < t_end) {
+    mk = mask_to_lds(a.mask, b, i_wg0 / mk.q_chunk, i_wg1 / mk.q_chunk, (t_begin * BN) / mk.kv_block,
+                     (min(d.Skv, t_end * BN) - 1) / mk.kv_block, (uint8_t*)smem + SM::RING + SM::BITS_BYTES,
+                     SM::WIN_BYTES, tid, 64 * NW);
+    if (t_end - t_begin <= (SM::BITS_BYTES - 16) * 8) {
+      have_bits = true;
+      build_bits(bits, t_end - t_begin, tid, 64 * NW, [&](int i) {
+        const int t = t_begin + i;
+        return mask_rect(mk, b, i_wg0, i_wg1, t * BN, min(d.Skv, t * BN + BN) - 1) != 0;
+      });
+    }
+  }
   auto next_tile = [&](int t) -> int {
-    if (a.mask.allow)
-      while (t < t_end && mask_rect(a.mask, b, i_wg0, i_wg1, t * BN, min(d.Skv, t * BN + BN) - 1) == 0) ++t;
-    return min(t, t_end);
+    if (mk.allow) {
+      if (have_bits) return t_begin + next_bit(bits, t - t_begin, t_end - t_begin);
+      while (t < t_end && mask_rect(mk, b, i_wg0, i_wg1, t * BN, min(d.Skv, t * BN + BN) - 1) == 0) ++t;
+    }
+    return __builtin_amdgcn_readfirstlane(min(t, t_end));      // wave-uniform (the bitmap is read through the vector path)
   };
   auto wave_class = [&](int t) -> int {               // 0 skip, 1 dense, 2 per-element mask
     if (t >= t_end || i_wave0 >= d.Sq) return 0;
-    if (!a.mask.allow) return 1;
-    return mask_rect(a.mask, b, i_wave0, min(d.Sq - 1, i_wave0 + 31), t * BN, min(d.Skv, t * BN + BN) - 1);
+    if (!mk.allow) return 1;
+    return mask_rect(mk, b, i_wave0, min(d.Sq - 1, i_wave0 + 31), t * BN, min(d.Skv, t * BN + BN) - 1);
   };
 
   f32x16 oacc[DB];
@@ -175,7 +197,7 @@ fwd_bf16_kernel(FwdArgs a) {
       for (int v = 0; v < 16; ++v) {
         const int j = j0 + 8 * (v / 4) + 4 * g + (v % 4);
         bool ok = j < d.Skv;
-        if (ok && cls == 2) ok = (i_lane < d.Sq) && mask_elem(a.mask, b, i_lane, j);
+        if (ok && cls == 2) ok = (i_lane < d.Sq) && mask_elem(mk, b, i_lane, j);
         if (!ok) s[v] = -INFINITY;
       }
     }
@@ -294,7 +316,7 @@ fwd_bf16_kernel(FwdArgs a) {
     if (id3 < t_end) issue_tile(id3, st_copy);
     return id3;
   };
-  const bool slow = a.mask.allow != nullptr || i_wave0 >= d.Sq;   // wave-uniform
+  const bool slow = mk.allow != nullptr || i_wave0 >= d.Sq;   // wave-uniform
   if (!slow) {
     // dense pipeline, one 32-key half ahead.  The three LDS stages a tile step touches are
     // distinct, and saying so (__restrict__) keeps the compiler from draining the copies in

@@ -100,13 +100,17 @@ __device__ __forceinline__ void dma16(const void* gsrc, void* lds_dst) {
 // The caller orders everything by hand: wait_vmcnt<N>() + barrier before the data is read, a
 // barrier before a stage is overwritten.  m0 (reserved, never live across statements) carries the
 // LDS address; one wait state separates its write from the copy.
+__device__ __forceinline__ unsigned lds_addr_uniform(void* p) {
+  // wave-uniform LDS byte address in a scalar register (a no-op when the compiler already keeps it there)
+  return (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(uintptr_t)LVX_LDS(p, char));
+}
 __device__ __forceinline__ void dma16s(const void* base, unsigned voff, void* lds_dst) {
-  const unsigned l = (unsigned)(uintptr_t)LVX_LDS(lds_dst, char);
+  const unsigned l = lds_addr_uniform(lds_dst);
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :: "v"(voff), "s"(base), "s"(l) : "memory");
 }
 __device__ __forceinline__ void dma4s(const void* base, unsigned voff, void* lds_dst) {
-  const unsigned l = (unsigned)(uintptr_t)LVX_LDS(lds_dst, char);
+  const unsigned l = lds_addr_uniform(lds_dst);
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
                :: "v"(voff), "s"(base), "s"(l) : "memory");
 }
@@ -161,6 +165,55 @@ __device__ __forceinline__ int mask_rect(const MaskDev& m, int b, int i0, int i1
 
 __device__ __forceinline__ bool mask_elem(const MaskDev& m, int b, int i, int j) {
   return m.allow[b * m.stride_b + (long)(i / m.q_chunk) * m.stride_q + (j / m.kv_block)] != 0;
+}
+
+// ---- media mask, staged for a workgroup -----------------------------------------------------
+// Reading the bitmap from global memory costs a round trip per probe, and a workgroup probes it
+// once per tile or step.  Two helpers take that off the critical path (every thread of the
+// workgroup, nthreads of them, must call them; both end with a barrier):
+//  * mask_to_lds copies the window [c0, c1] x [f0, f1] of batch b's bitmap into LDS when it fits
+//    in `cap` bytes and returns a MaskDev that addresses the copy (mask_rect / mask_elem work
+//    unchanged: the pointer is generic); otherwise it returns the mask as it is.
+//  * build_bits evaluates pred(i), i in [0, n), with all threads at once and leaves bit i in the
+//    word array bits[2 ..] (bits[0] = number of set bits); next_bit then finds the next set bit.
+__device__ inline MaskDev mask_to_lds(const MaskDev& m, int b, int c0, int c1, int f0, int f1,
+                                      uint8_t* lds, int cap, int tid, int nthreads) {
+  if (!m.allow) return m;
+  const int w = f1 - f0 + 1, h = c1 - c0 + 1;
+  if (w <= 0 || h <= 0 || (long)w * h > cap) return m;               // workgroup-uniform
+  for (int i = tid; i < w * h; i += nthreads)
+    lds[i] = m.allow[b * m.stride_b + (long)(c0 + i / w) * m.stride_q + f0 + i % w];
+  __syncthreads();
+  MaskDev r = m;
+  r.allow = lds - ((long)c0 * w + f0);          // never dereferenced outside the window
+  r.stride_b = 0;
+  r.stride_q = w;
+  return r;
+}
+template <typename Pred>
+__device__ inline int build_bits(unsigned* bits, int n, int tid, int nthreads, Pred pred) {
+  if (tid == 0) bits[0] = 0;
+  __syncthreads();
+  for (int base = 0; base < n; base += nthreads) {   // workgroup-uniform trip count
+    const int i = base + tid;
+    const bool on = i < n && pred(i);
+    const unsigned long long m = __ballot(on);
+    if ((tid & 63) == 0) {
+      *(unsigned long long*)(bits + 2 + i / 32) = m;
+      atomicAdd(&bits[0], (unsigned)__popcll(m));
+    }
+  }
+  __syncthreads();
+  return __builtin_amdgcn_readfirstlane((int)bits[0]);
+}
+__device__ inline int next_bit(const unsigned* bits, int i, int n) {    // first set bit >= i, or n
+  // (wave-uniform argument and result: the words are read through the vector path, so say so)
+  while (i < n) {
+    const unsigned w = (unsigned)__builtin_amdgcn_readfirstlane((int)bits[2 + (i >> 5)]) >> (i & 31);
+    if (w) return __builtin_amdgcn_readfirstlane(min(n, i + __ffs(w) - 1));
+    i = (i | 31) + 1;
+  }
+  return __builtin_amdgcn_readfirstlane(n);
 }
 
 // XCD-aware decode of a 1-D grid.  Workgroup ids are dealt round-robin to the 8 XCDs, each with
