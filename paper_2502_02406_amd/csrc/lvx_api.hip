@@ -77,11 +77,11 @@ MaskDev make_mask(const lvx_mask* m) {
   return r;
 }
 
-int fwd_split(const Dims& d, lvx_dtype dtype) {
-  return dtype == LVX_BF16 ? fwd_bf16_pick_split(d, device_cu_count()) : 1;
+int fwd_split(const Dims& d, lvx_dtype dtype, bool masked) {
+  return dtype == LVX_BF16 ? fwd_bf16_pick_split(d, device_cu_count(), masked) : 1;
 }
-int bwd_split(const Dims& d, lvx_dtype dtype) {
-  return dtype == LVX_BF16 ? bwd_bf16_pick_split(d, device_cu_count()) : 1;
+int bwd_split(const Dims& d, lvx_dtype dtype, bool masked) {
+  return dtype == LVX_BF16 ? bwd_bf16_pick_split(d, device_cu_count(), masked) : 1;
 }
 
 size_t fwd_ws(const Dims& d, int n_split) {
@@ -117,7 +117,7 @@ const char* lvx_strerror(lvx_status s) {
 size_t lvx_xattn_workspace_bytes(const lvx_problem* p, lvx_dtype dtype, int which) {
   if (check_problem(p, dtype) != LVX_OK) return 0;
   const Dims d = make_dims(p);
-  if (which == LVX_WS_FWD) return fwd_ws(d, fwd_split(d, dtype));
+  if (which == LVX_WS_FWD) return fwd_ws(d, fwd_split(d, dtype, true));   // a masked call splits at least as much
   if (which == LVX_WS_BWD) return bwd_ws(d);
   return 0;
 }
@@ -135,7 +135,7 @@ lvx_status lvx_xattn_fwd(const lvx_problem* p, lvx_dtype dtype, const void* q, c
   a.d = make_dims(p);
   a.mask = make_mask(mask);
   a.q = q; a.k = k; a.v = v; a.o = o; a.o_is_f32 = o_dtype == LVX_F32; a.lse = lse;
-  a.n_split = fwd_split(a.d, dtype);
+  a.n_split = fwd_split(a.d, dtype, mask != nullptr);
   a.o_part = nullptr; a.lse_part = nullptr;
   const size_t need = fwd_ws(a.d, a.n_split);
   if (!workspace || ((uintptr_t)workspace % ALIGN) != 0 || workspace_bytes < need) return LVX_ERR_WORKSPACE;
@@ -218,7 +218,7 @@ lvx_status lvx_xattn_bwd_stages(const lvx_problem* p, lvx_dtype dtype, const voi
   a.sq_pad = sq_padded(a.d);
   a.stats = (float*)((char*)workspace + align_up((size_t)a.d.B * a.d.Hq * a.d.Sq * sizeof(float)));
   a.dq_accum = dq_accum; a.dk = dk; a.dv = dv;
-  a.n_split_dq = bwd_split(a.d, dtype);
+  a.n_split_dq = bwd_split(a.d, dtype, mask != nullptr);
   hipStream_t s = (hipStream_t)hip_stream;
   hipError_t e = hipSuccess;
   if (stages & LVX_BWD_DELTA) e = launch_delta(a.d, o, d_o, dtype == LVX_F32, lse, a.delta, a.stats, a.sq_pad, s);

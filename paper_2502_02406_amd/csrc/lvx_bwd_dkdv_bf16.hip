@@ -27,22 +27,32 @@ namespace lvx {
 namespace {
 
 constexpr float LOG2E = 1.4426950408889634f;
-constexpr int KVB = 2;                 // 32-key blocks per wave
 constexpr int NWV = 4;                 // waves per workgroup
-constexpr int KN = NWV * 32 * KVB;     // keys per workgroup
+// 32-key blocks per wave: two in the dense kernel; one in the general kernel, whose mask code needs
+// registers and must leave the accumulation file half empty (see mfma32_acc)
+constexpr int kvb_of(bool general) { return general ? 1 : 2; }
 constexpr int KM = 32;                 // query rows per step
 constexpr int NSTG = 4;                // ring stages
-constexpr int XE = 32;                 // elements of a step converted during the contraction (the rest, if any,
-                                       // during scoring; measured: no gain from moving them)
 
 // dK^T / dV^T accumulation: the sixteen 32x32 accumulator blocks of a wave fill the accumulation
 // register file exactly, and only matrix instructions touch them until the epilogue.  The
 // instruction is written out so that the accumulator stays in that file by construction.
+// The compiler does not know that this is a matrix instruction, so it would not wait for the
+// result before a register move of its own.  The dense kernel has no such move inside its loops
+// (checked in the generated code: the accumulators never leave their file); the general kernel
+// is under more register pressure and the allocator may park an accumulator elsewhere between
+// uses, so there (SETTLE) the instruction is followed by enough idle states for the result to land.
+template <bool SETTLE>
 __device__ __forceinline__ void mfma32_acc(f32x16& acc, bf16x8 a, bf16x8 b) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+  if (SETTLE)
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\ts_nop 15\n\ts_nop 15\n\ts_nop 7"
+                 : "+a"(acc) : "v"(a), "v"(b));
+  else
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
 
-template <int D> struct DkvSmem {
+template <int D, int KVB> struct DkvSmem {
+  static constexpr int KN = NWV * 32 * KVB;         // keys per workgroup
   static constexpr int CPR = D / 8;                 // 16-byte chunks of data per row
   static constexpr int P = (D + 8) * 2;             // row pitch in bytes
   static constexpr int SPR = P / 16;                // 16-byte slots per row
@@ -64,7 +74,11 @@ template <int D, bool GENERAL>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 bwd_dkdv_bf16_kernel(BwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  using SM = DkvSmem<D>;
+  constexpr int KVB = kvb_of(GENERAL);
+  constexpr int XE = 16 * KVB;     // all elements of a step are converted during the contraction
+                                   // (measured: no gain from moving some of them to the scoring)
+  using SM = DkvSmem<D, KVB>;
+  constexpr int KN = SM::KN;
   constexpr int KS = D / 16, DB = D / 32, CPR = SM::CPR, NCR = SM::NCR;
 
   const Dims& d = a.d;
@@ -298,8 +312,8 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
         if (!ok) s[kb][v] = -INFINITY;
       }
   };
-  // Conversion of scores into operands, element x of a step (x = 0..31: four query rows q4 = x / 8
-  // of key block kb = (x / 4) % 2, row e = x % 4 of the four): p = exp2(s c2 - L2), dS = p (dP -
+  // Conversion of scores into operands, element x of a step (x = 0 .. 16 KVB - 1: four query rows
+  // q4 = x / (4 KVB) of key block kb = (x / 4) % KVB, row e = x % 4 of the four): p = exp2(s c2 - L2), dS = p (dP -
   // delta) with the difference already formed by the accumulation, packed in pairs as bf16 into word 2 (q4 % 2) + e / 2 of operand q4 / 2 of the key block.
   struct Conv { f32x4 l4; };
   struct Carry { float pr, ds; };
@@ -308,7 +322,7 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   };
   auto conv_elem = [&](int x, const Conv& cv, Carry& cy, const f32x16 (&s)[KVB], const f32x16 (&p)[KVB],
                        u32x4 (&pwo)[KVB][2], u32x4 (&swo)[KVB][2]) __attribute__((always_inline)) {
-    const int q4 = x / 8, kb = (x / 4) % 2, e = x % 4, v = 4 * q4 + e;
+    const int q4 = x / (4 * KVB), kb = (x / 4) % KVB, e = x % 4, v = 4 * q4 + e;
     const float pr = __builtin_amdgcn_exp2f(fmaf(s[kb][v], c2, -cv.l4[e]));
     const float ds = pr * p[kb][v];                 // p already holds dP - delta
     if (e % 2 == 0) { cy.pr = pr; cy.ds = ds; return; }
@@ -320,8 +334,8 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
     Conv cv;
     Carry cy;
 #pragma unroll
-    for (int x = 0; x < 32; ++x) {
-      if (x % 8 == 0) conv_stats(t, x / 8, cv);
+    for (int x = 0; x < 16 * KVB; ++x) {
+      if (x % (4 * KVB) == 0) conv_stats(t, x / (4 * KVB), cv);
       conv_elem(x, cv, cy, s, p, pwo, swo);
     }
   };
@@ -335,8 +349,8 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
         const bf16x8 qt = load_tr_operand_ilv<D>(t, 16 * t2, 32 * db, lane);
 #pragma unroll
         for (int kb = 0; kb < KVB; ++kb) {
-          mfma32_acc(dv[kb][db], gt, __builtin_bit_cast(bf16x8, pwi[kb][t2]));
-          mfma32_acc(dk[kb][db], qt, __builtin_bit_cast(bf16x8, swi[kb][t2]));
+          mfma32_acc<GENERAL>(dv[kb][db], gt, __builtin_bit_cast(bf16x8, pwi[kb][t2]));
+          mfma32_acc<GENERAL>(dk[kb][db], qt, __builtin_bit_cast(bf16x8, swi[kb][t2]));
         }
       }
   };
@@ -348,7 +362,7 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
                               const u32x4 (&pwi)[KVB][2], const u32x4 (&swi)[KVB][2],
                               const f32x16 (&s)[KVB], const f32x16 (&p)[KVB],
                               u32x4 (&pwo)[KVB][2], u32x4 (&swo)[KVB][2]) __attribute__((always_inline)) {
-    constexpr int NM = 8 * DB, EPM = (XE + NM - 1) / NM;   // matrix instructions, elements per instruction
+    constexpr int NM = 4 * KVB * DB, EPM = (XE + NM - 1) / NM;   // matrix instructions, elements per instruction
     bf16x8 gt[2], qt[2];                           // two operand sets, used alternately
     gt[0] = load_tr_operand_ilv<D>(t0, KM, 0, lane);
     qt[0] = load_tr_operand_ilv<D>(t0, 0, 0, lane);
@@ -357,17 +371,17 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
     conv_stats(t1, 0, cv[0]);
 #pragma unroll
     for (int m = 0; m < NM; ++m) {
-      const int c = m / 4, t2 = c / DB, db = c % DB, j = m % 4, cu = c & 1;
+      const int c = m / (2 * KVB), t2 = c / DB, db = c % DB, j = m % (2 * KVB), cu = c & 1;
       if (j == 0 && c + 1 < 2 * DB) {
         gt[cu ^ 1] = load_tr_operand_ilv<D>(t0, KM + 16 * ((c + 1) / DB), 32 * ((c + 1) % DB), lane);
         qt[cu ^ 1] = load_tr_operand_ilv<D>(t0, 16 * ((c + 1) / DB), 32 * ((c + 1) % DB), lane);
       }
-      if (j % 2 == 0) mfma32_acc(dv[j / 2][db], gt[cu], __builtin_bit_cast(bf16x8, pwi[j / 2][t2]));
-      else mfma32_acc(dk[j / 2][db], qt[cu], __builtin_bit_cast(bf16x8, swi[j / 2][t2]));
+      if (j % 2 == 0) mfma32_acc<GENERAL>(dv[j / 2][db], gt[cu], __builtin_bit_cast(bf16x8, pwi[j / 2][t2]));
+      else mfma32_acc<GENERAL>(dk[j / 2][db], qt[cu], __builtin_bit_cast(bf16x8, swi[j / 2][t2]));
 #pragma unroll
       for (int x = m * EPM; x < (m + 1) * EPM && x < XE; ++x) {
-        const int q4 = x / 8;
-        if (x % 8 == 0 && 8 * (q4 + 1) < XE) conv_stats(t1, q4 + 1, cv[(q4 + 1) & 1]);   // one q4 ahead
+        const int q4 = x / (4 * KVB);
+        if (x % (4 * KVB) == 0 && 4 * KVB * (q4 + 1) < XE) conv_stats(t1, q4 + 1, cv[(q4 + 1) & 1]);   // one q4 ahead
         conv_elem(x, cv[q4 & 1], cy, s, p, pwo, swo);
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -395,7 +409,6 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   const char* const vw = vres + (wave * 32 * KVB + kl) * SM::P + g * 16;
 
   f32x16 s[KVB], p[KVB];
-  f32x16 s2[KVB], p2[KVB];                         // second set of scores, only used when XE < 32
   u32x4 pf0[KVB][2] = {}, sf0[KVB][2] = {}, pf1[KVB][2] = {}, sf1[KVB][2] = {};   // packed P and dS operands
   if (n > 0) {
     score(smem, vw, s, p, nothing);
@@ -404,6 +417,8 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
     if (n > 1) { score(smem + SM::STAGE, vw, s, p, nothing); mask_scores(e[1], s); }
   }
   auto mid = [&](auto all_in_flight, bool issue, char* st_copy) __attribute__((always_inline)) {
+    // (The general variant may spill registers inside the loop; its spill stores are counted with
+    // the copies but complete out of order with them, so it always waits for everything.)
     // all_in_flight: steps i + 2 and i + 3 were both issued, so leaving one step's copies
     // outstanding still guarantees that step i + 2 has landed
     if constexpr (decltype(all_in_flight)::value) wait_vmcnt<NDMA>();
@@ -415,46 +430,21 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
       advance(cursor);
     }
   };
-  // With XE < 32 the remaining elements of step i + 1 are converted while step i + 2 is scored,
-  // which needs a second set of score registers (the two sets alternate between iterations).
   auto full_iter = [&](char* st_copy, const char* __restrict__ t0,
                        const char* __restrict__ t1, const char* __restrict__ t2,
                        const char* __restrict__ vw_, const u32x4 (&pfi)[KVB][2],
-                       const u32x4 (&sfi)[KVB][2], u32x4 (&pfo)[KVB][2], u32x4 (&sfo)[KVB][2],
-                       f32x16 (&s_cv)[KVB], f32x16 (&p_cv)[KVB], f32x16 (&s_sc)[KVB],
-                       f32x16 (&p_sc)[KVB]) __attribute__((always_inline)) {
-    contract_convert(t0, t1, pfi, sfi, s_cv, p_cv, pfo, sfo);
-    mid(std::true_type{}, true, st_copy);
-    if constexpr (XE == 32) {
-      score(t2, vw_, s_sc, p_sc, nothing);
-    } else {
-      constexpr int NU = 2 * KVB * KS;             // matrix instructions of a score phase
-      static_assert(XE % 8 == 0, "XE must cut at a four-row boundary");
-      Conv cv[2];
-      Carry cy;
-      conv_stats(t1, XE / 8, cv[(XE / 8) & 1]);
-      score(t2, vw_, s_sc, p_sc, [&](int m) __attribute__((always_inline)) {
-#pragma unroll
-        for (int x = XE + m * (32 - XE) / NU; x < XE + (m + 1) * (32 - XE) / NU; ++x) {
-          const int q4 = x / 8;
-          if (x % 8 == 0 && q4 + 1 < 4) conv_stats(t1, q4 + 1, cv[(q4 + 1) & 1]);
-          conv_elem(x, cv[q4 & 1], cy, s_cv, p_cv, pfo, sfo);
-        }
-      });
-    }
-    mask_scores(e[2], s_sc);
+                       const u32x4 (&sfi)[KVB][2], u32x4 (&pfo)[KVB][2], u32x4 (&sfo)[KVB][2]) __attribute__((always_inline)) {
+    contract_convert(t0, t1, pfi, sfi, s, p, pfo, sfo);
+    mid(std::bool_constant<!GENERAL>{}, true, st_copy);
+    score(t2, vw_, s, p, nothing);
+    mask_scores(e[2], s);
     e[0] = e[1]; e[1] = e[2]; e[2] = e[3]; e[3] = e[4];
   };
   auto stage = [&](int q) __attribute__((always_inline)) -> char* { return smem + (q % NSTG) * SM::STAGE; };
   int i = 0;
   while (i + 5 < n) {                              // two full iterations per trip, each issuing a step
-    if constexpr (XE == 32) {
-      full_iter(stage(i), stage(i), stage(i + 1), stage(i + 2), vw, pf0, sf0, pf1, sf1, s, p, s, p);
-      full_iter(stage(i + 1), stage(i + 1), stage(i + 2), stage(i + 3), vw, pf1, sf1, pf0, sf0, s, p, s, p);
-    } else {
-      full_iter(stage(i), stage(i), stage(i + 1), stage(i + 2), vw, pf0, sf0, pf1, sf1, s, p, s2, p2);
-      full_iter(stage(i + 1), stage(i + 1), stage(i + 2), stage(i + 3), vw, pf1, sf1, pf0, sf0, s2, p2, s, p);
-    }
+    full_iter(stage(i), stage(i), stage(i + 1), stage(i + 2), vw, pf0, sf0, pf1, sf1);
+    full_iter(stage(i + 1), stage(i + 1), stage(i + 2), stage(i + 3), vw, pf1, sf1, pf0, sf0);
     i += 2;
   }
   for (; i < n; ++i) {                             // the last (at most five) iterations
@@ -498,11 +488,13 @@ hipError_t set_smem_once(F* fn, int bytes, bool* done) {
 
 
 template <int D, bool GENERAL>
-hipError_t launch(const BwdArgs& a, long grid, hipStream_t s) {
+hipError_t launch(const BwdArgs& a, hipStream_t s) {
+  const long grid = xcd_grid(a.d.B * a.d.Hkv, (a.d.Skv + DkvSmem<D, kvb_of(GENERAL)>::KN - 1) / DkvSmem<D, kvb_of(GENERAL)>::KN);
   static bool once = false;
-  hipError_t e = set_smem_once(bwd_dkdv_bf16_kernel<D, GENERAL>, DkvSmem<D>::TOTAL, &once);
+  using SM = DkvSmem<D, kvb_of(GENERAL)>;
+  hipError_t e = set_smem_once(bwd_dkdv_bf16_kernel<D, GENERAL>, SM::TOTAL, &once);
   if (e != hipSuccess) return e;
-  bwd_dkdv_bf16_kernel<D, GENERAL><<<(unsigned)grid, 256, DkvSmem<D>::TOTAL, s>>>(a);
+  bwd_dkdv_bf16_kernel<D, GENERAL><<<(unsigned)grid, 256, SM::TOTAL, s>>>(a);
   return hipGetLastError();
 }
 
@@ -510,10 +502,9 @@ hipError_t launch(const BwdArgs& a, long grid, hipStream_t s) {
 
 hipError_t launch_bwd_dkdv_bf16(const BwdArgs& a, hipStream_t s) {
   const Dims& d = a.d;
-  const long grid = xcd_grid(d.B * d.Hkv, (d.Skv + KN - 1) / KN);
   const bool general = a.mask.allow != nullptr || d.Sq % KM != 0;
-  if (d.D == 64) return general ? launch<64, true>(a, grid, s) : launch<64, false>(a, grid, s);
-  return general ? launch<128, true>(a, grid, s) : launch<128, false>(a, grid, s);
+  if (d.D == 64) return general ? launch<64, true>(a, s) : launch<64, false>(a, s);
+  return general ? launch<128, true>(a, s) : launch<128, false>(a, s);
 }
 
 }  // namespace lvx

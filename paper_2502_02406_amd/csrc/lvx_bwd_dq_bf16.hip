@@ -115,8 +115,8 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   // KV range of this split, in tiles
   const int n_tiles = (d.Skv + TN - 1) / TN;
   const int tps = (n_tiles + a.n_split_dq - 1) / a.n_split_dq;
-  const int t_begin = split * tps;
-  const int t_end = min(n_tiles, t_begin + tps);
+  int t_begin = split * tps;                        // (with a media mask: re-cut below over the visible tiles)
+  int t_end = min(n_tiles, t_begin + tps);
 
   // ---- stationary operands and statistics of this lane's query rows i_wave0 + 32 qb + ql
   bf16x8 qf[QB][KS], gf[QB][KS];
@@ -166,16 +166,23 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   unsigned* const bits = (unsigned*)(smem + SM::RING);
   bool have_bits = false;
   int nt = max(t_end - t_begin, 0);                // number of tiles this workgroup performs
-  if (GENERAL && mk.allow && t_begin < t_end) {
-    mk = mask_to_lds(a.mask, b, i_wg0 / mk.q_chunk, i_wg1 / mk.q_chunk, (t_begin * TN) / mk.kv_block,
-                     (min(d.Skv, t_end * TN) - 1) / mk.kv_block, (uint8_t*)smem + SM::RING + SM::BITS_BYTES,
-                     SM::WIN_BYTES, tid, 256);
-    if (t_end - t_begin <= (SM::BITS_BYTES - 16) * 8) {
+  if (GENERAL && mk.allow) {
+    if (n_tiles <= (SM::BITS_BYTES - 16) * 8) {
+      // bits over ALL tiles of the key range; the splits then share the visible tiles evenly
+      mk = mask_to_lds(a.mask, b, i_wg0 / mk.q_chunk, i_wg1 / mk.q_chunk, 0, (d.Skv - 1) / mk.kv_block,
+                       (uint8_t*)smem + SM::RING + SM::BITS_BYTES, SM::WIN_BYTES, tid, 256);
       have_bits = true;
-      nt = build_bits(bits, t_end - t_begin, tid, 256, [&](int i) {
-        const int t = t_begin + i;
+      const int nn = build_bits(bits, n_tiles, tid, 256, [&](int t) {
         return mask_rect(mk, b, i_wg0, i_wg1, t * TN, min(d.Skv, t * TN + TN) - 1) != 0;
       });
+      const int k0 = (int)((long)split * nn / a.n_split_dq), k1 = (int)((long)(split + 1) * nn / a.n_split_dq);
+      t_begin = nth_bit(bits, k0, n_tiles);
+      t_end = k1 > k0 ? nth_bit(bits, k1 - 1, n_tiles) + 1 : t_begin;
+      nt = k1 - k0;
+    } else if (t_begin < t_end) {
+      mk = mask_to_lds(a.mask, b, i_wg0 / mk.q_chunk, i_wg1 / mk.q_chunk, (t_begin * TN) / mk.kv_block,
+                       (min(d.Skv, t_end * TN) - 1) / mk.kv_block, (uint8_t*)smem + SM::RING + SM::BITS_BYTES,
+                       SM::WIN_BYTES, tid, 256);
     }
   }
   auto tile_needed = [&](int t) __attribute__((always_inline)) -> bool {
@@ -183,7 +190,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
     return mask_rect(mk, b, i_wg0, i_wg1, t * TN, min(d.Skv, t * TN + TN) - 1) != 0;
   };
   auto next_tile = [&](int t) __attribute__((always_inline)) -> int {
-    if (GENERAL && have_bits) return t_begin + next_bit(bits, t - t_begin, t_end - t_begin);
+    if (GENERAL && have_bits) return next_bit(bits, t, t_end);
     while (t < t_end && !tile_needed(t)) ++t;
     return __builtin_amdgcn_readfirstlane(min(t, t_end));      // wave-uniform (the bitmap is read through the vector path)
   };
@@ -377,6 +384,8 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   __syncthreads();
   auto stage = [&](int q) __attribute__((always_inline)) -> char* { return smem + (q % NSTG) * SM::STAGE; };
   auto mid = [&](auto all_in_flight, bool issue, char* st_copy) __attribute__((always_inline)) {
+    // (The general variant may spill registers inside the loop; its spill stores are counted with
+    // the copies but complete out of order with them, so it always waits for everything.)
     // all_in_flight: tiles T + 2 and T + 3 were both issued, so leaving one tile's copies
     // outstanding still guarantees that tile T + 2 has landed
     if constexpr (decltype(all_in_flight)::value) wait_vmcnt<NDMA>();
@@ -405,7 +414,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
     score_convert(stage(T + 1), 0, s0, p0, s1, p1, ds1, cy);
     mask_scores(e[1], 0, s0);
     contract_convert(stage(T), 1, ds1, s0, p0, ds0, cy);
-    mid(std::true_type{}, true, stage(T));
+    mid(std::bool_constant<!GENERAL>{}, true, stage(T));
     score_convert(stage(T + 1), 1, s1, p1, s0, p0, ds0, cy);
     mask_scores(e[1], 1, s1);
     e[0] = e[1]; e[1] = e[2]; e[2] = e[3]; e[3] = e[4];
@@ -457,11 +466,12 @@ hipError_t launch(const BwdArgs& a, long grid, hipStream_t s) {
 
 }  // namespace
 
-int bwd_bf16_pick_split(const Dims& d, int n_cu) {
-  // one workgroup per CU; split the KV axis until the grid covers the chip
+int bwd_bf16_pick_split(const Dims& d, int n_cu, bool masked) {
+  // one workgroup per CU; split the KV axis until the grid covers the chip (four times as many
+  // workgroups with a media mask, whose visible work differs from one query tile to the next)
   const long base = (long)d.B * d.Hq * ((d.Sq + QM - 1) / QM);
   const int n_tiles = (d.Skv + TN - 1) / TN;
-  long want = (n_cu + base - 1) / base;
+  long want = ((masked ? 4L : 1L) * n_cu + base - 1) / base;
   if (want < 1) want = 1;
   long cap = n_tiles / 16;                // keep at least 16 tiles (1024 keys) per split
   if (cap < 1) cap = 1;

@@ -76,8 +76,8 @@ fwd_bf16_kernel(FwdArgs a) {
   // KV range of this split, in tiles
   const int n_tiles = (d.Skv + BN - 1) / BN;
   const int tps = (n_tiles + a.n_split - 1) / a.n_split;
-  const int t_begin = split * tps;
-  const int t_end = min(n_tiles, t_begin + tps);
+  int t_begin = split * tps;                        // (with a media mask: re-cut below over the visible tiles)
+  int t_end = min(n_tiles, t_begin + tps);
 
   // Q operands (B of S^T = K Q^T): lane holds row i_lane, columns 16 ks + 8 g + 0..7
   bf16x8 qf[KS];
@@ -148,21 +148,27 @@ fwd_bf16_kernel(FwdArgs a) {
   MaskDev mk = a.mask;
   unsigned* const bits = (unsigned*)(smem + SM::RING);
   bool have_bits = false;
-  if (mk.allow && t_begin < t_end) {
-    mk = mask_to_lds(a.mask, b, i_wg0 / mk.q_chunk, i_wg1 / mk.q_chunk, (t_begin * BN) / mk.kv_block,
-                     (min(d.Skv, t_end * BN) - 1) / mk.kv_block, (uint8_t*)smem + SM::RING + SM::BITS_BYTES,
-                     SM::WIN_BYTES, tid, 64 * NW);
-    if (t_end - t_begin <= (SM::BITS_BYTES - 16) * 8) {
+  if (mk.allow) {
+    if (n_tiles <= (SM::BITS_BYTES - 16) * 8) {
+      // bits over ALL tiles of the key range; the splits then share the visible tiles evenly
+      mk = mask_to_lds(a.mask, b, i_wg0 / mk.q_chunk, i_wg1 / mk.q_chunk, 0, (d.Skv - 1) / mk.kv_block,
+                       (uint8_t*)smem + SM::RING + SM::BITS_BYTES, SM::WIN_BYTES, tid, 64 * NW);
       have_bits = true;
-      build_bits(bits, t_end - t_begin, tid, 64 * NW, [&](int i) {
-        const int t = t_begin + i;
+      const int nn = build_bits(bits, n_tiles, tid, 64 * NW, [&](int t) {
         return mask_rect(mk, b, i_wg0, i_wg1, t * BN, min(d.Skv, t * BN + BN) - 1) != 0;
       });
+      const int k0 = (int)((long)split * nn / a.n_split), k1 = (int)((long)(split + 1) * nn / a.n_split);
+      t_begin = nth_bit(bits, k0, n_tiles);
+      t_end = k1 > k0 ? nth_bit(bits, k1 - 1, n_tiles) + 1 : t_begin;
+    } else if (t_begin < t_end) {
+      mk = mask_to_lds(a.mask, b, i_wg0 / mk.q_chunk, i_wg1 / mk.q_chunk, (t_begin * BN) / mk.kv_block,
+                       (min(d.Skv, t_end * BN) - 1) / mk.kv_block, (uint8_t*)smem + SM::RING + SM::BITS_BYTES,
+                       SM::WIN_BYTES, tid, 64 * NW);
     }
   }
   auto next_tile = [&](int t) -> int {
     if (mk.allow) {
-      if (have_bits) return t_begin + next_bit(bits, t - t_begin, t_end - t_begin);
+      if (have_bits) return next_bit(bits, t, t_end);
       while (t < t_end && mask_rect(mk, b, i_wg0, i_wg1, t * BN, min(d.Skv, t * BN + BN) - 1) == 0) ++t;
     }
     return __builtin_amdgcn_readfirstlane(min(t, t_end));      // wave-uniform (the bitmap is read through the vector path)
@@ -432,11 +438,13 @@ hipError_t launch(const FwdArgs& a, long grid, hipStream_t s) {
 
 }  // namespace
 
-int fwd_bf16_pick_split(const Dims& d, int n_cu) {
-  // one workgroup per CU; split the KV axis until the grid covers the chip
+int fwd_bf16_pick_split(const Dims& d, int n_cu, bool masked) {
+  // one workgroup per CU; split the KV axis until the grid covers the chip.  With a media mask the
+  // visible work differs from one query tile to the next (the splits of a tile share its visible
+  // key tiles evenly), so four times as many workgroups are made to even the load out.
   const long base = (long)d.B * d.Hq * ((d.Sq + BM - 1) / BM);
   const int n_tiles = (d.Skv + BN - 1) / BN;
-  long want = (n_cu + base - 1) / base;
+  long want = ((masked ? 4L : 1L) * n_cu + base - 1) / base;
   if (want < 1) want = 1;
   long cap = n_tiles / 16;                // keep at least 16 tiles (1024 keys) per split
   if (cap < 1) cap = 1;

@@ -68,8 +68,8 @@ hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t s);
 hipError_t launch_bwd_bf16(const BwdArgs& a, unsigned stages, hipStream_t s);
 hipError_t launch_bwd_dkdv_bf16(const BwdArgs& a, hipStream_t s);
 hipError_t launch_bwd_dq_bf16(const BwdArgs& a, hipStream_t s);
-int fwd_bf16_pick_split(const Dims& d, int n_cu);
-int bwd_bf16_pick_split(const Dims& d, int n_cu);
+int fwd_bf16_pick_split(const Dims& d, int n_cu, bool masked);
+int bwd_bf16_pick_split(const Dims& d, int n_cu, bool masked);
 // memory-bound helpers
 hipError_t launch_merge(const MergeArgs& a, int part_is_f32, int out_is_f32, hipStream_t s);
 hipError_t launch_delta(const Dims& d, const void* o, const void* d_o, int is_f32, const float* lse,

@@ -104,12 +104,21 @@ __device__ __forceinline__ unsigned lds_addr_uniform(void* p) {
   // wave-uniform LDS byte address in a scalar register (a no-op when the compiler already keeps it there)
   return (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(uintptr_t)LVX_LDS(p, char));
 }
+__device__ __forceinline__ const void* ptr_uniform(const void* p) {
+  // wave-uniform pointer in scalar registers (a no-op when the compiler already keeps it there)
+  const unsigned long long x = (unsigned long long)(uintptr_t)p;
+  const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)x);
+  const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(x >> 32));
+  return (const void*)(uintptr_t)(((unsigned long long)hi << 32) | lo);
+}
 __device__ __forceinline__ void dma16s(const void* base, unsigned voff, void* lds_dst) {
+  base = ptr_uniform(base);
   const unsigned l = lds_addr_uniform(lds_dst);
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :: "v"(voff), "s"(base), "s"(l) : "memory");
 }
 __device__ __forceinline__ void dma4s(const void* base, unsigned voff, void* lds_dst) {
+  base = ptr_uniform(base);
   const unsigned l = lds_addr_uniform(lds_dst);
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
                :: "v"(voff), "s"(base), "s"(l) : "memory");
@@ -185,7 +194,7 @@ __device__ inline MaskDev mask_to_lds(const MaskDev& m, int b, int c0, int c1, i
     lds[i] = m.allow[b * m.stride_b + (long)(c0 + i / w) * m.stride_q + f0 + i % w];
   __syncthreads();
   MaskDev r = m;
-  r.allow = lds - ((long)c0 * w + f0);          // never dereferenced outside the window
+  r.allow = lds - ((long)c0 * w + f0);
   r.stride_b = 0;
   r.stride_q = w;
   return r;
@@ -212,6 +221,19 @@ __device__ inline int next_bit(const unsigned* bits, int i, int n) {    // first
     const unsigned w = (unsigned)__builtin_amdgcn_readfirstlane((int)bits[2 + (i >> 5)]) >> (i & 31);
     if (w) return __builtin_amdgcn_readfirstlane(min(n, i + __ffs(w) - 1));
     i = (i | 31) + 1;
+  }
+  return __builtin_amdgcn_readfirstlane(n);
+}
+
+__device__ inline int nth_bit(const unsigned* bits, int k, int n) {     // index of the k-th set bit (k >= 0), or n
+  for (int w0 = 0; w0 < n; w0 += 32) {
+    unsigned w = (unsigned)__builtin_amdgcn_readfirstlane((int)bits[2 + (w0 >> 5)]);
+    const int c = __popc(w);
+    if (k < c) {
+      for (; k > 0; --k) w &= w - 1;
+      return __builtin_amdgcn_readfirstlane(min(n, w0 + __ffs(w) - 1));
+    }
+    k -= c;
   }
   return __builtin_amdgcn_readfirstlane(n);
 }
