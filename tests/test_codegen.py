@@ -1,0 +1,65 @@
+"""Generated-code checks of the two backward kernels (no GPU needed: hipcc cross-compiles).
+
+Both kernels write some matrix instructions out by hand so that accumulators and stationary
+operands stay in the accumulation register file.  The compiler does not know that those
+statements are matrix instructions, so it would not wait for their results before a register move
+or a spill of its own.  That is safe only while the steady-state loops of the dense kernels contain
+no such move: this test compiles the sources exactly as the build does and looks at the loops."""
+import os
+import re
+import subprocess
+import tempfile
+
+import pytest
+
+from paper_2502_02406_amd import build as B
+
+CSRC = B.CSRC
+
+
+def _asm(src):
+    with tempfile.TemporaryDirectory() as tmp:
+        out = os.path.join(tmp, "k.s")
+        cmd = [B.HIPCC] + B.FLAGS + B.FILE_FLAGS.get(src, []) + ["--cuda-device-only", "-S",
+                                                                   os.path.join(CSRC, src), "-o", out]
+        r = subprocess.run(cmd, capture_output=True, text=True, timeout=900)
+        assert r.returncode == 0, r.stderr[-2000:]
+        return open(out).read()
+
+
+def _kernel(asm, pattern):
+    m = re.search(r"^(_ZN[^\n]*" + pattern + r"[^\n]*):.*?s_endpgm", asm, re.S | re.M)
+    assert m, f"kernel {pattern} not found"
+    return m.group(0)
+
+
+def _blocks(body):
+    """basic blocks: split at labels"""
+    return re.split(r"^\.LBB\d+_\d+:.*$", body, flags=re.M)
+
+
+@pytest.mark.parametrize("src,kernel,loop_mfma", [
+    ("lvx_bwd_dkdv_bf16.hip", "bwd_dkdv_bf16_kernelILi128ELb0E", 128),   # two steps of 64 per trip
+    ("lvx_bwd_dq_bf16.hip", "bwd_dq_bf16_kernelILi128ELb0E", 96),        # one tile = two halves of 48
+])
+def test_dense_loop_moves_no_accumulator(src, kernel, loop_mfma):
+    body = _kernel(_asm(src), kernel)
+    loops = [b for b in _blocks(body) if b.count("v_mfma_f32_32x32x16_bf16") == loop_mfma]
+    assert len(loops) == 1, "steady-state loop not found as one basic block"
+    loop = loops[0]
+    assert "v_accvgpr" not in loop, "an accumulator or operand leaves the accumulation file inside the loop"
+    assert "scratch_" not in loop, "register spill inside the loop"
+    # LDS waits must be exact (no tile copy known to the compiler forces them to zero)
+    waits = re.findall(r"lgkmcnt\((\d+)\)", loop)
+    assert sum(1 for w in waits if w != "0") > len(waits) // 2
+
+
+def test_general_dkdv_leaves_half_the_accumulation_file():
+    asm = _asm("lvx_bwd_dkdv_bf16.hip")
+    body = _kernel(asm, "bwd_dkdv_bf16_kernelILi128ELb1E")
+    for blk in _blocks(body):
+        if "v_mfma_f32_32x32x16_bf16" in blk:
+            assert "v_accvgpr" not in blk, "accumulator moved next to matrix instructions"
+    # kernel metadata: ".agpr_count: N" precedes the ".name:" entry of its kernel
+    m = re.search(r"\.agpr_count:\s*(\d+)\n(?:(?!\.agpr_count).*\n)*?\s*\.name:\s*\S*bwd_dkdv_bf16_kernelILi128ELb1E", asm)
+    assert m and int(m.group(1)) <= 128
