@@ -168,6 +168,10 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   }
 
   // ---- K operands of this wave's keys: lane holds key j_wave0 + 32 kb + kl, columns 16 ks + 8 g ..
+  // They are held as bf16(K * scale * log2 e), so that the accumulation Q K'^T started at -L log2 e
+  // is already the exponent of P (Algorithm 2's recomputation P = exp(S - L)) and needs no
+  // multiply-add per element; dK uses Q and dS only, so nothing else sees the scaled copy.
+  const float c2 = d.scale * LOG2E;
   bf16x8 kf[KVB][KS];
 #pragma unroll
   for (int kb = 0; kb < KVB; ++kb) {
@@ -177,6 +181,9 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
     for (int ks = 0; ks < KS; ++ks) {
       u32x4 x = {0, 0, 0, 0};
       if (j < d.Skv) x = *(const u32x4*)((const uint16_t*)a.k + off + 16 * ks + 8 * g);
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+        x[w] = pack2_bf16(__uint_as_float(x[w] << 16) * c2, __uint_as_float(x[w] & 0xffff0000u) * c2);
       kf[kb][ks] = __builtin_bit_cast(bf16x8, x);
     }
   }
@@ -195,7 +202,6 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   for (int kb = 0; kb < KVB; ++kb)
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(kf[kb][ks]));
-  const float c2 = d.scale * LOG2E;
 
   // ---- tile copies.  In the interleaved tile the logical rows 4 j + w (j = 0..7) of Q occupy the
   // 8 consecutive physical rows 20 w .. 20 w + 7, and those of dO the next 8: a "run" of 8 SPR
@@ -216,33 +222,47 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
     const int sl = run_start(c) + lane;
     cp_off[c] = (unsigned)(4 * (sl / SM::SPR)) * row_bytes + (unsigned)min(sl % SM::SPR, CPR - 1) * 16;
   }
-  auto issue_tile = [&](const Cursor& c, char* st) __attribute__((always_inline)) {
+  // One step's copies: the scalar part (tile addresses) and the copies themselves, numbered
+  // 0 .. NDMA - 1 so that the dense loop can spread them over the matrix instructions of a phase.
+  constexpr int NDMA = 2 * NCR + 1;                // copies per wave and step
+  struct Tile { const char *qb, *gb, *lb; char* dst; int rows; long tile; };
+  auto tile_of = [&](const Cursor& c, char* st) __attribute__((always_inline)) -> Tile {
     // (wave-uniform by construction; said explicitly because with a media mask the cursor derives
     // from bitmap words read through the vector path)
     const int hq = __builtin_amdgcn_readfirstlane(hk * G + c.h), i0 = __builtin_amdgcn_readfirstlane(c.i0);
-    const long tile = ((long)hq * d.q_sh + (long)i0 * d.q_ss) * 2;
-    const char* qb = q0 + tile + (long)wave * row_bytes;        // this wave's first row: tile row w
-    const char* gb = g0 + tile + (long)wave * row_bytes;
-    const int rows = min(KM, d.Sq - i0);
-    char* const qdst = st + 20 * wave * SM::P;
-    char* const gdst = qdst + 8 * SM::P;
-    if (!GENERAL || rows == KM) {
+    Tile t;
+    t.tile = ((long)hq * d.q_sh + (long)i0 * d.q_ss) * 2;
+    t.qb = q0 + t.tile + (long)wave * row_bytes;   // this wave's first row: tile row w
+    t.gb = g0 + t.tile + (long)wave * row_bytes;
+    t.lb = l0 + ((long)hq * a.sq_pad + i0) * 8;
+    t.rows = min(KM, d.Sq - i0);
+    t.dst = st;
+    return t;
+  };
+  auto issue_part = [&](const Tile& t, int k) __attribute__((always_inline)) {   // full tiles only
+    char* const qdst = t.dst + 20 * wave * SM::P;
+    if (k == NDMA - 1) dma4s(t.lb, lane * 4, t.dst + SM::STAT_OFF);
+    else if (k % 2 == 0) dma16s(t.qb, cp_off[k / 2], qdst + run_start(k / 2) * 16);
+    else dma16s(t.gb, cp_off[k / 2], qdst + 8 * SM::P + run_start(k / 2) * 16);
+  };
+  auto issue_tile = [&](const Cursor& c, char* st) __attribute__((always_inline)) {
+    const Tile t = tile_of(c, st);
+    if (!GENERAL || t.rows == KM) {
 #pragma unroll
-      for (int c = 0; c < NCR; ++c) {
-        dma16s(qb, cp_off[c], qdst + run_start(c) * 16);
-        dma16s(gb, cp_off[c], gdst + run_start(c) * 16);
-      }
-    } else {                                       // ragged last tile of a head: clamp the rows
-#pragma unroll
-      for (int c = 0; c < NCR; ++c) {
-        const int sl = run_start(c) + lane;
-        const unsigned r = (unsigned)min(4 * (sl / SM::SPR) + wave, rows - 1);     // row of the tile
-        const unsigned off = r * row_bytes + (unsigned)min(sl % SM::SPR, CPR - 1) * 16;
-        dma16s(q0 + tile, off, qdst + run_start(c) * 16);
-        dma16s(g0 + tile, off, gdst + run_start(c) * 16);
-      }
+      for (int k = 0; k < NDMA; ++k) issue_part(t, k);
+      return;
     }
-    dma4s(l0 + ((long)hq * a.sq_pad + i0) * 8, lane * 4, st + SM::STAT_OFF);
+    char* const qdst = st + 20 * wave * SM::P;     // ragged last tile of a head: clamp the rows
+    char* const gdst = qdst + 8 * SM::P;
+#pragma unroll
+    for (int c = 0; c < NCR; ++c) {
+      const int sl = run_start(c) + lane;
+      const unsigned r = (unsigned)min(4 * (sl / SM::SPR) + wave, t.rows - 1);     // row of the tile
+      const unsigned off = r * row_bytes + (unsigned)min(sl % SM::SPR, CPR - 1) * 16;
+      dma16s(q0 + t.tile, off, qdst + run_start(c) * 16);
+      dma16s(g0 + t.tile, off, gdst + run_start(c) * 16);
+    }
+    dma4s(t.lb, lane * 4, st + SM::STAT_OFF);
   };
 
   f32x16 dk[KVB][DB], dv[KVB][DB];
@@ -256,16 +276,16 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   // LDS operands of a k-step are fetched while the matrix instructions of the previous one run.
   auto score = [&](const char* __restrict__ t, const char* __restrict__ vw, f32x16 (&s)[KVB],
                    f32x16 (&p)[KVB], auto&& per_unit) __attribute__((always_inline)) {
-    // dP starts at -delta of its query row (the statistics hold -delta), so that dP - delta needs
-    // no vector instruction
+    // The accumulations start at the statistics of their query rows: S at -L log2 e, dP at
+    // -delta, so that neither difference needs a vector instruction
 #pragma unroll
     for (int kb = 0; kb < KVB; ++kb) {
-      s[kb] = zero16();
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
+        const f32x4 nl = *(const f32x4*)(t + SM::STAT_OFF + (8 * q4 + 4 * g) * 4);
         const f32x4 nd = *(const f32x4*)(t + SM::STAT_OFF + 128 + (8 * q4 + 4 * g) * 4);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) p[kb][4 * q4 + e] = nd[e];
+        for (int e = 0; e < 4; ++e) { s[kb][4 * q4 + e] = nl[e]; p[kb][4 * q4 + e] = nd[e]; }
       }
     }
     const char* qrow = t + ilv_off<D>(kl, 0, 8 * g);
@@ -313,31 +333,24 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
       }
   };
   // Conversion of scores into operands, element x of a step (x = 0 .. 16 KVB - 1: four query rows
-  // q4 = x / (4 KVB) of key block kb = (x / 4) % KVB, row e = x % 4 of the four): p = exp2(s c2 - L2), dS = p (dP -
-  // delta) with the difference already formed by the accumulation, packed in pairs as bf16 into word 2 (q4 % 2) + e / 2 of operand q4 / 2 of the key block.
-  struct Conv { f32x4 l4; };
+  // q4 = x / (4 KVB) of key block kb = (x / 4) % KVB, row e = x % 4 of the four): p = exp2(s), dS = p dP,
+  // both differences already formed by the accumulation, packed in pairs as bf16 into word
+  // 2 (q4 % 2) + e / 2 of operand q4 / 2 of the key block.
   struct Carry { float pr, ds; };
-  auto conv_stats = [&](const char* __restrict__ t, int q4, Conv& cv) __attribute__((always_inline)) {
-    cv.l4 = *(const f32x4*)(t + SM::STAT_OFF + (8 * q4 + 4 * g) * 4);
-  };
-  auto conv_elem = [&](int x, const Conv& cv, Carry& cy, const f32x16 (&s)[KVB], const f32x16 (&p)[KVB],
+  auto conv_elem = [&](int x, Carry& cy, const f32x16 (&s)[KVB], const f32x16 (&p)[KVB],
                        u32x4 (&pwo)[KVB][2], u32x4 (&swo)[KVB][2]) __attribute__((always_inline)) {
     const int q4 = x / (4 * KVB), kb = (x / 4) % KVB, e = x % 4, v = 4 * q4 + e;
-    const float pr = __builtin_amdgcn_exp2f(fmaf(s[kb][v], c2, -cv.l4[e]));
-    const float ds = pr * p[kb][v];                 // p already holds dP - delta
+    const float pr = __builtin_amdgcn_exp2f(s[kb][v]);
+    const float ds = pr * p[kb][v];
     if (e % 2 == 0) { cy.pr = pr; cy.ds = ds; return; }
     pwo[kb][q4 >> 1][2 * (q4 & 1) + e / 2] = pack2_bf16(cy.pr, pr);
     swo[kb][q4 >> 1][2 * (q4 & 1) + e / 2] = pack2_bf16(cy.ds, ds);
   };
-  auto convert = [&](const char* __restrict__ t, const f32x16 (&s)[KVB], const f32x16 (&p)[KVB],
+  auto convert = [&](const f32x16 (&s)[KVB], const f32x16 (&p)[KVB],
                      u32x4 (&pwo)[KVB][2], u32x4 (&swo)[KVB][2]) __attribute__((always_inline)) {
-    Conv cv;
     Carry cy;
 #pragma unroll
-    for (int x = 0; x < 16 * KVB; ++x) {
-      if (x % (4 * KVB) == 0) conv_stats(t, x / (4 * KVB), cv);
-      conv_elem(x, cv, cy, s, p, pwo, swo);
-    }
+    for (int x = 0; x < 16 * KVB; ++x) conv_elem(x, cy, s, p, pwo, swo);
   };
   // dV^T += dO^T P and dK^T += Q^T dS of one step (two k-steps of 16 query rows)
   auto contract = [&](const char* __restrict__ t, const u32x4 (&pwi)[KVB][2], const u32x4 (&swi)[KVB][2]) __attribute__((always_inline)) {
@@ -358,7 +371,7 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   // matrix instruction is followed by the conversion of 32 / (8 DB) elements, and nothing is
   // scheduled across these units, so the two pipes stay busy together.  The transposed operands of
   // a group of four matrix instructions are fetched one group ahead.
-  auto contract_convert = [&](const char* __restrict__ t0, const char* __restrict__ t1,
+  auto contract_convert = [&](const char* __restrict__ t0,
                               const u32x4 (&pwi)[KVB][2], const u32x4 (&swi)[KVB][2],
                               const f32x16 (&s)[KVB], const f32x16 (&p)[KVB],
                               u32x4 (&pwo)[KVB][2], u32x4 (&swo)[KVB][2]) __attribute__((always_inline)) {
@@ -366,9 +379,7 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
     bf16x8 gt[2], qt[2];                           // two operand sets, used alternately
     gt[0] = load_tr_operand_ilv<D>(t0, KM, 0, lane);
     qt[0] = load_tr_operand_ilv<D>(t0, 0, 0, lane);
-    Conv cv[2];
     Carry cy;
-    conv_stats(t1, 0, cv[0]);
 #pragma unroll
     for (int m = 0; m < NM; ++m) {
       const int c = m / (2 * KVB), t2 = c / DB, db = c % DB, j = m % (2 * KVB), cu = c & 1;
@@ -379,11 +390,7 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
       if (j % 2 == 0) mfma32_acc<GENERAL>(dv[j / 2][db], gt[cu], __builtin_bit_cast(bf16x8, pwi[j / 2][t2]));
       else mfma32_acc<GENERAL>(dk[j / 2][db], qt[cu], __builtin_bit_cast(bf16x8, swi[j / 2][t2]));
 #pragma unroll
-      for (int x = m * EPM; x < (m + 1) * EPM && x < XE; ++x) {
-        const int q4 = x / (4 * KVB);
-        if (x % (4 * KVB) == 0 && 4 * KVB * (q4 + 1) < XE) conv_stats(t1, q4 + 1, cv[(q4 + 1) & 1]);   // one q4 ahead
-        conv_elem(x, cv[q4 & 1], cy, s, p, pwo, swo);
-      }
+      for (int x = m * EPM; x < (m + 1) * EPM && x < XE; ++x) conv_elem(x, cy, s, p, pwo, swo);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -392,7 +399,6 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   // Iteration i contracts step i while converting step i + 1 (already scored); then, at the one
   // barrier of the iteration, every wave is done with step i, whose stage takes step i + 4, and
   // step i + 2 -- issued two iterations ago -- has landed; then step i + 2 is scored.
-  constexpr int NDMA = 2 * NCR + 1;                // copies per wave and step
   int e[NSTG + 1];                                 // step ids of steps i .. i + 4 (static indexing only)
 #pragma unroll
   for (int q = 0; q <= NSTG; ++q) e[q] = n_all;
@@ -413,7 +419,7 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   if (n > 0) {
     score(smem, vw, s, p, nothing);
     mask_scores(e[0], s);
-    convert(smem, s, p, pf0, sf0);
+    convert(s, p, pf0, sf0);
     if (n > 1) { score(smem + SM::STAGE, vw, s, p, nothing); mask_scores(e[1], s); }
   }
   auto mid = [&](auto all_in_flight, bool issue, char* st_copy) __attribute__((always_inline)) {
@@ -430,27 +436,40 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
       advance(cursor);
     }
   };
-  auto full_iter = [&](char* st_copy, const char* __restrict__ t0,
-                       const char* __restrict__ t1, const char* __restrict__ t2,
+  auto full_iter = [&](char* st_copy, const char* __restrict__ t0, const char* __restrict__ t2,
                        const char* __restrict__ vw_, const u32x4 (&pfi)[KVB][2],
                        const u32x4 (&sfi)[KVB][2], u32x4 (&pfo)[KVB][2], u32x4 (&sfo)[KVB][2]) __attribute__((always_inline)) {
-    contract_convert(t0, t1, pfi, sfi, s, p, pfo, sfo);
-    mid(std::bool_constant<!GENERAL>{}, true, st_copy);
-    score(t2, vw_, s, p, nothing);
+    contract_convert(t0, pfi, sfi, s, p, pfo, sfo);
+    if constexpr (GENERAL) {
+      mid(std::false_type{}, true, st_copy);
+      score(t2, vw_, s, p, nothing);
+    } else {
+      // the copies of step i + 4 go out one at a time between the matrix instructions of the
+      // score phase, where the issue slots are otherwise idle
+      mid(std::true_type{}, false, st_copy);
+      e[4] = cursor.s;
+      const Tile tl = tile_of(cursor, st_copy);
+      advance(cursor);
+      constexpr int NU = 2 * KVB * KS, EVERY = NU / NDMA;
+      static_assert(EVERY >= 1, "more copies than matrix instructions in the score phase");
+      score(t2, vw_, s, p, [&](int m) __attribute__((always_inline)) {
+        if (m % EVERY == EVERY - 1 && m / EVERY < NDMA) issue_part(tl, m / EVERY);
+      });
+    }
     mask_scores(e[2], s);
     e[0] = e[1]; e[1] = e[2]; e[2] = e[3]; e[3] = e[4];
   };
   auto stage = [&](int q) __attribute__((always_inline)) -> char* { return smem + (q % NSTG) * SM::STAGE; };
   int i = 0;
   while (i + 5 < n) {                              // two full iterations per trip, each issuing a step
-    full_iter(stage(i), stage(i), stage(i + 1), stage(i + 2), vw, pf0, sf0, pf1, sf1);
-    full_iter(stage(i + 1), stage(i + 1), stage(i + 2), stage(i + 3), vw, pf1, sf1, pf0, sf0);
+    full_iter(stage(i), stage(i), stage(i + 2), vw, pf0, sf0, pf1, sf1);
+    full_iter(stage(i + 1), stage(i + 1), stage(i + 3), vw, pf1, sf1, pf0, sf0);
     i += 2;
   }
   for (; i < n; ++i) {                             // the last (at most five) iterations
     contract(stage(i), pf0, sf0);
     mid(std::false_type{}, i + 4 < n, stage(i));
-    if (i + 1 < n) convert(stage(i + 1), s, p, pf0, sf0);
+    if (i + 1 < n) convert(s, p, pf0, sf0);
     if (i + 2 < n) { score(stage(i + 2), vw, s, p, nothing); mask_scores(e[2], s); }
     e[0] = e[1]; e[1] = e[2]; e[2] = e[3]; e[3] = e[4];
   }

@@ -120,7 +120,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
 
   // ---- stationary operands and statistics of this lane's query rows i_wave0 + 32 qb + ql
   bf16x8 qf[QB][KS], gf[QB][KS];
-  float l2[QB], nd[QB];                // L log2(e) (+inf: no probability mass) and -delta
+  float nl2[QB], nd[QB];               // -L log2(e) (-inf: no probability mass) and -delta
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     const int i = i_wave0 + 32 * qb + ql;
@@ -136,11 +136,11 @@ bwd_dq_bf16_kernel(BwdArgs a) {
       qf[qb][ks] = __builtin_bit_cast(bf16x8, x);
       gf[qb][ks] = __builtin_bit_cast(bf16x8, y);
     }
-    l2[qb] = INFINITY;
+    nl2[qb] = -INFINITY;
     nd[qb] = 0.f;
     if (ok) {
       const long slot = (((long)b * d.Hq + hq) * a.sq_pad + (i & ~31)) * 2 + (i & 31);
-      l2[qb] = a.stats[slot];
+      nl2[qb] = a.stats[slot];
       nd[qb] = a.stats[slot + 32];
     }
   }
@@ -153,7 +153,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
       asm volatile("" : "+a"(qf[qb][ks]));
       asm volatile("" : "+a"(gf[qb][ks]));
     }
-    asm volatile("" : "+v"(l2[qb]), "+v"(nd[qb]));
+    asm volatile("" : "+v"(nl2[qb]), "+v"(nd[qb]));
   }
   const float c2 = d.scale * LOG2E;
 
@@ -312,7 +312,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   auto conv_elem = [&](int x, Carry& cy, const f32x16 (&s)[QB], const f32x16 (&p)[QB],
                        u32x4 (&dsw)[QB][2]) __attribute__((always_inline)) {
     const int qb = x / 16, v = x % 16;
-    const float pr = __builtin_amdgcn_exp2f(fmaf(s[qb][v], c2, -l2[qb]));
+    const float pr = __builtin_amdgcn_exp2f(fmaf(s[qb][v], c2, nl2[qb]));
     const float ds = pr * (p[qb][v] + nd[qb]);
     if (v % 2 == 0) { cy.ds = ds; return; }
     dsw[qb][v / 8][(v % 8) / 2] = pack2_bf16(cy.ds, ds);

@@ -104,7 +104,7 @@ hipError_t launch_merge(const MergeArgs& a, int part_is_f32, int out_is_f32, hip
 // delta[b,h,i] = sum_d dO[b,h,i,d] * O[b,h,i,d].  16 lanes per row.  The bf16 kernels read the
 // row statistics 32 rows at a time with aligned copies, so a padded, grouped copy is written as
 // well: stats[B,Hq,sq_pad/32][2][32] (sq_pad a multiple of 32) holds, per group of 32 rows, 32
-// values of L * log2(e) -- +inf for rows without keys and for pad rows, which makes their
+// values of -L * log2(e) -- -inf for rows without keys and for pad rows, which makes their
 // probabilities exp2(-inf) = 0 -- followed by the 32 values of -delta (0 in pad rows).
 template <bool F32>
 __global__ void __launch_bounds__(256) delta_kernel(Dims d, const void* o, const void* d_o,
@@ -138,15 +138,15 @@ __global__ void __launch_bounds__(256) delta_kernel(Dims d, const void* o, const
 #pragma unroll
   for (int m = 8; m >= 1; m >>= 1) s += __shfl_xor(s, m, 16);
   if (c != 0) return;
-  float l2 = INFINITY;
+  float nl2 = -INFINITY;
   if (i < d.Sq) {
     const long row = (b * d.Hq + h) * d.Sq + i;
     delta[row] = s;
     const float L = lse[row];
-    if (L != -INFINITY) l2 = L * 1.4426950408889634f;
+    if (L != -INFINITY) nl2 = -L * 1.4426950408889634f;
   }
   const long slot = (rowp / 32) * 64 + rowp % 32;     // sq_pad is a multiple of 32
-  stats[slot] = l2;
+  stats[slot] = nl2;
   stats[slot + 32] = -s;
 }
 

@@ -40,7 +40,7 @@ struct BwdArgs {
   const float* lse;     // final statistic, [B,Hq,Sq]
   float* delta;         // workspace, [B,Hq,Sq]: rowsum(dO * O)
   float* stats;         // workspace, [B,Hq,sq_pad/32][2][32]: per group of 32 query rows, 32 values of
-                        // L * log2(e) (+inf for rows without keys and pad rows), then 32 of -delta
+                        // -L * log2(e) (-inf for rows without keys and pad rows), then 32 of -delta
   int sq_pad;           // Sq rounded up to a multiple of 32
   float* dq_accum;      // [B,Hq,Sq,D] float32, accumulated into
   void *dk, *dv;        // K's strides, input dtype, overwritten
