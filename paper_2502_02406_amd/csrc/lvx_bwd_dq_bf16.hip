@@ -82,6 +82,9 @@ __device__ __forceinline__ bf16x8 tile_tr_operand(const char* tile, int kbase, i
 __device__ __forceinline__ void mfma_first(f32x16& c, bf16x8 a, bf16x8 b_acc) {     // c = a b
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(c) : "v"(a), "a"(b_acc));
 }
+__device__ __forceinline__ void mfma_from(f32x16& c, bf16x8 a, bf16x8 b_acc, const f32x16& c0) {   // c = a b + c0
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(c) : "v"(a), "a"(b_acc), "v"(c0));
+}
 __device__ __forceinline__ void mfma_next(f32x16& c, bf16x8 a, bf16x8 b_acc) {      // c += a b
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "a"(b_acc));
 }
@@ -119,6 +122,12 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   int t_end = min(n_tiles, t_begin + tps);
 
   // ---- stationary operands and statistics of this lane's query rows i_wave0 + 32 qb + ql
+  // The dense variant folds the statistics into the matrix products (FOLD): Q is held as
+  // bf16(Q * scale * log2 e) and the accumulations start from 16 copies of -L log2 e and of -delta
+  // (a lane's registers all belong to one query row), so that S^T comes out as the exponent of P
+  // and dP^T as dP - delta without a vector instruction.
+  constexpr bool FOLD = !GENERAL;
+  const float c2 = d.scale * LOG2E;
   bf16x8 qf[QB][KS], gf[QB][KS];
   float nl2[QB], nd[QB];               // -L log2(e) (-inf: no probability mass) and -delta
 #pragma unroll
@@ -132,6 +141,11 @@ bwd_dq_bf16_kernel(BwdArgs a) {
       if (ok) {
         x = *(const u32x4*)((const uint16_t*)a.q + off + 16 * ks + 8 * g);
         y = *(const u32x4*)((const uint16_t*)a.d_o + off + 16 * ks + 8 * g);
+      }
+      if (FOLD) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+          x[w] = pack2_bf16(__uint_as_float(x[w] << 16) * c2, __uint_as_float(x[w] & 0xffff0000u) * c2);
       }
       qf[qb][ks] = __builtin_bit_cast(bf16x8, x);
       gf[qb][ks] = __builtin_bit_cast(bf16x8, y);
@@ -155,7 +169,15 @@ bwd_dq_bf16_kernel(BwdArgs a) {
     }
     asm volatile("" : "+v"(nl2[qb]), "+v"(nd[qb]));
   }
-  const float c2 = d.scale * LOG2E;
+  f32x16 nl2x[FOLD ? QB : 1], ndx[FOLD ? QB : 1];  // the starting values of the accumulations
+  if (FOLD) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) { nl2x[qb][v] = nl2[qb]; ndx[qb][v] = nd[qb]; }
+      asm volatile("" : "+v"(nl2x[qb]), "+v"(ndx[qb]));
+    }
+  }
 
   // ---- tiles this workgroup needs (media mask: tiles visible to none of its rows are skipped).
   // The window of the bitmap that its rows and key range can touch is copied to LDS, and the
@@ -272,10 +294,12 @@ bwd_dq_bf16_kernel(BwdArgs a) {
       for (int j = 0; j < 2 * QB; ++j) {           // S^T of both query blocks, then dP^T
         const int qb = j % QB;
         if (j < QB) {
-          if (ks == 0) mfma_first(s[qb], ka[cu], qf[qb][ks]);
+          if (ks == 0 && FOLD) mfma_from(s[qb], ka[cu], qf[qb][ks], nl2x[qb]);
+          else if (ks == 0) mfma_first(s[qb], ka[cu], qf[qb][ks]);
           else mfma_next(s[qb], ka[cu], qf[qb][ks]);
         } else {
-          if (ks == 0) mfma_first(p[qb], va[cu], gf[qb][ks]);
+          if (ks == 0 && FOLD) mfma_from(p[qb], va[cu], gf[qb][ks], ndx[qb]);
+          else if (ks == 0) mfma_first(p[qb], va[cu], gf[qb][ks]);
           else mfma_next(p[qb], va[cu], gf[qb][ks]);
         }
         per_unit(ks * 2 * QB + j);                 // vector work in the shadow of this instruction
@@ -306,14 +330,15 @@ bwd_dq_bf16_kernel(BwdArgs a) {
       }
   };
   // Conversion of scores into the dS operands, element x of a half (x = 0..31: query block
-  // qb = x / 16, register v = x % 16): p = exp2(s c2 - L2), dS = p (dP - delta), packed in pairs
-  // as bf16 into word (v % 8) / 2 of operand v / 8 of the query block.
+  // qb = x / 16, register v = x % 16): p = exp2(s c2 - L2), dS = p (dP - delta) -- with FOLD both
+  // differences were formed by the accumulation already -- packed in pairs as bf16 into word
+  // (v % 8) / 2 of operand v / 8 of the query block.
   struct Carry { float ds; };
   auto conv_elem = [&](int x, Carry& cy, const f32x16 (&s)[QB], const f32x16 (&p)[QB],
                        u32x4 (&dsw)[QB][2]) __attribute__((always_inline)) {
     const int qb = x / 16, v = x % 16;
-    const float pr = __builtin_amdgcn_exp2f(fmaf(s[qb][v], c2, nl2[qb]));
-    const float ds = pr * (p[qb][v] + nd[qb]);
+    const float pr = __builtin_amdgcn_exp2f(FOLD ? s[qb][v] : fmaf(s[qb][v], c2, nl2[qb]));
+    const float ds = pr * (FOLD ? p[qb][v] : p[qb][v] + nd[qb]);
     if (v % 2 == 0) { cy.ds = ds; return; }
     dsw[qb][v / 8][(v % 8) / 2] = pack2_bf16(cy.ds, ds);
   };
