@@ -273,16 +273,25 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   // S^T = K Q^T and dP^T = V dO^T: lane = query column, registers = keys.  The LDS operands of a
   // k-step are fetched while the matrix instructions of the previous one run; per_unit(m) is
   // vector work issued right after matrix instruction m (0 .. 4 KS - 1), to run in its shadow.
+  static_assert(PF == 1, "the hand-over of first operands between phases assumes one set in flight");
+  struct FirstKV { bf16x8 k, v; };                 // first operands of a score phase
+  auto first_kv = [&](const char* __restrict__ st, int hb) __attribute__((always_inline)) -> FirstKV {
+    const char* krow = st + tile_off<D>(ql, 32 * hb, 16 * g);
+    return {*(const bf16x8*)krow, *(const bf16x8*)(krow + SM::TILE)};
+  };
+  auto first_kt = [&](const char* __restrict__ st, int hb) __attribute__((always_inline)) -> bf16x8 {
+    return tile_tr_operand<D>(st, 32 * hb, 0, lane);
+  };
+  // first: the operands of k-step 0, fetched by the caller (during the previous phase in the
+  // steady state); tail(): issued three matrix instructions before the end, fetches the first
+  // operands of the next phase, so that no phase starts by waiting for LDS.
   auto score = [&](const char* __restrict__ st, int hb, f32x16 (&s)[QB], f32x16 (&p)[QB],
-                   auto&& per_unit) __attribute__((always_inline)) {
+                   auto&& per_unit, const FirstKV& first, auto&& tail) __attribute__((always_inline)) {
     const char* krow = st + tile_off<D>(ql, 32 * hb, 16 * g);
     const char* vrow = krow + SM::TILE;
     bf16x8 ka[PF + 1], va[PF + 1];                 // operand sets, used in rotation
-#pragma unroll
-    for (int i = 0; i < PF; ++i) {
-      ka[i] = *(const bf16x8*)(krow + i * 32);
-      va[i] = *(const bf16x8*)(vrow + i * 32);
-    }
+    ka[0] = first.k;
+    va[0] = first.v;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       const int cu = ks % (PF + 1), nx = (ks + PF) % (PF + 1);
@@ -303,12 +312,14 @@ bwd_dq_bf16_kernel(BwdArgs a) {
           else mfma_next(p[qb], va[cu], gf[qb][ks]);
         }
         per_unit(ks * 2 * QB + j);                 // vector work in the shadow of this instruction
+        if (ks * 2 * QB + j == 2 * QB * KS - 3) tail();
         __builtin_amdgcn_sched_barrier(0);
       }
     }
     asm volatile("s_nop 7" ::: "memory");          // the last results settle before anything reads them
   };
   auto nothing = [](int) __attribute__((always_inline)) {};
+  auto no_tail = []() __attribute__((always_inline)) {};
   // key tail and masked elements of a half's scores -> -inf (wave-uniform decision, rarely taken)
   auto mask_scores = [&](int t, int hb, f32x16 (&s)[QB]) __attribute__((always_inline)) {
     if (!GENERAL) return;
@@ -363,11 +374,10 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   // ahead, and nothing is scheduled across the units.
   auto contract_convert = [&](const char* __restrict__ st, int hb, const u32x4 (&dsi)[QB][2],
                               const f32x16 (&s)[QB], const f32x16 (&p)[QB], u32x4 (&dso)[QB][2],
-                              Carry& cy) __attribute__((always_inline)) {
+                              Carry& cy, bf16x8 first, auto&& tail) __attribute__((always_inline)) {
     constexpr int NM = 2 * DB * QB;                // matrix instructions
     bf16x8 kt[PF + 1];
-#pragma unroll
-    for (int i = 0; i < PF; ++i) kt[i] = tile_tr_operand<D>(st, 32 * hb + 16 * (i / DB), 32 * (i % DB), lane);
+    kt[0] = first;
 #pragma unroll
     for (int m = 0; m < NM; ++m) {
       const int c = m / QB, t2 = c / DB, db = c % DB, qb = m % QB, cu = c % (PF + 1);
@@ -376,18 +386,19 @@ bwd_dq_bf16_kernel(BwdArgs a) {
       mfma_acc(dq[qb][db], kt[cu], __builtin_bit_cast(bf16x8, dsi[qb][t2]));
 #pragma unroll
       for (int x = m * XE / NM; x < (m + 1) * XE / NM; ++x) conv_elem(x, cy, s, p, dso);
+      if (m == NM - 3) tail();
       __builtin_amdgcn_sched_barrier(0);
     }
   };
   // score(half h+2) together with the remaining conversions of half h+1
   auto score_convert = [&](const char* __restrict__ st, int hb, f32x16 (&s_new)[QB], f32x16 (&p_new)[QB],
                            const f32x16 (&s)[QB], const f32x16 (&p)[QB], u32x4 (&dso)[QB][2],
-                           Carry& cy) __attribute__((always_inline)) {
+                           Carry& cy, const FirstKV& first, auto&& tail) __attribute__((always_inline)) {
     constexpr int NU = 2 * QB * KS;                // matrix instructions of a score phase
     score(st, hb, s_new, p_new, [&](int m) __attribute__((always_inline)) {
 #pragma unroll
       for (int x = XE + m * (32 - XE) / NU; x < XE + (m + 1) * (32 - XE) / NU; ++x) conv_elem(x, cy, s, p, dso);
-    });
+    }, first, tail);
   };
 
   // ---- pipeline.  Tile number q of the sequence lives in ring stage q % 4.  Per tile T (halves
@@ -427,20 +438,24 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   u32x4 ds0[QB][2] = {}, ds1[QB][2] = {};          // packed dS operands of even / odd halves
   Carry cy;
   if (nt > 0) {
-    score(smem, 0, s0, p0, nothing);
+    score(smem, 0, s0, p0, nothing, first_kv(smem, 0), no_tail);
     mask_scores(e[0], 0, s0);
     convert(s0, p0, ds0);
-    score(smem, 1, s1, p1, nothing);
+    score(smem, 1, s1, p1, nothing, first_kv(smem, 1), no_tail);
     mask_scores(e[0], 1, s1);
   }
   int T = 0;
+  FirstKV fkv;
+  bf16x8 fkt = first_kt(smem, 0);                  // handed from phase to phase
   for (; T + 4 < nt; ++T) {                        // full tiles: tile T + 1 is scored, tile T + 4 issued
-    contract_convert(stage(T), 0, ds0, s1, p1, ds1, cy);
-    score_convert(stage(T + 1), 0, s0, p0, s1, p1, ds1, cy);
+    char* const sa = stage(T);
+    char* const sb = stage(T + 1);
+    contract_convert(sa, 0, ds0, s1, p1, ds1, cy, fkt, [&]() __attribute__((always_inline)) { fkv = first_kv(sb, 0); });
+    score_convert(sb, 0, s0, p0, s1, p1, ds1, cy, fkv, [&]() __attribute__((always_inline)) { fkt = first_kt(sa, 1); });
     mask_scores(e[1], 0, s0);
-    contract_convert(stage(T), 1, ds1, s0, p0, ds0, cy);
-    mid(std::bool_constant<!GENERAL>{}, true, stage(T));
-    score_convert(stage(T + 1), 1, s1, p1, s0, p0, ds0, cy);
+    contract_convert(sa, 1, ds1, s0, p0, ds0, cy, fkt, [&]() __attribute__((always_inline)) { fkv = first_kv(sb, 1); });
+    mid(std::bool_constant<!GENERAL>{}, true, sa);
+    score_convert(sb, 1, s1, p1, s0, p0, ds0, cy, fkv, [&]() __attribute__((always_inline)) { fkt = first_kt(sb, 0); });
     mask_scores(e[1], 1, s1);
     e[0] = e[1]; e[1] = e[2]; e[2] = e[3]; e[3] = e[4];
   }
@@ -448,11 +463,11 @@ bwd_dq_bf16_kernel(BwdArgs a) {
     const bool more = T + 1 < nt;
     contract(stage(T), 0, ds0);
     convert(s1, p1, ds1);
-    if (more) { score(stage(T + 1), 0, s0, p0, nothing); mask_scores(e[1], 0, s0); }
+    if (more) { score(stage(T + 1), 0, s0, p0, nothing, first_kv(stage(T + 1), 0), no_tail); mask_scores(e[1], 0, s0); }
     contract(stage(T), 1, ds1);
     if (more) convert(s0, p0, ds0);
     mid(std::false_type{}, T + 4 < nt, stage(T));
-    if (more) { score(stage(T + 1), 1, s1, p1, nothing); mask_scores(e[1], 1, s1); }
+    if (more) { score(stage(T + 1), 1, s1, p1, nothing, first_kv(stage(T + 1), 1), no_tail); mask_scores(e[1], 1, s1); }
     e[0] = e[1]; e[1] = e[2]; e[2] = e[3]; e[3] = e[4];
   }
 
