@@ -237,28 +237,32 @@ bwd_dq_bf16_kernel(BwdArgs a) {
     const int sl = run_start(c) + lane;
     cp_off[c] = (unsigned)(4 * (sl / SM::SPR)) * row_bytes + (unsigned)min(sl % SM::SPR, CPR - 1) * 16;
   }
+  // A tile's copies are numbered 0 .. NDMA - 1, so that the dense loop can spread them over the
+  // matrix instructions of a phase: issued back to back, each waits for the one before it to be
+  // accepted by the memory pipeline, and the wave would stand still for hundreds of cycles.
+  auto issue_part = [&](int t, char* st, int k) __attribute__((always_inline)) {   // full tiles only
+    const long tile = (long)t * TN * row_bytes + (long)wave * row_bytes;           // this wave's first row: tile row w
+    char* const kdst = st + wave * SM::GS;
+    if (k % 2 == 0) dma16s(k0 + tile, cp_off[k / 2], kdst + run_start(k / 2) * 16);
+    else dma16s(v0 + tile, cp_off[k / 2], kdst + SM::TILE + run_start(k / 2) * 16);
+  };
   auto issue_tile = [&](int t, char* st) __attribute__((always_inline)) {
-    const long tile = (long)t * TN * row_bytes;
     const int rows = min(TN, d.Skv - t * TN);
+    if (!GENERAL || rows == TN) {
+#pragma unroll
+      for (int k = 0; k < 2 * NCR; ++k) issue_part(t, st, k);
+      return;
+    }
+    const long tile = (long)t * TN * row_bytes;    // ragged last tile: clamp the rows
     char* const kdst = st + wave * SM::GS;
     char* const vdst = kdst + SM::TILE;
-    if (!GENERAL || rows == TN) {
-      const char* kb = k0 + tile + (long)wave * row_bytes;     // this wave's first row: tile row w
-      const char* vb = v0 + tile + (long)wave * row_bytes;
 #pragma unroll
-      for (int c = 0; c < NCR; ++c) {
-        dma16s(kb, cp_off[c], kdst + run_start(c) * 16);
-        dma16s(vb, cp_off[c], vdst + run_start(c) * 16);
-      }
-    } else {                                       // ragged last tile: clamp the rows
-#pragma unroll
-      for (int c = 0; c < NCR; ++c) {
-        const int sl = run_start(c) + lane;
-        const unsigned r = (unsigned)min(4 * (sl / SM::SPR) + wave, rows - 1);
-        const unsigned off = r * row_bytes + (unsigned)min(sl % SM::SPR, CPR - 1) * 16;
-        dma16s(k0 + tile, off, kdst + run_start(c) * 16);
-        dma16s(v0 + tile, off, vdst + run_start(c) * 16);
-      }
+    for (int c = 0; c < NCR; ++c) {
+      const int sl = run_start(c) + lane;
+      const unsigned r = (unsigned)min(4 * (sl / SM::SPR) + wave, rows - 1);
+      const unsigned off = r * row_bytes + (unsigned)min(sl % SM::SPR, CPR - 1) * 16;
+      dma16s(k0 + tile, off, kdst + run_start(c) * 16);
+      dma16s(v0 + tile, off, vdst + run_start(c) * 16);
     }
   };
   constexpr int NDMA = 2 * NCR;                    // copies per wave and tile
@@ -393,11 +397,12 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   // score(half h+2) together with the remaining conversions of half h+1
   auto score_convert = [&](const char* __restrict__ st, int hb, f32x16 (&s_new)[QB], f32x16 (&p_new)[QB],
                            const f32x16 (&s)[QB], const f32x16 (&p)[QB], u32x4 (&dso)[QB][2],
-                           Carry& cy, const FirstKV& first, auto&& tail) __attribute__((always_inline)) {
+                           Carry& cy, const FirstKV& first, auto&& tail, auto&& extra) __attribute__((always_inline)) {
     constexpr int NU = 2 * QB * KS;                // matrix instructions of a score phase
     score(st, hb, s_new, p_new, [&](int m) __attribute__((always_inline)) {
 #pragma unroll
       for (int x = XE + m * (32 - XE) / NU; x < XE + (m + 1) * (32 - XE) / NU; ++x) conv_elem(x, cy, s, p, dso);
+      extra(m);
     }, first, tail);
   };
 
@@ -451,11 +456,24 @@ bwd_dq_bf16_kernel(BwdArgs a) {
     char* const sa = stage(T);
     char* const sb = stage(T + 1);
     contract_convert(sa, 0, ds0, s1, p1, ds1, cy, fkt, [&]() __attribute__((always_inline)) { fkv = first_kv(sb, 0); });
-    score_convert(sb, 0, s0, p0, s1, p1, ds1, cy, fkv, [&]() __attribute__((always_inline)) { fkt = first_kt(sa, 1); });
+    score_convert(sb, 0, s0, p0, s1, p1, ds1, cy, fkv, [&]() __attribute__((always_inline)) { fkt = first_kt(sa, 1); }, nothing);
     mask_scores(e[1], 0, s0);
     contract_convert(sa, 1, ds1, s0, p0, ds0, cy, fkt, [&]() __attribute__((always_inline)) { fkv = first_kv(sb, 1); });
-    mid(std::bool_constant<!GENERAL>{}, true, sa);
-    score_convert(sb, 1, s1, p1, s0, p0, ds0, cy, fkv, [&]() __attribute__((always_inline)) { fkt = first_kt(sb, 0); });
+    if constexpr (GENERAL) {
+      mid(std::false_type{}, true, sa);
+      score_convert(sb, 1, s1, p1, s0, p0, ds0, cy, fkv, [&]() __attribute__((always_inline)) { fkt = first_kt(sb, 0); }, nothing);
+    } else {
+      mid(std::true_type{}, false, sa);
+      const int t_new = cursor;                    // the copies of tile T + 4 go out during the phase
+      e[4] = t_new;
+      cursor = next_tile(cursor + 1);
+      constexpr int EVERY = 2 * QB * KS / NDMA;
+      static_assert(EVERY >= 1, "more copies than matrix instructions in the score phase");
+      score_convert(sb, 1, s1, p1, s0, p0, ds0, cy, fkv, [&]() __attribute__((always_inline)) { fkt = first_kt(sb, 0); },
+                    [&](int m) __attribute__((always_inline)) {
+                      if (m % EVERY == EVERY - 1 && m / EVERY < NDMA) issue_part(t_new, sa, m / EVERY);
+                    });
+    }
     mask_scores(e[1], 1, s1);
     e[0] = e[1]; e[1] = e[2]; e[2] = e[3]; e[3] = e[4];
   }
