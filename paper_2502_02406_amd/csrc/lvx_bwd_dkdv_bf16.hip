@@ -274,27 +274,38 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   // ---- building blocks ------------------------------------------------------------------------
   // S = Q K^T and dP = dO V^T of one step: lane = key column, registers = query rows.  The four
   // LDS operands of a k-step are fetched while the matrix instructions of the previous one run.
-  auto score = [&](const char* __restrict__ t, const char* __restrict__ vw, f32x16 (&s)[KVB],
-                   f32x16 (&p)[KVB], auto&& per_unit) __attribute__((always_inline)) {
-    // The accumulations start at the statistics of their query rows: S at -L log2 e, dP at
-    // -delta, so that neither difference needs a vector instruction
+  // What a score phase needs before its first matrix instruction: the operands of k-step 0 and the
+  // starting values of the accumulations, which are the statistics of the query rows -- S starts
+  // at -L log2 e and dP at -delta, so that neither difference needs a vector instruction.  The
+  // dense loop fetches them while the previous phase still computes.
+  struct FirstY { bf16x8 qa, ga, va[KVB]; f32x16 nl, nd; };
+  auto first_y = [&](const char* __restrict__ t, const char* __restrict__ vw) __attribute__((always_inline)) -> FirstY {
+    FirstY f;
+    f.qa = *(const bf16x8*)(t + ilv_off<D>(kl, 0, 8 * g));
+    f.ga = *(const bf16x8*)(t + ilv_off<D>(kl, KM, 8 * g));
 #pragma unroll
-    for (int kb = 0; kb < KVB; ++kb) {
+    for (int kb = 0; kb < KVB; ++kb) f.va[kb] = *(const bf16x8*)(vw + kb * 32 * SM::P);
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        const f32x4 nl = *(const f32x4*)(t + SM::STAT_OFF + (8 * q4 + 4 * g) * 4);
-        const f32x4 nd = *(const f32x4*)(t + SM::STAT_OFF + 128 + (8 * q4 + 4 * g) * 4);
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const f32x4 nl = *(const f32x4*)(t + SM::STAT_OFF + (8 * q4 + 4 * g) * 4);
+      const f32x4 nd = *(const f32x4*)(t + SM::STAT_OFF + 128 + (8 * q4 + 4 * g) * 4);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) { s[kb][4 * q4 + e] = nl[e]; p[kb][4 * q4 + e] = nd[e]; }
-      }
+      for (int e = 0; e < 4; ++e) { f.nl[4 * q4 + e] = nl[e]; f.nd[4 * q4 + e] = nd[e]; }
     }
+    return f;
+  };
+  // S = Q K^T and dP = dO V^T of one step: lane = key column, registers = query rows.  The four
+  // LDS operands of a k-step are fetched while the matrix instructions of the previous one run;
+  // per_unit(m) is issued right after matrix instruction m, tail() three instructions before the end.
+  auto score = [&](const char* __restrict__ t, const char* __restrict__ vw, f32x16 (&s)[KVB],
+                   f32x16 (&p)[KVB], auto&& per_unit, const FirstY& f, auto&& tail) __attribute__((always_inline)) {
     const char* qrow = t + ilv_off<D>(kl, 0, 8 * g);
     const char* grow = t + ilv_off<D>(kl, KM, 8 * g);
     bf16x8 qa[2], ga[2], va[2][KVB];               // two operand sets, used alternately
-    qa[0] = *(const bf16x8*)qrow;
-    ga[0] = *(const bf16x8*)grow;
+    qa[0] = f.qa;
+    ga[0] = f.ga;
 #pragma unroll
-    for (int kb = 0; kb < KVB; ++kb) va[0][kb] = *(const bf16x8*)(vw + kb * 32 * SM::P);
+    for (int kb = 0; kb < KVB; ++kb) va[0][kb] = f.va[kb];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       const int cu = ks & 1, nx = cu ^ 1;
@@ -307,14 +318,16 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
 #pragma unroll
       for (int j = 0; j < 2 * KVB; ++j) {          // S of both key blocks, then dP
         const int kb = j % KVB;
-        if (j < KVB) s[kb] = mfma32(qa[cu], kf[kb][ks], s[kb]);
-        else p[kb] = mfma32(ga[cu], va[cu][kb], p[kb]);
+        if (j < KVB) s[kb] = mfma32(qa[cu], kf[kb][ks], ks == 0 ? f.nl : s[kb]);
+        else p[kb] = mfma32(ga[cu], va[cu][kb], ks == 0 ? f.nd : p[kb]);
         per_unit(ks * 2 * KVB + j);                // vector work in the shadow of this instruction
+        if (ks * 2 * KVB + j == 2 * KVB * KS - 3) tail();
         __builtin_amdgcn_sched_barrier(0);
       }
     }
   };
   auto nothing = [](int) __attribute__((always_inline)) {};
+  auto no_tail = []() __attribute__((always_inline)) {};
   // masked elements of a step's scores -> -inf (wave-uniform decision, rarely taken)
   auto mask_scores = [&](int st, f32x16 (&s)[KVB]) __attribute__((always_inline)) {
     if (!GENERAL || !mk.allow) return;
@@ -371,14 +384,20 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   // matrix instruction is followed by the conversion of 32 / (8 DB) elements, and nothing is
   // scheduled across these units, so the two pipes stay busy together.  The transposed operands of
   // a group of four matrix instructions are fetched one group ahead.
+  struct FirstX { bf16x8 gt, qt; };                // the first transposed operands of a contraction
+  auto first_x = [&](const char* __restrict__ t0) __attribute__((always_inline)) -> FirstX {
+    return {load_tr_operand_ilv<D>(t0, KM, 0, lane), load_tr_operand_ilv<D>(t0, 0, 0, lane)};
+  };
+  // hook(m) is issued right after matrix instruction m.  From instruction NM - 4 on, every LDS
+  // read of step i has returned (its last operands are consumed there).
   auto contract_convert = [&](const char* __restrict__ t0,
                               const u32x4 (&pwi)[KVB][2], const u32x4 (&swi)[KVB][2],
                               const f32x16 (&s)[KVB], const f32x16 (&p)[KVB],
-                              u32x4 (&pwo)[KVB][2], u32x4 (&swo)[KVB][2]) __attribute__((always_inline)) {
+                              u32x4 (&pwo)[KVB][2], u32x4 (&swo)[KVB][2], const FirstX& f, auto&& hook) __attribute__((always_inline)) {
     constexpr int NM = 4 * KVB * DB, EPM = (XE + NM - 1) / NM;   // matrix instructions, elements per instruction
     bf16x8 gt[2], qt[2];                           // two operand sets, used alternately
-    gt[0] = load_tr_operand_ilv<D>(t0, KM, 0, lane);
-    qt[0] = load_tr_operand_ilv<D>(t0, 0, 0, lane);
+    gt[0] = f.gt;
+    qt[0] = f.qt;
     Carry cy;
 #pragma unroll
     for (int m = 0; m < NM; ++m) {
@@ -391,9 +410,11 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
       else mfma32_acc<GENERAL>(dk[j / 2][db], qt[cu], __builtin_bit_cast(bf16x8, swi[j / 2][t2]));
 #pragma unroll
       for (int x = m * EPM; x < (m + 1) * EPM && x < XE; ++x) conv_elem(x, cy, s, p, pwo, swo);
+      hook(m);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
+  constexpr int NM_X = 4 * KVB * DB;               // matrix instructions of a contraction
 
   // ---- pipeline over the needed steps.  Step number q of the sequence lives in ring stage q % 4.
   // Iteration i contracts step i while converting step i + 1 (already scored); then, at the one
@@ -417,10 +438,10 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   f32x16 s[KVB], p[KVB];
   u32x4 pf0[KVB][2] = {}, sf0[KVB][2] = {}, pf1[KVB][2] = {}, sf1[KVB][2] = {};   // packed P and dS operands
   if (n > 0) {
-    score(smem, vw, s, p, nothing);
+    score(smem, vw, s, p, nothing, first_y(smem, vw), no_tail);
     mask_scores(e[0], s);
     convert(s, p, pf0, sf0);
-    if (n > 1) { score(smem + SM::STAGE, vw, s, p, nothing); mask_scores(e[1], s); }
+    if (n > 1) { score(smem + SM::STAGE, vw, s, p, nothing, first_y(smem + SM::STAGE, vw), no_tail); mask_scores(e[1], s); }
   }
   auto mid = [&](auto all_in_flight, bool issue, char* st_copy) __attribute__((always_inline)) {
     // (The general variant may spill registers inside the loop; its spill stores are counted with
@@ -436,17 +457,30 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
       advance(cursor);
     }
   };
-  auto full_iter = [&](char* st_copy, const char* __restrict__ t0, const char* __restrict__ t2,
-                       const char* __restrict__ vw_, const u32x4 (&pfi)[KVB][2],
+  // One full iteration.  Dense variant: the barrier sits inside the contraction, right after the
+  // matrix instruction that consumes the last LDS operands of step i; behind it the first operands
+  // of the score phase (step i + 2, landed by then) are fetched while the contraction finishes, and
+  // the score phase in turn fetches the first operands of the next contraction (step i + 1) and
+  // sends out the copies of step i + 4 one at a time between its matrix instructions.
+  FirstX fx = first_x(smem);
+  FirstY fy;
+  auto full_iter = [&](char* st_copy, const char* __restrict__ t0, const char* __restrict__ t1,
+                       const char* __restrict__ t2, const char* __restrict__ vw_, const u32x4 (&pfi)[KVB][2],
                        const u32x4 (&sfi)[KVB][2], u32x4 (&pfo)[KVB][2], u32x4 (&sfo)[KVB][2]) __attribute__((always_inline)) {
-    contract_convert(t0, pfi, sfi, s, p, pfo, sfo);
+    auto next_x = [&]() __attribute__((always_inline)) { fx = first_x(t1); };
     if constexpr (GENERAL) {
+      contract_convert(t0, pfi, sfi, s, p, pfo, sfo, fx, nothing);
       mid(std::false_type{}, true, st_copy);
-      score(t2, vw_, s, p, nothing);
+      score(t2, vw_, s, p, nothing, first_y(t2, vw_), next_x);
     } else {
-      // the copies of step i + 4 go out one at a time between the matrix instructions of the
-      // score phase, where the issue slots are otherwise idle
-      mid(std::true_type{}, false, st_copy);
+      contract_convert(t0, pfi, sfi, s, p, pfo, sfo, fx, [&](int m) __attribute__((always_inline)) {
+        if (m == NM_X - 4) {
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // (nothing is in flight here any more)
+          mid(std::true_type{}, false, st_copy);
+          asm volatile("" ::: "memory");
+        }
+        if (m == NM_X - 3) fy = first_y(t2, vw_);
+      });
       e[4] = cursor.s;
       const Tile tl = tile_of(cursor, st_copy);
       advance(cursor);
@@ -454,7 +488,7 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
       static_assert(EVERY >= 1, "more copies than matrix instructions in the score phase");
       score(t2, vw_, s, p, [&](int m) __attribute__((always_inline)) {
         if (m % EVERY == EVERY - 1 && m / EVERY < NDMA) issue_part(tl, m / EVERY);
-      });
+      }, fy, next_x);
     }
     mask_scores(e[2], s);
     e[0] = e[1]; e[1] = e[2]; e[2] = e[3]; e[3] = e[4];
@@ -462,15 +496,15 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   auto stage = [&](int q) __attribute__((always_inline)) -> char* { return smem + (q % NSTG) * SM::STAGE; };
   int i = 0;
   while (i + 5 < n) {                              // two full iterations per trip, each issuing a step
-    full_iter(stage(i), stage(i), stage(i + 2), vw, pf0, sf0, pf1, sf1);
-    full_iter(stage(i + 1), stage(i + 1), stage(i + 3), vw, pf1, sf1, pf0, sf0);
+    full_iter(stage(i), stage(i), stage(i + 1), stage(i + 2), vw, pf0, sf0, pf1, sf1);
+    full_iter(stage(i + 1), stage(i + 1), stage(i + 2), stage(i + 3), vw, pf1, sf1, pf0, sf0);
     i += 2;
   }
   for (; i < n; ++i) {                             // the last (at most five) iterations
     contract(stage(i), pf0, sf0);
     mid(std::false_type{}, i + 4 < n, stage(i));
     if (i + 1 < n) convert(s, p, pf0, sf0);
-    if (i + 2 < n) { score(stage(i + 2), vw, s, p, nothing); mask_scores(e[2], s); }
+    if (i + 2 < n) { score(stage(i + 2), vw, s, p, nothing, first_y(stage(i + 2), vw), no_tail); mask_scores(e[2], s); }
     e[0] = e[1]; e[1] = e[2]; e[2] = e[3]; e[3] = e[4];
   }
 

@@ -1,66 +1,51 @@
 // bf16 forward kernel: the FlashAttention call of Algorithm 1 for a short query block against a
 // long local K/V block, on the gfx950 matrix cores.
 //
-// Workgroup = 8 wavefronts = 256 query rows of one (batch, query head), one workgroup per CU; each
-// wave owns 32 rows whose Q operands stay in registers for the whole kernel.  K/V tiles of 64 keys
-// travel HBM -> LDS by direct global-to-LDS copies (no staging registers) into a ring of four
-// stages, issued three tiles ahead, so that one barrier per tile is the only synchronisation and
-// memory latency has two full tiles of math to hide behind.
-// Per tile a wave computes S^T = K Q^T (keys in registers, one query column per lane), the online
-// softmax in that layout (row statistics are per-lane scalars; the two half-waves exchange one
-// value per tile), and O^T += V^T P^T with P^T taken straight from the score registers and V^T
-// fetched by transposing LDS reads.  The loop is software pipelined inside each wave: the score
-// product of tile t+1 is issued together with the softmax of tile t, so the matrix core and the
-// vector ALU of a SIMD work at the same time.  The running maximum is only raised when a tile
-// exceeds it by more than 2^6 (the result is still exact: any reference value cancels between the
-// numerator and the denominator), which removes the rescaling of O from almost every tile.
+// Workgroup = 4 wavefronts = 256 query rows of one (batch, query head), one wave per SIMD with
+// the whole register file.  A wave owns 64 query rows (two 32-row blocks): their Q operands and
+// the O^T accumulators live in the accumulation registers for the whole kernel, so every K or V
+// operand fetched from LDS feeds two matrix instructions.
+// K/V tiles of 64 keys travel HBM -> LDS by direct global-to-LDS copies into a ring of four
+// stages, issued two tiles ahead, one barrier per tile.
+// Transposed tiles S^T = K Q^T put one QUERY per lane (the softmax statistics are per-lane
+// scalars; the two half-waves exchange one value per half) and 16 keys in a lane's registers, so
+// P^T, rounded to bf16, is already the B operand of O^T += V^T P^T, with V^T fetched by
+// transposing LDS reads.
+// Online softmax with a lazy reference r per row, in units of log2: p = exp2(s scale log2 e - r),
+// and r is only raised when a half tops it by more than 2^LAZY; the result is still exact, since
+// any reference cancels between numerator and denominator.  (Q is not pre-multiplied by the
+// scale: rounding the product to bf16 would cost about 1e-3 of L on rows with large scores.)
+// The loop runs over 32-key halves and is software pipelined inside each wave: while the matrix
+// core contracts half h (O) and scores half h+2 (S), the vector ALU turns the scores of half h+1
+// into probabilities; two sets of score registers alternate.
 // The grid is cut along the KV axis (split-KV) when the query block alone cannot fill the chip;
 // partial (O, L) pairs are combined by the merge kernel.
 #include "lvx_internal.h"
 #include "lvx_mfma.h"
+#include "lvx_kv_ring.h"
 
 #include <type_traits>
-
 
 namespace lvx {
 
 namespace {
 
-constexpr int BM = 256;       // query rows per workgroup
-constexpr int BN = 64;        // keys per tile
-constexpr int NW = 8;         // waves per workgroup
-constexpr int NS = 4;         // LDS ring stages
-constexpr float LOG2E = 1.4426950408889634f;
-constexpr float LAZY = 6.0f;  // raise the running max only when a tile tops it by 2^LAZY
+using namespace kvring;
+constexpr float LAZY = 6.0f;           // raise the reference only when a half tops it by 2^LAZY
+constexpr int XE = 8;                  // elements of a half converted during the contraction (of 32)
 
-template <int D> struct FwdSmem {
-  static constexpr int CPR = D / 8;            // 16-byte chunks of real data per row
-  static constexpr int KCH = CPR + 1;          // K row: + 16 B pad  (conflict-free b128 reads)
-  static constexpr int VCH = CPR + 4;          // V row: + 64 B pad  (conflict-free transposing reads)
-  static constexpr int KP = KCH * 16, VP = VCH * 16;
-  static constexpr int K_BYTES = BN * KP;      // = KCH wave-copies of 1 KB
-  static constexpr int V_BYTES = BN * VP;      // = VCH wave-copies of 1 KB
-  static constexpr int STAGE = K_BYTES + V_BYTES;
-  static constexpr int NCOPY = KCH + VCH;      // wave-level copies per tile
-  static constexpr int L = (NCOPY + NW - 1) / NW;   // copies issued by every wave per tile
-  static constexpr int RING = NS * STAGE;
-  static constexpr int BITS_BYTES = 4096;      // visibility bits of up to 32704 tiles (media mask only)
-  static constexpr int WIN_BYTES = 8192;       // window of the mask bitmap (media mask only)
-  static constexpr int TOTAL = RING + BITS_BYTES + WIN_BYTES;
-};
-
-template <int D>
-__global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+// GENERAL = false: dense attention and Skv a multiple of 64 (no mask code, no ragged tile);
+// GENERAL = true: everything else.
+template <int D, bool GENERAL>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 fwd_bf16_kernel(FwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  using SM = FwdSmem<D>;
-  constexpr int KS = D / 16;            // k-steps of the QK^T product
-  constexpr int DB = D / 32;            // 32-row blocks of O^T
-  constexpr int L = SM::L;
+  using SM = KvSmem<D>;
+  constexpr int KS = D / 16, DB = D / 32, CPR = SM::CPR, NCR = SM::NCR;
 
   const Dims& d = a.d;
   const int G = d.Hq / d.Hkv;
-  const int n_qt = (d.Sq + BM - 1) / BM;
+  const int n_qt = (d.Sq + QM - 1) / QM;
   HeadWork hw;
   if (!xcd_decode(blockIdx.x, d.B * d.Hkv, a.n_split * G * n_qt, &hw)) return;
   const int b = hw.head / d.Hkv, hk = hw.head % d.Hkv;
@@ -70,369 +55,466 @@ fwd_bf16_kernel(FwdArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ql = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int i_wave0 = qt * BM + wave * 32;          // first query row of this wave
-  const int i_lane = i_wave0 + ql;                  // this lane's query row (column of S^T)
+  const int i_wave0 = qt * QM + wave * 32 * QB;     // first query row of this wave
 
   // KV range of this split, in tiles
-  const int n_tiles = (d.Skv + BN - 1) / BN;
+  const int n_tiles = (d.Skv + TN - 1) / TN;
   const int tps = (n_tiles + a.n_split - 1) / a.n_split;
   int t_begin = split * tps;                        // (with a media mask: re-cut below over the visible tiles)
   int t_end = min(n_tiles, t_begin + tps);
 
-  // Q operands (B of S^T = K Q^T): lane holds row i_lane, columns 16 ks + 8 g + 0..7
-  bf16x8 qf[KS];
-  {
-    const uint16_t* qrow = (const uint16_t*)a.q + b * d.q_sb + hq * d.q_sh + (long)i_lane * d.q_ss;
+  // ---- stationary operands: Q of this lane's query rows i_wave0 + 32 qb + ql
+  const float c2 = d.scale * LOG2E;
+  bf16x8 qf[QB][KS];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const int i = i_wave0 + 32 * qb + ql;
+    const long off = b * d.q_sb + hq * d.q_sh + (long)i * d.q_ss;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       u32x4 x = {0, 0, 0, 0};
-      if (i_lane < d.Sq) x = *(const u32x4*)(qrow + 16 * ks + 8 * g);
-      qf[ks] = __builtin_bit_cast(bf16x8, x);
+      if (i < d.Sq) x = *(const u32x4*)((const uint16_t*)a.q + off + 16 * ks + 8 * g);
+      qf[qb][ks] = __builtin_bit_cast(bf16x8, x);
     }
-    // Touch the registers now, so that these loads are complete before the tile copies start:
-    // otherwise the first use inside the loop would make the compiler drain every copy in flight.
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]));
   }
+  // Finish these loads (and move the operands into the accumulation registers) before the tile
+  // copies start: the copies are not counted by the compiler, so nothing may wait on memory later.
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[qb][ks]));
 
-  // ---- tile copies: wave w issues copies n = w, w + 8, ... (mod NCOPY; the few surplus copies
-  // repeat an earlier one).  Copy n < KCH fills 1 KB of the K stage, the others of the V stage;
-  // lane l of copy n fills 16-byte slot 64 n + l = (row, chunk) of the padded tile; pad slots
-  // re-read the row's last chunk.
-  const char* kbase = (const char*)((const uint16_t*)a.k + b * d.kv_sb + hk * d.kv_sh);
-  const char* vbase = (const char*)((const uint16_t*)a.v + b * d.kv_sb + hk * d.kv_sh);
-  const long row_bytes = d.kv_ss * 2;
-  auto copy_slot = [&](int i, int& row, int& col, int& lds, bool& is_k) {
-    const int n = (wave + NW * i) % SM::NCOPY;
-    is_k = n < SM::KCH;
-    const int slot = 64 * (is_k ? n : n - SM::KCH) + lane;
-    const int ch = is_k ? SM::KCH : SM::VCH;
-    row = slot / ch;
-    col = min(slot % ch, SM::CPR - 1) * 16;
-    lds = is_k ? n * 1024 : SM::K_BYTES + (n - SM::KCH) * 1024;
-  };
-  unsigned cp_off[L];
-#pragma unroll
-  for (int i = 0; i < L; ++i) {
-    int row, col, lds; bool is_k;
-    copy_slot(i, row, col, lds, is_k);
-    cp_off[i] = (unsigned)(row * row_bytes + col);
-  }
-  auto issue_tile = [&](int t, char* st) {
-    const int j0 = t * BN;
-    const int rows = min(BN, d.Skv - j0);
-    const char* kt = kbase + (long)j0 * row_bytes;
-    const char* vt = vbase + (long)j0 * row_bytes;
-    if (rows == BN) {
-#pragma unroll
-      for (int i = 0; i < L; ++i) {
-        int row, col, lds; bool is_k;
-        copy_slot(i, row, col, lds, is_k);           // lds, is_k: wave-uniform
-        dma16s(is_k ? kt : vt, cp_off[i], st + lds);
-      }
-    } else {                                          // ragged last tile: re-read its last row
-      asm volatile("" ::: "memory");
-#pragma unroll
-      for (int i = 0; i < L; ++i) {
-        int row, col, lds; bool is_k;
-        copy_slot(i, row, col, lds, is_k);
-        dma16s(is_k ? kt : vt, (unsigned)(min(row, rows - 1) * row_bytes + col), st + lds);
-      }
-    }
-  };
-
-  // which tiles does this workgroup need at all (media mask)?  The window of the bitmap that its
-  // rows and key range can touch is copied to LDS, and the visibility of every tile is worked out
-  // by all threads at once into a bit array, so that the loop never waits on the bitmap.
-  const int i_wg0 = qt * BM, i_wg1 = min(d.Sq, i_wg0 + BM) - 1;
+  // ---- tiles this workgroup needs (media mask: tiles visible to none of its rows are skipped).
+  // The window of the bitmap that its rows and key range can touch is copied to LDS, and the
+  // visibility of every tile is worked out by all threads at once into a bit array, so that the
+  // loop never waits on the bitmap.
+  const int i_wg0 = qt * QM, i_wg1 = min(d.Sq, i_wg0 + QM) - 1;
   MaskDev mk = a.mask;
   unsigned* const bits = (unsigned*)(smem + SM::RING);
   bool have_bits = false;
-  if (mk.allow) {
+  int nt = max(t_end - t_begin, 0);                // number of tiles this workgroup performs
+  if (GENERAL && mk.allow) {
     if (n_tiles <= (SM::BITS_BYTES - 16) * 8) {
       // bits over ALL tiles of the key range; the splits then share the visible tiles evenly
       mk = mask_to_lds(a.mask, b, i_wg0 / mk.q_chunk, i_wg1 / mk.q_chunk, 0, (d.Skv - 1) / mk.kv_block,
-                       (uint8_t*)smem + SM::RING + SM::BITS_BYTES, SM::WIN_BYTES, tid, 64 * NW);
+                       (uint8_t*)smem + SM::RING + SM::BITS_BYTES, SM::WIN_BYTES, tid, 256);
       have_bits = true;
-      const int nn = build_bits(bits, n_tiles, tid, 64 * NW, [&](int t) {
-        return mask_rect(mk, b, i_wg0, i_wg1, t * BN, min(d.Skv, t * BN + BN) - 1) != 0;
+      const int nn = build_bits(bits, n_tiles, tid, 256, [&](int t) {
+        return mask_rect(mk, b, i_wg0, i_wg1, t * TN, min(d.Skv, t * TN + TN) - 1) != 0;
       });
       const int k0 = (int)((long)split * nn / a.n_split), k1 = (int)((long)(split + 1) * nn / a.n_split);
       t_begin = nth_bit(bits, k0, n_tiles);
       t_end = k1 > k0 ? nth_bit(bits, k1 - 1, n_tiles) + 1 : t_begin;
+      nt = k1 - k0;
     } else if (t_begin < t_end) {
-      mk = mask_to_lds(a.mask, b, i_wg0 / mk.q_chunk, i_wg1 / mk.q_chunk, (t_begin * BN) / mk.kv_block,
-                       (min(d.Skv, t_end * BN) - 1) / mk.kv_block, (uint8_t*)smem + SM::RING + SM::BITS_BYTES,
-                       SM::WIN_BYTES, tid, 64 * NW);
+      mk = mask_to_lds(a.mask, b, i_wg0 / mk.q_chunk, i_wg1 / mk.q_chunk, (t_begin * TN) / mk.kv_block,
+                       (min(d.Skv, t_end * TN) - 1) / mk.kv_block, (uint8_t*)smem + SM::RING + SM::BITS_BYTES,
+                       SM::WIN_BYTES, tid, 256);
     }
   }
-  auto next_tile = [&](int t) -> int {
-    if (mk.allow) {
-      if (have_bits) return next_bit(bits, t, t_end);
-      while (t < t_end && mask_rect(mk, b, i_wg0, i_wg1, t * BN, min(d.Skv, t * BN + BN) - 1) == 0) ++t;
-    }
+  auto tile_needed = [&](int t) __attribute__((always_inline)) -> bool {
+    if (!GENERAL || !mk.allow) return true;
+    return mask_rect(mk, b, i_wg0, i_wg1, t * TN, min(d.Skv, t * TN + TN) - 1) != 0;
+  };
+  auto next_tile = [&](int t) __attribute__((always_inline)) -> int {
+    if (GENERAL && have_bits) return next_bit(bits, t, t_end);
+    while (t < t_end && !tile_needed(t)) ++t;
     return __builtin_amdgcn_readfirstlane(min(t, t_end));      // wave-uniform (the bitmap is read through the vector path)
   };
-  auto wave_class = [&](int t) -> int {               // 0 skip, 1 dense, 2 per-element mask
-    if (t >= t_end || i_wave0 >= d.Sq) return 0;
-    if (!mk.allow) return 1;
-    return mask_rect(mk, b, i_wave0, min(d.Sq - 1, i_wave0 + 31), t * BN, min(d.Skv, t * BN + BN) - 1);
-  };
+  int cursor = next_tile(t_begin);                 // next tile to issue
+  if (GENERAL && mk.allow && !have_bits) {
+    nt = 0;
+    for (int t = cursor; t < t_end; t = next_tile(t + 1)) ++nt;
+  }
 
-  f32x16 oacc[DB];
+  // ---- tile copies.  Group w of a tile (logical rows 4 j + w, j = 0..15) is contiguous in LDS:
+  // RUN slots of 16 bytes.  Wave w copies group w of the K tile and of the V tile, each with NCR
+  // wave-level copies of 64 slots (the last one re-covers the tail of the previous so that no copy
+  // crosses the group); lane l of a copy starting at slot a fills slot a + l = (row (a + l) / SPR
+  // of the group, chunk (a + l) % SPR; the pad chunk re-reads the last one).
+  const char* const k0 = (const char*)a.k + (b * d.kv_sb + hk * d.kv_sh) * 2;
+  const char* const v0 = (const char*)a.v + (b * d.kv_sb + hk * d.kv_sh) * 2;
+  const unsigned row_bytes = (unsigned)(d.kv_ss * 2);
+  auto run_start = [&](int c) __attribute__((always_inline)) -> int { return c + 1 < NCR ? 64 * c : SM::RUN - 64; };
+  unsigned cp_off[NCR];
 #pragma unroll
-  for (int i = 0; i < DB; ++i) oacc[i] = zero16();
-  float m_ref = -INFINITY;     // reference maximum of raw scores baked into l_run and oacc
-  float l_run = 0.f;           // this lane's share of the running sum of exp
-  const float c2 = d.scale * LOG2E;
-
-  // ---- building blocks, all on one 32-key HALF of a tile (kb = 0 or 1) -----------------------
-  // S^T half: 32 keys x 32 queries
-  auto scores_half = [&](const char* ks_, int kb, f32x16& s) {
-    s = zero16();
-    const char* krow = ks_ + (kb * 32 + ql) * SM::KP + g * 16;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) s = mfma32(*(const bf16x8*)(krow + ks * 32), qf[ks], s);
+  for (int c = 0; c < NCR; ++c) {
+    const int sl = run_start(c) + lane;
+    cp_off[c] = (unsigned)(4 * (sl / SM::SPR)) * row_bytes + (unsigned)min(sl % SM::SPR, CPR - 1) * 16;
+  }
+  // A tile's copies are numbered 0 .. NDMA - 1, so that the dense loop can spread them over the
+  // matrix instructions of a phase: issued back to back, each waits for the one before it to be
+  // accepted by the memory pipeline, and the wave would stand still for hundreds of cycles.
+  auto issue_part = [&](int t, char* st, int k) __attribute__((always_inline)) {   // full tiles only
+    const long tile = (long)t * TN * row_bytes + (long)wave * row_bytes;           // this wave's first row: tile row w
+    char* const kdst = st + wave * SM::GS;
+    if (k % 2 == 0) dma16s(k0 + tile, cp_off[k / 2], kdst + run_start(k / 2) * 16);
+    else dma16s(v0 + tile, cp_off[k / 2], kdst + SM::TILE + run_start(k / 2) * 16);
   };
-  // key tail and mixed-mask elements -> -inf
-  auto mask_half = [&](int t, int kb, int cls, f32x16& s) {
-    const int j0 = t * BN + kb * 32;
-    if (j0 + 32 > d.Skv || cls == 2) {
-      asm volatile("" ::: "memory");            // a real branch: never speculate this into the hot path
+  auto issue_tile = [&](int t, char* st) __attribute__((always_inline)) {
+    const int rows = min(TN, d.Skv - t * TN);
+    if (!GENERAL || rows == TN) {
+#pragma unroll
+      for (int k = 0; k < 2 * NCR; ++k) issue_part(t, st, k);
+      return;
+    }
+    const long tile = (long)t * TN * row_bytes;    // ragged last tile: clamp the rows
+    char* const kdst = st + wave * SM::GS;
+    char* const vdst = kdst + SM::TILE;
+#pragma unroll
+    for (int c = 0; c < NCR; ++c) {
+      const int sl = run_start(c) + lane;
+      const unsigned r = (unsigned)min(4 * (sl / SM::SPR) + wave, rows - 1);
+      const unsigned off = r * row_bytes + (unsigned)min(sl % SM::SPR, CPR - 1) * 16;
+      dma16s(k0 + tile, off, kdst + run_start(c) * 16);
+      dma16s(v0 + tile, off, vdst + run_start(c) * 16);
+    }
+  };
+  constexpr int NDMA = 2 * NCR;                    // copies per wave and tile
+
+  // ---- softmax state of this lane's two query rows (both half-waves keep identical copies)
+  f32x16 oacc[QB][DB];                 // O^T, relative to the reference
+  float m_ref[QB], r[QB], l_run[QB];   // true reference (-inf before the first key), r = finite
+                                       // stand-in (0 for -inf), this lane's share of the sum of p
+  float pend[QB];                      // factor still to be applied to oacc (1: none)
+  bool pending = false;
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+#pragma unroll
+    for (int i = 0; i < DB; ++i) { oacc[qb][i] = zero16(); asm volatile("" : "+a"(oacc[qb][i])); }
+    m_ref[qb] = -INFINITY;
+    r[qb] = 0.f;
+    l_run[qb] = 0.f;
+    pend[qb] = 1.f;
+  }
+
+  // ---- building blocks, all on one 32-key half hb of the tile at st ---------------------------
+  struct FirstK { bf16x8 k; };
+  auto first_k = [&](const char* __restrict__ st, int hb) __attribute__((always_inline)) -> bf16x8 {
+    return *(const bf16x8*)(st + tile_off<D>(ql, 32 * hb, 16 * g));
+  };
+  auto first_vt = [&](const char* __restrict__ st, int hb) __attribute__((always_inline)) -> bf16x8 {
+    return tile_tr_operand<D>(st + SM::TILE, 32 * hb, 0, lane);
+  };
+  // S^T = K Q^T: lane = query column, registers = keys.  first: the K operand of k-step 0,
+  // fetched by the caller (during the previous phase in the steady state); per_unit(m) is vector
+  // work issued right after matrix instruction m (0 .. 2 KS - 1), to run in its shadow; tail(),
+  // issued three instructions before the end, fetches the first operand of the next phase.
+  auto score = [&](const char* __restrict__ st, int hb, f32x16 (&s)[QB], auto&& per_unit, bf16x8 first,
+                   auto&& tail) __attribute__((always_inline)) {
+    const char* krow = st + tile_off<D>(ql, 32 * hb, 16 * g);
+    bf16x8 ka[2];
+    ka[0] = first;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int cu = ks & 1;
+      if (ks + 1 < KS) ka[cu ^ 1] = *(const bf16x8*)(krow + (ks + 1) * 32);
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        if (ks == 0) mfma_first(s[qb], ka[cu], qf[qb][ks]);
+        else mfma_next(s[qb], ka[cu], qf[qb][ks]);
+        per_unit(ks * QB + qb);
+        if (ks * QB + qb == QB * KS - 3) tail();
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    asm volatile("s_nop 7" ::: "memory");          // the last results settle before anything reads them
+  };
+  auto nothing = [](int) __attribute__((always_inline)) {};
+  auto no_tail = []() __attribute__((always_inline)) {};
+  // key tail and masked elements of a half's scores -> -inf (wave-uniform decision, rarely taken)
+  auto mask_scores = [&](int t, int hb, f32x16 (&s)[QB]) __attribute__((always_inline)) {
+    if (!GENERAL) return;
+    const int j0 = t * TN + 32 * hb;
+    int cls = 1;
+    if (mk.allow && i_wave0 < d.Sq)
+      cls = mask_rect(mk, b, i_wave0, min(d.Sq, i_wave0 + 32 * QB) - 1, min(j0, d.Skv - 1),
+                      min(d.Skv, j0 + 32) - 1);
+    if (cls == 1 && j0 + 32 <= d.Skv) return;
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int j = j0 + 8 * (v / 4) + 4 * g + (v % 4);
+        const int j = j0 + 8 * (v / 4) + 4 * g + (v % 4), i = i_wave0 + 32 * qb + ql;
         bool ok = j < d.Skv;
-        if (ok && cls == 2) ok = (i_lane < d.Sq) && mask_elem(mk, b, i_lane, j);
-        if (!ok) s[v] = -INFINITY;
+        if (ok && cls != 1) ok = i < d.Sq && mask_elem(mk, b, i, j);
+        if (!ok) s[qb][v] = -INFINITY;
       }
+  };
+  // Before a half's scores are exponentiated: does any row top its reference by more than
+  // 2^LAZY?  Then (rarely) the reference of the rows that grew is raised to their new maximum:
+  // the sums shrink by alpha = 2^(old - new), and the factor for O^T is kept in pend until no
+  // matrix instruction on O^T is in flight.
+  auto check = [&](const f32x16 (&s)[QB]) __attribute__((always_inline)) {
+    float tm[QB];
+    bool need = false;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      float m = fmaxf(fmaxf(s[qb][0], s[qb][1]), s[qb][2]);
+#pragma unroll
+      for (int v = 3; v < 15; v += 2) m = fmaxf(fmaxf(m, s[qb][v]), s[qb][v + 1]);
+      m = fmaxf(m, s[qb][15]);
+      tm[qb] = xhalf_max(m) * c2;                  // the row's maximum in units of log2 (c2 > 0)
+      need |= tm[qb] - m_ref[qb] > LAZY;           // NaN (-inf - -inf) compares false
+    }
+    if (__any(need)) {
+      asm volatile("" ::: "memory");               // keep this a real, rarely taken branch
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        const float m_new = fmaxf(m_ref[qb], tm[qb]);
+        const float r_new = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_ref[qb] - r_new);   // m_ref = -inf -> 0
+        m_ref[qb] = m_new;
+        r[qb] = r_new;
+        l_run[qb] *= alpha;
+        pend[qb] *= alpha;
+      }
+      pending = true;
     }
   };
-  auto half_max = [&](const f32x16& s) -> float {
-    float m = s[0];
+  // Waits until every matrix instruction issued so far has written its result.  The accumulators
+  // are operands of the statement, so that the compiler cannot read them before it.
+  auto drain_oacc = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int v = 1; v < 16; ++v) m = fmaxf(m, s[v]);
-    return m;
+    for (int qb = 0; qb < QB; ++qb) {
+      if constexpr (DB == 4)
+        asm volatile("s_nop 15\n\ts_nop 15" : "+a"(oacc[qb][0]), "+a"(oacc[qb][1]), "+a"(oacc[qb][2]), "+a"(oacc[qb][3]));
+      else
+        asm volatile("s_nop 15\n\ts_nop 15" : "+a"(oacc[qb][0]), "+a"(oacc[qb][1]));
+    }
   };
-  // the (rare) raise of the reference maximum, given this lane's maximum of a new score half
-  auto raise_ref = [&](float tmax) {
-    tmax = xhalf_max(tmax);
-    // (tmax - m_ref) * c2 > LAZY: NaN (both -inf) compares false, m_ref = -inf with a finite tmax true
-    if (__any((tmax - m_ref) * c2 > LAZY)) {
-      asm volatile("" ::: "memory");            // keep this a real, rarely taken branch
-      const float m_new = fmaxf(m_ref, tmax);
-      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f((m_ref - m_safe) * c2);   // m_ref = -inf -> 0
-      m_ref = m_new;
-      l_run *= alpha;
+  // apply the pending factors to O^T, between two phases
+  auto settle = [&]() __attribute__((always_inline)) {
+    if (pending) {
+      drain_oacc();
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) oacc[qb][db][v] *= pend[qb];
+        }
+        pend[qb] = 1.f;
+      }
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {            // the new values settle before a matrix instruction reads them
+        if constexpr (DB == 4)
+          asm volatile("s_nop 7" : "+a"(oacc[qb][0]), "+a"(oacc[qb][1]), "+a"(oacc[qb][2]), "+a"(oacc[qb][3]));
+        else
+          asm volatile("s_nop 7" : "+a"(oacc[qb][0]), "+a"(oacc[qb][1]));
+      }
+      pending = false;
+    }
+  };
+  // Conversion of scores into the P^T operands, element x of a half (x = 0..31: query block
+  // qb = x / 16, register v = x % 16): p = exp2(s c2 - r), added to the row's sum and packed in pairs as
+  // bf16 into word (v % 8) / 2 of operand v / 8 of the query block.
+  struct Carry { float p; };
+  auto conv_elem = [&](int x, Carry& cy, const f32x16 (&s)[QB], u32x4 (&pw)[QB][2]) __attribute__((always_inline)) {
+    const int qb = x / 16, v = x % 16;
+    const float pr = __builtin_amdgcn_exp2f(fmaf(s[qb][v], c2, -r[qb]));
+    l_run[qb] += pr;
+    if (v % 2 == 0) { cy.p = pr; return; }
+    pw[qb][v / 8][(v % 8) / 2] = pack2_bf16(cy.p, pr);
+  };
+  auto convert = [&](const f32x16 (&s)[QB], u32x4 (&pw)[QB][2]) __attribute__((always_inline)) {
+    Carry cy;
+#pragma unroll
+    for (int x = 0; x < 32; ++x) conv_elem(x, cy, s, pw);
+  };
+  // O^T += V^T P^T over the 32 keys of a half (two k-steps of 16 keys)
+  auto contract = [&](const char* __restrict__ st, int hb, const u32x4 (&pw)[QB][2]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const bf16x8 vt = tile_tr_operand<D>(st + SM::TILE, 32 * hb + 16 * t2, 32 * db, lane);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) mfma_acc(oacc[qb][db], vt, __builtin_bit_cast(bf16x8, pw[qb][t2]));
+      }
+  };
+  // contract(half h) on the matrix core; on the vector ALU, after two matrix instructions (the
+  // scores of half h+1 have settled by then), the check of half h+1 and its first XE conversions.
+  // The transposed operand of a pair of matrix instructions is fetched one pair ahead, and nothing
+  // is scheduled across the units.
+  auto contract_convert = [&](const char* __restrict__ st, int hb, const u32x4 (&pi)[QB][2],
+                              f32x16 (&s)[QB], u32x4 (&po)[QB][2], Carry& cy, bf16x8 first,
+                              auto&& tail) __attribute__((always_inline)) {
+    constexpr int NM = 2 * DB * QB;                // matrix instructions
+    constexpr int M0 = 2;                          // first unit with conversions
+    static_assert(NM > M0 + 1, "no room for the conversions");
+    bf16x8 vt[2];
+    vt[0] = first;
+#pragma unroll
+    for (int m = 0; m < NM; ++m) {
+      const int c = m / QB, t2 = c / DB, db = c % DB, qb = m % QB, cu = c & 1;
+      if (qb == 0 && c + 1 < 2 * DB)
+        vt[cu ^ 1] = tile_tr_operand<D>(st + SM::TILE, 32 * hb + 16 * ((c + 1) / DB), 32 * ((c + 1) % DB), lane);
+      mfma_acc(oacc[qb][db], vt[cu], __builtin_bit_cast(bf16x8, pi[qb][t2]));
+      if (m == M0 - 1) check(s);
+      if (m >= M0) {
+#pragma unroll
+        for (int x = (m - M0) * XE / (NM - M0); x < (m - M0 + 1) * XE / (NM - M0); ++x) conv_elem(x, cy, s, po);
+      }
+      if (m == NM - 3) tail();
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    settle();
+  };
+  // score(half h+2) together with the remaining conversions of half h+1
+  auto score_convert = [&](const char* __restrict__ st, int hb, f32x16 (&s_new)[QB], const f32x16 (&s)[QB],
+                           u32x4 (&po)[QB][2], Carry& cy, bf16x8 first, auto&& tail,
+                           auto&& extra) __attribute__((always_inline)) {
+    constexpr int NU = QB * KS;                    // matrix instructions of a score phase
+    score(st, hb, s_new, [&](int m) __attribute__((always_inline)) {
+#pragma unroll
+      for (int x = XE + m * (32 - XE) / NU; x < XE + (m + 1) * (32 - XE) / NU; ++x) conv_elem(x, cy, s, po);
+      extra(m);
+    }, first, tail);
+  };
+
+  // ---- pipeline.  Tile number q of the sequence lives in ring stage q % 4.  Per tile T (halves
+  // 2T and 2T+1): contract 2T | convert 2T+1 | score 2T+2, then contract 2T+1 | convert 2T+2, the
+  // one barrier of the tile -- every wave is done with tile T, whose stage takes tile T + 4, and
+  // tile T + 2, issued two tiles ago, has landed -- and score 2T+3.
+  int e[NSTG + 1];                                 // tile ids of tiles T .. T + 4 (static indexing only)
+#pragma unroll
+  for (int q = 0; q <= NSTG; ++q) e[q] = t_end;
+#pragma unroll
+  for (int q = 0; q < NSTG; ++q) {
+    if (q < nt) {
+      e[q] = cursor;
+      issue_tile(cursor, smem + q * SM::STAGE);
+      cursor = next_tile(cursor + 1);
+    }
+  }
+  wait_vmcnt<0>();
+  __syncthreads();
+  auto stage = [&](int q) __attribute__((always_inline)) -> char* { return smem + (q % NSTG) * SM::STAGE; };
+  auto mid = [&](auto all_in_flight, bool issue, char* st_copy) __attribute__((always_inline)) {
+    // (The general variant may spill registers inside the loop; its spill stores are counted with
+    // the copies but complete out of order with them, so it always waits for everything.)
+    // all_in_flight: tiles T + 2 and T + 3 were both issued, so leaving one tile's copies
+    // outstanding still guarantees that tile T + 2 has landed
+    if constexpr (decltype(all_in_flight)::value) wait_vmcnt<NDMA>();
+    else wait_vmcnt<0>();
+    wg_barrier();
+    if (issue) {
+      e[4] = cursor;
+      issue_tile(cursor, st_copy);
+      cursor = next_tile(cursor + 1);
+    }
+  };
+
+  f32x16 s0[QB], s1[QB];                           // scores of even / odd halves
+  u32x4 p0[QB][2] = {}, p1[QB][2] = {};            // packed P^T operands of even / odd halves
+  Carry cy;
+  if (nt > 0) {
+    score(smem, 0, s0, nothing, first_k(smem, 0), no_tail);
+    mask_scores(e[0], 0, s0);
+    check(s0);
+    settle();                                      // (O^T is still zero: this only clears the factor)
+    convert(s0, p0);
+    score(smem, 1, s1, nothing, first_k(smem, 1), no_tail);
+    mask_scores(e[0], 1, s1);
+  }
+  int T = 0;
+  bf16x8 fk;
+  bf16x8 fvt = first_vt(smem, 0);                  // handed from phase to phase
+  for (; T + 4 < nt; ++T) {                        // full tiles: tile T + 1 is scored, tile T + 4 issued
+    char* const sa = stage(T);
+    char* const sb = stage(T + 1);
+    contract_convert(sa, 0, p0, s1, p1, cy, fvt, [&]() __attribute__((always_inline)) { fk = first_k(sb, 0); });
+    score_convert(sb, 0, s0, s1, p1, cy, fk, [&]() __attribute__((always_inline)) { fvt = first_vt(sa, 1); }, nothing);
+    mask_scores(e[1], 0, s0);
+    contract_convert(sa, 1, p1, s0, p0, cy, fvt, [&]() __attribute__((always_inline)) { fk = first_k(sb, 1); });
+    if constexpr (GENERAL) {
+      mid(std::false_type{}, true, sa);
+      score_convert(sb, 1, s1, s0, p0, cy, fk, [&]() __attribute__((always_inline)) { fvt = first_vt(sb, 0); }, nothing);
+    } else {
+      mid(std::true_type{}, false, sa);
+      const int t_new = cursor;                    // the copies of tile T + 4 go out during the phase
+      e[4] = t_new;
+      cursor = next_tile(cursor + 1);
+      constexpr int EVERY = QB * KS / NDMA;
+      static_assert(EVERY >= 1, "more copies than matrix instructions in the score phase");
+      score_convert(sb, 1, s1, s0, p0, cy, fk, [&]() __attribute__((always_inline)) { fvt = first_vt(sb, 0); },
+                    [&](int m) __attribute__((always_inline)) {
+                      if (m % EVERY == EVERY - 1 && m / EVERY < NDMA) issue_part(t_new, sa, m / EVERY);
+                    });
+    }
+    mask_scores(e[1], 1, s1);
+    e[0] = e[1]; e[1] = e[2]; e[2] = e[3]; e[3] = e[4];
+  }
+  for (; T < nt; ++T) {                            // the last (at most four) tiles, phase after phase
+    const bool more = T + 1 < nt;
+    contract(stage(T), 0, p0);
+    check(s1);
+    settle();                                      // before anything relative to the new reference is added
+    convert(s1, p1);
+    if (more) { score(stage(T + 1), 0, s0, nothing, first_k(stage(T + 1), 0), no_tail); mask_scores(e[1], 0, s0); }
+    contract(stage(T), 1, p1);
+    if (more) { check(s0); settle(); convert(s0, p0); }
+    mid(std::false_type{}, T + 4 < nt, stage(T));
+    if (more) { score(stage(T + 1), 1, s1, nothing, first_k(stage(T + 1), 1), no_tail); mask_scores(e[1], 1, s1); }
+    e[0] = e[1]; e[1] = e[2]; e[2] = e[3]; e[3] = e[4];
+  }
+
+  // ---- epilogue: O = acc / l, L = r ln 2 + ln l (the reference is in units of log2).  The last
+  // matrix instructions must have retired before their registers are read.
+  drain_oacc();
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const float l_tot = xhalf_sum(l_run[qb]);
+    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+    const float lse = l_tot > 0.f ? m_ref[qb] * (1.f / LOG2E) + logf(l_tot) : -INFINITY;
+    const int i = i_wave0 + 32 * qb + ql;
+    if (i >= d.Sq) continue;
+    const long row = ((long)b * d.Hq + hq) * d.Sq + i;
+    if (a.n_split > 1) {
+      float* o = a.o_part + ((long)split * d.B * d.Hq * d.Sq + row) * D;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
+        for (int q4 = 0; q4 < 4; ++q4) {
+          f32x4 y = {oacc[qb][db][4 * q4] * inv, oacc[qb][db][4 * q4 + 1] * inv, oacc[qb][db][4 * q4 + 2] * inv,
+                     oacc[qb][db][4 * q4 + 3] * inv};
+          *(f32x4*)(o + 32 * db + 8 * q4 + 4 * g) = y;
+        }
+      if (g == 0) a.lse_part[(long)split * d.B * d.Hq * d.Sq + row] = lse;
+      continue;
     }
-  };
-  // P half = exp2((s - m_ref) c2), row sums, and O^T += V^T P^T for these 32 keys (no overlap)
-  auto probs_pv_half = [&](const char* vs_, int kb, f32x16& s) {
-    const float mc = (m_ref == -INFINITY) ? 0.f : m_ref * c2;
-    float psum = 0.f;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const float pr = __builtin_amdgcn_exp2f(fmaf(s[v], c2, -mc));
-      s[v] = pr;
-      psum += pr;
-    }
-    l_run += psum;
-#pragma unroll
-    for (int t2 = 0; t2 < 2; ++t2) {
-      const bf16x8 pf = cvt_operand(s, 8 * t2);
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-        oacc[db] = mfma32(load_tr_operand(vs_, SM::VP, 32 * kb + 16 * t2, 32 * db, lane), pf, oacc[db]);
-    }
-  };
-  // Hand-interleaved half step of the dense pipeline.  The score product of the NEXT half (nxt)
-  // runs on the matrix core while the vector ALU turns the CURRENT half's scores (cur, keys kb of
-  // the tile at vs_) into probabilities; then P V of the current half runs while the vector ALU
-  // takes the maximum of the next half.  LDS operands are fetched one phase ahead, so that no
-  // matrix instruction waits for an LDS round trip: kop holds the K operands of the half being
-  // scored and is refilled, during the P V phase, with those of half kb_pre of the tile at k_pre;
-  // the V operands are fetched during the score phase.  Scheduling barriers keep the chunks (and
-  // with them the register pressure) as written.  Returns this lane's maximum of nxt.
-  auto fused_half = [&](const char* k_pre, int kb_pre, const char* vs_, int kb, f32x16& cur,
-                        f32x16& nxt, bf16x8 (&kop)[KS]) -> float {
-    constexpr int EPC = 16 / KS;                  // probabilities produced per score k-step
-    const float mc = (m_ref == -INFINITY) ? 0.f : m_ref * c2;
-    float psum = 0.f;
-    bf16x8 pfrag[2], vop[KS];                     // KS == 2 * DB V operands per half
-    nxt = zero16();
-#pragma unroll
-    for (int c = 0; c < KS; ++c) {
-      vop[c] = load_tr_operand(vs_, SM::VP, 32 * kb + 16 * (c / DB), 32 * (c % DB), lane);
-      nxt = mfma32(kop[c], qf[c], nxt);
-#pragma unroll
-      for (int i = 0; i < EPC; ++i) {
-        const int e = c * EPC + i;
-        const float pr = __builtin_amdgcn_exp2f(fmaf(cur[e], c2, -mc));
-        cur[e] = pr;
-        psum += pr;
-      }
-      if ((c + 1) * EPC == 8) pfrag[0] = cvt_operand(cur, 0);
-      if ((c + 1) * EPC == 16) pfrag[1] = cvt_operand(cur, 8);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    l_run += psum;
-    const char* krow = k_pre + (kb_pre * 32 + ql) * SM::KP + g * 16;
-    float tmax = -INFINITY;
-#pragma unroll
-    for (int t2 = 0; t2 < 2; ++t2) {
-#pragma unroll
-      for (int db = 0; db < DB; ++db) oacc[db] = mfma32(vop[t2 * DB + db], pfrag[t2], oacc[db]);
-#pragma unroll
-      for (int i = 0; i < KS / 2; ++i) kop[t2 * (KS / 2) + i] = *(const bf16x8*)(krow + (t2 * (KS / 2) + i) * 32);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) tmax = fmaxf(tmax, nxt[8 * t2 + i]);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    return tmax;
-  };
-
-  // ---- pipeline over the needed tiles: id0 is being finished, id1 gets its scores, id2 is in
-  // flight, id3 is issued.  Tile number q of the sequence lives in ring stage q % NS.
-  int id0 = next_tile(t_begin);
-  int id1 = id0 < t_end ? next_tile(id0 + 1) : t_end;
-  int id2 = id1 < t_end ? next_tile(id1 + 1) : t_end;
-  if (id0 < t_end) issue_tile(id0, smem);
-  if (id1 < t_end) issue_tile(id1, smem + SM::STAGE);
-  if (id2 < t_end) issue_tile(id2, smem + 2 * SM::STAGE);
-  if (id0 < t_end) {
-    if (id2 < t_end) wait_vmcnt<2 * L>();
-    else if (id1 < t_end) wait_vmcnt<L>();
-    else wait_vmcnt<0>();
-    wg_barrier();
-  }
-  int seq = 0;                                   // sequence number of id0
-  // Per tile, in both loops: wait until tile id1 has landed (tile id0 already has), cross the
-  // barrier (every wave is then done with tile seq - 1, whose stage is free), issue tile id3.
-  auto advance = [&](char* st_copy) {
-    if (id1 < t_end && id2 < t_end) wait_vmcnt<L>();
-    else wait_vmcnt<0>();
-    wg_barrier();
-    int id3 = t_end;
-    if (id2 < t_end) id3 = next_tile(id2 + 1);
-    if (id3 < t_end) issue_tile(id3, st_copy);
-    return id3;
-  };
-  const bool slow = mk.allow != nullptr || i_wave0 >= d.Sq;   // wave-uniform
-  if (!slow) {
-    // dense pipeline, one 32-key half ahead.  The three LDS stages a tile step touches are
-    // distinct, and saying so (__restrict__) keeps the compiler from draining the copies in
-    // flight before the LDS reads of the step.
-    const int ragged_tile = (d.Skv % BN) ? n_tiles - 1 : -1;
-    f32x16 s0, s1;
-    bf16x8 kop[KS];
-    if (id0 < t_end) {
-      scores_half(smem, 0, s0);
-      if (id0 == ragged_tile) { asm volatile("" ::: "memory"); mask_half(id0, 0, 1, s0); }
-      raise_ref(half_max(s0));
-#pragma unroll
-      for (int c = 0; c < KS; ++c) kop[c] = *(const bf16x8*)(smem + (32 + ql) * SM::KP + g * 16 + c * 32);
-    }
-    auto tile_step = [&](auto last_t, char* __restrict__ st_copy, const char* __restrict__ st_next,
-                         const char* __restrict__ st_cur) {
-      constexpr bool LAST = decltype(last_t)::value;
-      const int id3 = advance(st_copy);            // tile id1 (if any) has landed from here on
-      const char* vs_ = st_cur + SM::K_BYTES;
-      // first half -> probabilities, second half of the same tile -> scores
-      float tm = fused_half(st_next, 0, vs_, 0, s0, s1, kop);
-      if (id0 == ragged_tile) { asm volatile("" ::: "memory"); mask_half(id0, 1, 1, s1); tm = half_max(s1); }
-      raise_ref(tm);
-      if constexpr (!LAST) {
-        // second half -> probabilities, first half of the next tile -> scores
-        tm = fused_half(st_next, 1, vs_, 1, s1, s0, kop);
-        if (id1 == ragged_tile) { asm volatile("" ::: "memory"); mask_half(id1, 0, 1, s0); tm = half_max(s0); }
-        raise_ref(tm);
-      } else {
-        probs_pv_half(vs_, 1, s1);
-      }
-      id0 = id1; id1 = id2; id2 = id3;
-      ++seq;
-    };
-    while (id1 < t_end)
-      tile_step(std::false_type{}, smem + ((seq + 3) % NS) * SM::STAGE, smem + ((seq + 1) % NS) * SM::STAGE,
-                smem + (seq % NS) * SM::STAGE);
-    if (id0 < t_end)
-      tile_step(std::true_type{}, smem + ((seq + 3) % NS) * SM::STAGE, smem + ((seq + 1) % NS) * SM::STAGE,
-                smem + (seq % NS) * SM::STAGE);
-  } else {
-    // general path (media mask, or a wave without query rows): tile by tile, no software pipeline
-    auto tile_step = [&](char* __restrict__ st_copy, const char* __restrict__ st_cur) {
-      const int cls = wave_class(id0);
-      if (cls != 0) {
-        f32x16 s0, s1;
-        scores_half(st_cur, 0, s0);
-        scores_half(st_cur, 1, s1);
-        mask_half(id0, 0, cls, s0);
-        mask_half(id0, 1, cls, s1);
-        raise_ref(fmaxf(half_max(s0), half_max(s1)));
-        probs_pv_half(st_cur + SM::K_BYTES, 0, s0);
-        probs_pv_half(st_cur + SM::K_BYTES, 1, s1);
-      }
-      const int id3 = advance(st_copy);
-      id0 = id1; id1 = id2; id2 = id3;
-      ++seq;
-    };
-    while (id0 < t_end)
-      tile_step(smem + ((seq + 3) % NS) * SM::STAGE, smem + (seq % NS) * SM::STAGE);
-  }
-
-  // ---- epilogue: O = acc / l, L = m * scale + ln l
-  const float l_tot = xhalf_sum(l_run);
-  const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-  const float lse = l_tot > 0.f ? m_ref * d.scale + logf(l_tot) : -INFINITY;
-  if (i_lane >= d.Sq) return;
-  const long row = ((long)b * d.Hq + hq) * d.Sq + i_lane;
-  if (a.n_split > 1) {
-    float* o = a.o_part + ((long)split * d.B * d.Hq * d.Sq + row) * D;
+    const long off = b * d.q_sb + hq * d.q_sh + (long)i * d.q_ss;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
-        f32x4 y = {oacc[db][4 * q4] * inv, oacc[db][4 * q4 + 1] * inv, oacc[db][4 * q4 + 2] * inv,
-                   oacc[db][4 * q4 + 3] * inv};
-        *(f32x4*)(o + 32 * db + 8 * q4 + 4 * g) = y;
+        const float y0 = oacc[qb][db][4 * q4] * inv, y1 = oacc[qb][db][4 * q4 + 1] * inv,
+                    y2 = oacc[qb][db][4 * q4 + 2] * inv, y3 = oacc[qb][db][4 * q4 + 3] * inv;
+        const int col = 32 * db + 8 * q4 + 4 * g;
+        if (a.o_is_f32) {
+          f32x4 y = {y0, y1, y2, y3};
+          *(f32x4*)((float*)a.o + off + col) = y;
+        } else {
+          u32x2 y = {pack2_bf16(y0, y1), pack2_bf16(y2, y3)};
+          *(u32x2*)((uint16_t*)a.o + off + col) = y;
+        }
       }
-    if (g == 0) a.lse_part[(long)split * d.B * d.Hq * d.Sq + row] = lse;
-    return;
+    if (g == 0) a.lse[row] = lse;
   }
-  const long off = b * d.q_sb + hq * d.q_sh + (long)i_lane * d.q_ss;
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {
-      const float y0 = oacc[db][4 * q4] * inv, y1 = oacc[db][4 * q4 + 1] * inv,
-                  y2 = oacc[db][4 * q4 + 2] * inv, y3 = oacc[db][4 * q4 + 3] * inv;
-      const int col = 32 * db + 8 * q4 + 4 * g;
-      if (a.o_is_f32) {
-        f32x4 y = {y0, y1, y2, y3};
-        *(f32x4*)((float*)a.o + off + col) = y;
-      } else {
-        u32x2 y = {pack2_bf16(y0, y1), pack2_bf16(y2, y3)};
-        *(u32x2*)((uint16_t*)a.o + off + col) = y;
-      }
-    }
-  if (g == 0) a.lse[row] = lse;
 }
 
-template <int D>
+template <int D, bool GENERAL>
 hipError_t launch(const FwdArgs& a, long grid, hipStream_t s) {
   static bool once = false;
   if (!once) {
-    hipError_t e = hipFuncSetAttribute((const void*)fwd_bf16_kernel<D>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, FwdSmem<D>::TOTAL);
+    hipError_t e = hipFuncSetAttribute((const void*)fwd_bf16_kernel<D, GENERAL>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, KvSmem<D>::TOTAL);
     if (e != hipSuccess) return e;
     once = true;
   }
-  fwd_bf16_kernel<D><<<(unsigned)grid, 512, FwdSmem<D>::TOTAL, s>>>(a);
+  fwd_bf16_kernel<D, GENERAL><<<(unsigned)grid, 256, KvSmem<D>::TOTAL, s>>>(a);
   return hipGetLastError();
 }
 
@@ -442,8 +524,8 @@ int fwd_bf16_pick_split(const Dims& d, int n_cu, bool masked) {
   // one workgroup per CU; split the KV axis until the grid covers the chip.  With a media mask the
   // visible work differs from one query tile to the next (the splits of a tile share its visible
   // key tiles evenly), so four times as many workgroups are made to even the load out.
-  const long base = (long)d.B * d.Hq * ((d.Sq + BM - 1) / BM);
-  const int n_tiles = (d.Skv + BN - 1) / BN;
+  const long base = (long)d.B * d.Hq * ((d.Sq + QM - 1) / QM);
+  const int n_tiles = (d.Skv + TN - 1) / TN;
   long want = ((masked ? 4L : 1L) * n_cu + base - 1) / base;
   if (want < 1) want = 1;
   long cap = n_tiles / 16;                // keep at least 16 tiles (1024 keys) per split
@@ -456,9 +538,11 @@ int fwd_bf16_pick_split(const Dims& d, int n_cu, bool masked) {
 hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t s) {
   const Dims& d = a.d;
   const int G = d.Hq / d.Hkv;
-  const int n_qt = (d.Sq + BM - 1) / BM;
+  const int n_qt = (d.Sq + QM - 1) / QM;
   const long grid = xcd_grid(d.B * d.Hkv, a.n_split * G * n_qt);
-  return d.D == 64 ? launch<64>(a, grid, s) : launch<128>(a, grid, s);
+  const bool general = a.mask.allow != nullptr || d.Skv % TN != 0;
+  if (d.D == 64) return general ? launch<64, true>(a, grid, s) : launch<64, false>(a, grid, s);
+  return general ? launch<128, true>(a, grid, s) : launch<128, false>(a, grid, s);
 }
 
 }  // namespace lvx
