@@ -258,7 +258,7 @@ fwd_bf16_kernel(FwdArgs a) {
       tm[qb] = xhalf_max(m) * c2;                  // the row's maximum in units of log2 (c2 > 0)
       need |= tm[qb] - m_ref[qb] > LAZY;           // NaN (-inf - -inf) compares false
     }
-    if (__any(need)) {
+    if (__builtin_expect(__any(need), 0)) {
       asm volatile("" ::: "memory");               // keep this a real, rarely taken branch
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
@@ -286,7 +286,7 @@ fwd_bf16_kernel(FwdArgs a) {
   };
   // apply the pending factors to O^T, between two phases
   auto settle = [&]() __attribute__((always_inline)) {
-    if (pending) {
+    if (__builtin_expect(pending, false)) {
       drain_oacc();
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
@@ -352,7 +352,10 @@ fwd_bf16_kernel(FwdArgs a) {
       if (qb == 0 && c + 1 < 2 * DB)
         vt[cu ^ 1] = tile_tr_operand<D>(st + SM::TILE, 32 * hb + 16 * ((c + 1) / DB), 32 * ((c + 1) % DB), lane);
       mfma_acc(oacc[qb][db], vt[cu], __builtin_bit_cast(bf16x8, pi[qb][t2]));
-      if (m == M0 - 1) check(s);
+      if (m == M0 - 1) {                           // (after, not around, the matrix instruction)
+        __builtin_amdgcn_sched_barrier(0);
+        check(s);
+      }
       if (m >= M0) {
 #pragma unroll
         for (int x = (m - M0) * XE / (NM - M0); x < (m - M0 + 1) * XE / (NM - M0); ++x) conv_elem(x, cy, s, po);
@@ -360,6 +363,10 @@ fwd_bf16_kernel(FwdArgs a) {
       if (m == NM - 3) tail();
       __builtin_amdgcn_sched_barrier(0);
     }
+    // the conversions stay in this phase (their results are only used two phases later, and the
+    // branch below would otherwise let them sink)
+    static_assert(XE == 8, "the words pinned here are those of elements 0 .. 7");
+    asm volatile("" : "+v"(po[0][0]), "+v"(l_run[0]));
     settle();
   };
   // score(half h+2) together with the remaining conversions of half h+1
@@ -422,13 +429,17 @@ fwd_bf16_kernel(FwdArgs a) {
   int T = 0;
   bf16x8 fk;
   bf16x8 fvt = first_vt(smem, 0);                  // handed from phase to phase
+  asm volatile("" : "+v"(fvt));                    // (in hand before the loop: both ways into it then agree on what is in flight)
   for (; T + 4 < nt; ++T) {                        // full tiles: tile T + 1 is scored, tile T + 4 issued
     char* const sa = stage(T);
     char* const sb = stage(T + 1);
     contract_convert(sa, 0, p0, s1, p1, cy, fvt, [&]() __attribute__((always_inline)) { fk = first_k(sb, 0); });
+    asm volatile("" : "+v"(fk));                   // (waited for here, where the compiler still knows what is in flight)
     score_convert(sb, 0, s0, s1, p1, cy, fk, [&]() __attribute__((always_inline)) { fvt = first_vt(sa, 1); }, nothing);
+    asm volatile("" : "+v"(fvt));
     mask_scores(e[1], 0, s0);
     contract_convert(sa, 1, p1, s0, p0, cy, fvt, [&]() __attribute__((always_inline)) { fk = first_k(sb, 1); });
+    asm volatile("" : "+v"(fk));
     if constexpr (GENERAL) {
       mid(std::false_type{}, true, sa);
       score_convert(sb, 1, s1, s0, p0, cy, fk, [&]() __attribute__((always_inline)) { fvt = first_vt(sb, 0); }, nothing);
@@ -444,6 +455,7 @@ fwd_bf16_kernel(FwdArgs a) {
                       if (m % EVERY == EVERY - 1 && m / EVERY < NDMA) issue_part(t_new, sa, m / EVERY);
                     });
     }
+    asm volatile("" : "+v"(fvt));
     mask_scores(e[1], 1, s1);
     e[0] = e[1]; e[1] = e[2]; e[2] = e[3]; e[3] = e[4];
   }
