@@ -127,7 +127,8 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   const int i_wg0 = qt * QM, i_wg1 = min(d.Sq, i_wg0 + QM) - 1;
   MaskDev mk = a.mask;
   unsigned* const bits = (unsigned*)(smem + SM::RING);
-  bool have_bits = false;
+  bool have_bits = false, have_cls = false;
+  const unsigned *cls_any = bits, *cls_all = bits; // this wave's class planes (valid with have_cls)
   int nt = max(t_end - t_begin, 0);                // number of tiles this workgroup performs
   if (GENERAL && mk.allow) {
     if (n_tiles <= (SM::BITS_BYTES - 16) * 8) {
@@ -142,6 +143,20 @@ bwd_dq_bf16_kernel(BwdArgs a) {
       t_begin = nth_bit(bits, k0, n_tiles);
       t_end = k1 > k0 ? nth_bit(bits, k1 - 1, n_tiles) + 1 : t_begin;
       nt = k1 - k0;
+      // the class (nothing / everything / mixed) of every tile for every wave's rows, when the
+      // planes fit beside the visibility bits: the loop then reads the bitmap for mixed tiles only
+      const int pw = bit_plane_words(n_tiles);
+      if ((1 + 2 * NWV) * pw * 4 <= SM::BITS_BYTES) {
+        have_cls = true;
+        for (int w = 0; w < NWV; ++w) {
+          const int r0 = i_wg0 + 32 * QB * w, r1 = min(d.Sq, r0 + 32 * QB) - 1;
+          build_class_bits(bits + (1 + 2 * w) * pw, bits + (2 + 2 * w) * pw, n_tiles, tid, 256, [&](int t) {
+            return r0 > r1 ? 0 : mask_rect(mk, b, r0, r1, t * TN, min(d.Skv, t * TN + TN) - 1);
+          });
+        }
+        cls_any = bits + (1 + 2 * wave) * pw;
+        cls_all = bits + (2 + 2 * wave) * pw;
+      }
     } else if (t_begin < t_end) {
       mk = mask_to_lds(a.mask, b, i_wg0 / mk.q_chunk, i_wg1 / mk.q_chunk, (t_begin * TN) / mk.kv_block,
                        (min(d.Skv, t_end * TN) - 1) / mk.kv_block, (uint8_t*)smem + SM::RING + SM::BITS_BYTES,
@@ -271,8 +286,9 @@ bwd_dq_bf16_kernel(BwdArgs a) {
     const int j0 = t * TN + 32 * hb;
     int cls = 1;
     if (mk.allow && i_wave0 < d.Sq)
-      cls = mask_rect(mk, b, i_wave0, min(d.Sq, i_wave0 + 32 * QB) - 1, min(j0, d.Skv - 1),
-                      min(d.Skv, j0 + 32) - 1);
+      cls = have_cls ? class_of(cls_any, cls_all, t)      // (of the whole tile: fine for either half)
+                     : mask_rect(mk, b, i_wave0, min(d.Sq, i_wave0 + 32 * QB) - 1, min(j0, d.Skv - 1),
+                                 min(d.Skv, j0 + 32) - 1);
     if (cls == 1 && j0 + 32 <= d.Skv) return;
     asm volatile("" ::: "memory");
 #pragma unroll
@@ -280,8 +296,8 @@ bwd_dq_bf16_kernel(BwdArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int j = j0 + 8 * (v / 4) + 4 * g + (v % 4), i = i_wave0 + 32 * qb + ql;
-        bool ok = j < d.Skv;
-        if (ok && cls != 1) ok = i < d.Sq && mask_elem(mk, b, i, j);
+        bool ok = j < d.Skv && cls != 0;
+        if (ok && cls == 2) ok = i < d.Sq && mask_elem(mk, b, i, j);
         if (!ok) s[qb][v] = -INFINITY;
       }
   };

@@ -185,6 +185,9 @@ __device__ __forceinline__ bool mask_elem(const MaskDev& m, int b, int i, int j)
 //    unchanged: the pointer is generic); otherwise it returns the mask as it is.
 //  * build_bits evaluates pred(i), i in [0, n), with all threads at once and leaves bit i in the
 //    word array bits[2 ..] (bits[0] = number of set bits); next_bit then finds the next set bit.
+//  * build_class_bits does the same for a three-way classification (two planes), read back by
+//    class_of: the kernels keep one pair of planes per wave, so that inside the loop the class of
+//    a (wave, tile) pair is two LDS words away and only mixed tiles ever touch the bitmap.
 __device__ inline MaskDev mask_to_lds(const MaskDev& m, int b, int c0, int c1, int f0, int f1,
                                       uint8_t* lds, int cap, int tid, int nthreads) {
   if (!m.allow) return m;
@@ -215,6 +218,27 @@ __device__ inline int build_bits(unsigned* bits, int n, int tid, int nthreads, P
   __syncthreads();
   return __builtin_amdgcn_readfirstlane((int)bits[0]);
 }
+// Two bit planes at once from a classification cls(i) in {0 nothing, 1 everything, 2 mixed}:
+// bit i of `any` = (cls != 0), of `all` = (cls == 1); same layout as build_bits (words from [2]).
+template <typename Cls>
+__device__ inline void build_class_bits(unsigned* any, unsigned* all, int n, int tid, int nthreads, Cls cls) {
+  for (int base = 0; base < n; base += nthreads) {   // workgroup-uniform trip count
+    const int i = base + tid;
+    const int c = i < n ? cls(i) : 0;
+    const unsigned long long ma = __ballot(c != 0), ml = __ballot(c == 1);
+    if ((tid & 63) == 0) {
+      *(unsigned long long*)(any + 2 + i / 32) = ma;
+      *(unsigned long long*)(all + 2 + i / 32) = ml;
+    }
+  }
+  __syncthreads();
+}
+__device__ inline int class_of(const unsigned* any, const unsigned* all, int i) {   // wave-uniform i
+  const unsigned a = (unsigned)__builtin_amdgcn_readfirstlane((int)any[2 + (i >> 5)]) >> (i & 31);
+  const unsigned l = (unsigned)__builtin_amdgcn_readfirstlane((int)all[2 + (i >> 5)]) >> (i & 31);
+  return (l & 1) ? 1 : ((a & 1) ? 2 : 0);
+}
+constexpr __host__ __device__ int bit_plane_words(int n) { return 2 + ((n + 63) / 64) * 2; }   // words one plane of n bits takes
 __device__ inline int next_bit(const unsigned* bits, int i, int n) {    // first set bit >= i, or n
   // (wave-uniform argument and result: the words are read through the vector path, so say so)
   while (i < n) {
