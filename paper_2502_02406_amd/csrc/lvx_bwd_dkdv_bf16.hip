@@ -336,14 +336,21 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
                               min(d.Skv - 1, j_wave0 + 32 * KVB - 1));
     if (cls == 1) return;
     asm volatile("" ::: "memory");
+    // all rows of the step in one chunk of the bitmap (the usual case): one probe per key
+    // instead of one per element
+    const bool one_chunk = cls == 2 && i0 / mk.q_chunk == (min(d.Sq, i0 + KM) - 1) / mk.q_chunk;
 #pragma unroll
-    for (int kb = 0; kb < KVB; ++kb)
+    for (int kb = 0; kb < KVB; ++kb) {
+      const int j = j_wave0 + 32 * kb + kl;
+      const bool key_ok = one_chunk && j < d.Skv && mask_elem(mk, b, i0, j);
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int j = j_wave0 + 32 * kb + kl, i = i0 + 8 * (v / 4) + 4 * g + (v % 4);
-        const bool ok = j < d.Skv && i < d.Sq && mask_elem(mk, b, i, j);
+        const int i = i0 + 8 * (v / 4) + 4 * g + (v % 4);
+        bool ok = cls != 0 && j < d.Skv && i < d.Sq;
+        if (ok) ok = one_chunk ? key_ok : mask_elem(mk, b, i, j);
         if (!ok) s[kb][v] = -INFINITY;
       }
+    }
   };
   // Conversion of scores into operands, element x of a step (x = 0 .. 16 KVB - 1: four query rows
   // q4 = x / (4 KVB) of key block kb = (x / 4) % KVB, row e = x % 4 of the four): p = exp2(s), dS = p dP,

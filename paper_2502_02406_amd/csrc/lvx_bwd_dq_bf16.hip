@@ -131,36 +131,33 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   const unsigned *cls_any = bits, *cls_all = bits; // this wave's class planes (valid with have_cls)
   int nt = max(t_end - t_begin, 0);                // number of tiles this workgroup performs
   if (GENERAL && mk.allow) {
-    if (n_tiles <= (SM::BITS_BYTES - 16) * 8) {
-      // bits over ALL tiles of the key range; the splits then share the visible tiles evenly
-      mk = mask_to_lds(a.mask, b, i_wg0 / mk.q_chunk, i_wg1 / mk.q_chunk, 0, (d.Skv - 1) / mk.kv_block,
-                       (uint8_t*)smem + SM::RING + SM::BITS_BYTES, SM::WIN_BYTES, tid, 256);
-      have_bits = true;
-      const int nn = build_bits(bits, n_tiles, tid, 256, [&](int t) {
-        return mask_rect(mk, b, i_wg0, i_wg1, t * TN, min(d.Skv, t * TN + TN) - 1) != 0;
-      });
+    auto share = [&](int nn) __attribute__((always_inline)) {   // the splits share the visible tiles evenly
       const int k0 = (int)((long)split * nn / a.n_split_dq), k1 = (int)((long)(split + 1) * nn / a.n_split_dq);
       t_begin = nth_bit(bits, k0, n_tiles);
       t_end = k1 > k0 ? nth_bit(bits, k1 - 1, n_tiles) + 1 : t_begin;
       nt = k1 - k0;
-      // the class (nothing / everything / mixed) of every tile for every wave's rows, when the
-      // planes fit beside the visibility bits: the loop then reads the bitmap for mixed tiles only
+    };
+    uint8_t* const win = (uint8_t*)smem + SM::RING + SM::BITS_BYTES;
+    if (plan_masked_tiles<D>(a.mask, b, i_wg0, i_wg1, d.Sq, d.Skv, n_tiles, bits, SM::BITS_BYTES, win,
+                             SM::WIN_BYTES, tid, &mk)) {
+      // visibility of every tile, and its class (nothing / everything / mixed) for every wave's
+      // rows: the loop then reads the bitmap for mixed tiles only
+      have_bits = have_cls = true;
       const int pw = bit_plane_words(n_tiles);
-      if ((1 + 2 * NWV) * pw * 4 <= SM::BITS_BYTES) {
-        have_cls = true;
-        for (int w = 0; w < NWV; ++w) {
-          const int r0 = i_wg0 + 32 * QB * w, r1 = min(d.Sq, r0 + 32 * QB) - 1;
-          build_class_bits(bits + (1 + 2 * w) * pw, bits + (2 + 2 * w) * pw, n_tiles, tid, 256, [&](int t) {
-            return r0 > r1 ? 0 : mask_rect(mk, b, r0, r1, t * TN, min(d.Skv, t * TN + TN) - 1);
-          });
-        }
-        cls_any = bits + (1 + 2 * wave) * pw;
-        cls_all = bits + (2 + 2 * wave) * pw;
-      }
+      cls_any = bits + (1 + 2 * wave) * pw;
+      cls_all = bits + (2 + 2 * wave) * pw;
+      share(__builtin_amdgcn_readfirstlane((int)bits[0]));
+    } else if (n_tiles <= (SM::BITS_BYTES - 16) * 8) {
+      // (shapes the planner does not take) bits over ALL tiles of the key range, probe by probe
+      mk = mask_to_lds(a.mask, b, i_wg0 / mk.q_chunk, i_wg1 / mk.q_chunk, 0, (d.Skv - 1) / mk.kv_block, win,
+                       SM::WIN_BYTES, tid, 256);
+      have_bits = true;
+      share(build_bits(bits, n_tiles, tid, 256, [&](int t) {
+        return mask_rect(mk, b, i_wg0, i_wg1, t * TN, min(d.Skv, t * TN + TN) - 1) != 0;
+      }));
     } else if (t_begin < t_end) {
       mk = mask_to_lds(a.mask, b, i_wg0 / mk.q_chunk, i_wg1 / mk.q_chunk, (t_begin * TN) / mk.kv_block,
-                       (min(d.Skv, t_end * TN) - 1) / mk.kv_block, (uint8_t*)smem + SM::RING + SM::BITS_BYTES,
-                       SM::WIN_BYTES, tid, 256);
+                       (min(d.Skv, t_end * TN) - 1) / mk.kv_block, win, SM::WIN_BYTES, tid, 256);
     }
   }
   auto tile_needed = [&](int t) __attribute__((always_inline)) -> bool {
@@ -291,15 +288,21 @@ bwd_dq_bf16_kernel(BwdArgs a) {
                                  min(d.Skv, j0 + 32) - 1);
     if (cls == 1 && j0 + 32 <= d.Skv) return;
     asm volatile("" ::: "memory");
+    // mixed, but all keys of the half in one block of the bitmap (the usual case: blocks are
+    // frames): one probe per query row instead of one per element
+    const bool one_block = cls == 2 && j0 / mk.kv_block == (min(d.Skv, j0 + 32) - 1) / mk.kv_block;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
+    for (int qb = 0; qb < QB; ++qb) {
+      const int i = i_wave0 + 32 * qb + ql;
+      const bool row_ok = one_block && i < d.Sq && mask_elem(mk, b, i, j0);
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int j = j0 + 8 * (v / 4) + 4 * g + (v % 4), i = i_wave0 + 32 * qb + ql;
+        const int j = j0 + 8 * (v / 4) + 4 * g + (v % 4);
         bool ok = j < d.Skv && cls != 0;
-        if (ok && cls == 2) ok = i < d.Sq && mask_elem(mk, b, i, j);
+        if (ok && cls == 2) ok = one_block ? row_ok : (i < d.Sq && mask_elem(mk, b, i, j));
         if (!ok) s[qb][v] = -INFINITY;
       }
+    }
   };
   // Conversion of scores into the dS operands, element x of a half (x = 0..31: query block
   // qb = x / 16, register v = x % 16): p = exp2(s c2 - L2), dS = p (dP - delta) -- with FOLD both
@@ -446,19 +449,51 @@ bwd_dq_bf16_kernel(BwdArgs a) {
     e[0] = e[1]; e[1] = e[2]; e[2] = e[3]; e[3] = e[4];
   }
 
-  // ---- dQ += scale * acc (transposed accumulators: lane = query row).  The last matrix
-  // instructions must have retired before their registers are read.
-  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+  // ---- dQ += scale * acc.  The accumulators are transposed (lane = query row, registers =
+  // columns), which would make every store instruction touch 64 rows; each wave therefore turns
+  // its 64 rows around through LDS (the ring is free by now) and adds them to dq_accum a row
+  // pair at a time, 64 lanes on 1 KB of consecutive addresses: plain read-add-write when this
+  // workgroup is the only one on its rows in this launch (launches follow each other in stream
+  // order), float atomics when the key range is split over several workgroups.
+  // The last matrix instructions must have retired before their registers are read.
+  if constexpr (DB == 4) {
+    asm volatile("s_nop 15\n\ts_nop 15" : "+a"(dq[0][0]), "+a"(dq[0][1]), "+a"(dq[0][2]), "+a"(dq[0][3]),
+                 "+a"(dq[1][0]), "+a"(dq[1][1]), "+a"(dq[1][2]), "+a"(dq[1][3]));
+  } else {
+    asm volatile("s_nop 15\n\ts_nop 15" : "+a"(dq[0][0]), "+a"(dq[0][1]), "+a"(dq[1][0]), "+a"(dq[1][1]));
+  }
+  __syncthreads();                                 // every wave is done reading the ring
+  constexpr int RP = (D + 4) * 4;                  // row pitch in bytes (+16: the b128 writes of 16 rows tile the banks)
+  static_assert(NWV * 32 * QB * RP <= SM::RING, "the turn-around buffer must fit the ring");
+  char* const tbuf = smem + wave * (32 * QB * RP);
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const int i = i_wave0 + 32 * qb + ql;
-    if (i >= d.Sq) continue;
-    float* out = a.dq_accum + (((long)b * d.Hq + hq) * d.Sq + i) * D;
+  for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int v = 0; v < 16; ++v)
-        unsafeAtomicAdd(out + 32 * db + 8 * (v / 4) + 4 * g + (v % 4), dq[qb][db][v] * d.scale);
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const f32x4 y = {dq[qb][db][4 * q4] * d.scale, dq[qb][db][4 * q4 + 1] * d.scale,
+                         dq[qb][db][4 * q4 + 2] * d.scale, dq[qb][db][4 * q4 + 3] * d.scale};
+        *(f32x4*)(tbuf + (32 * qb + ql) * RP + (32 * db + 8 * q4 + 4 * g) * 4) = y;
+      }
+  // (each wave reads back only what it wrote itself: no barrier, the LDS queue keeps the order)
+  constexpr int LPR = D / 4;                       // lanes per row, four floats each
+  constexpr int RPI = 64 / LPR;                    // rows per instruction
+  const int rsub = lane / LPR, col = (lane % LPR) * 4;
+  float* const out0 = a.dq_accum + (((long)b * d.Hq + hq) * d.Sq) * D;
+  for (int r0 = 0; r0 < 32 * QB; r0 += RPI) {
+    const int r = r0 + rsub, i = i_wave0 + r;
+    if (i >= d.Sq) continue;
+    const f32x4 y = *(const f32x4*)(tbuf + r * RP + col * 4);
+    float* const out = out0 + (long)i * D + col;
+    if (a.n_split_dq == 1) {
+      f32x4 x = *(const f32x4*)out;
+      x += y;
+      *(f32x4*)out = x;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) unsafeAtomicAdd(out + e, y[e]);
+    }
   }
 }
 

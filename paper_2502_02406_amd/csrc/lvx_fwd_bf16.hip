@@ -95,36 +95,33 @@ fwd_bf16_kernel(FwdArgs a) {
   const unsigned *cls_any = bits, *cls_all = bits; // this wave's class planes (valid with have_cls)
   int nt = max(t_end - t_begin, 0);                // number of tiles this workgroup performs
   if (GENERAL && mk.allow) {
-    if (n_tiles <= (SM::BITS_BYTES - 16) * 8) {
-      // bits over ALL tiles of the key range; the splits then share the visible tiles evenly
-      mk = mask_to_lds(a.mask, b, i_wg0 / mk.q_chunk, i_wg1 / mk.q_chunk, 0, (d.Skv - 1) / mk.kv_block,
-                       (uint8_t*)smem + SM::RING + SM::BITS_BYTES, SM::WIN_BYTES, tid, 256);
-      have_bits = true;
-      const int nn = build_bits(bits, n_tiles, tid, 256, [&](int t) {
-        return mask_rect(mk, b, i_wg0, i_wg1, t * TN, min(d.Skv, t * TN + TN) - 1) != 0;
-      });
+    auto share = [&](int nn) __attribute__((always_inline)) {   // the splits share the visible tiles evenly
       const int k0 = (int)((long)split * nn / a.n_split), k1 = (int)((long)(split + 1) * nn / a.n_split);
       t_begin = nth_bit(bits, k0, n_tiles);
       t_end = k1 > k0 ? nth_bit(bits, k1 - 1, n_tiles) + 1 : t_begin;
       nt = k1 - k0;
-      // the class (nothing / everything / mixed) of every tile for every wave's rows, when the
-      // planes fit beside the visibility bits: the loop then reads the bitmap for mixed tiles only
+    };
+    uint8_t* const win = (uint8_t*)smem + SM::RING + SM::BITS_BYTES;
+    if (plan_masked_tiles<D>(a.mask, b, i_wg0, i_wg1, d.Sq, d.Skv, n_tiles, bits, SM::BITS_BYTES, win,
+                             SM::WIN_BYTES, tid, &mk)) {
+      // visibility of every tile, and its class (nothing / everything / mixed) for every wave's
+      // rows: the loop then reads the bitmap for mixed tiles only
+      have_bits = have_cls = true;
       const int pw = bit_plane_words(n_tiles);
-      if ((1 + 2 * NWV) * pw * 4 <= SM::BITS_BYTES) {
-        have_cls = true;
-        for (int w = 0; w < NWV; ++w) {
-          const int r0 = i_wg0 + 32 * QB * w, r1 = min(d.Sq, r0 + 32 * QB) - 1;
-          build_class_bits(bits + (1 + 2 * w) * pw, bits + (2 + 2 * w) * pw, n_tiles, tid, 256, [&](int t) {
-            return r0 > r1 ? 0 : mask_rect(mk, b, r0, r1, t * TN, min(d.Skv, t * TN + TN) - 1);
-          });
-        }
-        cls_any = bits + (1 + 2 * wave) * pw;
-        cls_all = bits + (2 + 2 * wave) * pw;
-      }
+      cls_any = bits + (1 + 2 * wave) * pw;
+      cls_all = bits + (2 + 2 * wave) * pw;
+      share(__builtin_amdgcn_readfirstlane((int)bits[0]));
+    } else if (n_tiles <= (SM::BITS_BYTES - 16) * 8) {
+      // (shapes the planner does not take) bits over ALL tiles of the key range, probe by probe
+      mk = mask_to_lds(a.mask, b, i_wg0 / mk.q_chunk, i_wg1 / mk.q_chunk, 0, (d.Skv - 1) / mk.kv_block, win,
+                       SM::WIN_BYTES, tid, 256);
+      have_bits = true;
+      share(build_bits(bits, n_tiles, tid, 256, [&](int t) {
+        return mask_rect(mk, b, i_wg0, i_wg1, t * TN, min(d.Skv, t * TN + TN) - 1) != 0;
+      }));
     } else if (t_begin < t_end) {
       mk = mask_to_lds(a.mask, b, i_wg0 / mk.q_chunk, i_wg1 / mk.q_chunk, (t_begin * TN) / mk.kv_block,
-                       (min(d.Skv, t_end * TN) - 1) / mk.kv_block, (uint8_t*)smem + SM::RING + SM::BITS_BYTES,
-                       SM::WIN_BYTES, tid, 256);
+                       (min(d.Skv, t_end * TN) - 1) / mk.kv_block, win, SM::WIN_BYTES, tid, 256);
     }
   }
   auto tile_needed = [&](int t) __attribute__((always_inline)) -> bool {
@@ -248,15 +245,21 @@ fwd_bf16_kernel(FwdArgs a) {
                                  min(d.Skv, j0 + 32) - 1);
     if (cls == 1 && j0 + 32 <= d.Skv) return;
     asm volatile("" ::: "memory");
+    // mixed, but all keys of the half in one block of the bitmap (the usual case: blocks are
+    // frames): one probe per query row instead of one per element
+    const bool one_block = cls == 2 && j0 / mk.kv_block == (min(d.Skv, j0 + 32) - 1) / mk.kv_block;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
+    for (int qb = 0; qb < QB; ++qb) {
+      const int i = i_wave0 + 32 * qb + ql;
+      const bool row_ok = one_block && i < d.Sq && mask_elem(mk, b, i, j0);
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int j = j0 + 8 * (v / 4) + 4 * g + (v % 4), i = i_wave0 + 32 * qb + ql;
+        const int j = j0 + 8 * (v / 4) + 4 * g + (v % 4);
         bool ok = j < d.Skv && cls != 0;
-        if (ok && cls == 2) ok = i < d.Sq && mask_elem(mk, b, i, j);
+        if (ok && cls == 2) ok = one_block ? row_ok : (i < d.Sq && mask_elem(mk, b, i, j));
         if (!ok) s[qb][v] = -INFINITY;
       }
+    }
   };
   // Before a half's scores are exponentiated: does any row top its reference by more than
   // 2^LAZY?  Then (rarely) the reference of the rows that grew is raised to their new maximum:

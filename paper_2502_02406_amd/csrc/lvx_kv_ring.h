@@ -70,5 +70,81 @@ __device__ __forceinline__ void mfma_acc(f32x16& c_acc, bf16x8 a, bf16x8 b) {   
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c_acc) : "v"(a), "v"(b));
 }
 
+// Media mask, analysed once per workgroup (all 256 threads call this; it ends with a barrier).
+// The window of the bitmap that the workgroup's rows can touch -- chunks c0 .. c0 + h - 1, every
+// key block -- is copied to LDS; from it one word per key block is made (bit c: chunk c0 + c sees
+// the block), and from those words, for every key tile, nine bits: visible to the workgroup at
+// all, and for each wave whether its rows see something / everything of the tile.  They are left
+// as bit planes of bit_plane_words(n_tiles) words each from `bits` on: plane 0 the workgroup's
+// (bits[0] = number of visible tiles), planes 1 + 2 w and 2 + 2 w wave w's `any` and `all`.
+// Every read of the window and of the words is an LDS read; nothing here goes through the generic
+// pointer of MaskDev, whose every probe costs a round trip of the flat path.
+// Returns false, having done nothing, when the shapes do not fit (more than 32 chunks per
+// workgroup, window and words beyond win_cap bytes, planes beyond bits_cap bytes); on success *mk
+// addresses the LDS copy of the window, for the probes of mixed tiles inside the loop.
+template <int D>
+__device__ inline bool plan_masked_tiles(const MaskDev& m, int b, int i_wg0, int i_wg1, int Sq, int Skv,
+                                         int n_tiles, unsigned* bits, int bits_cap, uint8_t* win,
+                                         int win_cap, int tid, MaskDev* mk) {
+  const int c0 = i_wg0 / m.q_chunk, h = i_wg1 / m.q_chunk - c0 + 1;
+  const int w = (Skv - 1) / m.kv_block + 1;
+  const int pw = bit_plane_words(n_tiles);
+  const int win_bytes = (h * w + 3) & ~3;
+  if (h > 32 || (long)h * w + 4L * w + 4 > win_cap || (1 + 2 * NWV) * pw * 4 > bits_cap) return false;
+  for (int i = tid; i < w * h; i += 256)
+    win[i] = m.allow[b * m.stride_b + (long)(c0 + i / w) * m.stride_q + i % w];
+  if (tid == 0) bits[0] = 0;
+  __syncthreads();
+  unsigned* const seen = (unsigned*)(win + win_bytes);     // seen[f]: bit c = chunk c0 + c sees block f
+  for (int f = tid; f < w; f += 256) {
+    unsigned x = 0;
+    for (int c = 0; c < h; ++c) x |= (win[c * w + f] != 0 ? 1u : 0u) << c;
+    seen[f] = x;
+  }
+  __syncthreads();
+  unsigned wmask[NWV];                                       // chunk bits of each wave's rows (0: no rows)
+#pragma unroll
+  for (int wv = 0; wv < NWV; ++wv) {
+    const int r0 = i_wg0 + 32 * QB * wv, r1 = min(Sq, r0 + 32 * QB) - 1;
+    wmask[wv] = 0;
+    if (r0 <= r1) {
+      const int a = r0 / m.q_chunk - c0, z = r1 / m.q_chunk - c0;           // 0 <= a <= z < h <= 32
+      wmask[wv] = (z - a == 31 ? ~0u : ((1u << (z - a + 1)) - 1u)) << a;
+    }
+  }
+  for (int base = 0; base < n_tiles; base += 256) {          // workgroup-uniform trip count
+    const int t = base + tid;
+    unsigned any = 0, all = ~0u;
+    if (t < n_tiles) {
+      const int fa = (t * TN) / m.kv_block, fb = (min(Skv, t * TN + TN) - 1) / m.kv_block;
+      for (int f = fa; f <= fb; ++f) { any |= seen[f]; all &= seen[f]; }
+    } else {
+      all = 0;
+    }
+    const unsigned long long vis = __ballot(any != 0);
+    unsigned long long wa[NWV], wl[NWV];
+#pragma unroll
+    for (int wv = 0; wv < NWV; ++wv) {
+      wa[wv] = __ballot((any & wmask[wv]) != 0);
+      wl[wv] = __ballot(wmask[wv] != 0 && (all & wmask[wv]) == wmask[wv]);
+    }
+    if ((tid & 63) == 0) {
+      *(unsigned long long*)(bits + 2 + t / 32) = vis;
+      atomicAdd(&bits[0], (unsigned)__popcll(vis));
+#pragma unroll
+      for (int wv = 0; wv < NWV; ++wv) {
+        *(unsigned long long*)(bits + (1 + 2 * wv) * pw + 2 + t / 32) = wa[wv];
+        *(unsigned long long*)(bits + (2 + 2 * wv) * pw + 2 + t / 32) = wl[wv];
+      }
+    }
+  }
+  __syncthreads();
+  *mk = m;
+  mk->allow = win - ((long)c0 * w);
+  mk->stride_b = 0;
+  mk->stride_q = w;
+  return true;
+}
+
 }  // namespace kvring
 }  // namespace lvx
