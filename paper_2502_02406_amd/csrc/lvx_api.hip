@@ -90,9 +90,13 @@ size_t fwd_ws(const Dims& d, int n_split) {
   return align_up(rows * d.D * sizeof(float) * n_split) + align_up(rows * sizeof(float) * n_split);
 }
 int sq_padded(const Dims& d) { return (d.Sq + 31) / 32 * 32; }
-size_t bwd_ws(const Dims& d) {      // delta [B,Hq,Sq] + padded statistics [B,Hq,sq_pad/32][2][32]
+size_t bwd_ws_fixed(const Dims& d) {   // delta [B,Hq,Sq] + padded statistics [B,Hq,sq_pad/32][2][32]
   return align_up((size_t)d.B * d.Hq * d.Sq * sizeof(float)) +
          align_up(2 * (size_t)d.B * d.Hq * sq_padded(d) * sizeof(float));
+}
+size_t bwd_ws(const Dims& d, int n_split) {   // ... + the dQ kernel's partial sums [n_split, B,Hq,Sq,D] when it splits
+  const size_t part = n_split > 1 ? align_up((size_t)n_split * d.B * d.Hq * d.Sq * d.D * sizeof(float)) : 0;
+  return bwd_ws_fixed(d) + part;
 }
 
 }  // namespace
@@ -118,7 +122,7 @@ size_t lvx_xattn_workspace_bytes(const lvx_problem* p, lvx_dtype dtype, int whic
   if (check_problem(p, dtype) != LVX_OK) return 0;
   const Dims d = make_dims(p);
   if (which == LVX_WS_FWD) return fwd_ws(d, fwd_split(d, dtype, true));   // a masked call splits at least as much
-  if (which == LVX_WS_BWD) return bwd_ws(d);
+  if (which == LVX_WS_BWD) return bwd_ws(d, bwd_split(d, dtype, true));   // a masked call splits at least as much
   return 0;
 }
 
@@ -211,14 +215,15 @@ lvx_status lvx_xattn_bwd_stages(const lvx_problem* p, lvx_dtype dtype, const voi
   BwdArgs a;
   a.d = make_dims(p);
   a.mask = make_mask(mask);
-  const size_t need = bwd_ws(a.d);
+  a.n_split_dq = bwd_split(a.d, dtype, mask != nullptr);
+  const size_t need = bwd_ws(a.d, a.n_split_dq);
   if (!workspace || ((uintptr_t)workspace % ALIGN) != 0 || workspace_bytes < need) return LVX_ERR_WORKSPACE;
   a.q = q; a.k = k; a.v = v; a.o = o; a.d_o = d_o; a.lse = lse;
   a.delta = (float*)workspace;
   a.sq_pad = sq_padded(a.d);
   a.stats = (float*)((char*)workspace + align_up((size_t)a.d.B * a.d.Hq * a.d.Sq * sizeof(float)));
   a.dq_accum = dq_accum; a.dk = dk; a.dv = dv;
-  a.n_split_dq = bwd_split(a.d, dtype, mask != nullptr);
+  a.dq_part = a.n_split_dq > 1 ? (float*)((char*)workspace + bwd_ws_fixed(a.d)) : nullptr;
   hipStream_t s = (hipStream_t)hip_stream;
   hipError_t e = hipSuccess;
   if (stages & LVX_BWD_DELTA) e = launch_delta(a.d, o, d_o, dtype == LVX_F32, lse, a.delta, a.stats, a.sq_pad, s);

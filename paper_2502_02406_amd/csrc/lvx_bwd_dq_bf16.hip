@@ -277,6 +277,12 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   };
   auto nothing = [](int) __attribute__((always_inline)) {};
   auto no_tail = []() __attribute__((always_inline)) {};
+  // The matrix instructions are opaque to the compiler, so nothing makes a reader (or writer) of
+  // fresh scores wait for them.  In the pipelined loop a half's scores are first touched two
+  // matrix instructions into the next phase; everywhere else this wait comes first.
+  auto settle_scores = [&](f32x16 (&s)[QB]) __attribute__((always_inline)) {
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" : "+v"(s[0]), "+v"(s[1]));
+  };
   // key tail and masked elements of a half's scores -> -inf (wave-uniform decision, rarely taken)
   auto mask_scores = [&](int t, int hb, f32x16 (&s)[QB]) __attribute__((always_inline)) {
     if (!GENERAL) return;
@@ -288,6 +294,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
                                  min(d.Skv, j0 + 32) - 1);
     if (cls == 1 && j0 + 32 <= d.Skv) return;
     asm volatile("" ::: "memory");
+    settle_scores(s);
     // mixed, but all keys of the half in one block of the bitmap (the usual case: blocks are
     // frames): one probe per query row instead of one per element
     const bool one_block = cls == 2 && j0 / mk.kv_block == (min(d.Skv, j0 + 32) - 1) / mk.kv_block;
@@ -405,6 +412,8 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   if (nt > 0) {
     score(smem, 0, s0, p0, nothing, first_kv(smem, 0), no_tail);
     mask_scores(e[0], 0, s0);
+    settle_scores(s0);
+    settle_scores(p0);
     convert(s0, p0, ds0);
     score(smem, 1, s1, p1, nothing, first_kv(smem, 1), no_tail);
     mask_scores(e[0], 1, s1);
@@ -452,9 +461,11 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   // ---- dQ += scale * acc.  The accumulators are transposed (lane = query row, registers =
   // columns), which would make every store instruction touch 64 rows; each wave therefore turns
   // its 64 rows around through LDS (the ring is free by now) and adds them to dq_accum a row
-  // pair at a time, 64 lanes on 1 KB of consecutive addresses: plain read-add-write when this
-  // workgroup is the only one on its rows in this launch (launches follow each other in stream
-  // order), float atomics when the key range is split over several workgroups.
+  // pair at a time, 64 lanes on 1 KB of consecutive addresses: read-add-write when this workgroup
+  // is the only one on its rows in this launch (launches follow each other in stream order);
+  // when the key range is split over several workgroups, each stores its sums in its own slice
+  // of the workspace and a reduction follows the kernel (float atomics from every split would
+  // be bounded by the L2 atomic rate, about 50 G per second).
   // The last matrix instructions must have retired before their registers are read.
   if constexpr (DB == 4) {
     asm volatile("s_nop 15\n\ts_nop 15" : "+a"(dq[0][0]), "+a"(dq[0][1]), "+a"(dq[0][2]), "+a"(dq[0][3]),
@@ -480,20 +491,16 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   constexpr int LPR = D / 4;                       // lanes per row, four floats each
   constexpr int RPI = 64 / LPR;                    // rows per instruction
   const int rsub = lane / LPR, col = (lane % LPR) * 4;
-  float* const out0 = a.dq_accum + (((long)b * d.Hq + hq) * d.Sq) * D;
+  const bool whole = a.n_split_dq == 1;            // else: this split's own slice of the partial sums
+  float* const out0 = (whole ? a.dq_accum : a.dq_part + (long)split * d.B * d.Hq * d.Sq * D) +
+                      (((long)b * d.Hq + hq) * d.Sq) * D;
   for (int r0 = 0; r0 < 32 * QB; r0 += RPI) {
     const int r = r0 + rsub, i = i_wave0 + r;
     if (i >= d.Sq) continue;
-    const f32x4 y = *(const f32x4*)(tbuf + r * RP + col * 4);
+    f32x4 y = *(const f32x4*)(tbuf + r * RP + col * 4);
     float* const out = out0 + (long)i * D + col;
-    if (a.n_split_dq == 1) {
-      f32x4 x = *(const f32x4*)out;
-      x += y;
-      *(f32x4*)out = x;
-    } else {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) unsafeAtomicAdd(out + e, y[e]);
-    }
+    if (whole) y += *(const f32x4*)out;
+    *(f32x4*)out = y;
   }
 }
 
@@ -536,8 +543,12 @@ hipError_t launch_bwd_dq_bf16(const BwdArgs& a, hipStream_t s) {
   const int n_qt = (d.Sq + QM - 1) / QM;
   const long grid = xcd_grid(d.B * d.Hkv, a.n_split_dq * G * n_qt);
   const bool general = a.mask.allow != nullptr || d.Skv % TN != 0;
-  if (d.D == 64) return general ? launch<64, true>(a, grid, s) : launch<64, false>(a, grid, s);
-  return general ? launch<128, true>(a, grid, s) : launch<128, false>(a, grid, s);
+  hipError_t e;
+  if (d.D == 64) e = general ? launch<64, true>(a, grid, s) : launch<64, false>(a, grid, s);
+  else e = general ? launch<128, true>(a, grid, s) : launch<128, false>(a, grid, s);
+  if (e == hipSuccess && a.n_split_dq > 1)
+    e = launch_dq_reduce(a.dq_part, a.n_split_dq, (long)d.B * d.Hq * d.Sq * d.D, a.dq_accum, s);
+  return e;
 }
 
 hipError_t launch_bwd_bf16(const BwdArgs& a, unsigned stages, hipStream_t s) {

@@ -159,6 +159,21 @@ hipError_t launch_delta(const Dims& d, const void* o, const void* d_o, int is_f3
   return hipGetLastError();
 }
 
+// dq_accum += sum of the KV splits' partial dQ (float32, contiguous).  One thread per 4 elements.
+__global__ void __launch_bounds__(256) dq_reduce_kernel(const float* parts, int n_parts, long n, float* acc) {
+  const long i = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i >= n) return;
+  f32x4 x = *(const f32x4*)(acc + i);
+  for (int k = 0; k < n_parts; ++k) x += *(const f32x4*)(parts + (long)k * n + i);
+  *(f32x4*)(acc + i) = x;
+}
+
+hipError_t launch_dq_reduce(const float* parts, int n_parts, long n, float* dq_accum, hipStream_t s) {
+  const unsigned blocks = (unsigned)((n / 4 + 255) / 256);
+  dq_reduce_kernel<<<blocks, 256, 0, s>>>(parts, n_parts, n, dq_accum);
+  return hipGetLastError();
+}
+
 // dq (input dtype, Q's strides) = dq_accum (float32, contiguous).  One thread per 8 elements.
 template <bool F32>
 __global__ void __launch_bounds__(256) dq_finalize_kernel(Dims d, const float* acc, void* dq) {

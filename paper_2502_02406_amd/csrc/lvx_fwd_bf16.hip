@@ -234,6 +234,12 @@ fwd_bf16_kernel(FwdArgs a) {
   };
   auto nothing = [](int) __attribute__((always_inline)) {};
   auto no_tail = []() __attribute__((always_inline)) {};
+  // The matrix instructions are opaque to the compiler, so nothing makes a reader (or writer) of
+  // fresh scores wait for them.  In the pipelined loop a half's scores are first touched two
+  // matrix instructions into the next phase; everywhere else this wait comes first.
+  auto settle_scores = [&](f32x16 (&s)[QB]) __attribute__((always_inline)) {
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" : "+v"(s[0]), "+v"(s[1]));
+  };
   // key tail and masked elements of a half's scores -> -inf (wave-uniform decision, rarely taken)
   auto mask_scores = [&](int t, int hb, f32x16 (&s)[QB]) __attribute__((always_inline)) {
     if (!GENERAL) return;
@@ -245,6 +251,7 @@ fwd_bf16_kernel(FwdArgs a) {
                                  min(d.Skv, j0 + 32) - 1);
     if (cls == 1 && j0 + 32 <= d.Skv) return;
     asm volatile("" ::: "memory");
+    settle_scores(s);
     // mixed, but all keys of the half in one block of the bitmap (the usual case: blocks are
     // frames): one probe per query row instead of one per element
     const bool one_block = cls == 2 && j0 / mk.kv_block == (min(d.Skv, j0 + 32) - 1) / mk.kv_block;
@@ -439,6 +446,7 @@ fwd_bf16_kernel(FwdArgs a) {
   if (nt > 0) {
     score(smem, 0, s0, nothing, first_k(smem, 0), no_tail);
     mask_scores(e[0], 0, s0);
+    settle_scores(s0);
     check(s0);
     settle();                                      // (O^T is still zero: this only clears the factor)
     convert(s0, p0);

@@ -44,7 +44,9 @@ struct BwdArgs {
   int sq_pad;           // Sq rounded up to a multiple of 32
   float* dq_accum;      // [B,Hq,Sq,D] float32, accumulated into
   void *dk, *dv;        // K's strides, input dtype, overwritten
-  int n_split_dq;       // KV splits of the dQ kernel (each adds into dq_accum)
+  int n_split_dq;       // KV splits of the dQ kernel
+  float* dq_part;       // workspace, [n_split_dq, B,Hq,Sq,D] float32: the splits' sums (n_split_dq > 1),
+                        // added to dq_accum by a reduction that follows the kernel
 };
 
 struct MergeArgs {
@@ -74,6 +76,8 @@ int bwd_bf16_pick_split(const Dims& d, int n_cu, bool masked);
 hipError_t launch_merge(const MergeArgs& a, int part_is_f32, int out_is_f32, hipStream_t s);
 hipError_t launch_delta(const Dims& d, const void* o, const void* d_o, int is_f32, const float* lse,
                         float* delta, float* stats, int sq_pad, hipStream_t s);
+// dq_accum[i] += sum over the n_parts slices of `parts` (each n floats, n a multiple of 4)
+hipError_t launch_dq_reduce(const float* parts, int n_parts, long n, float* dq_accum, hipStream_t s);
 hipError_t launch_dq_finalize(const Dims& d, const float* dq_accum, void* dq, int is_f32,
                               hipStream_t s);
 

@@ -128,7 +128,7 @@ __device__ inline bool plan_masked_tiles(const MaskDev& m, int b, int i_wg0, int
       wa[wv] = __ballot((any & wmask[wv]) != 0);
       wl[wv] = __ballot(wmask[wv] != 0 && (all & wmask[wv]) == wmask[wv]);
     }
-    if ((tid & 63) == 0) {
+    if ((tid & 63) == 0 && t < n_tiles) {              // (a wave wholly past the end has no words in the planes)
       *(unsigned long long*)(bits + 2 + t / 32) = vis;
       atomicAdd(&bits[0], (unsigned)__popcll(vis));
 #pragma unroll

@@ -185,9 +185,9 @@ __device__ __forceinline__ bool mask_elem(const MaskDev& m, int b, int i, int j)
 //    unchanged: the pointer is generic); otherwise it returns the mask as it is.
 //  * build_bits evaluates pred(i), i in [0, n), with all threads at once and leaves bit i in the
 //    word array bits[2 ..] (bits[0] = number of set bits); next_bit then finds the next set bit.
-//  * build_class_bits does the same for a three-way classification (two planes), read back by
-//    class_of: the kernels keep one pair of planes per wave, so that inside the loop the class of
-//    a (wave, tile) pair is two LDS words away and only mixed tiles ever touch the bitmap.
+//  * class_of reads a three-way classification back from two such planes: the query-stationary
+//    kernels keep one pair per wave, so that inside the loop the class of a (wave, tile) pair is
+//    two LDS words away and only mixed tiles ever touch the bitmap.
 __device__ inline MaskDev mask_to_lds(const MaskDev& m, int b, int c0, int c1, int f0, int f1,
                                       uint8_t* lds, int cap, int tid, int nthreads) {
   if (!m.allow) return m;
@@ -210,7 +210,7 @@ __device__ inline int build_bits(unsigned* bits, int n, int tid, int nthreads, P
     const int i = base + tid;
     const bool on = i < n && pred(i);
     const unsigned long long m = __ballot(on);
-    if ((tid & 63) == 0) {
+    if ((tid & 63) == 0 && i < n) {
       *(unsigned long long*)(bits + 2 + i / 32) = m;
       atomicAdd(&bits[0], (unsigned)__popcll(m));
     }
@@ -218,21 +218,8 @@ __device__ inline int build_bits(unsigned* bits, int n, int tid, int nthreads, P
   __syncthreads();
   return __builtin_amdgcn_readfirstlane((int)bits[0]);
 }
-// Two bit planes at once from a classification cls(i) in {0 nothing, 1 everything, 2 mixed}:
-// bit i of `any` = (cls != 0), of `all` = (cls == 1); same layout as build_bits (words from [2]).
-template <typename Cls>
-__device__ inline void build_class_bits(unsigned* any, unsigned* all, int n, int tid, int nthreads, Cls cls) {
-  for (int base = 0; base < n; base += nthreads) {   // workgroup-uniform trip count
-    const int i = base + tid;
-    const int c = i < n ? cls(i) : 0;
-    const unsigned long long ma = __ballot(c != 0), ml = __ballot(c == 1);
-    if ((tid & 63) == 0) {
-      *(unsigned long long*)(any + 2 + i / 32) = ma;
-      *(unsigned long long*)(all + 2 + i / 32) = ml;
-    }
-  }
-  __syncthreads();
-}
+// Class of item i from two bit planes laid out like build_bits' (words from [2]): bit i of `any`
+// = something visible, of `all` = everything visible.
 __device__ inline int class_of(const unsigned* any, const unsigned* all, int i) {   // wave-uniform i
   const unsigned a = (unsigned)__builtin_amdgcn_readfirstlane((int)any[2 + (i >> 5)]) >> (i & 31);
   const unsigned l = (unsigned)__builtin_amdgcn_readfirstlane((int)all[2 + (i >> 5)]) >> (i & 31);
