@@ -93,6 +93,7 @@ fwd_bf16_kernel(FwdArgs a) {
   unsigned* const bits = (unsigned*)(smem + SM::RING);
   bool have_bits = false, have_cls = false;
   const unsigned *cls_any = bits, *cls_all = bits; // this wave's class planes (valid with have_cls)
+  const unsigned* seen = bits;                     // per key block: which chunks of the workgroup see it (valid with have_cls)
   int nt = max(t_end - t_begin, 0);                // number of tiles this workgroup performs
   if (GENERAL && mk.allow) {
     auto share = [&](int nn) __attribute__((always_inline)) {   // the splits share the visible tiles evenly
@@ -103,7 +104,7 @@ fwd_bf16_kernel(FwdArgs a) {
     };
     uint8_t* const win = (uint8_t*)smem + SM::RING + SM::BITS_BYTES;
     if (plan_masked_tiles<D>(a.mask, b, i_wg0, i_wg1, d.Sq, d.Skv, n_tiles, bits, SM::BITS_BYTES, win,
-                             SM::WIN_BYTES, tid, &mk)) {
+                             SM::WIN_BYTES, tid, &mk, &seen)) {
       // visibility of every tile, and its class (nothing / everything / mixed) for every wave's
       // rows: the loop then reads the bitmap for mixed tiles only
       have_bits = have_cls = true;
@@ -124,6 +125,18 @@ fwd_bf16_kernel(FwdArgs a) {
                        (min(d.Skv, t_end * TN) - 1) / mk.kv_block, win, SM::WIN_BYTES, tid, 256);
     }
   }
+  int crow[QB] = {};                               // this lane's rows' chunks, relative to the window
+  if (GENERAL && have_cls) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+      crow[qb] = min(i_wave0 + 32 * qb + ql, d.Sq - 1) / mk.q_chunk - i_wg0 / mk.q_chunk;
+  }
+  // does row (qb, this lane) see key j?  From the per-block words in LDS when the planner ran,
+  // else from the bitmap itself.
+  auto sees = [&](int qb, int i, int j) __attribute__((always_inline)) -> bool {
+    if (have_cls) return (seen[j / mk.kv_block] >> crow[qb]) & 1u;
+    return mask_elem(mk, b, i, j);
+  };
   auto tile_needed = [&](int t) __attribute__((always_inline)) -> bool {
     if (!GENERAL || !mk.allow) return true;
     return mask_rect(mk, b, i_wg0, i_wg1, t * TN, min(d.Skv, t * TN + TN) - 1) != 0;
@@ -258,12 +271,12 @@ fwd_bf16_kernel(FwdArgs a) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       const int i = i_wave0 + 32 * qb + ql;
-      const bool row_ok = one_block && i < d.Sq && mask_elem(mk, b, i, j0);
+      const bool row_ok = one_block && i < d.Sq && sees(qb, i, j0);
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int j = j0 + 8 * (v / 4) + 4 * g + (v % 4);
         bool ok = j < d.Skv && cls != 0;
-        if (ok && cls == 2) ok = one_block ? row_ok : (i < d.Sq && mask_elem(mk, b, i, j));
+        if (ok && cls == 2) ok = one_block ? row_ok : (i < d.Sq && sees(qb, i, j));
         if (!ok) s[qb][v] = -INFINITY;
       }
     }

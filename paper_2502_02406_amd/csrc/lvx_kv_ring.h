@@ -81,11 +81,12 @@ __device__ __forceinline__ void mfma_acc(f32x16& c_acc, bf16x8 a, bf16x8 b) {   
 // pointer of MaskDev, whose every probe costs a round trip of the flat path.
 // Returns false, having done nothing, when the shapes do not fit (more than 32 chunks per
 // workgroup, window and words beyond win_cap bytes, planes beyond bits_cap bytes); on success *mk
-// addresses the LDS copy of the window, for the probes of mixed tiles inside the loop.
+// addresses the LDS copy of the window and *seen_out the per-block words, which is what the loop
+// probes for mixed tiles: (seen[j / kv_block] >> (i / q_chunk - c0)) & 1 says whether row i sees key j.
 template <int D>
 __device__ inline bool plan_masked_tiles(const MaskDev& m, int b, int i_wg0, int i_wg1, int Sq, int Skv,
                                          int n_tiles, unsigned* bits, int bits_cap, uint8_t* win,
-                                         int win_cap, int tid, MaskDev* mk) {
+                                         int win_cap, int tid, MaskDev* mk, const unsigned** seen_out) {
   const int c0 = i_wg0 / m.q_chunk, h = i_wg1 / m.q_chunk - c0 + 1;
   const int w = (Skv - 1) / m.kv_block + 1;
   const int pw = bit_plane_words(n_tiles);
@@ -139,6 +140,7 @@ __device__ inline bool plan_masked_tiles(const MaskDev& m, int b, int i_wg0, int
     }
   }
   __syncthreads();
+  *seen_out = seen;
   *mk = m;
   mk->allow = win - ((long)c0 * w);
   mk->stride_b = 0;
