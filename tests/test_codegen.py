@@ -1,10 +1,11 @@
-"""Generated-code checks of the two backward kernels (no GPU needed: hipcc cross-compiles).
+"""Generated-code checks of the matrix-core kernels (no GPU needed: hipcc cross-compiles).
 
-Both kernels write some matrix instructions out by hand so that accumulators and stationary
+The kernels write some matrix instructions out by hand so that accumulators and stationary
 operands stay in the accumulation register file.  The compiler does not know that those
 statements are matrix instructions, so it would not wait for their results before a register move
 or a spill of its own.  That is safe only while the steady-state loops of the dense kernels contain
 no such move: this test compiles the sources exactly as the build does and looks at the loops."""
+import functools
 import os
 import re
 import subprocess
@@ -17,6 +18,7 @@ from paper_2502_02406_amd import build as B
 CSRC = B.CSRC
 
 
+@functools.lru_cache(maxsize=None)
 def _asm(src):
     with tempfile.TemporaryDirectory() as tmp:
         out = os.path.join(tmp, "k.s")
@@ -63,3 +65,23 @@ def test_general_dkdv_leaves_half_the_accumulation_file():
     # kernel metadata: ".agpr_count: N" precedes the ".name:" entry of its kernel
     m = re.search(r"\.agpr_count:\s*(\d+)\n(?:(?!\.agpr_count).*\n)*?\s*\.name:\s*\S*bwd_dkdv_bf16_kernelILi128ELb1E", asm)
     assert m and int(m.group(1)) <= 128
+
+
+@pytest.mark.parametrize("src,kernel", [
+    ("lvx_fwd_bf16.hip", "fwd_bf16_kernelILi128ELb0E"),
+    ("lvx_fwd_bf16.hip", "fwd_bf16_kernelILi128ELb1E"),
+    ("lvx_bwd_dq_bf16.hip", "bwd_dq_bf16_kernelILi128ELb1E"),
+])
+def test_blocks_with_matrix_instructions_move_no_accumulator(src, kernel):
+    """The forward's loop has (rare) branches and the general kernels have mask code, so their
+    loops are several basic blocks; the rule is then per block: where matrix instructions are
+    issued, no accumulator move and no spill.  The moves of the deferred rescale of O^T sit in
+    blocks of their own, behind an explicit wait."""
+    body = _kernel(_asm(src), kernel)
+    n = 0
+    for blk in _blocks(body):
+        if "v_mfma_f32_32x32x16_bf16" in blk:
+            n += 1
+            assert "v_accvgpr" not in blk, "accumulator moved next to matrix instructions"
+            assert "scratch_" not in blk, "register spill next to matrix instructions"
+    assert n > 0
