@@ -113,6 +113,14 @@ FWD_BWD_CASES = [
     small("bf16_mixed_mask", Hq=2, Sq=100, Skv=600, q_chunk=5, kv_block=24),
     small("bf16_outliers", Hq=4, Sq=128, Skv=4096, outlier_frac=0.01, outlier_scale=8.0, n_blocks=2),
     small("bf16_splitkv", Hq=2, Sq=64, Skv=16384),
+    small("bf16_long_q", Sq=1100, Skv=384),                                    # five query tiles, six key tiles
+    small("bf16_gqa8_d64_blocks", D=64, Hq=8, Hkv=1, Sq=96, Skv=1536, n_blocks=3),
+    # the structure of the masked bench workload at a size the oracle does in seconds: 32-row
+    # chunks, 1024-key frames, chunk i sees frames <= i -- every wave meets tiles that are
+    # visible to one of its two row blocks only, inside the pipelined loop
+    small("bf16_blockcausal_frames", Sq=512, Skv=16384, q_chunk=32, kv_block=1024),
+    small("bf16_mask_unaligned_d64", D=64, Hq=4, Sq=300, Skv=3000, q_chunk=50, kv_block=700),
+    small("bf16_mask_many_chunks", Sq=256, Skv=1024, q_chunk=4, kv_block=64),   # 64 chunks per workgroup
 ]
 
 
