@@ -2,7 +2,8 @@
 """Benchmark of the LV-XAttn cross-attention path on ONE MI355X.
 
 A "step" is one pass of the whole hot path over one batch of synthetic input: the forward
-block loop (Algorithm 1 with the send/recv removed: per K/V block lvx_xattn_fwd + lvx_xattn_merge)
+block loop (Algorithm 1 with the send/recv removed: lvx_xattn_fwd for the first K/V block, then
+lvx_xattn_fwd_merge -- the FlashAttention call and Rescale in one call -- for each further block)
 followed by the backward block loop (per block lvx_xattn_bwd, then lvx_xattn_dq_finalize).
 The workload is the long-video share: B=1, Hq=32, Hkv=8, D=128, Sq=2048, Skv=262144 in 8 blocks
 of 32768, bf16.  FLOPs follow the paper's Table 1 convention (forward 4, backward 10 times

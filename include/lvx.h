@@ -76,11 +76,12 @@ typedef struct {
   int64_t stride_b, stride_q;    /* element strides; stride_b = 0 shares the bitmap across batch */
 } lvx_mask;
 
-enum { LVX_WS_FWD = 0, LVX_WS_BWD = 1 };
+enum { LVX_WS_FWD = 0, LVX_WS_BWD = 1, LVX_WS_FWD_MERGE = 2 };
 enum { LVX_MAX_PARTS = 64 };
 
-/* Bytes of workspace lvx_xattn_fwd (which = LVX_WS_FWD) or lvx_xattn_bwd (LVX_WS_BWD) needs for
- * this problem and dtype.  Returns 0 on invalid arguments. */
+/* Bytes of workspace lvx_xattn_fwd (which = LVX_WS_FWD), lvx_xattn_bwd (LVX_WS_BWD) or
+ * lvx_xattn_fwd_merge (LVX_WS_FWD_MERGE) needs for this problem and dtype.  Returns 0 on invalid
+ * arguments. */
 size_t lvx_xattn_workspace_bytes(const lvx_problem* p, lvx_dtype dtype, int which);
 
 /* Forward pass of one visit (Algorithm 1, the FlashAttention call; Section 2 defines the result):
@@ -103,6 +104,18 @@ lvx_status lvx_xattn_merge(int32_t B, int32_t Hq, int32_t Sq, int32_t D, int32_t
                            const void* const* o_parts, const float* const* lse_parts,
                            lvx_dtype part_dtype, void* o_out, lvx_dtype out_dtype, float* lse_out,
                            void* hip_stream);
+
+/* One visit of Algorithm 1 in a single call: the FlashAttention call on the K/V block passed,
+ * followed by Rescale into the running result of the query block.  On entry (o_acc, lse_acc) hold
+ * the result over the keys visited so far -- float32, contiguous [B,Hq,Sq,D] and [B,Hq,Sq];
+ * (0, -inf) before the first visit -- and on return the result over those keys and the Skv keys
+ * passed, exactly as lvx_xattn_fwd into a float32 partial result followed by lvx_xattn_merge of
+ * the two would leave it (the partial result never goes through memory when the kernel does not
+ * split the key range).  Both are updated in place.  With dtype LVX_F32, Q must be contiguous
+ * (LVX_ERR_STRIDE otherwise). */
+lvx_status lvx_xattn_fwd_merge(const lvx_problem* p, lvx_dtype dtype, const void* q, const void* k,
+                               const void* v, const lvx_mask* mask, float* o_acc, float* lse_acc,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Backward pass of one visit: gradients of loss = sum(O * dO) for the K/V block passed, with the
  * attention probabilities recomputed as p_ij = exp(scale * <Q_i, K_j> - L_i) from the saved L

@@ -16,12 +16,12 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblvx.so")
 
 LVX_F32, LVX_BF16 = 0, 1
-LVX_WS_FWD, LVX_WS_BWD = 0, 1
+LVX_WS_FWD, LVX_WS_BWD, LVX_WS_FWD_MERGE = 0, 1, 2
 LVX_MAX_PARTS = 64
 
 LVX_BWD_DELTA, LVX_BWD_DKDV, LVX_BWD_DQ, LVX_BWD_ALL = 1, 2, 4, 7
 
-EXPORTS = ("lvx_xattn_workspace_bytes", "lvx_xattn_fwd", "lvx_xattn_merge", "lvx_xattn_bwd",
+EXPORTS = ("lvx_xattn_workspace_bytes", "lvx_xattn_fwd", "lvx_xattn_fwd_merge", "lvx_xattn_merge", "lvx_xattn_bwd",
            "lvx_xattn_bwd_stages", "lvx_xattn_dq_finalize", "lvx_strerror")
 
 
@@ -62,6 +62,10 @@ def load() -> C.CDLL:
         lib.lvx_xattn_fwd.argtypes = [C.POINTER(lvx_problem), C.c_int, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.POINTER(lvx_mask), C.c_void_p, C.c_int,
                                       C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.lvx_xattn_fwd_merge.restype = C.c_int
+        lib.lvx_xattn_fwd_merge.argtypes = [C.POINTER(lvx_problem), C.c_int, C.c_void_p, C.c_void_p,
+                                            C.c_void_p, C.POINTER(lvx_mask), C.c_void_p, C.c_void_p,
+                                            C.c_void_p, C.c_size_t, C.c_void_p]
         lib.lvx_xattn_merge.restype = C.c_int
         lib.lvx_xattn_merge.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                         C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int,
@@ -144,6 +148,19 @@ def lvx_xattn_fwd(p: lvx_problem, q, k, v, mask: Optional[lvx_mask], o, lse, wor
                                 workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                 _stream())
     _check(code, "lvx_xattn_fwd")
+
+
+def lvx_xattn_fwd_merge(p: lvx_problem, q, k, v, mask: Optional[lvx_mask], o_acc, lse_acc, workspace) -> None:
+    """One visit merged into the running result: o_acc (float32, contiguous [B,Hq,Sq,D]) and
+    lse_acc (float32 [B,Hq,Sq]) are updated in place."""
+    if not q.is_cuda:
+        raise RuntimeError("lvx_xattn_fwd_merge needs device tensors")
+    assert o_acc.dtype == torch.float32 and o_acc.is_contiguous() and lse_acc.is_contiguous()
+    code = load().lvx_xattn_fwd_merge(C.byref(p), dtype_code(q.dtype), q.data_ptr(), k.data_ptr(),
+                                      v.data_ptr(), C.byref(mask) if mask is not None else None,
+                                      o_acc.data_ptr(), lse_acc.data_ptr(), workspace.data_ptr(),
+                                      workspace.numel() * workspace.element_size(), _stream())
+    _check(code, "lvx_xattn_fwd_merge")
 
 
 def lvx_xattn_merge(o_parts: Sequence[torch.Tensor], lse_parts: Sequence[torch.Tensor],

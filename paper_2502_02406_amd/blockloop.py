@@ -50,9 +50,7 @@ class BlockLoop:
         self.lse = torch.empty(rows, **f32)
         self.o = torch.empty(q_shape, dtype=dtype, device=device)
         if n_blocks > 1:
-            self.o_acc = torch.empty(q_shape, **f32)       # running O_j of Algorithm 1
-            self.o_part = torch.empty(q_shape, **f32)      # delta-O of one visit
-            self.lse_part = torch.empty(rows, **f32)
+            self.o_acc = torch.empty(q_shape, **f32)       # running O_j of Algorithm 1 (L_j lives in self.lse)
         self.dq_accum = torch.empty(q_shape, **f32)
         self.dq = torch.empty(q_shape, dtype=dtype, device=device)
         # one workspace sized for the larger of the two passes
@@ -63,6 +61,7 @@ class BlockLoop:
         p.kv_sb = self.Hkv * self.Skv * self.D
         code = B.dtype_code(dtype)
         nbytes = max(B.lvx_xattn_workspace_bytes(p, code, B.LVX_WS_FWD),
+                     B.lvx_xattn_workspace_bytes(p, code, B.LVX_WS_FWD_MERGE),
                      B.lvx_xattn_workspace_bytes(p, code, B.LVX_WS_BWD))
         if nbytes == 0:
             raise B.LvxError(-2, "lvx_xattn_workspace_bytes")
@@ -87,10 +86,8 @@ class BlockLoop:
             p = B.make_problem(q, kb, self.scale)
             if n == 0:      # merging with the identity (0, -inf) is a no-op: write the state directly
                 B.lvx_xattn_fwd(p, q, kb, vb, self._mask_for(n), self.o_acc, self.lse, self.ws)
-            else:
-                B.lvx_xattn_fwd(p, q, kb, vb, self._mask_for(n), self.o_part, self.lse_part, self.ws)
-                B.lvx_xattn_merge([self.o_acc, self.o_part], [self.lse, self.lse_part],
-                                  self.o_acc, self.lse)
+            else:           # the FlashAttention call and Rescale of Algorithm 1 in one call
+                B.lvx_xattn_fwd_merge(p, q, kb, vb, self._mask_for(n), self.o_acc, self.lse, self.ws)
         B.lvx_xattn_merge([self.o_acc], [self.lse], self.o, self.lse)    # round to the output dtype
         return self.o, self.lse
 

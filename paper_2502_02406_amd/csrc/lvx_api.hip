@@ -89,6 +89,15 @@ size_t fwd_ws(const Dims& d, int n_split) {
   const size_t rows = (size_t)d.B * d.Hq * d.Sq;
   return align_up(rows * d.D * sizeof(float) * n_split) + align_up(rows * sizeof(float) * n_split);
 }
+// lvx_xattn_fwd_merge: the splits' partial results (bf16 kernels that split the key range), or one
+// float32 partial result (float32 kernels, which have no fused epilogue)
+int fwd_merge_split(const Dims& d, lvx_dtype dtype, bool masked) {
+  const int n = fwd_split(d, dtype, masked);
+  return n < LVX_MAX_PARTS ? n : LVX_MAX_PARTS - 1;     // the running state is one more part of the combine
+}
+size_t fwd_merge_ws(const Dims& d, lvx_dtype dtype, int n_split) {
+  return fwd_ws(d, dtype == LVX_F32 ? 2 : n_split);      // (fwd_ws(d, 2) holds more than one partial result)
+}
 int sq_padded(const Dims& d) { return (d.Sq + 31) / 32 * 32; }
 size_t bwd_ws_fixed(const Dims& d) {   // delta [B,Hq,Sq] + padded statistics [B,Hq,sq_pad/32][2][32]
   return align_up((size_t)d.B * d.Hq * d.Sq * sizeof(float)) +
@@ -123,6 +132,7 @@ size_t lvx_xattn_workspace_bytes(const lvx_problem* p, lvx_dtype dtype, int whic
   const Dims d = make_dims(p);
   if (which == LVX_WS_FWD) return fwd_ws(d, fwd_split(d, dtype, true));   // a masked call splits at least as much
   if (which == LVX_WS_BWD) return bwd_ws(d, bwd_split(d, dtype, true));   // a masked call splits at least as much
+  if (which == LVX_WS_FWD_MERGE) return fwd_merge_ws(d, dtype, fwd_merge_split(d, dtype, true));
   return 0;
 }
 
@@ -139,6 +149,7 @@ lvx_status lvx_xattn_fwd(const lvx_problem* p, lvx_dtype dtype, const void* q, c
   a.d = make_dims(p);
   a.mask = make_mask(mask);
   a.q = q; a.k = k; a.v = v; a.o = o; a.o_is_f32 = o_dtype == LVX_F32; a.lse = lse;
+  a.merge_into = 0;
   a.n_split = fwd_split(a.d, dtype, mask != nullptr);
   a.o_part = nullptr; a.lse_part = nullptr;
   const size_t need = fwd_ws(a.d, a.n_split);
@@ -164,6 +175,58 @@ lvx_status lvx_xattn_fwd(const lvx_problem* p, lvx_dtype dtype, const void* q, c
     if (e != hipSuccess) return LVX_ERR_HIP;
   }
   return LVX_OK;
+}
+
+lvx_status lvx_xattn_fwd_merge(const lvx_problem* p, lvx_dtype dtype, const void* q, const void* k,
+                               const void* v, const lvx_mask* mask, float* o_acc, float* lse_acc,
+                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+  lvx_status st = check_problem(p, dtype);
+  if (st != LVX_OK) return st;
+  if (!q || !k || !v || !o_acc || !lse_acc) return LVX_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o_acc)) return LVX_ERR_STRIDE;
+  if ((st = check_mask(p, mask)) != LVX_OK) return st;
+  FwdArgs a;
+  a.d = make_dims(p);
+  if (dtype == LVX_F32 && (a.d.q_ss != a.d.D || a.d.q_sh != (long)a.d.Sq * a.d.D ||
+                           a.d.q_sb != (long)a.d.Hq * a.d.Sq * a.d.D))
+    return LVX_ERR_STRIDE;      // the float32 kernels write their result with Q's strides
+  a.mask = make_mask(mask);
+  a.q = q; a.k = k; a.v = v; a.o_is_f32 = 1;
+  a.n_split = fwd_merge_split(a.d, dtype, mask != nullptr);
+  a.o_part = nullptr; a.lse_part = nullptr;
+  const size_t need = fwd_merge_ws(a.d, dtype, a.n_split);
+  if (!workspace || ((uintptr_t)workspace % ALIGN) != 0 || workspace_bytes < need) return LVX_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)hip_stream;
+  const size_t rows = (size_t)a.d.B * a.d.Hq * a.d.Sq;
+  if (dtype == LVX_BF16 && a.n_split == 1) {            // Rescale in the kernel's epilogue
+    a.o = o_acc; a.lse = lse_acc; a.merge_into = 1;
+    return launch_fwd_bf16(a, s) == hipSuccess ? LVX_OK : LVX_ERR_HIP;
+  }
+  // partial result(s) in the workspace, then one combine over the running state and them
+  a.merge_into = 0;
+  const int n_parts = dtype == LVX_BF16 ? a.n_split : 1;
+  float* const o_part = (float*)workspace;
+  float* const l_part = (float*)((char*)workspace + align_up(rows * a.d.D * sizeof(float) * n_parts));
+  hipError_t e;
+  if (dtype == LVX_BF16) {
+    a.o = nullptr; a.lse = nullptr; a.o_part = o_part; a.lse_part = l_part;
+    e = launch_fwd_bf16(a, s);
+  } else {
+    a.o = o_part; a.lse = l_part; a.n_split = 1;
+    e = launch_fwd_f32(a, s);
+  }
+  if (e != hipSuccess) return LVX_ERR_HIP;
+  MergeArgs m;
+  m.n_parts = n_parts + 1;
+  m.o_parts[0] = o_acc; m.lse_parts[0] = lse_acc;
+  for (int i = 0; i < n_parts; ++i) {
+    m.o_parts[i + 1] = o_part + (size_t)i * rows * a.d.D;
+    m.lse_parts[i + 1] = l_part + (size_t)i * rows;
+  }
+  m.rows = (long)rows; m.D = a.d.D; m.o_out = o_acc; m.lse_out = lse_acc;
+  m.Hq = a.d.Hq; m.Sq = a.d.Sq; m.o_ss = a.d.D; m.o_sh = (long)a.d.Sq * a.d.D; m.o_sb = (long)a.d.Hq * a.d.Sq * a.d.D;
+  e = launch_merge(m, 1, 1, s);
+  return e == hipSuccess ? LVX_OK : LVX_ERR_HIP;
 }
 
 lvx_status lvx_xattn_merge(int32_t B, int32_t Hq, int32_t Sq, int32_t D, int32_t n_parts,

@@ -537,6 +537,33 @@ fwd_bf16_kernel(FwdArgs a) {
       if (g == 0) a.lse_part[(long)split * d.B * d.Hq * d.Sq + row] = lse;
       continue;
     }
+    if (a.merge_into) {
+      // Rescale of Algorithm 1 with the running (O, L) of this row: L' = ln(e^L + e^dL),
+      // O' = e^(L - L') O + e^(dL - L') dO, where dO = acc / l is this visit's result
+      const float L0 = a.lse[row];
+      const float M = fmaxf(L0, lse);
+      float w0 = 0.f, w1 = 0.f, L1 = -INFINITY;
+      if (M != -INFINITY) {
+        const float e0 = expf(L0 - M), e1 = expf(lse - M);
+        L1 = M + logf(e0 + e1);
+        w0 = expf(L0 - L1);
+        w1 = expf(lse - L1) * inv;
+      }
+      float* o = (float*)a.o + row * D;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          float* dst = o + 32 * db + 8 * q4 + 4 * g;
+          const f32x4 x = *(const f32x4*)dst;
+          f32x4 y = {w0 * x[0] + w1 * oacc[qb][db][4 * q4], w0 * x[1] + w1 * oacc[qb][db][4 * q4 + 1],
+                     w0 * x[2] + w1 * oacc[qb][db][4 * q4 + 2], w0 * x[3] + w1 * oacc[qb][db][4 * q4 + 3]};
+          *(f32x4*)dst = y;
+        }
+      // (both half-waves of the row have read L0 above: the loads precede this store in program order)
+      if (g == 0) a.lse[row] = L1;
+      continue;
+    }
     const long off = b * d.q_sb + hq * d.q_sh + (long)i * d.q_ss;
 #pragma unroll
     for (int db = 0; db < DB; ++db)

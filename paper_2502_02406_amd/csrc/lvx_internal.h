@@ -27,6 +27,8 @@ struct FwdArgs {
   const void *q, *k, *v;
   void* o;              // final output (Q's strides) when n_split == 1
   int o_is_f32;         // 1: o is float32, 0: o has the input dtype
+  int merge_into;       // 1 (n_split == 1 only): o (float32, CONTIGUOUS [B,Hq,Sq,D]) and lse hold a running
+                        // result; the kernel leaves in them the Rescale of it with this visit's result
   float* lse;           // [B,Hq,Sq]
   int n_split;          // number of KV splits handled by separate workgroups
   float* o_part;        // [n_split, B,Hq,Sq,D] float32, contiguous (n_split > 1)

@@ -107,6 +107,26 @@ def test_merge_and_bwd_errors(lib):
     assert lib.lvx_xattn_dq_finalize(C.byref(p), None, FAKE, B.LVX_BF16, None) == -1
 
 
+def test_fwd_merge_errors(lib):
+    p = problem()
+    args = [C.byref(p), B.LVX_BF16, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, 1 << 40, None]
+    bad = list(args); bad[6] = None                              # o_acc
+    assert lib.lvx_xattn_fwd_merge(*bad) == -1
+    bad = list(args); bad[7] = None                              # lse_acc
+    assert lib.lvx_xattn_fwd_merge(*bad) == -1
+    bad = list(args); bad[9] = 16                                # workspace too small
+    assert lib.lvx_xattn_fwd_merge(*bad) == -6
+    bad = list(args); bad[2] = FAKE + 4                          # misaligned q
+    assert lib.lvx_xattn_fwd_merge(*bad) == -4
+    strided = problem()
+    strided.q_ss = 2 * strided.D                                 # float32 kernels need a contiguous Q here
+    assert lib.lvx_xattn_fwd_merge(C.byref(strided), B.LVX_F32, *args[2:]) == -4
+    assert lib.lvx_xattn_fwd_merge(C.byref(problem(D=96)), B.LVX_BF16, *args[2:]) == -7
+    n = B.lvx_xattn_workspace_bytes(p, B.LVX_F32, B.LVX_WS_FWD_MERGE)
+    assert n >= p.B * p.Hq * p.Sq * (p.D + 1) * 4                # one float32 partial result and its L
+    assert B.lvx_xattn_workspace_bytes(p, B.LVX_BF16, B.LVX_WS_FWD_MERGE) >= 256
+
+
 def test_workspace_sizes_and_strerror(lib):
     p = problem(B=1, Hq=32, Hkv=8, Sq=2048, Skv=32768)
     rows = 32 * 2048

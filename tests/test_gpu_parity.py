@@ -113,6 +113,9 @@ FWD_BWD_CASES = [
     small("bf16_mixed_mask", Hq=2, Sq=100, Skv=600, q_chunk=5, kv_block=24),
     small("bf16_outliers", Hq=4, Sq=128, Skv=4096, outlier_frac=0.01, outlier_scale=8.0, n_blocks=2),
     small("bf16_splitkv", Hq=2, Sq=64, Skv=16384),
+    # as many workgroups as the chip has compute units: the key range is not split, so that the
+    # Rescale of the block loop runs in the forward kernel's own epilogue
+    small("bf16_fused_rescale", B=4, Hq=64, Hkv=8, D=64, Sq=32, Skv=512, n_blocks=4),
     small("bf16_long_q", Sq=1100, Skv=384),                                    # five query tiles, six key tiles
     small("bf16_gqa8_d64_blocks", D=64, Hq=8, Hkv=1, Sq=96, Skv=1536, n_blocks=3),
     # the structure of the masked bench workload at a size the oracle does in seconds: 32-row
