@@ -34,9 +34,9 @@ using namespace kvring;
 constexpr float LAZY = 6.0f;           // raise the reference only when a half tops it by 2^LAZY
 constexpr int XE = 8;                  // elements of a half converted during the contraction (of 32)
 
-// GENERAL = false: dense attention and Skv a multiple of 64 (no mask code, no ragged tile);
-// GENERAL = true: everything else.
-template <int D, bool GENERAL>
+// Dense attention with Skv a multiple of 64 only: no mask code and no ragged tile, so that nothing
+// stands between the phases of the pipeline (masked and ragged problems: lvx_fwd_general_bf16.hip).
+template <int D>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 fwd_bf16_kernel(FwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -60,8 +60,8 @@ fwd_bf16_kernel(FwdArgs a) {
   // KV range of this split, in tiles
   const int n_tiles = (d.Skv + TN - 1) / TN;
   const int tps = (n_tiles + a.n_split - 1) / a.n_split;
-  int t_begin = split * tps;                        // (with a media mask: re-cut below over the visible tiles)
-  int t_end = min(n_tiles, t_begin + tps);
+  const int t_begin = split * tps;
+  const int t_end = min(n_tiles, t_begin + tps);
 
   // ---- stationary operands: Q of this lane's query rows i_wave0 + 32 qb + ql
   const float c2 = d.scale * LOG2E;
@@ -84,73 +84,9 @@ fwd_bf16_kernel(FwdArgs a) {
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[qb][ks]));
 
-  // ---- tiles this workgroup needs (media mask: tiles visible to none of its rows are skipped).
-  // The window of the bitmap that its rows and key range can touch is copied to LDS, and the
-  // visibility of every tile is worked out by all threads at once into a bit array, so that the
-  // loop never waits on the bitmap.
-  const int i_wg0 = qt * QM, i_wg1 = min(d.Sq, i_wg0 + QM) - 1;
-  MaskDev mk = a.mask;
-  unsigned* const bits = (unsigned*)(smem + SM::RING);
-  bool have_bits = false, have_cls = false;
-  const unsigned *cls_any = bits, *cls_all = bits; // this wave's class planes (valid with have_cls)
-  const unsigned* seen = bits;                     // per key block: which chunks of the workgroup see it (valid with have_cls)
-  int nt = max(t_end - t_begin, 0);                // number of tiles this workgroup performs
-  if (GENERAL && mk.allow) {
-    auto share = [&](int nn) __attribute__((always_inline)) {   // the splits share the visible tiles evenly
-      const int k0 = (int)((long)split * nn / a.n_split), k1 = (int)((long)(split + 1) * nn / a.n_split);
-      t_begin = nth_bit(bits, k0, n_tiles);
-      t_end = k1 > k0 ? nth_bit(bits, k1 - 1, n_tiles) + 1 : t_begin;
-      nt = k1 - k0;
-    };
-    uint8_t* const win = (uint8_t*)smem + SM::RING + SM::BITS_BYTES;
-    if (plan_masked_tiles<D>(a.mask, b, i_wg0, i_wg1, d.Sq, d.Skv, n_tiles, bits, SM::BITS_BYTES, win,
-                             SM::WIN_BYTES, tid, &mk, &seen)) {
-      // visibility of every tile, and its class (nothing / everything / mixed) for every wave's
-      // rows: the loop then reads the bitmap for mixed tiles only
-      have_bits = have_cls = true;
-      const int pw = bit_plane_words(n_tiles);
-      cls_any = bits + (1 + 2 * wave) * pw;
-      cls_all = bits + (2 + 2 * wave) * pw;
-      share(__builtin_amdgcn_readfirstlane((int)bits[0]));
-    } else if (n_tiles <= (SM::BITS_BYTES - 16) * 8) {
-      // (shapes the planner does not take) bits over ALL tiles of the key range, probe by probe
-      mk = mask_to_lds(a.mask, b, i_wg0 / mk.q_chunk, i_wg1 / mk.q_chunk, 0, (d.Skv - 1) / mk.kv_block, win,
-                       SM::WIN_BYTES, tid, 256);
-      have_bits = true;
-      share(build_bits(bits, n_tiles, tid, 256, [&](int t) {
-        return mask_rect(mk, b, i_wg0, i_wg1, t * TN, min(d.Skv, t * TN + TN) - 1) != 0;
-      }));
-    } else if (t_begin < t_end) {
-      mk = mask_to_lds(a.mask, b, i_wg0 / mk.q_chunk, i_wg1 / mk.q_chunk, (t_begin * TN) / mk.kv_block,
-                       (min(d.Skv, t_end * TN) - 1) / mk.kv_block, win, SM::WIN_BYTES, tid, 256);
-    }
-  }
-  int crow[QB] = {};                               // this lane's rows' chunks, relative to the window
-  if (GENERAL && have_cls) {
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
-      crow[qb] = min(i_wave0 + 32 * qb + ql, d.Sq - 1) / mk.q_chunk - i_wg0 / mk.q_chunk;
-  }
-  // does row (qb, this lane) see key j?  From the per-block words in LDS when the planner ran,
-  // else from the bitmap itself.
-  auto sees = [&](int qb, int i, int j) __attribute__((always_inline)) -> bool {
-    if (have_cls) return (seen[j / mk.kv_block] >> crow[qb]) & 1u;
-    return mask_elem(mk, b, i, j);
-  };
-  auto tile_needed = [&](int t) __attribute__((always_inline)) -> bool {
-    if (!GENERAL || !mk.allow) return true;
-    return mask_rect(mk, b, i_wg0, i_wg1, t * TN, min(d.Skv, t * TN + TN) - 1) != 0;
-  };
-  auto next_tile = [&](int t) __attribute__((always_inline)) -> int {
-    if (GENERAL && have_bits) return next_bit(bits, t, t_end);
-    while (t < t_end && !tile_needed(t)) ++t;
-    return __builtin_amdgcn_readfirstlane(min(t, t_end));      // wave-uniform (the bitmap is read through the vector path)
-  };
-  int cursor = next_tile(t_begin);                 // next tile to issue
-  if (GENERAL && mk.allow && !have_bits) {
-    nt = 0;
-    for (int t = cursor; t < t_end; t = next_tile(t + 1)) ++nt;
-  }
+  const int nt = max(t_end - t_begin, 0);          // number of tiles this workgroup performs
+  auto next_tile = [&](int t) __attribute__((always_inline)) -> int { return min(t, t_end); };
+  int cursor = t_begin;                            // next tile to issue
 
   // ---- tile copies.  Group w of a tile (logical rows 4 j + w, j = 0..15) is contiguous in LDS:
   // RUN slots of 16 bytes.  Wave w copies group w of the K tile and of the V tile, each with NCR
@@ -177,23 +113,8 @@ fwd_bf16_kernel(FwdArgs a) {
     else dma16s(v0 + tile, cp_off[k / 2], kdst + SM::TILE + run_start(k / 2) * 16);
   };
   auto issue_tile = [&](int t, char* st) __attribute__((always_inline)) {
-    const int rows = min(TN, d.Skv - t * TN);
-    if (!GENERAL || rows == TN) {
 #pragma unroll
-      for (int k = 0; k < 2 * NCR; ++k) issue_part(t, st, k);
-      return;
-    }
-    const long tile = (long)t * TN * row_bytes;    // ragged last tile: clamp the rows
-    char* const kdst = st + wave * SM::GS;
-    char* const vdst = kdst + SM::TILE;
-#pragma unroll
-    for (int c = 0; c < NCR; ++c) {
-      const int sl = run_start(c) + lane;
-      const unsigned r = (unsigned)min(4 * (sl / SM::SPR) + wave, rows - 1);
-      const unsigned off = r * row_bytes + (unsigned)min(sl % SM::SPR, CPR - 1) * 16;
-      dma16s(k0 + tile, off, kdst + run_start(c) * 16);
-      dma16s(v0 + tile, off, vdst + run_start(c) * 16);
-    }
+    for (int k = 0; k < 2 * NCR; ++k) issue_part(t, st, k);
   };
   constexpr int NDMA = 2 * NCR;                    // copies per wave and tile
 
@@ -252,34 +173,6 @@ fwd_bf16_kernel(FwdArgs a) {
   // matrix instructions into the next phase; everywhere else this wait comes first.
   auto settle_scores = [&](f32x16 (&s)[QB]) __attribute__((always_inline)) {
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" : "+v"(s[0]), "+v"(s[1]));
-  };
-  // key tail and masked elements of a half's scores -> -inf (wave-uniform decision, rarely taken)
-  auto mask_scores = [&](int t, int hb, f32x16 (&s)[QB]) __attribute__((always_inline)) {
-    if (!GENERAL) return;
-    const int j0 = t * TN + 32 * hb;
-    int cls = 1;
-    if (mk.allow && i_wave0 < d.Sq)
-      cls = have_cls ? class_of(cls_any, cls_all, t)      // (of the whole tile: fine for either half)
-                     : mask_rect(mk, b, i_wave0, min(d.Sq, i_wave0 + 32 * QB) - 1, min(j0, d.Skv - 1),
-                                 min(d.Skv, j0 + 32) - 1);
-    if (cls == 1 && j0 + 32 <= d.Skv) return;
-    asm volatile("" ::: "memory");
-    settle_scores(s);
-    // mixed, but all keys of the half in one block of the bitmap (the usual case: blocks are
-    // frames): one probe per query row instead of one per element
-    const bool one_block = cls == 2 && j0 / mk.kv_block == (min(d.Skv, j0 + 32) - 1) / mk.kv_block;
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      const int i = i_wave0 + 32 * qb + ql;
-      const bool row_ok = one_block && i < d.Sq && sees(qb, i, j0);
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int j = j0 + 8 * (v / 4) + 4 * g + (v % 4);
-        bool ok = j < d.Skv && cls != 0;
-        if (ok && cls == 2) ok = one_block ? row_ok : (i < d.Sq && sees(qb, i, j));
-        if (!ok) s[qb][v] = -INFINITY;
-      }
-    }
   };
   // Before a half's scores are exponentiated: does any row top its reference by more than
   // 2^LAZY?  Then (rarely) the reference of the rows that grew is raised to their new maximum:
@@ -424,13 +317,9 @@ fwd_bf16_kernel(FwdArgs a) {
   // 2T and 2T+1): contract 2T | convert 2T+1 | score 2T+2, then contract 2T+1 | convert 2T+2, the
   // one barrier of the tile -- every wave is done with tile T, whose stage takes tile T + 4, and
   // tile T + 2, issued two tiles ago, has landed -- and score 2T+3.
-  int e[NSTG + 1];                                 // tile ids of tiles T .. T + 4 (static indexing only)
-#pragma unroll
-  for (int q = 0; q <= NSTG; ++q) e[q] = t_end;
 #pragma unroll
   for (int q = 0; q < NSTG; ++q) {
     if (q < nt) {
-      e[q] = cursor;
       issue_tile(cursor, smem + q * SM::STAGE);
       cursor = next_tile(cursor + 1);
     }
@@ -439,15 +328,12 @@ fwd_bf16_kernel(FwdArgs a) {
   __syncthreads();
   auto stage = [&](int q) __attribute__((always_inline)) -> char* { return smem + (q % NSTG) * SM::STAGE; };
   auto mid = [&](auto all_in_flight, bool issue, char* st_copy) __attribute__((always_inline)) {
-    // (The general variant may spill registers inside the loop; its spill stores are counted with
-    // the copies but complete out of order with them, so it always waits for everything.)
     // all_in_flight: tiles T + 2 and T + 3 were both issued, so leaving one tile's copies
     // outstanding still guarantees that tile T + 2 has landed
     if constexpr (decltype(all_in_flight)::value) wait_vmcnt<NDMA>();
     else wait_vmcnt<0>();
     wg_barrier();
     if (issue) {
-      e[4] = cursor;
       issue_tile(cursor, st_copy);
       cursor = next_tile(cursor + 1);
     }
@@ -458,13 +344,11 @@ fwd_bf16_kernel(FwdArgs a) {
   Carry cy;
   if (nt > 0) {
     score(smem, 0, s0, nothing, first_k(smem, 0), no_tail);
-    mask_scores(e[0], 0, s0);
     settle_scores(s0);
     check(s0);
     settle();                                      // (O^T is still zero: this only clears the factor)
     convert(s0, p0);
     score(smem, 1, s1, nothing, first_k(smem, 1), no_tail);
-    mask_scores(e[0], 1, s1);
   }
   int T = 0;
   bf16x8 fk;
@@ -477,27 +361,18 @@ fwd_bf16_kernel(FwdArgs a) {
     asm volatile("" : "+v"(fk));                   // (waited for here, where the compiler still knows what is in flight)
     score_convert(sb, 0, s0, s1, p1, cy, fk, [&]() __attribute__((always_inline)) { fvt = first_vt(sa, 1); }, nothing);
     asm volatile("" : "+v"(fvt));
-    mask_scores(e[1], 0, s0);
     contract_convert(sa, 1, p1, s0, p0, cy, fvt, [&]() __attribute__((always_inline)) { fk = first_k(sb, 1); });
     asm volatile("" : "+v"(fk));
-    if constexpr (GENERAL) {
-      mid(std::false_type{}, true, sa);
-      score_convert(sb, 1, s1, s0, p0, cy, fk, [&]() __attribute__((always_inline)) { fvt = first_vt(sb, 0); }, nothing);
-    } else {
-      mid(std::true_type{}, false, sa);
-      const int t_new = cursor;                    // the copies of tile T + 4 go out during the phase
-      e[4] = t_new;
-      cursor = next_tile(cursor + 1);
-      constexpr int EVERY = QB * KS / NDMA;
-      static_assert(EVERY >= 1, "more copies than matrix instructions in the score phase");
-      score_convert(sb, 1, s1, s0, p0, cy, fk, [&]() __attribute__((always_inline)) { fvt = first_vt(sb, 0); },
-                    [&](int m) __attribute__((always_inline)) {
-                      if (m % EVERY == EVERY - 1 && m / EVERY < NDMA) issue_part(t_new, sa, m / EVERY);
-                    });
-    }
+    mid(std::true_type{}, false, sa);
+    const int t_new = cursor;                      // the copies of tile T + 4 go out during the phase
+    cursor = next_tile(cursor + 1);
+    constexpr int EVERY = QB * KS / NDMA;
+    static_assert(EVERY >= 1, "more copies than matrix instructions in the score phase");
+    score_convert(sb, 1, s1, s0, p0, cy, fk, [&]() __attribute__((always_inline)) { fvt = first_vt(sb, 0); },
+                  [&](int m) __attribute__((always_inline)) {
+                    if (m % EVERY == EVERY - 1 && m / EVERY < NDMA) issue_part(t_new, sa, m / EVERY);
+                  });
     asm volatile("" : "+v"(fvt));
-    mask_scores(e[1], 1, s1);
-    e[0] = e[1]; e[1] = e[2]; e[2] = e[3]; e[3] = e[4];
   }
   for (; T < nt; ++T) {                            // the last (at most four) tiles, phase after phase
     const bool more = T + 1 < nt;
@@ -505,12 +380,11 @@ fwd_bf16_kernel(FwdArgs a) {
     check(s1);
     settle();                                      // before anything relative to the new reference is added
     convert(s1, p1);
-    if (more) { score(stage(T + 1), 0, s0, nothing, first_k(stage(T + 1), 0), no_tail); mask_scores(e[1], 0, s0); }
+    if (more) { score(stage(T + 1), 0, s0, nothing, first_k(stage(T + 1), 0), no_tail); }
     contract(stage(T), 1, p1);
     if (more) { check(s0); settle(); convert(s0, p0); }
     mid(std::false_type{}, T + 4 < nt, stage(T));
-    if (more) { score(stage(T + 1), 1, s1, nothing, first_k(stage(T + 1), 1), no_tail); mask_scores(e[1], 1, s1); }
-    e[0] = e[1]; e[1] = e[2]; e[2] = e[3]; e[3] = e[4];
+    if (more) { score(stage(T + 1), 1, s1, nothing, first_k(stage(T + 1), 1), no_tail); }
   }
 
   // ---- epilogue: O = acc / l, L = r ln 2 + ln l (the reference is in units of log2).  The last
@@ -584,16 +458,16 @@ fwd_bf16_kernel(FwdArgs a) {
   }
 }
 
-template <int D, bool GENERAL>
+template <int D>
 hipError_t launch(const FwdArgs& a, long grid, hipStream_t s) {
   static bool once = false;
   if (!once) {
-    hipError_t e = hipFuncSetAttribute((const void*)fwd_bf16_kernel<D, GENERAL>,
+    hipError_t e = hipFuncSetAttribute((const void*)fwd_bf16_kernel<D>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, KvSmem<D>::TOTAL);
     if (e != hipSuccess) return e;
     once = true;
   }
-  fwd_bf16_kernel<D, GENERAL><<<(unsigned)grid, 256, KvSmem<D>::TOTAL, s>>>(a);
+  fwd_bf16_kernel<D><<<(unsigned)grid, 256, KvSmem<D>::TOTAL, s>>>(a);
   return hipGetLastError();
 }
 
@@ -619,9 +493,8 @@ hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t s) {
   const int G = d.Hq / d.Hkv;
   const int n_qt = (d.Sq + QM - 1) / QM;
   const long grid = xcd_grid(d.B * d.Hkv, a.n_split * G * n_qt);
-  const bool general = a.mask.allow != nullptr || d.Skv % TN != 0;
-  if (d.D == 64) return general ? launch<64, true>(a, grid, s) : launch<64, false>(a, grid, s);
-  return general ? launch<128, true>(a, grid, s) : launch<128, false>(a, grid, s);
+  if (a.mask.allow != nullptr || d.Skv % TN != 0) return launch_fwd_general_bf16(a, s);
+  return d.D == 64 ? launch<64>(a, grid, s) : launch<128>(a, grid, s);
 }
 
 }  // namespace lvx

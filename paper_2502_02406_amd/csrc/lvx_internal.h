@@ -73,6 +73,7 @@ hipError_t launch_bwd_bf16(const BwdArgs& a, unsigned stages, hipStream_t s);
 hipError_t launch_bwd_dkdv_bf16(const BwdArgs& a, hipStream_t s);
 hipError_t launch_bwd_dq_bf16(const BwdArgs& a, hipStream_t s);
 int fwd_bf16_pick_split(const Dims& d, int n_cu, bool masked);
+hipError_t launch_fwd_general_bf16(const FwdArgs& a, hipStream_t s);   // masked or ragged problems
 int bwd_bf16_pick_split(const Dims& d, int n_cu, bool masked);
 // memory-bound helpers
 hipError_t launch_merge(const MergeArgs& a, int part_is_f32, int out_is_f32, hipStream_t s);

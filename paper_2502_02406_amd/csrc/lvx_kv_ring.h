@@ -1,6 +1,6 @@
-// Shared by the query-stationary kernels (forward, and the dQ kernel of the backward): a workgroup
-// of four wavefronts, one per SIMD, each owning 64 query rows (two 32-row blocks), and a ring of
-// K/V tiles of 64 keys in LDS.
+// Shared by the query-stationary kernels (dense forward, and the dQ kernel of the backward): a
+// workgroup of four wavefronts, one per SIMD, each owning 64 query rows (two 32-row blocks), and a
+// ring of K/V tiles of 64 keys in LDS.  The mask planner at the end serves the dQ kernel.
 #pragma once
 #include "lvx_mfma.h"
 

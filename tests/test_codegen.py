@@ -68,13 +68,12 @@ def test_general_dkdv_leaves_half_the_accumulation_file():
 
 
 @pytest.mark.parametrize("src,kernel", [
-    ("lvx_fwd_bf16.hip", "fwd_bf16_kernelILi128ELb0E"),
-    ("lvx_fwd_bf16.hip", "fwd_bf16_kernelILi128ELb1E"),
+    ("lvx_fwd_bf16.hip", "fwd_bf16_kernelILi128EE"),
     ("lvx_bwd_dq_bf16.hip", "bwd_dq_bf16_kernelILi128ELb1E"),
 ])
 def test_blocks_with_matrix_instructions_move_no_accumulator(src, kernel):
-    """The forward's loop has (rare) branches and the general kernels have mask code, so their
-    loops are several basic blocks; the rule is then per block: where matrix instructions are
+    """The dense forward's loop has (rare) branches and the general dQ kernel has mask code, so
+    their loops are several basic blocks; the rule is then per block: where matrix instructions are
     issued, no accumulator move and no spill.  The moves of the deferred rescale of O^T sit in
     blocks of their own, behind an explicit wait."""
     body = _kernel(_asm(src), kernel)
