@@ -517,7 +517,15 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
 
   // ---- write dK = scale * acc, dV = acc (transposed accumulators: lane = key row).  The last
   // matrix instructions must have retired before their registers are read.
-  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+  // (the accumulators are operands of the statement, so that the compiler cannot read them before it)
+#pragma unroll
+  for (int kb = 0; kb < KVB; ++kb) {
+    if constexpr (DB == 4)
+      asm volatile("s_nop 15\n\ts_nop 15" : "+a"(dk[kb][0]), "+a"(dk[kb][1]), "+a"(dk[kb][2]), "+a"(dk[kb][3]),
+                   "+a"(dv[kb][0]), "+a"(dv[kb][1]), "+a"(dv[kb][2]), "+a"(dv[kb][3]));
+    else
+      asm volatile("s_nop 15\n\ts_nop 15" : "+a"(dk[kb][0]), "+a"(dk[kb][1]), "+a"(dv[kb][0]), "+a"(dv[kb][1]));
+  }
 #pragma unroll
   for (int kb = 0; kb < KVB; ++kb) {
     const int j = j_wave0 + 32 * kb + kl;

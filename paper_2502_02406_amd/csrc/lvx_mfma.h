@@ -98,8 +98,8 @@ __device__ __forceinline__ void dma16(const void* gsrc, void* lds_dst) {
 // a memory instruction here: it neither counts the copy in vmcnt nor lets it force the waits of
 // unrelated LDS reads to zero, which it does for the builtin above while any copy is in flight.
 // The caller orders everything by hand: wait_vmcnt<N>() + barrier before the data is read, a
-// barrier before a stage is overwritten.  m0 (reserved, never live across statements) carries the
-// LDS address; one wait state separates its write from the copy.
+// barrier before a stage is overwritten.  m0 (declared clobbered) carries the LDS address; one wait
+// state separates its write from the copy.
 __device__ __forceinline__ unsigned lds_addr_uniform(void* p) {
   // wave-uniform LDS byte address in a scalar register (a no-op when the compiler already keeps it there)
   return (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(uintptr_t)LVX_LDS(p, char));
@@ -115,13 +115,13 @@ __device__ __forceinline__ void dma16s(const void* base, unsigned voff, void* ld
   base = ptr_uniform(base);
   const unsigned l = lds_addr_uniform(lds_dst);
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-               :: "v"(voff), "s"(base), "s"(l) : "memory");
+               :: "v"(voff), "s"(base), "s"(l) : "memory", "m0");
 }
 __device__ __forceinline__ void dma4s(const void* base, unsigned voff, void* lds_dst) {
   base = ptr_uniform(base);
   const unsigned l = lds_addr_uniform(lds_dst);
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
-               :: "v"(voff), "s"(base), "s"(l) : "memory");
+               :: "v"(voff), "s"(base), "s"(l) : "memory", "m0");
 }
 // s_waitcnt vmcnt(N) only (expcnt and lgkmcnt left at "no wait").
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
