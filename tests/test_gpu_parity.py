@@ -60,10 +60,13 @@ def check_grad(g, ref, tol, tag, cancel_atol=0.0):
     assert rel_max(g, ref) <= tol["grad"], f"{tag}: max-abs rel err {rel_max(g, ref)}"
 
 
-def run_case(w: W.Workload, seed=W.BASE_SEED, do_bwd=True, v_mean=0.0):
+def run_case(w: W.Workload, seed=W.BASE_SEED, do_bwd=True, v_mean=0.0, k_ramp=0.0):
     x = W.make_inputs(w, seed)
     if v_mean:
         x["v"] = (x["v"].float() + v_mean).to(x["v"].dtype)
+    if k_ramp:      # key norms grow along the sequence by a factor 1 + k_ramp in all
+        ramp = 1.0 + k_ramp * torch.arange(w.Skv, dtype=torch.float32) / max(w.Skv - 1, 1)
+        x["k"] = (x["k"].float() * ramp[None, None, :, None]).to(x["k"].dtype)
     qn, kn, vn, gn = (W.as_f32_numpy(x[n]) for n in ("q", "k", "v", "do"))
     omask = dmask = None
     dev = {n: t.cuda() for n, t in x.items()}
@@ -140,6 +143,13 @@ def test_fwd_bwd_parity(w):
 def test_fwd_structured_values_order_one():
     # V with mean 1 makes |O| = O(1), so the absolute tolerance on O is a real constraint
     run_case(small("bf16_vmean1", Hq=4, Sq=256, Skv=2048), do_bwd=True, v_mean=1.0)
+
+
+def test_rising_scores_raise_the_reference_often():
+    # keys grow 12-fold along the sequence, so the row maxima keep rising and the forward's lazy
+    # reference is raised (and O rescaled) again and again, in every wave, instead of once
+    run_case(small("bf16_rising", Hq=4, Sq=256, Skv=4096), do_bwd=True, k_ramp=11.0)
+    run_case(small("bf16_rising_blocks", Hq=2, Sq=128, Skv=8192, n_blocks=2), do_bwd=False, k_ramp=23.0)
 
 
 def test_masked_rows_without_keys():
