@@ -60,8 +60,10 @@ def check_grad(g, ref, tol, tag, cancel_atol=0.0):
     assert rel_max(g, ref) <= tol["grad"], f"{tag}: max-abs rel err {rel_max(g, ref)}"
 
 
-def run_case(w: W.Workload, seed=W.BASE_SEED, do_bwd=True, v_mean=0.0, k_ramp=0.0):
+def run_case(w: W.Workload, seed=W.BASE_SEED, do_bwd=True, v_mean=0.0, k_ramp=0.0, allow=None):
     x = W.make_inputs(w, seed)
+    if allow is not None:                # a bitmap other than the workload's block-causal one
+        x["allow"] = torch.from_numpy(np.ascontiguousarray(allow, dtype=np.uint8))
     if v_mean:
         x["v"] = (x["v"].float() + v_mean).to(x["v"].dtype)
     if k_ramp:      # key norms grow along the sequence by a factor 1 + k_ramp in all
@@ -150,6 +152,23 @@ def test_rising_scores_raise_the_reference_often():
     # reference is raised (and O rescaled) again and again, in every wave, instead of once
     run_case(small("bf16_rising", Hq=4, Sq=256, Skv=4096), do_bwd=True, k_ramp=11.0)
     run_case(small("bf16_rising_blocks", Hq=2, Sq=128, Skv=8192, n_blocks=2), do_bwd=False, k_ramp=23.0)
+
+
+@pytest.mark.parametrize("name,kw,per_batch,p_on", [
+    ("bf16_randmask_batch", dict(B=2, Hq=4, Hkv=2, Sq=384, Skv=4096, q_chunk=16, kv_block=128), True, 0.5),
+    ("bf16_randmask_unaligned_d64", dict(D=64, Hq=4, Sq=200, Skv=2500, q_chunk=7, kv_block=100), False, 0.3),
+    ("bf16_randmask_half_tiles", dict(Sq=256, Skv=2048, q_chunk=32, kv_block=32), False, 0.7),
+    ("bf16_randmask_blocks", dict(Hq=4, Hkv=1, Sq=128, Skv=4096, q_chunk=32, kv_block=256, n_blocks=2), False, 0.4),
+    ("bf16_randmask_sparse", dict(Sq=512, Skv=8192, q_chunk=64, kv_block=512), False, 0.1),
+])
+def test_random_media_masks(name, kw, per_batch, p_on):
+    # seeded random bitmaps: mixed tiles everywhere, rows and keys that nobody pairs with,
+    # a different bitmap per batch entry in the first case
+    w = small(name, **kw)
+    rng = np.random.Generator(np.random.Philox(1234 + len(name)))
+    nq, nk = -(-w.Sq // w.q_chunk), -(-w.Skv // w.kv_block)
+    shape = (w.B, nq, nk) if per_batch else (nq, nk)
+    run_case(w, do_bwd=True, allow=(rng.random(shape) < p_on))
 
 
 def test_masked_rows_without_keys():
