@@ -74,6 +74,14 @@ WORKLOADS: Dict[str, Workload] = {
     "c5_extreme_1m": Workload("c5_extreme_1m", B=1, Hq=32, Hkv=8, D=128, Sq=512, Skv=1048576,
                               dtype="bf16", std=0.5, n_blocks=16, outlier_frac=0.01,
                               outlier_scale=8.0, note="16 blocks of 65536, 1% of key tokens x8"),
+    # further shapes (the paper's models with short visual blocks have much longer text sides,
+    # Section 4): measured for the record, not part of the graded set
+    "x1_sq32k_skv64k": Workload("x1_sq32k_skv64k", B=1, Hq=32, Hkv=8, D=128, Sq=32768, Skv=65536,
+                                dtype="bf16", std=0.5, note="text side as long as half the visual side"),
+    "x2_d64_sq8k_skv256k": Workload("x2_d64_sq8k_skv256k", B=1, Hq=32, Hkv=8, D=64, Sq=8192, Skv=262144,
+                                    dtype="bf16", std=0.5, n_blocks=4, note="64-wide heads, 4 blocks of 65536"),
+    "x3_sq65k_skv8k": Workload("x3_sq65k_skv8k", B=1, Hq=32, Hkv=8, D=128, Sq=65536, Skv=8192,
+                               dtype="bf16", std=0.5, note="text side longer than the visual side"),
 }
 
 
