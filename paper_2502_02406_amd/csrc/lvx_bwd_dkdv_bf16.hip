@@ -546,21 +546,12 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   }
 }
 
-template <typename F>
-hipError_t set_smem_once(F* fn, int bytes, bool* done) {
-  if (*done) return hipSuccess;
-  hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-  if (e == hipSuccess) *done = true;
-  return e;
-}
-
-
 template <int D, bool GENERAL>
 hipError_t launch(const BwdArgs& a, hipStream_t s) {
   const long grid = xcd_grid(a.d.B * a.d.Hkv, (a.d.Skv + DkvSmem<D, kvb_of(GENERAL)>::KN - 1) / DkvSmem<D, kvb_of(GENERAL)>::KN);
-  static bool once = false;
+  static SmemOnce once;
   using SM = DkvSmem<D, kvb_of(GENERAL)>;
-  hipError_t e = set_smem_once(bwd_dkdv_bf16_kernel<D, GENERAL>, SM::TOTAL, &once);
+  hipError_t e = ensure_dynamic_lds((const void*)bwd_dkdv_bf16_kernel<D, GENERAL>, SM::TOTAL, &once);
   if (e != hipSuccess) return e;
   bwd_dkdv_bf16_kernel<D, GENERAL><<<(unsigned)grid, 256, SM::TOTAL, s>>>(a);
   return hipGetLastError();

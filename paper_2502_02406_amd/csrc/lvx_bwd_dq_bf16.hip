@@ -517,18 +517,10 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   }
 }
 
-template <typename F>
-hipError_t set_smem_once(F* fn, int bytes, bool* done) {
-  if (*done) return hipSuccess;
-  hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-  if (e == hipSuccess) *done = true;
-  return e;
-}
-
 template <int D, bool GENERAL>
 hipError_t launch(const BwdArgs& a, long grid, hipStream_t s) {
-  static bool once = false;
-  hipError_t e = set_smem_once(bwd_dq_bf16_kernel<D, GENERAL>, DqSmem<D>::TOTAL, &once);
+  static SmemOnce once;
+  hipError_t e = ensure_dynamic_lds((const void*)bwd_dq_bf16_kernel<D, GENERAL>, DqSmem<D>::TOTAL, &once);
   if (e != hipSuccess) return e;
   bwd_dq_bf16_kernel<D, GENERAL><<<(unsigned)grid, 256, DqSmem<D>::TOTAL, s>>>(a);
   return hipGetLastError();

@@ -460,13 +460,9 @@ fwd_bf16_kernel(FwdArgs a) {
 
 template <int D>
 hipError_t launch(const FwdArgs& a, long grid, hipStream_t s) {
-  static bool once = false;
-  if (!once) {
-    hipError_t e = hipFuncSetAttribute((const void*)fwd_bf16_kernel<D>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, KvSmem<D>::TOTAL);
-    if (e != hipSuccess) return e;
-    once = true;
-  }
+  static SmemOnce once;
+  const hipError_t e = ensure_dynamic_lds((const void*)fwd_bf16_kernel<D>, KvSmem<D>::TOTAL, &once);
+  if (e != hipSuccess) return e;
   fwd_bf16_kernel<D><<<(unsigned)grid, 256, KvSmem<D>::TOTAL, s>>>(a);
   return hipGetLastError();
 }

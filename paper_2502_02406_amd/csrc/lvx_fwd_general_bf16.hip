@@ -455,13 +455,9 @@ fwd_general_bf16_kernel(FwdArgs a) {
 
 template <int D>
 hipError_t launch(const FwdArgs& a, long grid, hipStream_t s) {
-  static bool once = false;
-  if (!once) {
-    hipError_t e = hipFuncSetAttribute((const void*)fwd_general_bf16_kernel<D>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, FwdSmem<D>::TOTAL);
-    if (e != hipSuccess) return e;
-    once = true;
-  }
+  static SmemOnce once;
+  const hipError_t e = ensure_dynamic_lds((const void*)fwd_general_bf16_kernel<D>, FwdSmem<D>::TOTAL, &once);
+  if (e != hipSuccess) return e;
   fwd_general_bf16_kernel<D><<<(unsigned)grid, 512, FwdSmem<D>::TOTAL, s>>>(a);
   return hipGetLastError();
 }

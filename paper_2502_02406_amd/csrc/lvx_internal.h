@@ -72,6 +72,22 @@ hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t s);
 hipError_t launch_bwd_bf16(const BwdArgs& a, unsigned stages, hipStream_t s);
 hipError_t launch_bwd_dkdv_bf16(const BwdArgs& a, hipStream_t s);
 hipError_t launch_bwd_dq_bf16(const BwdArgs& a, hipStream_t s);
+// Raises a kernel's dynamic LDS limit once per device (the attribute belongs to the device's copy
+// of the kernel).  `done` is the caller's per-kernel table; a race between host threads only
+// repeats a harmless call.
+constexpr int LVX_MAX_DEVICES = 64;
+struct SmemOnce { bool done[LVX_MAX_DEVICES] = {}; };
+inline hipError_t ensure_dynamic_lds(const void* kernel, int bytes, SmemOnce* once) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const bool tracked = dev >= 0 && dev < LVX_MAX_DEVICES;
+  if (tracked && once->done[dev]) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess && tracked) once->done[dev] = true;
+  return e;
+}
+
 int fwd_bf16_pick_split(const Dims& d, int n_cu, bool masked);
 hipError_t launch_fwd_general_bf16(const FwdArgs& a, hipStream_t s);   // masked or ragged problems
 int bwd_bf16_pick_split(const Dims& d, int n_cu, bool masked);
