@@ -98,8 +98,11 @@ class BlockLoop:
             sl = slice(n * self.blk, (n + 1) * self.blk)
             kb, vb = k[:, :, sl], v[:, :, sl]
             p = B.make_problem(q, kb, self.scale)
+            # delta = rowsum(dO * O) depends on the query block only: the first visit computes it
+            # into the workspace, the others reuse it
+            stages = B.LVX_BWD_ALL if n == 0 else (B.LVX_BWD_DKDV | B.LVX_BWD_DQ)
             B.lvx_xattn_bwd(p, q, kb, vb, o, lse, d_o, self._mask_for(n), self.dq_accum,
-                            dk[:, :, sl], dv[:, :, sl], self.ws)
+                            dk[:, :, sl], dv[:, :, sl], self.ws, stages)
         p = B.make_problem(q, k, self.scale)
         B.lvx_xattn_dq_finalize(p, self.dq_accum, self.dq)
         return self.dq
