@@ -11,9 +11,12 @@
 // scalars; the two half-waves exchange one value per half) and 16 keys in a lane's registers, so
 // P^T, rounded to bf16, is already the B operand of O^T += V^T P^T, with V^T fetched by
 // transposing LDS reads.
-// Online softmax with a lazy reference r per row, in units of log2: p = exp2(s scale log2 e - r),
-// and r is only raised when a half tops it by more than 2^LAZY; the result is still exact, since
-// any reference cancels between numerator and denominator.  (Q is not pre-multiplied by the
+// Online softmax with a lazy reference r per row, in units of log2: p = exp2(s scale log2 e - r).
+// r starts as the maximum of the row's first 32 scores.  Later halves are converted against the
+// current r without looking at their maximum first; the sum of the 16 probabilities a lane
+// produced tells afterwards whether one of them can have topped 2^LAZY, and only then (rarely) r
+// is raised to the new maximum, O^T and the sums shrink, and the half is converted again.  The
+// result is still exact, since any reference cancels between numerator and denominator.  (Q is not pre-multiplied by the
 // scale: rounding the product to bf16 would cost about 1e-3 of L on rows with large scores.)
 // The loop runs over 32-key halves and is software pipelined inside each wave: while the matrix
 // core contracts half h (O) and scores half h+2 (S), the vector ALU turns the scores of half h+1
@@ -31,8 +34,12 @@ namespace lvx {
 namespace {
 
 using namespace kvring;
-constexpr float LAZY = 6.0f;           // raise the reference only when a half tops it by 2^LAZY
-constexpr int XE = 8;                  // elements of a half converted during the contraction (of 32)
+constexpr float LAZY_SUM = 64.0f;      // a lane's 16 probabilities of a half may add up to this (2^LAZY, LAZY = 6)
+                                       // before the reference is raised: no probability in use exceeds it
+#ifndef LVX_FWD_XE
+#define LVX_FWD_XE 8
+#endif
+constexpr int XE = LVX_FWD_XE;                  // elements of a half converted during the contraction (of 32)
 
 // Dense attention with Skv a multiple of 64 only: no mask code and no ragged tile, so that nothing
 // stands between the phases of the pipeline (masked and ragged problems: lvx_fwd_general_bf16.hip).
@@ -120,18 +127,15 @@ fwd_bf16_kernel(FwdArgs a) {
 
   // ---- softmax state of this lane's two query rows (both half-waves keep identical copies)
   f32x16 oacc[QB][DB];                 // O^T, relative to the reference
-  float m_ref[QB], r[QB], l_run[QB];   // true reference (-inf before the first key), r = finite
-                                       // stand-in (0 for -inf), this lane's share of the sum of p
-  float pend[QB];                      // factor still to be applied to oacc (1: none)
-  bool pending = false;
+  float r[QB], l_run[QB], l_half[QB];  // reference, this lane's share of the sum of p over the halves
+                                       // accepted so far, and over the half being converted
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
 #pragma unroll
     for (int i = 0; i < DB; ++i) { oacc[qb][i] = zero16(); asm volatile("" : "+a"(oacc[qb][i])); }
-    m_ref[qb] = -INFINITY;
     r[qb] = 0.f;
     l_run[qb] = 0.f;
-    pend[qb] = 1.f;
+    l_half[qb] = 0.f;
   }
 
   // ---- building blocks, all on one 32-key half hb of the tile at st ---------------------------
@@ -174,37 +178,6 @@ fwd_bf16_kernel(FwdArgs a) {
   auto settle_scores = [&](f32x16 (&s)[QB]) __attribute__((always_inline)) {
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" : "+v"(s[0]), "+v"(s[1]));
   };
-  // Before a half's scores are exponentiated: does any row top its reference by more than
-  // 2^LAZY?  Then (rarely) the reference of the rows that grew is raised to their new maximum:
-  // the sums shrink by alpha = 2^(old - new), and the factor for O^T is kept in pend until no
-  // matrix instruction on O^T is in flight.
-  auto check = [&](const f32x16 (&s)[QB]) __attribute__((always_inline)) {
-    float tm[QB];
-    bool need = false;
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      float m = fmaxf(fmaxf(s[qb][0], s[qb][1]), s[qb][2]);
-#pragma unroll
-      for (int v = 3; v < 15; v += 2) m = fmaxf(fmaxf(m, s[qb][v]), s[qb][v + 1]);
-      m = fmaxf(m, s[qb][15]);
-      tm[qb] = xhalf_max(m) * c2;                  // the row's maximum in units of log2 (c2 > 0)
-      need |= tm[qb] - m_ref[qb] > LAZY;           // NaN (-inf - -inf) compares false
-    }
-    if (__builtin_expect(__any(need), 0)) {
-      asm volatile("" ::: "memory");               // keep this a real, rarely taken branch
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        const float m_new = fmaxf(m_ref[qb], tm[qb]);
-        const float r_new = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m_ref[qb] - r_new);   // m_ref = -inf -> 0
-        m_ref[qb] = m_new;
-        r[qb] = r_new;
-        l_run[qb] *= alpha;
-        pend[qb] *= alpha;
-      }
-      pending = true;
-    }
-  };
   // Waits until every matrix instruction issued so far has written its result.  The accumulators
   // are operands of the statement, so that the compiler cannot read them before it.
   auto drain_oacc = [&]() __attribute__((always_inline)) {
@@ -216,18 +189,56 @@ fwd_bf16_kernel(FwdArgs a) {
         asm volatile("s_nop 15\n\ts_nop 15" : "+a"(oacc[qb][0]), "+a"(oacc[qb][1]));
     }
   };
-  // apply the pending factors to O^T, between two phases
-  auto settle = [&]() __attribute__((always_inline)) {
-    if (__builtin_expect(pending, false)) {
+  // Conversion of scores into the P^T operands, element x of a half (x = 0..31: query block
+  // qb = x / 16, register v = x % 16): p = exp2(s c2 - r), added to the half's sum and packed in pairs as
+  // bf16 into word (v % 8) / 2 of operand v / 8 of the query block.
+  struct Carry { float p; };
+  auto conv_elem = [&](int x, Carry& cy, const f32x16 (&s)[QB], u32x4 (&pw)[QB][2]) __attribute__((always_inline)) {
+    const int qb = x / 16, v = x % 16;
+    const float pr = __builtin_amdgcn_exp2f(fmaf(s[qb][v], c2, -r[qb]));
+    if (v == 0) l_half[qb] = pr;
+    else l_half[qb] += pr;
+    if (v % 2 == 0) { cy.p = pr; return; }
+    pw[qb][v / 8][(v % 8) / 2] = pack2_bf16(cy.p, pr);
+  };
+  auto convert = [&](const f32x16 (&s)[QB], u32x4 (&pw)[QB][2]) __attribute__((always_inline)) {
+    Carry cy;
+#pragma unroll
+    for (int x = 0; x < 32; ++x) conv_elem(x, cy, s, pw);
+  };
+  // a row's largest score of a half, in units of log2 (c2 > 0)
+  auto row_max = [&](const f32x16& sv) __attribute__((always_inline)) -> float {
+    float m = fmaxf(fmaxf(sv[0], sv[1]), sv[2]);
+#pragma unroll
+    for (int v = 3; v < 15; v += 2) m = fmaxf(fmaxf(m, sv[v]), sv[v + 1]);
+    return xhalf_max(fmaxf(m, sv[15])) * c2;
+  };
+  // After a half has been converted, before its probabilities are used: accept it, or (rarely)
+  // redo it.  A lane's sum of 16 probabilities bounds each of them, so a sum within LAZY_SUM
+  // proves that none overflowed or is too large for the accumulation; a larger one (infinity
+  // included) sends the whole wave through the raise: r goes up to the row's maximum where that
+  // is larger, O^T -- no matrix instruction on it is in flight between two phases once drained
+  // -- and the accepted sums shrink by alpha = 2^(old - new), and the half is converted again
+  // from its scores, which are still in their registers.  Rows that keep their reference get
+  // identical values again.
+  auto commit = [&](const f32x16 (&s)[QB], u32x4 (&pw)[QB][2]) __attribute__((always_inline)) {
+    bool need = false;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) need |= !(l_half[qb] <= LAZY_SUM);
+    if (__builtin_expect(__any(need), 0)) {
+      asm volatile("" ::: "memory");               // keep this a real, rarely taken branch
       drain_oacc();
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
+        const float r_new = fmaxf(r[qb], row_max(s[qb]));
+        const float alpha = __builtin_amdgcn_exp2f(r[qb] - r_new);
+        r[qb] = r_new;
+        l_run[qb] *= alpha;
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
 #pragma unroll
-          for (int v = 0; v < 16; ++v) oacc[qb][db][v] *= pend[qb];
+          for (int v = 0; v < 16; ++v) oacc[qb][db][v] *= alpha;
         }
-        pend[qb] = 1.f;
       }
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {            // the new values settle before a matrix instruction reads them
@@ -236,24 +247,10 @@ fwd_bf16_kernel(FwdArgs a) {
         else
           asm volatile("s_nop 7" : "+a"(oacc[qb][0]), "+a"(oacc[qb][1]));
       }
-      pending = false;
+      convert(s, pw);
     }
-  };
-  // Conversion of scores into the P^T operands, element x of a half (x = 0..31: query block
-  // qb = x / 16, register v = x % 16): p = exp2(s c2 - r), added to the row's sum and packed in pairs as
-  // bf16 into word (v % 8) / 2 of operand v / 8 of the query block.
-  struct Carry { float p; };
-  auto conv_elem = [&](int x, Carry& cy, const f32x16 (&s)[QB], u32x4 (&pw)[QB][2]) __attribute__((always_inline)) {
-    const int qb = x / 16, v = x % 16;
-    const float pr = __builtin_amdgcn_exp2f(fmaf(s[qb][v], c2, -r[qb]));
-    l_run[qb] += pr;
-    if (v % 2 == 0) { cy.p = pr; return; }
-    pw[qb][v / 8][(v % 8) / 2] = pack2_bf16(cy.p, pr);
-  };
-  auto convert = [&](const f32x16 (&s)[QB], u32x4 (&pw)[QB][2]) __attribute__((always_inline)) {
-    Carry cy;
 #pragma unroll
-    for (int x = 0; x < 32; ++x) conv_elem(x, cy, s, pw);
+    for (int qb = 0; qb < QB; ++qb) l_run[qb] += l_half[qb];
   };
   // O^T += V^T P^T over the 32 keys of a half (two k-steps of 16 keys)
   auto contract = [&](const char* __restrict__ st, int hb, const u32x4 (&pw)[QB][2]) __attribute__((always_inline)) {
@@ -267,7 +264,7 @@ fwd_bf16_kernel(FwdArgs a) {
       }
   };
   // contract(half h) on the matrix core; on the vector ALU, after two matrix instructions (the
-  // scores of half h+1 have settled by then), the check of half h+1 and its first XE conversions.
+  // scores of half h+1 have settled by then), the first XE conversions of half h+1.
   // The transposed operand of a pair of matrix instructions is fetched one pair ahead, and nothing
   // is scheduled across the units.
   auto contract_convert = [&](const char* __restrict__ st, int hb, const u32x4 (&pi)[QB][2],
@@ -284,10 +281,6 @@ fwd_bf16_kernel(FwdArgs a) {
       if (qb == 0 && c + 1 < 2 * DB)
         vt[cu ^ 1] = tile_tr_operand<D>(st + SM::TILE, 32 * hb + 16 * ((c + 1) / DB), 32 * ((c + 1) % DB), lane);
       mfma_acc(oacc[qb][db], vt[cu], __builtin_bit_cast(bf16x8, pi[qb][t2]));
-      if (m == M0 - 1) {                           // (after, not around, the matrix instruction)
-        __builtin_amdgcn_sched_barrier(0);
-        check(s);
-      }
       if (m >= M0) {
 #pragma unroll
         for (int x = (m - M0) * XE / (NM - M0); x < (m - M0 + 1) * XE / (NM - M0); ++x) conv_elem(x, cy, s, po);
@@ -295,11 +288,12 @@ fwd_bf16_kernel(FwdArgs a) {
       if (m == NM - 3) tail();
       __builtin_amdgcn_sched_barrier(0);
     }
-    // the conversions stay in this phase (their results are only used two phases later, and the
-    // branch below would otherwise let them sink)
-    static_assert(XE == 8, "the words pinned here are those of elements 0 .. 7");
-    asm volatile("" : "+v"(po[0][0]), "+v"(l_run[0]));
-    settle();
+    // the conversions stay in this phase (their results are only used two phases later, and
+    // would otherwise sink towards the branch that follows the next phase)
+    static_assert(XE % 8 == 0 && XE <= 16, "the words pinned here are those of elements 0 .. XE - 1");
+    float& lh0 = l_half[0];
+    asm volatile("" : "+v"(po[0][0]), "+v"(lh0));
+    if constexpr (XE == 16) asm volatile("" : "+v"(po[0][1]));
   };
   // score(half h+2) together with the remaining conversions of half h+1
   auto score_convert = [&](const char* __restrict__ st, int hb, f32x16 (&s_new)[QB], const f32x16 (&s)[QB],
@@ -345,9 +339,10 @@ fwd_bf16_kernel(FwdArgs a) {
   if (nt > 0) {
     score(smem, 0, s0, nothing, first_k(smem, 0), no_tail);
     settle_scores(s0);
-    check(s0);
-    settle();                                      // (O^T is still zero: this only clears the factor)
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) r[qb] = row_max(s0[qb]);     // no probability of the first half exceeds 1
     convert(s0, p0);
+    commit(s0, p0);
     score(smem, 1, s1, nothing, first_k(smem, 1), no_tail);
   }
   int T = 0;
@@ -361,6 +356,7 @@ fwd_bf16_kernel(FwdArgs a) {
     asm volatile("" : "+v"(fk));                   // (waited for here, where the compiler still knows what is in flight)
     score_convert(sb, 0, s0, s1, p1, cy, fk, [&]() __attribute__((always_inline)) { fvt = first_vt(sa, 1); }, nothing);
     asm volatile("" : "+v"(fvt));
+    commit(s1, p1);
     contract_convert(sa, 1, p1, s0, p0, cy, fvt, [&]() __attribute__((always_inline)) { fk = first_k(sb, 1); });
     asm volatile("" : "+v"(fk));
     mid(std::true_type{}, false, sa);
@@ -373,16 +369,16 @@ fwd_bf16_kernel(FwdArgs a) {
                     if (m % EVERY == EVERY - 1 && m / EVERY < NDMA) issue_part(t_new, sa, m / EVERY);
                   });
     asm volatile("" : "+v"(fvt));
+    commit(s0, p0);
   }
   for (; T < nt; ++T) {                            // the last (at most four) tiles, phase after phase
     const bool more = T + 1 < nt;
     contract(stage(T), 0, p0);
-    check(s1);
-    settle();                                      // before anything relative to the new reference is added
     convert(s1, p1);
+    commit(s1, p1);                                // (a raise comes before anything relative to the new reference is added)
     if (more) { score(stage(T + 1), 0, s0, nothing, first_k(stage(T + 1), 0), no_tail); }
     contract(stage(T), 1, p1);
-    if (more) { check(s0); settle(); convert(s0, p0); }
+    if (more) { convert(s0, p0); commit(s0, p0); }
     mid(std::false_type{}, T + 4 < nt, stage(T));
     if (more) { score(stage(T + 1), 1, s1, nothing, first_k(stage(T + 1), 1), no_tail); }
   }
@@ -394,7 +390,7 @@ fwd_bf16_kernel(FwdArgs a) {
   for (int qb = 0; qb < QB; ++qb) {
     const float l_tot = xhalf_sum(l_run[qb]);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    const float lse = l_tot > 0.f ? m_ref[qb] * (1.f / LOG2E) + logf(l_tot) : -INFINITY;
+    const float lse = l_tot > 0.f ? r[qb] * (1.f / LOG2E) + logf(l_tot) : -INFINITY;
     const int i = i_wave0 + 32 * qb + ql;
     if (i >= d.Sq) continue;
     const long row = ((long)b * d.Hq + hq) * d.Sq + i;

@@ -74,7 +74,7 @@ def test_general_dkdv_leaves_half_the_accumulation_file():
 def test_blocks_with_matrix_instructions_move_no_accumulator(src, kernel):
     """The dense forward's loop has (rare) branches and the general dQ kernel has mask code, so
     their loops are several basic blocks; the rule is then per block: where matrix instructions are
-    issued, no accumulator move and no spill.  The moves of the deferred rescale of O^T sit in
+    issued, no accumulator move and no spill.  The moves of the (rare) rescale of O^T sit in
     blocks of their own, behind an explicit wait."""
     body = _kernel(_asm(src), kernel)
     n = 0
