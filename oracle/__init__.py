@@ -10,9 +10,10 @@ Inputs are float32 arrays holding values already rounded to the workload's
 storage type; every result is float64.
 
 Functions follow the paper as stated in the header of ``lvx_oracle.c``:
-the attention definition of Section 2, the Rescale step of Algorithm 1, and
-the derivative of the definition (Table 1 counts its FLOPs, Section 3.2 names
-what is saved for it).
+the attention definition of Section 2, the Rescale step of Algorithm 1, the
+derivative of the definition (Table 1 counts its FLOPs, Section 3.2 names
+what is saved for it), and the projections x W_Q, y W_K, y W_V of Section 2
+that Section 3.2 recomputes in the backward pass.
 """
 from __future__ import annotations
 
@@ -200,3 +201,24 @@ def bwd_block(q, k, v, dO, O, L, kv0, kv1, scale=None, mask=None):
     _load().lvx_oracle_bwd_block(C.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(dO), _ptr(O), _ptr(L),
                                  C.c_int(kv0), C.c_int(kv1), _ptr(dQ), _ptr(dK), _ptr(dV))
     return dQ, dK, dV
+
+
+def project(x, w, n_heads: int, rows=None) -> np.ndarray:
+    """The projection of Section 2 cut into heads: x [B,S,E], w [n_heads*D, E] (the transposed
+    projection matrix, one row per output column) -> [B, n_heads, S, D]; with rows ([n,2] of
+    (b, s)) only those tokens, [n, n_heads, D]."""
+    x, w = _f32(x), _f32(w)
+    B, S, E = x.shape
+    N, Ew = w.shape
+    assert Ew == E and N % n_heads == 0
+    D = N // n_heads
+    if rows is None:
+        out = np.empty((B, n_heads, S, D), dtype=np.float64)
+        _load().lvx_oracle_project(C.c_int(B), C.c_int(S), C.c_int(E), C.c_int(n_heads), C.c_int(D),
+                                   _ptr(x), _ptr(w), C.c_int(0), None, _ptr(out))
+        return out
+    rows = np.ascontiguousarray(rows, dtype=np.int32).reshape(-1, 2)
+    out = np.empty((rows.shape[0], n_heads, D), dtype=np.float64)
+    _load().lvx_oracle_project(C.c_int(B), C.c_int(S), C.c_int(E), C.c_int(n_heads), C.c_int(D),
+                               _ptr(x), _ptr(w), C.c_int(rows.shape[0]), _ptr(rows), _ptr(out))
+    return out

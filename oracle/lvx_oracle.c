@@ -24,6 +24,11 @@
  *   - block backward: the step one worker takes for its own K/V block when
  *     only the final O and L are available (Section 3.2 saves nothing else):
  *     p = exp(s - L), delta = rowsum(dO * O).
+ *   - projection: the products of Section 2 that make the operands of the
+ *     attention, Q = x W_Q and K, V = y W_K, y W_V, which Section 3.2 has the
+ *     backward pass compute again instead of keeping Q, K and V.  Written
+ *     out as the definition of a matrix product, one dot product per output
+ *     element, with the d columns of the result cut into heads.
  *
  * Conventions:
  *   Q, dO      [B, Hq,  Sq,  D]  float32, contiguous, values already rounded
@@ -449,4 +454,36 @@ void lvx_oracle_bwd_block(const lvx_oracle_problem *p, const float *q, const flo
         for (int d = 0; d < p->D; ++d) dk[d] *= p->scale;
     }
     free(delta);
+}
+
+/* ---------------------------------------------------------------------------
+ * Projection (Section 2: Q = x W_Q, K = y W_K, V = y W_V; Section 3.2: done
+ * again in the backward pass).  x is [B, S, E]; w holds W TRANSPOSED, one row
+ * of E weights per output column, [H * D, E] (the way a linear layer stores
+ * it); column h * D + c of the product is element c of head h:
+ *     out[b, h, s, c] = sum_e x[b, s, e] * w[h * D + c, e].
+ * rows == NULL: every token, out is [B, H, S, D].  Otherwise rows holds n_rows
+ * pairs (b, s) and out is [n_rows, H, D].
+ * ------------------------------------------------------------------------- */
+void lvx_oracle_project(int B, int S, int E, int H, int D, const float *x, const float *w,
+                        int n_rows, const int32_t *rows, double *out)
+{
+    const long n = rows ? n_rows : (long)B * S;
+#pragma omp parallel for schedule(static)
+    for (long r = 0; r < n; ++r) {
+        const int b = rows ? rows[2 * r] : (int)(r / S);
+        const int s = rows ? rows[2 * r + 1] : (int)(r % S);
+        const float *xr = x + ((long)b * S + s) * E;
+        for (int h = 0; h < H; ++h)
+            for (int c = 0; c < D; ++c) {
+                const float *wr = w + ((long)h * D + c) * E;
+                double acc = 0.0;
+                for (int e = 0; e < E; ++e)
+                    acc += (double)xr[e] * (double)wr[e];
+                if (rows)
+                    out[(r * H + h) * D + c] = acc;
+                else
+                    out[(((long)b * H + h) * S + s) * D + c] = acc;
+            }
+    }
 }
