@@ -6,7 +6,8 @@
  *   FlashAttention(Q_j, K_i, V_i) -> (dO partial, dL partial)   lvx_xattn_fwd
  *   Rescale(O_j, L_j, dO, dL)                                    lvx_xattn_merge
  * and, in the backward pass, recomputes the attention probabilities from the
- * saved statistic L instead of storing them (Section 3.2)       lvx_xattn_bwd.
+ * saved statistic L instead of storing them (Section 3.2)       lvx_xattn_bwd,
+ * after recomputing Q, K and V from the token features          lvx_xattn_project.
  *
  * General rules for every entry point
  *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The library
@@ -49,7 +50,7 @@ typedef enum {
   LVX_ERR_STRIDE = -4,      /* stride too small for the shape, or misaligned for vector access */
   LVX_ERR_MASK = -5,        /* mask geometry does not cover Sq x Skv */
   LVX_ERR_WORKSPACE = -6,   /* workspace NULL, misaligned or smaller than required */
-  LVX_ERR_UNSUPPORTED = -7, /* head dim other than 64 / 128 */
+  LVX_ERR_UNSUPPORTED = -7, /* head dim other than 64 / 128; projection shape the bf16 kernel does not take */
   LVX_ERR_HIP = -8          /* a kernel launch failed (hipGetLastError) */
 } lvx_status;
 
@@ -146,6 +147,29 @@ lvx_status lvx_xattn_bwd_stages(const lvx_problem* p, lvx_dtype dtype, const voi
 /* dq (type `dtype`, Q's strides) = dq_accum (float32, contiguous) rounded to `dtype`. */
 lvx_status lvx_xattn_dq_finalize(const lvx_problem* p, const float* dq_accum, void* dq,
                                  lvx_dtype dtype, void* hip_stream);
+
+/* The projections of Section 2 that make the attention operands, Q = x W_Q and K, V = y W_K,
+ * y W_V, which Section 3.2 has the backward pass compute again from the saved token features
+ * instead of keeping Q, K and V:
+ *     out[o][b, h, s, c] = sum_e x[b, s, e] * w[(o * H + h) * D + c, e],   o = 0 .. n_out - 1.
+ * x      device, [B, S, E] of `dtype`, strides x_sb, x_ss in elements (features contiguous);
+ *        the batches must follow each other, x_sb == S * x_ss (LVX_ERR_STRIDE otherwise).
+ * w      device, [n_out * H * D, E] of `dtype`, contiguous: the projection matrices TRANSPOSED
+ *        (one row of E weights per output column, the layout of a linear layer's weight) and
+ *        stacked, e.g. W_K^T on top of W_V^T with n_out = 2, so that y is read once for both.
+ * out    host array of n_out (1 or 2) device pointers, each [B, H, S, D] of `dtype`, contiguous
+ *        -- the layout lvx_xattn_fwd / lvx_xattn_bwd read -- overwritten.
+ * LVX_BF16 runs on the matrix cores (float32 accumulation, one rounding of the result) and needs
+ * E % 32 == 0, (n_out * H * D) % 256 == 0 and (H * D) % 128 == 0 (LVX_ERR_UNSUPPORTED
+ * otherwise); B * S is arbitrary.  LVX_F32 takes any shape (plain FMA, correctness-grade).
+ * LVX_BF16: pointers and x's row stride must be 16-byte aligned.  No workspace. */
+typedef struct {
+  int32_t B, S, E;          /* batches, tokens per batch, embedding width */
+  int32_t H, D;             /* heads and head dim of ONE output */
+  int64_t x_sb, x_ss;       /* strides of x in elements */
+} lvx_projection;
+lvx_status lvx_xattn_project(const lvx_projection* p, lvx_dtype dtype, const void* x, const void* w,
+                             int n_out, void* const* out, void* hip_stream);
 
 /* Human-readable name of a status code (static storage). */
 const char* lvx_strerror(lvx_status s);

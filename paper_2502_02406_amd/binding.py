@@ -22,7 +22,7 @@ LVX_MAX_PARTS = 64
 LVX_BWD_DELTA, LVX_BWD_DKDV, LVX_BWD_DQ, LVX_BWD_ALL = 1, 2, 4, 7
 
 EXPORTS = ("lvx_xattn_workspace_bytes", "lvx_xattn_fwd", "lvx_xattn_fwd_merge", "lvx_xattn_merge", "lvx_xattn_bwd",
-           "lvx_xattn_bwd_stages", "lvx_xattn_dq_finalize", "lvx_strerror")
+           "lvx_xattn_bwd_stages", "lvx_xattn_dq_finalize", "lvx_xattn_project", "lvx_strerror")
 
 
 class LvxError(RuntimeError):
@@ -43,6 +43,11 @@ class lvx_mask(C.Structure):
     _fields_ = [("allow", C.c_void_p), ("q_chunk", C.c_int32), ("kv_block", C.c_int32),
                 ("n_q_chunks", C.c_int32), ("n_kv_blocks", C.c_int32),
                 ("stride_b", C.c_int64), ("stride_q", C.c_int64)]
+
+
+class lvx_projection(C.Structure):
+    _fields_ = [("B", C.c_int32), ("S", C.c_int32), ("E", C.c_int32), ("H", C.c_int32),
+                ("D", C.c_int32), ("x_sb", C.c_int64), ("x_ss", C.c_int64)]
 
 
 _lib = None
@@ -80,6 +85,9 @@ def load() -> C.CDLL:
         lib.lvx_xattn_dq_finalize.restype = C.c_int
         lib.lvx_xattn_dq_finalize.argtypes = [C.POINTER(lvx_problem), C.c_void_p, C.c_void_p,
                                               C.c_int, C.c_void_p]
+        lib.lvx_xattn_project.restype = C.c_int
+        lib.lvx_xattn_project.argtypes = [C.POINTER(lvx_projection), C.c_int, C.c_void_p, C.c_void_p,
+                                          C.c_int, C.POINTER(C.c_void_p), C.c_void_p]
         lib.lvx_strerror.restype = C.c_char_p
         lib.lvx_strerror.argtypes = [C.c_int]
         _lib = lib
@@ -204,3 +212,21 @@ def lvx_xattn_dq_finalize(p: lvx_problem, dq_accum, dq) -> None:
     code = load().lvx_xattn_dq_finalize(C.byref(p), dq_accum.data_ptr(), dq.data_ptr(),
                                         dtype_code(dq.dtype), _stream())
     _check(code, "lvx_xattn_dq_finalize")
+
+
+def lvx_xattn_project(x, w, outs) -> None:
+    """outs: one or two tensors [B, H, S, D] (contiguous, dtype of x), overwritten with the heads of
+    x [B, S, E] times the rows of w [len(outs) * H * D, E]."""
+    if not x.is_cuda:
+        raise RuntimeError("lvx_xattn_project needs device tensors")
+    assert x.dim() == 3 and x.stride(2) == 1 and w.dim() == 2 and w.is_contiguous()
+    assert all(o.dim() == 4 and o.is_contiguous() and o.dtype == x.dtype for o in outs) and w.dtype == x.dtype
+    p = lvx_projection()
+    p.B, p.S, p.E = x.shape
+    _, p.H, _, p.D = outs[0].shape
+    assert all(tuple(o.shape) == (p.B, p.H, p.S, p.D) for o in outs) and tuple(w.shape) == (len(outs) * p.H * p.D, p.E)
+    p.x_sb, p.x_ss = x.stride(0), x.stride(1)
+    arr = (C.c_void_p * len(outs))(*[o.data_ptr() for o in outs])
+    code = load().lvx_xattn_project(C.byref(p), dtype_code(x.dtype), x.data_ptr(), w.data_ptr(),
+                                    len(outs), arr, _stream())
+    _check(code, "lvx_xattn_project")

@@ -306,4 +306,38 @@ lvx_status lvx_xattn_dq_finalize(const lvx_problem* p, const float* dq_accum, vo
   return e == hipSuccess ? LVX_OK : LVX_ERR_HIP;
 }
 
+lvx_status lvx_xattn_project(const lvx_projection* p, lvx_dtype dtype, const void* x, const void* w,
+                             int n_out, void* const* out, void* hip_stream) {
+  if (!p || !x || !w || !out) return LVX_ERR_NULL;
+  if (n_out < 1 || n_out > 2) return LVX_ERR_SHAPE;
+  for (int o = 0; o < n_out; ++o)
+    if (!out[o]) return LVX_ERR_NULL;
+  if (p->B <= 0 || p->S <= 0 || p->E <= 0 || p->H <= 0 || p->D <= 0) return LVX_ERR_SHAPE;
+  if ((long)n_out * p->H * p->D > INT32_MAX) return LVX_ERR_SHAPE;
+  if (dtype != LVX_F32 && dtype != LVX_BF16) return LVX_ERR_DTYPE;
+  const int esz = dtype == LVX_F32 ? 4 : 2;
+  if (p->x_ss < p->E || p->x_sb != (int64_t)p->S * p->x_ss) return LVX_ERR_STRIDE;
+  if (dtype == LVX_BF16) {                           // 16-byte copies and stores
+    if ((p->x_ss * esz) % 16 != 0 || !aligned16(x) || !aligned16(w)) return LVX_ERR_STRIDE;
+    for (int o = 0; o < n_out; ++o)
+      if (!aligned16(out[o])) return LVX_ERR_STRIDE;
+  }
+  ProjArgs a{};
+  a.x = x;
+  a.w = w;
+  for (int o = 0; o < n_out; ++o) a.out[o] = out[o];
+  a.M = (long)p->B * p->S;
+  a.ldx = p->x_ss;
+  a.S = p->S;
+  a.E = p->E;
+  a.N = n_out * p->H * p->D;
+  a.H = p->H;
+  a.D = p->D;
+  if (dtype == LVX_BF16 && !project_bf16_supported(a)) return LVX_ERR_UNSUPPORTED;
+  // (a tile's copies address its rows with 32-bit byte offsets from the tile's first row)
+  if (dtype == LVX_BF16 && 256 * p->x_ss * esz > (int64_t)UINT32_MAX) return LVX_ERR_STRIDE;
+  const hipError_t e = launch_project(a, dtype == LVX_F32, (hipStream_t)hip_stream);
+  return e == hipSuccess ? LVX_OK : LVX_ERR_HIP;
+}
+
 }  // extern "C"

@@ -64,6 +64,17 @@ struct MergeArgs {
   long o_sb, o_sh, o_ss;
 };
 
+// Projection out[o][b, h, s, c] = sum_e x[b, s, e] w[(o H + h) D + c, e], tokens flattened to M = B S rows.
+struct ProjArgs {
+  const void* x;        // [M, E], row stride ldx elements
+  const void* w;        // [N, E] contiguous, N = n_out * H * D
+  void* out[2];         // each [B, H, S, D] contiguous, x's dtype
+  long M, ldx;
+  int S, E, N, H, D;
+};
+bool project_bf16_supported(const ProjArgs& a);   // shapes the matrix-core kernel takes
+hipError_t launch_project(const ProjArgs& a, int is_f32, hipStream_t s);
+
 // kernels for float32 tensors (plain FMA, correctness-grade)
 hipError_t launch_fwd_f32(const FwdArgs& a, hipStream_t s);
 hipError_t launch_bwd_f32(const BwdArgs& a, unsigned stages, hipStream_t s);   // stages: 2 = dK/dV, 4 = dQ

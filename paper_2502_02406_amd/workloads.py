@@ -19,7 +19,7 @@ import numpy as np
 import torch
 
 BASE_SEED = 20250204
-_TENSOR_ID = {"q": 0, "k": 1, "v": 2, "do": 3, "outliers": 4}
+_TENSOR_ID = {"q": 0, "k": 1, "v": 2, "do": 3, "outliers": 4, "tokens": 5, "weights": 6}
 
 
 @dataclass(frozen=True)
@@ -153,3 +153,18 @@ def make_inputs(w: Workload, seed: int = BASE_SEED, with_do: bool = True) -> Dic
 def as_f32_numpy(t: torch.Tensor) -> np.ndarray:
     """Exact widening of a storage-typed tensor to float32 numpy (what the oracle reads)."""
     return t.detach().to("cpu", torch.float32).contiguous().numpy()
+
+
+def projection_inputs(B: int, S: int, E: int, N: int, dtype: str, seed: int = BASE_SEED,
+                      std_out: float = 0.5) -> Dict[str, torch.Tensor]:
+    """CPU tensors for the projections of Section 2 (recomputed in the backward pass, Section 3.2):
+    token features 'x' [B, S, E] ~ N(0, 1) (what a normalisation layer hands over) and stacked,
+    transposed projection weights 'w' [N, E] ~ N(0, std_out^2 / E), so that the projected heads
+    have the spread the attention workloads use.  Rounded to the storage type here, once."""
+    dt = torch_dtype(dtype)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed + _TENSOR_ID["tokens"])
+    x = torch.empty((B, S, E), dtype=torch.float32).normal_(0.0, 1.0, generator=g)
+    g.manual_seed(seed + _TENSOR_ID["weights"])
+    w = torch.empty((N, E), dtype=torch.float32).normal_(0.0, std_out / float(E) ** 0.5, generator=g)
+    return {"x": x.to(dt), "w": w.to(dt)}
