@@ -160,7 +160,7 @@ lvx_status lvx_xattn_dq_finalize(const lvx_problem* p, const float* dq_accum, vo
  * out    host array of n_out (1 or 2) device pointers, each [B, H, S, D] of `dtype`, contiguous
  *        -- the layout lvx_xattn_fwd / lvx_xattn_bwd read -- overwritten.
  * LVX_BF16 runs on the matrix cores (float32 accumulation, one rounding of the result) and needs
- * E % 32 == 0, (n_out * H * D) % 256 == 0 and (H * D) % 128 == 0 (LVX_ERR_UNSUPPORTED
+ * E % 64 == 0, (n_out * H * D) % 256 == 0 and (H * D) % 128 == 0 (LVX_ERR_UNSUPPORTED
  * otherwise); B * S is arbitrary.  LVX_F32 takes any shape (plain FMA, correctness-grade).
  * LVX_BF16: pointers and x's row stride must be 16-byte aligned.  No workspace. */
 typedef struct {

@@ -11,12 +11,14 @@
 // accumulators fill the accumulation registers, so each operand read from LDS feeds four matrix
 // instructions.  The product is formed transposed (columns of w as the A operand, tokens as B):
 // a lane then holds ONE token and, per block, groups of four consecutive columns.
-// x and w tiles of 32 features travel HBM -> LDS by direct copies into a ring of four stages,
-// issued three stages ahead and spread over the matrix instructions; a row of a tile is 64
-// bytes, and its four 16-byte chunks are stored permuted (chunk c of row r at position
-// c ^ (r / 4 % 4)) so that the 16 rows a quarter-wave reads together cover all banks.  The
-// barrier of a stage sits in the middle of the stage before it, so that the first operands of the
-// next stage are read while the matrix core still works on this one.
+// x and w tiles of 64 features travel HBM -> LDS by direct copies, whole 128-byte lines per row
+// (half lines cost as many entries of the memory pipeline as whole ones and halve its
+// throughput), into two slots of 64 KB that alternate; the copies of a tile pair go out while
+// the pair before it is being multiplied, spread over the matrix instructions.  The eight
+// 16-byte chunks of a tile row are stored permuted (perm_of) so that the rows a quarter-wave
+// reads together cover all banks.  The one barrier per 64 matrix instructions sits before the
+// last quarter of a tile pair, when its last operands are already in registers: behind it the
+// first operands of the next pair are read and the slot is free for the pair after that.
 // The epilogue turns the tile around in LDS (rounded to bf16) and writes whole 256-byte rows.
 #include "lvx_internal.h"
 #include "lvx_mfma.h"
@@ -29,16 +31,22 @@ namespace lvx {
 namespace {
 
 constexpr int TM = 256, TN = 256;      // tokens x columns per workgroup
-constexpr int BK = 32;                 // features per stage
-constexpr int NSTG = 4;                // ring stages
-constexpr int ROWB = BK * 2;           // bytes of a tile row
+constexpr int BK = 64;                 // features per tile pair
+constexpr int NSLOT = 2;               // LDS slots
+constexpr int ROWB = BK * 2;           // bytes of a tile row: one 128-byte line
 constexpr int TILE_B = 256 * ROWB;     // one operand's tile
-constexpr int STAGE_B = 2 * TILE_B;    // x tile, then w tile
-constexpr int RING_B = NSTG * STAGE_B;
+constexpr int SLOT_B = 2 * TILE_B;     // x tile, then w tile
+constexpr int RING_B = NSLOT * SLOT_B;
 constexpr int TB_PITCH = 128 * 2 + 16; // epilogue: a wave's 128 tokens x 128 columns of bf16, padded rows
 constexpr int TB_WAVE = 128 * TB_PITCH;
 constexpr int SMEM_B = RING_B > 4 * TB_WAVE ? RING_B : 4 * TB_WAVE;
-constexpr int NPART = 8;               // copies per wave and stage: 4 of x, 4 of w (16 rows each)
+constexpr int NPART = 16;              // copies per wave and tile pair: 8 of x, 8 of w (8 rows each)
+
+// Position permutation of a tile row's eight chunks: chunk c of row r sits at position
+// c ^ perm_of(r).  Eight consecutive rows get eight different values, and two rows eight apart
+// differ too, so the 16-byte reads of 8 or of 16 consecutive rows at one chunk never meet in a
+// bank (rows are 128 bytes apart).
+__device__ __forceinline__ int perm_of(int r) { return (r & 7) ^ ((r >> 3) & 1); }
 
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 project_bf16_kernel(ProjArgs a) {
@@ -53,39 +61,41 @@ project_bf16_kernel(ProjArgs a) {
   const int wm = wave >> 1, wn = wave & 1;           // this wave's 128 tokens / 128 columns of the tile
   const int nk = a.E / BK;
 
-  // ---- copies: one instruction moves 16 rows x 64 bytes; lane l fills slot l of them, i.e. row
-  // l / 4, position l % 4, which holds chunk (l % 4) ^ (row / 4 % 4).  Rows past the last token
-  // re-read the last one (their results are never stored).
+  // ---- copies: one instruction moves 8 rows x 128 bytes; lane l fills slot l of them, i.e. row
+  // l / 8, position l % 8, which holds chunk (l % 8) ^ perm_of(row).  A wave copies rows
+  // 64 wave + 8 j + l / 8 of both tiles, j = 0 .. 7.  Rows past the last token re-read the last
+  // one (their results are never stored).
   const unsigned xrow_b = (unsigned)(a.ldx * 2), wrow_b = (unsigned)(a.E * 2);
-  const unsigned swz = 16u * (unsigned)((lane & 3) ^ ((lane >> 4) & 3));
   const long m_last = a.M - 1 - m0;
-  unsigned xo[4], wo[4];
+  unsigned xo[8], wo[2];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int r = 64 * wave + 16 * j + (lane >> 2);
+  for (int j = 0; j < 8; ++j) {
+    const int r = 64 * wave + 8 * j + (lane >> 3);
+    const unsigned swz = 16u * (unsigned)((lane & 7) ^ perm_of(8 * j + (lane >> 3)));
     xo[j] = (unsigned)(r < m_last ? r : (int)m_last) * xrow_b + swz;
-    wo[j] = (unsigned)r * wrow_b + swz;
+    if (j < 2) wo[j] = (unsigned)(lane >> 3) * wrow_b + swz;      // (the permutation repeats every 16 rows)
   }
   const char* const xg = (const char*)a.x + m0 * (long)xrow_b;
-  const char* const wg = (const char*)a.w + (long)n0 * wrow_b;
+  const char* const wg = (const char*)a.w + ((long)n0 + 64 * wave) * wrow_b;
   auto issue_part = [&](int kt, int part) __attribute__((always_inline)) {
-    char* const st = smem + (kt % NSTG) * STAGE_B;
-    const int j = part & 3;
-    char* const dst = st + (part >> 2) * TILE_B + (64 * wave + 16 * j) * ROWB;
-    if (part < 4) dma16s(xg + (long)kt * ROWB, xo[j], dst);
-    else dma16s(wg + (long)kt * ROWB, wo[j], dst);
+    char* const st = smem + (kt % NSLOT) * SLOT_B;
+    const int j = part & 7;
+    char* const dst = st + (part >> 3) * TILE_B + (64 * wave + 8 * j) * ROWB;
+    if (part < 8) dma16s(xg + (long)kt * ROWB, xo[j], dst);
+    else dma16s(wg + (long)(8 * j) * wrow_b + (long)kt * ROWB, wo[j & 1], dst);
   };
 
-  // ---- operands: block i of this wave's tokens / block j of its columns, k-step ks of a stage.
-  // Lane l reads row l % 32, chunk 2 ks + g, at position chunk ^ (row / 4 % 4).
-  const int rd0 = l31 * ROWB + 16 * (g ^ ((lane >> 2) & 3));
-  const int rd1 = rd0 ^ 32;
+  // ---- operands: block i of this wave's tokens / block j of its columns, k-step q = 0 .. 3 of a
+  // tile pair.  Lane l reads row l % 32, chunk 2 q + g, at position chunk ^ perm_of(row).
+  int rd[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) rd[q] = l31 * ROWB + 16 * ((2 * q + g) ^ perm_of(l31));
   const int xbase = wm * 128 * ROWB, wbase = TILE_B + wn * 128 * ROWB;
-  auto x_op = [&](const char* st, int ks, int i) __attribute__((always_inline)) -> bf16x8 {
-    return *(const bf16x8*)(st + xbase + 32 * i * ROWB + (ks ? rd1 : rd0));
+  auto x_op = [&](const char* st, int q, int i) __attribute__((always_inline)) -> bf16x8 {
+    return *(const bf16x8*)(st + xbase + 32 * i * ROWB + rd[q]);
   };
-  auto w_op = [&](const char* st, int ks, int j) __attribute__((always_inline)) -> bf16x8 {
-    return *(const bf16x8*)(st + wbase + 32 * j * ROWB + (ks ? rd1 : rd0));
+  auto w_op = [&](const char* st, int q, int j) __attribute__((always_inline)) -> bf16x8 {
+    return *(const bf16x8*)(st + wbase + 32 * j * ROWB + rd[q]);
   };
 
   f32x16 acc[4][4];                                  // [column block j][token block i], transposed blocks
@@ -106,49 +116,55 @@ project_bf16_kernel(ProjArgs a) {
       }
   };
 
-  // ---- pipeline
+  // ---- pipeline: pairs 0 and 1 go out whole; later, pair P + 2 goes out in two batches, the
+  // first during the last k-step of pair P (right behind the barrier that frees its slot), the
+  // second during the first k-step of pair P + 1
 #pragma unroll
-  for (int q = 0; q < NSTG - 1; ++q)
+  for (int q = 0; q < NSLOT; ++q)
     if (q < nk) {
 #pragma unroll
       for (int part = 0; part < NPART; ++part) issue_part(q, part);
     }
-  wait_vmcnt<0>();
+  if (nk > 1) wait_vmcnt<NPART>();
+  else wait_vmcnt<0>();
   wg_barrier();
-  bf16x8 x0[4], w0[4], x1[4], w1[4];                 // operands of k-step 0 / 1 of a stage
+  bf16x8 xa[4], wa[4], xb[4], wb[4];                 // operands of even / odd k-steps
 #pragma unroll
-  for (int i = 0; i < 4; ++i) { x0[i] = x_op(smem, 0, i); w0[i] = w_op(smem, 0, i); }
+  for (int i = 0; i < 4; ++i) { xa[i] = x_op(smem, 0, i); wa[i] = w_op(smem, 0, i); }
 
-  // one stage; steady: stages kt + 1 .. kt + 3 all exist (nothing to decide inside)
-  auto stage = [&](int kt, auto steady) __attribute__((always_inline)) {
-    constexpr bool STEADY = decltype(steady)::value;
-    const char* const st = smem + (kt % NSTG) * STAGE_B;
-    const char* const sn = smem + ((kt + 1) % NSTG) * STAGE_B;
-    // k-step 0; the operands of k-step 1 are fetched under it
-    mma16(x0, w0, [&](int u) __attribute__((always_inline)) {
-      if (u < 4) x1[u] = x_op(st, 1, u);
-      else if (u < 8) w1[u - 4] = w_op(st, 1, u - 4);
+  // fetches the operands of k-step q of the pair in slot st, one per matrix instruction
+  auto fetch = [&](const char* st, int q, int u, bf16x8 (&xv)[4], bf16x8 (&wv)[4]) __attribute__((always_inline)) {
+    if (u < 4) xv[u] = x_op(st, q, u);
+    else if (u < 8) wv[u - 4] = w_op(st, q, u - 4);
+  };
+  auto pair = [&](int P, auto steady, bool send2, bool send1, bool more) __attribute__((always_inline)) {
+    constexpr bool STEADY = decltype(steady)::value;   // send2, send1 and more are all true
+    const char* const st = smem + (P % NSLOT) * SLOT_B;
+    const char* const sn = smem + ((P + 1) % NSLOT) * SLOT_B;
+    mma16(xa, wa, [&](int u) __attribute__((always_inline)) {
+      fetch(st, 1, u, xb, wb);
+      if ((STEADY || send2) && u % 2 == 1) issue_part(P + 1, 8 + u / 2);
     });
-    // Stage kt + 1 (copied three stages ago) has landed once at most the copies of stage kt + 2
-    // are outstanding; behind the barrier every wave has it, and every wave is done with stage
-    // kt - 1, whose slot the copies of stage kt + 3 may now overwrite.
-    if (STEADY || kt + 2 < nk) wait_vmcnt<NPART>();
-    else wait_vmcnt<0>();
-    wg_barrier();
-    const bool more = STEADY || kt + 1 < nk;
-    mma16(x1, w1, [&](int u) __attribute__((always_inline)) {
-      if (more) {
-        if (u < 4) x0[u] = x_op(sn, 0, u);
-        else if (u < 8) w0[u - 4] = w_op(sn, 0, u - 4);
-      }
-      if (STEADY && u % 2 == 1) issue_part(kt + NSTG - 1, u / 2);
+    mma16(xb, wb, [&](int u) __attribute__((always_inline)) { fetch(st, 2, u, xa, wa); });
+    mma16(xa, wa, [&](int u) __attribute__((always_inline)) { fetch(st, 3, u, xb, wb); });
+    // Pair P + 1 has landed when none of this wave's copies is outstanding, and this wave's last
+    // reads of pair P have returned; behind the barrier that holds for every wave: pair P + 1 can
+    // be read, and the slot of pair P be overwritten.
+    if (STEADY || more) {
+      __builtin_amdgcn_s_waitcnt(0x0070);              // vmcnt(0) and lgkmcnt(0)
+      wg_barrier();
+    }
+    mma16(xb, wb, [&](int u) __attribute__((always_inline)) {
+      if (STEADY || more) fetch(sn, 0, u, xa, wa);
+      if ((STEADY || send1) && u % 2 == 1) issue_part(P + 2, u / 2);
     });
   };
-  int kt = 0;
-  for (; kt + NSTG - 1 < nk; ++kt) stage(kt, std::true_type{});
-  for (; kt < nk; ++kt) stage(kt, std::false_type{});        // the last three: nothing left to copy
+  int P = 0;
+  if (nk > 0) { pair(0, std::false_type{}, false, 2 < nk, 1 < nk); P = 1; }
+  for (; P + 2 < nk; ++P) pair(P, std::true_type{}, true, true, true);
+  for (; P < nk; ++P) pair(P, std::false_type{}, P + 1 < nk, false, P + 1 < nk);
 
-  // ---- epilogue.  Every wave has left the ring (its stages become the turn-around buffers) and
+  // ---- epilogue.  Every wave has left the ring (its slots become the turn-around buffers) and
   // the last matrix instructions have retired before their registers are read.
   wg_barrier();
 #pragma unroll

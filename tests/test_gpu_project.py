@@ -50,9 +50,10 @@ def check(x, w, outs, H, dtype, tag, rows=None):
 
 CASES = [
     # B, S, E, H, D, n_out, x_pad
-    ("one_tile_two_stages", 1, 256, 64, 2, 128, 1, 0),
-    ("one_stage", 1, 100, 32, 2, 128, 1, 0),
-    ("ragged_tokens_three_stages", 1, 300, 96, 2, 128, 2, 0),
+    ("one_tile_two_pairs", 1, 256, 128, 2, 128, 1, 0),
+    ("one_pair", 1, 100, 64, 2, 128, 1, 0),
+    ("ragged_tokens_three_pairs", 1, 300, 192, 2, 128, 2, 0),
+    ("four_pairs", 1, 260, 256, 2, 128, 1, 0),
     ("d64_batches_fold", 2, 333, 320, 4, 64, 2, 0),
     ("llama_like_kv", 1, 1000, 1024, 8, 128, 2, 0),
     ("strided_tokens", 1, 515, 256, 2, 128, 1, 64),
@@ -74,8 +75,8 @@ def test_project_f32_any_shape():
 
 def test_project_unsupported_shapes_are_refused():
     from paper_2502_02406_amd import binding as Bn
-    x = torch.zeros((1, 64, 48), dtype=torch.bfloat16, device="cuda")        # E % 32 != 0
-    w = torch.zeros((256, 48), dtype=torch.bfloat16, device="cuda")
+    x = torch.zeros((1, 64, 96), dtype=torch.bfloat16, device="cuda")        # E % 64 != 0
+    w = torch.zeros((256, 96), dtype=torch.bfloat16, device="cuda")
     out = torch.zeros((1, 2, 64, 128), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(Bn.LvxError) as e:
         Bn.lvx_xattn_project(x, w, [out])
