@@ -11,7 +11,9 @@ Sq*Skv*h*d).  Inputs are seeded, synthetic and resident in HBM before the timed 
 
 Prints ONE JSON line.  `roofline` is for the dominant kernel, timed live with HIP events on the
 stream the kernels run on; `cpu_baseline` is the fp64 oracle timed on the host cores on a bounded
-sample of the same workload.
+sample of the same workload.  `recompute` times the projections that the backward pass would
+run again under the activation recomputation of Section 3.2 (lvx_xattn_project); it is reported
+beside the attention figures and is no part of `value`.
 """
 from __future__ import annotations
 
@@ -155,6 +157,32 @@ def main():
         "merge": {"ms": ms_merge, "bytes": merge_bytes, "gbs": merge_bytes / ms_merge * 1e-6,
                   "frac_hbm": merge_bytes / ms_merge * 1e-6 / PEAK_HBM_GBS},
     }
+    # ---- the recomputation of Section 3.2 beside it (not part of `value`): K and V of one block
+    # from that block's visual tokens, and Q from the text tokens, with an embedding width of
+    # Hq * D (the width of the language model the shapes stand for) and seeded synthetic weights
+    recompute = None
+    if w.dtype == "bf16" and (w.Hq * w.D) % 64 == 0 and (w.Hkv * w.D) % 128 == 0:
+        E = w.Hq * w.D
+        pin = W.projection_inputs(w.B, blk, E, 2 * w.Hkv * w.D, w.dtype, seed)
+        y_d, wkv_d = pin["x"].cuda(), pin["w"].cuda()
+        pin = W.projection_inputs(w.B, w.Sq, E, w.Hq * w.D, w.dtype, seed + 100)
+        x_d, wq_d = pin["x"].cuda(), pin["w"].cuda()
+        del pin
+        k_re, v_re = torch.empty_like(kb, memory_format=torch.contiguous_format), torch.empty_like(kb, memory_format=torch.contiguous_format)
+        q_re = torch.empty_like(q)
+        ms_kv = timed(lambda: B.lvx_xattn_project(y_d, wkv_d, [k_re, v_re]), reps)
+        ms_q = timed(lambda: B.lvx_xattn_project(x_d, wq_d, [q_re]), reps)
+        f_kv = 2.0 * w.B * blk * E * 2 * w.Hkv * w.D
+        f_q = 2.0 * w.B * w.Sq * E * w.Hq * w.D
+        extra_ms = w.n_blocks * ms_kv + ms_q
+        recompute = {"embed": E,
+                     "kv_block": {"ms": ms_kv, "flops": f_kv, "tflops": f_kv / ms_kv * 1e-9,
+                                  "frac": f_kv / ms_kv * 1e-9 / PEAK_BF16_TFLOPS},
+                     "q": {"ms": ms_q, "flops": f_q, "tflops": f_q / ms_q * 1e-9},
+                     "ms_per_step": extra_ms, "overhead_of_step": extra_ms / (sec * 1e3),
+                     "note": "lvx_xattn_project: K and V of every block and Q made again in the backward "
+                             "pass; overhead = that time over the attention forward + backward above"}
+        del y_d, wkv_d, x_d, wq_d, k_re, v_re, q_re
     dom = max(("bwd_dkdv", "bwd_dq", "fwd"), key=lambda n: kernels[n]["ms"])
     roofline = {"bound": "mfma", "kernel": dom, "achieved": kernels[dom]["tflops"],
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
@@ -176,6 +204,8 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
     }
+    if recompute is not None:
+        out["recompute"] = recompute
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, seed)
     print(json.dumps(out))

@@ -127,6 +127,34 @@ def test_fwd_merge_errors(lib):
     assert B.lvx_xattn_workspace_bytes(p, B.LVX_BF16, B.LVX_WS_FWD_MERGE) >= 256
 
 
+def test_project_errors(lib):
+    p = B.lvx_projection()
+    p.B, p.S, p.E, p.H, p.D = 1, 100, 256, 2, 128
+    p.x_ss, p.x_sb = p.E, p.S * p.E
+    outs = (C.c_void_p * 2)(FAKE, FAKE)
+    one = (C.c_void_p * 2)(FAKE, None)
+
+    def call(pp=p, dtype=B.LVX_BF16, x=FAKE, w=FAKE, n_out=2, out=outs):
+        return lib.lvx_xattn_project(C.byref(pp) if pp is not None else None, dtype, x, w, n_out, out, None)
+
+    assert call(pp=None) == -1
+    assert call(x=None) == -1
+    assert call(out=one) == -1
+    assert call(n_out=3) == -2
+    assert call(dtype=5) == -3
+    assert call(x=FAKE + 2) == -4
+    bad = B.lvx_projection.from_buffer_copy(p); bad.S = 0
+    assert call(pp=bad) == -2
+    bad = B.lvx_projection.from_buffer_copy(p); bad.x_ss = p.E - 8
+    assert call(pp=bad) == -4
+    bad = B.lvx_projection.from_buffer_copy(p); bad.x_sb = p.S * p.E + 64     # batches must follow each other
+    assert call(pp=bad) == -4
+    bad = B.lvx_projection.from_buffer_copy(p); bad.E = 96; bad.x_ss = 96; bad.x_sb = 96 * p.S
+    assert call(pp=bad) == -7                                                 # E % 64 != 0 on the matrix cores
+    bad = B.lvx_projection.from_buffer_copy(p); bad.D = 64                    # 2 * 2 * 64 = 256 columns, heads of 64: fine shape-wise ...
+    assert call(pp=bad, n_out=1) == -7                                        # ... but one output of 128 columns is not a tile
+
+
 def test_workspace_sizes_and_strerror(lib):
     p = problem(B=1, Hq=32, Hkv=8, Sq=2048, Skv=32768)
     rows = 32 * 2048
