@@ -51,6 +51,11 @@ __device__ __forceinline__ void mfma32_acc(f32x16& acc, bf16x8 a, bf16x8 b) {
     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
 
+template <int D, int KVB> struct DkvSmem;
+// entries the step list of the STEPS variant can hold (the mask areas of the dense layout, less
+// one word for the length)
+template <int D> constexpr int dkdv_step_list_cap();
+
 template <int D, int KVB> struct DkvSmem {
   static constexpr int KN = NWV * 32 * KVB;         // keys per workgroup
   static constexpr int CPR = D / 8;                 // 16-byte chunks of data per row
@@ -67,13 +72,22 @@ template <int D, int KVB> struct DkvSmem {
   static constexpr int TOTAL = RING + BITS_BYTES + WIN_BYTES;
   static_assert(RUN >= 64, "a run must hold at least one full copy");
 };
+template <int D> constexpr int dkdv_step_list_cap() {
+  return (DkvSmem<D, 2>::BITS_BYTES + DkvSmem<D, 2>::WIN_BYTES) / 4 - 1;
+}
 
 // GENERAL = false: dense attention and Sq a multiple of 32 (no mask code, no ragged query tile, so
 // that the steady-state loop is one basic block); GENERAL = true: everything else.
-template <int D, bool GENERAL>
+// STEPS (with GENERAL = false): a media mask whose chunks are multiples of the 32 query rows of a
+// step and whose key blocks are multiples of a workgroup's 256 keys.  A step is then either
+// visible to all of a workgroup's keys or to none, so the mask only selects WHICH steps a
+// workgroup performs: the dense kernel runs over a list of them and nothing inside a step
+// changes.
+template <int D, bool GENERAL, bool STEPS = false>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 bwd_dkdv_bf16_kernel(BwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
+  static_assert(!(GENERAL && STEPS), "the step list is a variant of the dense kernel");
   constexpr int KVB = kvb_of(GENERAL);
   constexpr int XE = 16 * KVB;     // all elements of a step are converted during the contraction
                                    // (measured: no gain from moving some of them to the scoring)
@@ -113,14 +127,47 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
       });
     }
   }
+  // STEPS: the row tiles that see this workgroup's keys (the same for every head), compacted
+  // into a list by one wave; its length goes into the last word of the area.
+  constexpr int LIST_CAP = dkdv_step_list_cap<D>();
+  int* const tl = (int*)(smem + SM::RING);
+  if (STEPS) {
+    const uint8_t* const col = a.mask.allow + b * a.mask.stride_b + j_wg0 / a.mask.kv_block;
+    if (wave == 0) {
+      int count = 0;
+      for (int base = 0; base < spH; base += 64) {     // (wave-uniform trip count)
+        const int t = base + lane;
+        const bool on = t < spH && col[(long)((t * KM) / a.mask.q_chunk) * a.mask.stride_q] != 0;
+        const unsigned long long m = __ballot(on);
+        if (on) tl[count + __popcll(m & ((1ull << lane) - 1ull))] = t;
+        count += (int)__popcll(m);
+      }
+      if (lane == 0) tl[LIST_CAP] = count;
+    }
+    __syncthreads();
+    per_head = __builtin_amdgcn_readfirstlane(tl[LIST_CAP]);
+  }
   // cursor over the steps in issue order: step id s = head * spH + tile, kept with its head and
-  // first row so that no division is needed per step
-  struct Cursor { int s, h, i0; };
+  // first row so that no division is needed per step (STEPS: k = position in the list, tp = the
+  // list entry after it, fetched a step ahead so that nothing waits for it)
+  struct Cursor { int s, h, i0, k, tp; };
   auto step_needed = [&](const Cursor& c) __attribute__((always_inline)) -> bool {
     if (!GENERAL || !mk.allow) return true;
     return mask_rect(mk, b, c.i0, min(d.Sq, c.i0 + KM) - 1, j_wg0, j_wg1) != 0;
   };
   auto advance = [&](Cursor& c) __attribute__((always_inline)) {      // to the next needed step (or the end)
+    if (STEPS) {
+      int k = c.k + 1, h = c.h;
+      if (k == per_head) { k = 0; ++h; }
+      c.i0 = __builtin_amdgcn_readfirstlane(c.tp) * KM;
+      c.k = k;
+      c.h = h;
+      ++c.s;
+      int kn = k + 1;
+      if (kn == per_head) kn = 0;
+      c.tp = tl[kn];
+      return;
+    }
     if (GENERAL && have_bits) {
       int t = next_bit(bits, c.i0 / KM + 1, spH);
       if (t >= spH) { ++c.h; t = next_bit(bits, 0, spH); }
@@ -139,8 +186,13 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
       c.i0 = __builtin_amdgcn_readfirstlane(c.i0);
     }
   };
-  Cursor cursor = {0, 0, 0};
-  if (GENERAL && have_bits) {
+  Cursor cursor = {0, 0, 0, 0, 0};
+  if (STEPS) {
+    if (per_head > 0) {
+      cursor.i0 = __builtin_amdgcn_readfirstlane(tl[0]) * KM;
+      cursor.tp = tl[per_head > 1 ? 1 : 0];
+    }
+  } else if (GENERAL && have_bits) {
     const int t = next_bit(bits, 0, spH);
     cursor.i0 = t * KM;
     cursor.s = t < spH ? t : n_all;
@@ -148,6 +200,7 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
     advance(cursor);
   }
   int n = n_all;                                   // number of steps this workgroup performs
+  if (STEPS) n = G * per_head;
   if (GENERAL && mk.allow) {
     n = G * per_head;
     if (!have_bits) {
@@ -155,7 +208,7 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
       for (Cursor c = cursor; c.s < n_all; advance(c)) ++n;
     }
   }
-  if (GENERAL && n == 0) {                         // keys that no query sees: dK = dV = 0, nothing to read
+  if ((GENERAL || STEPS) && n == 0) {              // keys that no query sees: dK = dV = 0, nothing to read
     const u32x4 z = {0, 0, 0, 0};
     for (int c = tid; c < KN * CPR; c += 256) {
       const int j = j_wg0 + c / CPR, col = (c % CPR) * 8;
@@ -546,14 +599,14 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   }
 }
 
-template <int D, bool GENERAL>
+template <int D, bool GENERAL, bool STEPS = false>
 hipError_t launch(const BwdArgs& a, hipStream_t s) {
   const long grid = xcd_grid(a.d.B * a.d.Hkv, (a.d.Skv + DkvSmem<D, kvb_of(GENERAL)>::KN - 1) / DkvSmem<D, kvb_of(GENERAL)>::KN);
   static SmemOnce once;
   using SM = DkvSmem<D, kvb_of(GENERAL)>;
-  hipError_t e = ensure_dynamic_lds((const void*)bwd_dkdv_bf16_kernel<D, GENERAL>, SM::TOTAL, &once);
+  hipError_t e = ensure_dynamic_lds((const void*)bwd_dkdv_bf16_kernel<D, GENERAL, STEPS>, SM::TOTAL, &once);
   if (e != hipSuccess) return e;
-  bwd_dkdv_bf16_kernel<D, GENERAL><<<(unsigned)grid, 256, SM::TOTAL, s>>>(a);
+  bwd_dkdv_bf16_kernel<D, GENERAL, STEPS><<<(unsigned)grid, 256, SM::TOTAL, s>>>(a);
   return hipGetLastError();
 }
 
@@ -561,6 +614,12 @@ hipError_t launch(const BwdArgs& a, hipStream_t s) {
 
 hipError_t launch_bwd_dkdv_bf16(const BwdArgs& a, hipStream_t s) {
   const Dims& d = a.d;
+  // a mask that only selects whole steps for whole workgroups runs on the dense kernel
+  const bool steps = a.mask.allow != nullptr && d.Sq % KM == 0 && a.mask.q_chunk % KM == 0 &&
+                     a.mask.kv_block % DkvSmem<128, 2>::KN == 0 && d.Sq / KM <= dkdv_step_list_cap<128>();
+  static_assert(DkvSmem<64, 2>::KN == DkvSmem<128, 2>::KN && dkdv_step_list_cap<64>() == dkdv_step_list_cap<128>(),
+                "the test above is the same for both head dims");
+  if (steps) return d.D == 64 ? launch<64, false, true>(a, s) : launch<128, false, true>(a, s);
   const bool general = a.mask.allow != nullptr || d.Sq % KM != 0;
   if (d.D == 64) return general ? launch<64, true>(a, s) : launch<64, false>(a, s);
   return general ? launch<128, true>(a, s) : launch<128, false>(a, s);

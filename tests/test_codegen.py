@@ -41,7 +41,8 @@ def _blocks(body):
 
 
 @pytest.mark.parametrize("src,kernel,loop_mfma", [
-    ("lvx_bwd_dkdv_bf16.hip", "bwd_dkdv_bf16_kernelILi128ELb0E", 128),   # two steps of 64 per trip
+    ("lvx_bwd_dkdv_bf16.hip", "bwd_dkdv_bf16_kernelILi128ELb0ELb0E", 128),   # two steps of 64 per trip
+    ("lvx_bwd_dkdv_bf16.hip", "bwd_dkdv_bf16_kernelILi128ELb0ELb1E", 128),   # the same loop over a list of steps
     ("lvx_bwd_dq_bf16.hip", "bwd_dq_bf16_kernelILi128ELb0E", 96),        # one tile = two halves of 48
 ])
 def test_dense_loop_moves_no_accumulator(src, kernel, loop_mfma):
@@ -58,12 +59,12 @@ def test_dense_loop_moves_no_accumulator(src, kernel, loop_mfma):
 
 def test_general_dkdv_leaves_half_the_accumulation_file():
     asm = _asm("lvx_bwd_dkdv_bf16.hip")
-    body = _kernel(asm, "bwd_dkdv_bf16_kernelILi128ELb1E")
+    body = _kernel(asm, "bwd_dkdv_bf16_kernelILi128ELb1ELb0E")
     for blk in _blocks(body):
         if "v_mfma_f32_32x32x16_bf16" in blk:
             assert "v_accvgpr" not in blk, "accumulator moved next to matrix instructions"
     # kernel metadata: ".agpr_count: N" precedes the ".name:" entry of its kernel
-    m = re.search(r"\.agpr_count:\s*(\d+)\n(?:(?!\.agpr_count).*\n)*?\s*\.name:\s*\S*bwd_dkdv_bf16_kernelILi128ELb1E", asm)
+    m = re.search(r"\.agpr_count:\s*(\d+)\n(?:(?!\.agpr_count).*\n)*?\s*\.name:\s*\S*bwd_dkdv_bf16_kernelILi128ELb1ELb0E", asm)
     assert m and int(m.group(1)) <= 128
 
 

@@ -171,6 +171,22 @@ def test_random_media_masks(name, kw, per_batch, p_on):
     run_case(w, do_bwd=True, allow=(rng.random(shape) < p_on))
 
 
+@pytest.mark.parametrize("name,kw,per_batch,p_on", [
+    ("bf16_stepmask_gqa", dict(B=2, Hq=8, Hkv=2, Sq=256, Skv=2048, q_chunk=32, kv_block=256), True, 0.4),
+    ("bf16_stepmask_d64_ragged_keys", dict(D=64, Hq=4, Hkv=2, Sq=192, Skv=1900, q_chunk=64, kv_block=512), False, 0.5),
+    ("bf16_stepmask_single_steps", dict(Hq=2, Sq=320, Skv=1536, q_chunk=32, kv_block=256), False, 0.12),
+])
+def test_step_aligned_media_masks(name, kw, per_batch, p_on):
+    # chunks that are multiples of 32 rows and key blocks that are multiples of 256 keys: the
+    # dK/dV kernel then runs its dense loop over a list of visible steps (several heads per
+    # group walk the list again; lists of one entry; key blocks nobody sees; a ragged last block)
+    w = small(name, **kw)
+    rng = np.random.Generator(np.random.Philox(4321 + len(name)))
+    nq, nk = -(-w.Sq // w.q_chunk), -(-w.Skv // w.kv_block)
+    shape = (w.B, nq, nk) if per_batch else (nq, nk)
+    run_case(w, do_bwd=True, allow=(rng.random(shape) < p_on))
+
+
 def test_masked_rows_without_keys():
     # block-causal mask whose first chunks see nothing inside the second K/V block
     w = small("bf16_blockcausal_blocks", B=1, Hq=2, Sq=128, Skv=1024, q_chunk=32, kv_block=256,
