@@ -13,7 +13,8 @@ Prints ONE JSON line.  `roofline` is for the dominant kernel, timed live with HI
 stream the kernels run on; `cpu_baseline` is the fp64 oracle timed on the host cores on a bounded
 sample of the same workload.  `recompute` times the projections that the backward pass would
 run again under the activation recomputation of Section 3.2 (lvx_xattn_project); it is reported
-beside the attention figures and is no part of `value`.
+beside the attention figures and is no part of `value`; `model` is the paper's per-round runtime
+model (Section 3.1) evaluated with the measured forward visit.
 """
 from __future__ import annotations
 
@@ -206,6 +207,14 @@ def main():
     }
     if recompute is not None:
         out["recompute"] = recompute
+    # ---- Section 3.1's runtime model fed with the measured visit: what a forward round would take
+    # with the transfers of LV-XAttn (Q, running O, L) or of Ring Attention (K, V) on one link
+    from dataclasses import asdict
+    from paper_2502_02406_amd import runtime_model as RM
+    out["model"] = {"f_ms": ms_fwd, "note": "per-round max(f, comm) of Equations 2 and 3 with the measured forward visit; "
+                                            "one xGMI link, and the paper's two slower interconnects",
+                    "rounds": [asdict(RM.predict_forward_round(ms_fwd, w.Sq, blk, w.D, w.Hq, w.Hkv, name, gbs))
+                               for name, gbs in (("xgmi_link", 153.0), ("net_25GBs", 25.0), ("net_1.25GBs", 1.25))]}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, seed)
     print(json.dumps(out))
