@@ -99,9 +99,12 @@ size_t fwd_merge_ws(const Dims& d, lvx_dtype dtype, int n_split) {
   return fwd_ws(d, dtype == LVX_F32 ? 2 : n_split);      // (fwd_ws(d, 2) holds more than one partial result)
 }
 int sq_padded(const Dims& d) { return (d.Sq + 31) / 32 * 32; }
+bool has_stats_ovl(const Dims& d) { return d.Sq % 32 != 0 && d.Sq >= 32; }
+size_t stats_floats(const Dims& d) { return 2 * (size_t)d.B * d.Hq * sq_padded(d); }
 size_t bwd_ws_fixed(const Dims& d) {   // delta [B,Hq,Sq] + padded statistics [B,Hq,sq_pad/32][2][32]
+                                       // (+ those of the last 32 rows, [B,Hq][2][32], when Sq is ragged)
   return align_up((size_t)d.B * d.Hq * d.Sq * sizeof(float)) +
-         align_up(2 * (size_t)d.B * d.Hq * sq_padded(d) * sizeof(float));
+         align_up((stats_floats(d) + (has_stats_ovl(d) ? (size_t)d.B * d.Hq * 64 : 0)) * sizeof(float));
 }
 size_t bwd_ws(const Dims& d, int n_split) {   // ... + the dQ kernel's partial sums [n_split, B,Hq,Sq,D] when it splits
   const size_t part = n_split > 1 ? align_up((size_t)n_split * d.B * d.Hq * d.Sq * d.D * sizeof(float)) : 0;
@@ -285,11 +288,12 @@ lvx_status lvx_xattn_bwd_stages(const lvx_problem* p, lvx_dtype dtype, const voi
   a.delta = (float*)workspace;
   a.sq_pad = sq_padded(a.d);
   a.stats = (float*)((char*)workspace + align_up((size_t)a.d.B * a.d.Hq * a.d.Sq * sizeof(float)));
+  a.stats_ovl = has_stats_ovl(a.d) ? a.stats + stats_floats(a.d) : nullptr;
   a.dq_accum = dq_accum; a.dk = dk; a.dv = dv;
   a.dq_part = a.n_split_dq > 1 ? (float*)((char*)workspace + bwd_ws_fixed(a.d)) : nullptr;
   hipStream_t s = (hipStream_t)hip_stream;
   hipError_t e = hipSuccess;
-  if (stages & LVX_BWD_DELTA) e = launch_delta(a.d, o, d_o, dtype == LVX_F32, lse, a.delta, a.stats, a.sq_pad, s);
+  if (stages & LVX_BWD_DELTA) e = launch_delta(a.d, o, d_o, dtype == LVX_F32, lse, a.delta, a.stats, a.sq_pad, a.stats_ovl, s);
   if (e != hipSuccess) return LVX_ERR_HIP;
   if (stages & (LVX_BWD_DKDV | LVX_BWD_DQ))
     e = dtype == LVX_BF16 ? launch_bwd_bf16(a, stages, s) : launch_bwd_f32(a, stages, s);

@@ -76,8 +76,10 @@ template <int D> constexpr int dkdv_step_list_cap() {
   return (DkvSmem<D, 2>::BITS_BYTES + DkvSmem<D, 2>::WIN_BYTES) / 4 - 1;
 }
 
-// GENERAL = false: dense attention and Sq a multiple of 32 (no mask code, no ragged query tile, so
-// that the steady-state loop is one basic block); GENERAL = true: everything else.
+// GENERAL = false: dense attention (no mask code, so that the steady-state loop is one basic
+// block; when Sq is no multiple of 32, the last step of a head takes rows Sq-32 .. Sq-1 with the
+// statistics of BwdArgs::stats_ovl instead of a short tile -- Sq >= 32 then); GENERAL = true:
+// everything else.
 // STEPS (with GENERAL = false): a media mask whose chunks are multiples of the 32 query rows of a
 // step and whose key blocks are multiples of a workgroup's 256 keys.  A step is then either
 // visible to all of a workgroup's keys or to none, so the mask only selects WHICH steps a
@@ -284,11 +286,21 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
     // from bitmap words read through the vector path)
     const int hq = __builtin_amdgcn_readfirstlane(hk * G + c.h), i0 = __builtin_amdgcn_readfirstlane(c.i0);
     Tile t;
-    t.tile = ((long)hq * d.q_sh + (long)i0 * d.q_ss) * 2;
+    t.rows = min(KM, d.Sq - i0);
+    // the dense kernel's short last step takes rows Sq-32 .. Sq-1 and their own statistics
+    // (selected by arithmetic: a branch here would cut the steady-state loop into pieces)
+    const int i0_eff = GENERAL ? i0 : min(i0, d.Sq - KM);
+    t.tile = ((long)hq * d.q_sh + (long)i0_eff * d.q_ss) * 2;
     t.qb = q0 + t.tile + (long)wave * row_bytes;   // this wave's first row: tile row w
     t.gb = g0 + t.tile + (long)wave * row_bytes;
-    t.lb = l0 + ((long)hq * a.sq_pad + i0) * 8;
-    t.rows = min(KM, d.Sq - i0);
+    const long lb_std = (long)(uintptr_t)l0 + ((long)hq * a.sq_pad + i0) * 8;
+    if (GENERAL) {
+      t.lb = (const char*)(uintptr_t)lb_std;
+    } else {
+      const long lb_ovl = (long)(uintptr_t)a.stats_ovl + ((long)b * d.Hq + hq) * 256;
+      const long pick = -(long)(i0 != i0_eff);     // all ones for the short step
+      t.lb = (const char*)(uintptr_t)(lb_std + ((lb_ovl - lb_std) & pick));
+    }
     t.dst = st;
     return t;
   };
@@ -615,12 +627,13 @@ hipError_t launch(const BwdArgs& a, hipStream_t s) {
 hipError_t launch_bwd_dkdv_bf16(const BwdArgs& a, hipStream_t s) {
   const Dims& d = a.d;
   // a mask that only selects whole steps for whole workgroups runs on the dense kernel
-  const bool steps = a.mask.allow != nullptr && d.Sq % KM == 0 && a.mask.q_chunk % KM == 0 &&
-                     a.mask.kv_block % DkvSmem<128, 2>::KN == 0 && d.Sq / KM <= dkdv_step_list_cap<128>();
+  const bool rows_ok = d.Sq % KM == 0 || d.Sq >= KM;           // (a ragged Sq needs 32 rows to overlap)
+  const bool steps = a.mask.allow != nullptr && rows_ok && a.mask.q_chunk % KM == 0 &&
+                     a.mask.kv_block % DkvSmem<128, 2>::KN == 0 && (d.Sq + KM - 1) / KM <= dkdv_step_list_cap<128>();
   static_assert(DkvSmem<64, 2>::KN == DkvSmem<128, 2>::KN && dkdv_step_list_cap<64>() == dkdv_step_list_cap<128>(),
                 "the test above is the same for both head dims");
   if (steps) return d.D == 64 ? launch<64, false, true>(a, s) : launch<128, false, true>(a, s);
-  const bool general = a.mask.allow != nullptr || d.Sq % KM != 0;
+  const bool general = a.mask.allow != nullptr || !rows_ok;
   if (d.D == 64) return general ? launch<64, true>(a, s) : launch<64, false>(a, s);
   return general ? launch<128, true>(a, s) : launch<128, false>(a, s);
 }

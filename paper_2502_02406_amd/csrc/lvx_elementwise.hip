@@ -106,10 +106,12 @@ hipError_t launch_merge(const MergeArgs& a, int part_is_f32, int out_is_f32, hip
 // well: stats[B,Hq,sq_pad/32][2][32] (sq_pad a multiple of 32) holds, per group of 32 rows, 32
 // values of -L * log2(e) -- -inf for rows without keys and for pad rows, which makes their
 // probabilities exp2(-inf) = 0 -- followed by the 32 values of -delta (0 in pad rows).
+// stats_ovl (optional, [B,Hq][2][32]): the same for rows Sq-32 .. Sq-1, with -inf for those of them
+// that belong to a full group of 32.
 template <bool F32>
 __global__ void __launch_bounds__(256) delta_kernel(Dims d, const void* o, const void* d_o,
                                                     const float* lse, float* delta, float* stats,
-                                                    int sq_pad) {
+                                                    int sq_pad, float* stats_ovl) {
   const long rows = (long)d.B * d.Hq * sq_pad;
   const long rowp = ((long)blockIdx.x * 256 + threadIdx.x) / 16;
   const int c = threadIdx.x % 16;
@@ -148,14 +150,19 @@ __global__ void __launch_bounds__(256) delta_kernel(Dims d, const void* o, const
   const long slot = (rowp / 32) * 64 + rowp % 32;     // sq_pad is a multiple of 32
   stats[slot] = nl2;
   stats[slot + 32] = -s;
+  if (stats_ovl && i >= d.Sq - 32 && i < d.Sq) {
+    const long j = (b * d.Hq + h) * 64 + (i - (d.Sq - 32));
+    stats_ovl[j] = i >= (d.Sq & ~31) ? nl2 : -INFINITY;
+    stats_ovl[j + 32] = -s;
+  }
 }
 
 hipError_t launch_delta(const Dims& d, const void* o, const void* d_o, int is_f32, const float* lse,
-                        float* delta, float* stats, int sq_pad, hipStream_t s) {
+                        float* delta, float* stats, int sq_pad, float* stats_ovl, hipStream_t s) {
   const long rows = (long)d.B * d.Hq * sq_pad;
   const unsigned blocks = (unsigned)((rows * 16 + 255) / 256);
-  if (is_f32) delta_kernel<true><<<blocks, 256, 0, s>>>(d, o, d_o, lse, delta, stats, sq_pad);
-  else delta_kernel<false><<<blocks, 256, 0, s>>>(d, o, d_o, lse, delta, stats, sq_pad);
+  if (is_f32) delta_kernel<true><<<blocks, 256, 0, s>>>(d, o, d_o, lse, delta, stats, sq_pad, stats_ovl);
+  else delta_kernel<false><<<blocks, 256, 0, s>>>(d, o, d_o, lse, delta, stats, sq_pad, stats_ovl);
   return hipGetLastError();
 }
 

@@ -44,6 +44,11 @@ struct BwdArgs {
   float* stats;         // workspace, [B,Hq,sq_pad/32][2][32]: per group of 32 query rows, 32 values of
                         // -L * log2(e) (-inf for rows without keys and pad rows), then 32 of -delta
   int sq_pad;           // Sq rounded up to a multiple of 32
+  float* stats_ovl;     // workspace, [B,Hq][2][32], only when Sq % 32 != 0 and Sq >= 32 (else nullptr): the
+                        // same two rows of 32 values for the query rows Sq-32 .. Sq-1, with -inf in place of
+                        // -L * log2(e) for the rows that the last full group already covers.  A kernel that
+                        // walks the rows 32 at a time takes rows Sq-32 .. Sq-1 as its last step instead of a
+                        // short one: the rows it has seen before then contribute nothing.
   float* dq_accum;      // [B,Hq,Sq,D] float32, accumulated into
   void *dk, *dv;        // K's strides, input dtype, overwritten
   int n_split_dq;       // KV splits of the dQ kernel
@@ -105,7 +110,7 @@ int bwd_bf16_pick_split(const Dims& d, int n_cu, bool masked);
 // memory-bound helpers
 hipError_t launch_merge(const MergeArgs& a, int part_is_f32, int out_is_f32, hipStream_t s);
 hipError_t launch_delta(const Dims& d, const void* o, const void* d_o, int is_f32, const float* lse,
-                        float* delta, float* stats, int sq_pad, hipStream_t s);
+                        float* delta, float* stats, int sq_pad, float* stats_ovl, hipStream_t s);
 // dq_accum[i] += sum over the n_parts slices of `parts` (each n floats, n a multiple of 4)
 hipError_t launch_dq_reduce(const float* parts, int n_parts, long n, float* dq_accum, hipStream_t s);
 hipError_t launch_dq_finalize(const Dims& d, const float* dq_accum, void* dq, int is_f32,

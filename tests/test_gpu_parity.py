@@ -129,6 +129,9 @@ FWD_BWD_CASES = [
     small("bf16_blockcausal_frames", Sq=512, Skv=16384, q_chunk=32, kv_block=1024),
     small("bf16_mask_unaligned_d64", D=64, Hq=4, Sq=300, Skv=3000, q_chunk=50, kv_block=700),
     small("bf16_mask_many_chunks", Sq=256, Skv=1024, q_chunk=4, kv_block=64),   # 64 chunks per workgroup
+    # text lengths are arbitrary: a last query tile of 13 rows per head, several heads per group
+    small("bf16_ragged_rows_gqa_d64", D=64, Hq=8, Hkv=2, Sq=77, Skv=640, n_blocks=2),
+    small("bf16_ragged_rows_one_short_tile", Hq=2, Sq=3, Skv=512),
 ]
 
 
@@ -175,6 +178,7 @@ def test_random_media_masks(name, kw, per_batch, p_on):
     ("bf16_stepmask_gqa", dict(B=2, Hq=8, Hkv=2, Sq=256, Skv=2048, q_chunk=32, kv_block=256), True, 0.4),
     ("bf16_stepmask_d64_ragged_keys", dict(D=64, Hq=4, Hkv=2, Sq=192, Skv=1900, q_chunk=64, kv_block=512), False, 0.5),
     ("bf16_stepmask_single_steps", dict(Hq=2, Sq=320, Skv=1536, q_chunk=32, kv_block=256), False, 0.12),
+    ("bf16_stepmask_ragged_rows", dict(Hq=4, Hkv=2, Sq=200, Skv=1024, q_chunk=32, kv_block=256), False, 0.6),
 ])
 def test_step_aligned_media_masks(name, kw, per_batch, p_on):
     # chunks that are multiples of 32 rows and key blocks that are multiples of 256 keys: the
