@@ -542,18 +542,43 @@ int bwd_bf16_pick_split(const Dims& d, int n_cu, bool masked) {
   return (int)want;
 }
 
-hipError_t launch_bwd_dq_bf16(const BwdArgs& a, hipStream_t s) {
+namespace {
+
+hipError_t launch_one(const BwdArgs& a, bool general, hipStream_t s) {
   const Dims& d = a.d;
   const int G = d.Hq / d.Hkv;
   const int n_qt = (d.Sq + QM - 1) / QM;
   const long grid = xcd_grid(d.B * d.Hkv, a.n_split_dq * G * n_qt);
-  const bool general = a.mask.allow != nullptr || d.Skv % TN != 0;
   hipError_t e;
   if (d.D == 64) e = general ? launch<64, true>(a, grid, s) : launch<64, false>(a, grid, s);
   else e = general ? launch<128, true>(a, grid, s) : launch<128, false>(a, grid, s);
   if (e == hipSuccess && a.n_split_dq > 1)
     e = launch_dq_reduce(a.dq_part, a.n_split_dq, (long)d.B * d.Hq * d.Sq * d.D, a.dq_accum, s);
   return e;
+}
+
+}  // namespace
+
+hipError_t launch_bwd_dq_bf16(const BwdArgs& a, hipStream_t s) {
+  const Dims& d = a.d;
+  if (a.mask.allow != nullptr) return launch_one(a, true, s);
+  const int tail = d.Skv % TN;
+  if (tail == 0) return launch_one(a, false, s);
+  if (d.Skv < 2 * TN) return launch_one(a, true, s);
+  // A key count that is no multiple of the tile: the dense kernel takes the whole tiles, the
+  // general one the few keys that are left; dQ is a sum over keys, and both add into dq_accum
+  // one after the other on the stream.
+  BwdArgs head = a;
+  head.d.Skv = d.Skv - tail;
+  hipError_t e = launch_one(head, false, s);
+  if (e != hipSuccess) return e;
+  BwdArgs rest = a;
+  rest.k = (const uint16_t*)a.k + (long)head.d.Skv * d.kv_ss;
+  rest.v = (const uint16_t*)a.v + (long)head.d.Skv * d.kv_ss;
+  rest.d.Skv = tail;
+  rest.n_split_dq = 1;
+  rest.dq_part = nullptr;
+  return launch_one(rest, true, s);
 }
 
 hipError_t launch_bwd_bf16(const BwdArgs& a, unsigned stages, hipStream_t s) {
