@@ -133,9 +133,12 @@ const char* lvx_strerror(lvx_status s) {
 size_t lvx_xattn_workspace_bytes(const lvx_problem* p, lvx_dtype dtype, int which) {
   if (check_problem(p, dtype) != LVX_OK) return 0;
   const Dims d = make_dims(p);
-  if (which == LVX_WS_FWD) return fwd_ws(d, fwd_split(d, dtype, true));   // a masked call splits at least as much
-  if (which == LVX_WS_BWD) return bwd_ws(d, bwd_split(d, dtype, true));   // a masked call splits at least as much
-  if (which == LVX_WS_FWD_MERGE) return fwd_merge_ws(d, dtype, fwd_merge_split(d, dtype, true));
+  // (the size does not depend on whether the call will carry a mask: the larger of the two split counts)
+  const auto larger = [](int x, int y) { return x > y ? x : y; };
+  if (which == LVX_WS_FWD) return fwd_ws(d, larger(fwd_split(d, dtype, true), fwd_split(d, dtype, false)));
+  if (which == LVX_WS_BWD) return bwd_ws(d, larger(bwd_split(d, dtype, true), bwd_split(d, dtype, false)));
+  if (which == LVX_WS_FWD_MERGE)
+    return fwd_merge_ws(d, dtype, larger(fwd_merge_split(d, dtype, true), fwd_merge_split(d, dtype, false)));
   return 0;
 }
 

@@ -471,10 +471,17 @@ int fwd_bf16_pick_split(const Dims& d, int n_cu, bool masked) {
   // key tiles evenly), so four times as many workgroups are made to even the load out.
   const long base = (long)d.B * d.Hq * ((d.Sq + QM - 1) / QM);
   const int n_tiles = (d.Skv + TN - 1) / TN;
-  long want = ((masked ? 4L : 1L) * n_cu + base - 1) / base;
-  if (want < 1) want = 1;
   long cap = n_tiles / 16;                // keep at least 16 tiles (1024 keys) per split
   if (cap < 1) cap = 1;
+  if (!masked) {
+    // about 4.5 TFLOP/s per compute unit in this kernel; partial results are float32 rows written
+    // once and read once at about 3 TB/s
+    const double t_full = 4.0 * QM * (double)d.Skv * d.D / 4.5e12;
+    const double t_part = 2.0 * (double)d.B * d.Hq * d.Sq * d.D * 4.0 / 3e12;
+    return pick_split_balanced(base, n_cu, cap, t_full, t_part);
+  }
+  long want = (4L * n_cu + base - 1) / base;
+  if (want < 1) want = 1;
   if (want > cap) want = cap;
   if (want > 64) want = 64;
   return (int)want;

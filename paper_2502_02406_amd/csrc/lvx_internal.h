@@ -104,6 +104,25 @@ inline hipError_t ensure_dynamic_lds(const void* kernel, int bytes, SmemOnce* on
   return e;
 }
 
+// Number of KV splits for `base` workgroups that each walk the whole key range on n_cu compute
+// units: the count (at most cap) that minimises rounds * t_full / splits + splits * t_part, where
+// rounds = ceil(base * splits / n_cu), t_full is one workgroup's time over the whole range and
+// t_part what one more set of partial results costs (written, read again and summed).  Covers
+// both a grid smaller than the chip and one slightly larger than a multiple of it (288
+// workgroups on 256 units would take two rounds for the work of 1.125).
+inline int pick_split_balanced(long base, int n_cu, long cap, double t_full, double t_part) {
+  int best = 1;
+  double best_t = 1e300;
+  for (long s = 1; s <= cap && s <= 64; ++s) {
+    const long rounds = (base * s + n_cu - 1) / n_cu;
+    const double t = (double)rounds * t_full / (double)s + (s > 1 ? (double)s * t_part + 10e-6 : 0.0);
+    if (t < best_t * 0.97) {                       // more splits only for a gain of 3 %
+      best_t = t;
+      best = (int)s;
+    }
+  }
+  return best;
+}
 int fwd_bf16_pick_split(const Dims& d, int n_cu, bool masked);
 hipError_t launch_fwd_general_bf16(const FwdArgs& a, hipStream_t s);   // masked or ragged problems
 int bwd_bf16_pick_split(const Dims& d, int n_cu, bool masked);
