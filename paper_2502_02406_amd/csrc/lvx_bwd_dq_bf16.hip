@@ -44,17 +44,24 @@ bwd_dq_bf16_kernel(BwdArgs a) {
 
   const Dims& d = a.d;
   const int G = d.Hq / d.Hkv;
-  const int n_qt = (d.Sq + QM - 1) / QM;
+  // Dense variant (PACK): the query rows of the G heads that share a K/V head are one list of
+  // G * Sq rows (row r = head r / Sq of the group, its row r % Sq), cut into tiles of 256, so that
+  // short query blocks fill tiles instead of leaving one mostly empty tile per head.  The general
+  // variant tiles each head's rows (its mask code works on rows of one head).
+  constexpr bool PACK = !GENERAL;
+  const int rows_lim = PACK ? G * d.Sq : d.Sq;      // rows of the list this workgroup's tiles are cut from
+  const int n_qt = (rows_lim + QM - 1) / QM;
+  const int per_split = PACK ? n_qt : G * n_qt;
   HeadWork hw;
-  if (!xcd_decode(blockIdx.x, d.B * d.Hkv, a.n_split_dq * G * n_qt, &hw)) return;
+  if (!xcd_decode(blockIdx.x, d.B * d.Hkv, a.n_split_dq * per_split, &hw)) return;
   const int b = hw.head / d.Hkv, hk = hw.head % d.Hkv;
-  const int split = hw.item / (G * n_qt);
-  const int hq = hk * G + (hw.item % (G * n_qt)) / n_qt;
+  const int split = hw.item / per_split;
+  const int hq = hk * G + (PACK ? 0 : (hw.item % per_split) / n_qt);   // PACK: the first head of the group
   const int qt = hw.item % n_qt;
 
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ql = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int i_wave0 = qt * QM + wave * 32 * QB;     // first query row of this wave
+  const int i_wave0 = qt * QM + wave * 32 * QB;     // first row (of the head, or of the group's list) of this wave
 
   // KV range of this split, in tiles
   const int n_tiles = (d.Skv + TN - 1) / TN;
@@ -73,9 +80,10 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   float nl2[QB], nd[QB];               // -L log2(e) (-inf: no probability mass) and -delta
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
-    const int i = i_wave0 + 32 * qb + ql;
-    const bool ok = i < d.Sq;
-    const long off = b * d.q_sb + hq * d.q_sh + (long)i * d.q_ss;
+    const int r = i_wave0 + 32 * qb + ql;
+    const bool ok = r < rows_lim;
+    const int hq_l = PACK ? hq + r / d.Sq : hq, i = PACK ? r % d.Sq : r;
+    const long off = b * d.q_sb + hq_l * d.q_sh + (long)i * d.q_ss;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       u32x4 x = {0, 0, 0, 0}, y = {0, 0, 0, 0};
@@ -94,7 +102,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
     nl2[qb] = -INFINITY;
     nd[qb] = 0.f;
     if (ok) {
-      const long slot = (((long)b * d.Hq + hq) * a.sq_pad + (i & ~31)) * 2 + (i & 31);
+      const long slot = (((long)b * d.Hq + hq_l) * a.sq_pad + (i & ~31)) * 2 + (i & 31);
       nl2[qb] = a.stats[slot];
       nd[qb] = a.stats[slot + 32];
     }
@@ -507,9 +515,11 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   const bool whole = a.n_split_dq == 1;            // else: this split's own slice of the partial sums
   float* const out0 = (whole ? a.dq_accum : a.dq_part + (long)split * d.B * d.Hq * d.Sq * D) +
                       (((long)b * d.Hq + hq) * d.Sq) * D;
+  // (dq_accum and the partial sums are contiguous [B,Hq,Sq,D]: row i of the group's list is row i
+  // past the first row of the group's first head)
   for (int r0 = 0; r0 < 32 * QB; r0 += RPI) {
     const int r = r0 + rsub, i = i_wave0 + r;
-    if (i >= d.Sq) continue;
+    if (i >= rows_lim) continue;
     f32x4 y = *(const f32x4*)(tbuf + r * RP + col * 4);
     float* const out = out0 + (long)i * D + col;
     if (whole) y += *(const f32x4*)out;
@@ -531,7 +541,10 @@ hipError_t launch(const BwdArgs& a, long grid, hipStream_t s) {
 int bwd_bf16_pick_split(const Dims& d, int n_cu, bool masked) {
   // one workgroup per CU; split the KV axis until the grid covers the chip (four times as many
   // workgroups with a media mask, whose visible work differs from one query tile to the next)
-  const long base = (long)d.B * d.Hq * ((d.Sq + QM - 1) / QM);
+  // (the dense kernel tiles the rows of a whole group of query heads, the general one each head's)
+  const bool dense = !masked && (d.Skv % TN == 0 || d.Skv >= 2 * TN);
+  const long base = dense ? (long)d.B * d.Hkv * (((long)(d.Hq / d.Hkv) * d.Sq + QM - 1) / QM)
+                          : (long)d.B * d.Hq * ((d.Sq + QM - 1) / QM);
   const int n_tiles = (d.Skv + TN - 1) / TN;
   long cap = n_tiles / 16;                // keep at least 16 tiles (1024 keys) per split
   if (cap < 1) cap = 1;
@@ -554,8 +567,8 @@ namespace {
 hipError_t launch_one(const BwdArgs& a, bool general, hipStream_t s) {
   const Dims& d = a.d;
   const int G = d.Hq / d.Hkv;
-  const int n_qt = (d.Sq + QM - 1) / QM;
-  const long grid = xcd_grid(d.B * d.Hkv, a.n_split_dq * G * n_qt);
+  const long per_split = general ? (long)G * ((d.Sq + QM - 1) / QM) : ((long)G * d.Sq + QM - 1) / QM;
+  const long grid = xcd_grid(d.B * d.Hkv, (int)(a.n_split_dq * per_split));
   hipError_t e;
   if (d.D == 64) e = general ? launch<64, true>(a, grid, s) : launch<64, false>(a, grid, s);
   else e = general ? launch<128, true>(a, grid, s) : launch<128, false>(a, grid, s);

@@ -1,7 +1,8 @@
 // bf16 forward kernel: the FlashAttention call of Algorithm 1 for a short query block against a
 // long local K/V block, on the gfx950 matrix cores.
 //
-// Workgroup = 4 wavefronts = 256 query rows of one (batch, query head), one wave per SIMD with
+// Workgroup = 4 wavefronts = 256 query rows of one (batch, K/V head) -- the rows of its group of
+// query heads, one after the other -- one wave per SIMD with
 // the whole register file.  A wave owns 64 query rows (two 32-row blocks): their Q operands and
 // the O^T accumulators live in the accumulation registers for the whole kernel, so every K or V
 // operand fetched from LDS feeds two matrix instructions.
@@ -52,17 +53,21 @@ fwd_bf16_kernel(FwdArgs a) {
 
   const Dims& d = a.d;
   const int G = d.Hq / d.Hkv;
-  const int n_qt = (d.Sq + QM - 1) / QM;
+  // The query rows of the G heads that share a K/V head are one list of G * Sq rows (row r = head
+  // r / Sq of the group, its row r % Sq), cut into tiles of 256: short query blocks -- one
+  // worker's share of the text, or a single token -- then fill tiles instead of leaving one
+  // mostly empty tile per head, and every K/V tile fetched serves all heads of the group.
+  const int rows_kv = G * d.Sq;
+  const int n_qt = (rows_kv + QM - 1) / QM;
   HeadWork hw;
-  if (!xcd_decode(blockIdx.x, d.B * d.Hkv, a.n_split * G * n_qt, &hw)) return;
+  if (!xcd_decode(blockIdx.x, d.B * d.Hkv, a.n_split * n_qt, &hw)) return;
   const int b = hw.head / d.Hkv, hk = hw.head % d.Hkv;
-  const int split = hw.item / (G * n_qt);
-  const int hq = hk * G + (hw.item % (G * n_qt)) / n_qt;
+  const int split = hw.item / n_qt;
   const int qt = hw.item % n_qt;
 
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ql = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int i_wave0 = qt * QM + wave * 32 * QB;     // first query row of this wave
+  const int r_wave0 = qt * QM + wave * 32 * QB;     // first row (of the group's list) of this wave
 
   // KV range of this split, in tiles
   const int n_tiles = (d.Skv + TN - 1) / TN;
@@ -70,17 +75,18 @@ fwd_bf16_kernel(FwdArgs a) {
   const int t_begin = split * tps;
   const int t_end = min(n_tiles, t_begin + tps);
 
-  // ---- stationary operands: Q of this lane's query rows i_wave0 + 32 qb + ql
+  // ---- stationary operands: Q of this lane's rows r_wave0 + 32 qb + ql of the list
   const float c2 = d.scale * LOG2E;
   bf16x8 qf[QB][KS];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
-    const int i = i_wave0 + 32 * qb + ql;
+    const int r = r_wave0 + 32 * qb + ql;
+    const int hq = hk * G + r / d.Sq, i = r % d.Sq;
     const long off = b * d.q_sb + hq * d.q_sh + (long)i * d.q_ss;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       u32x4 x = {0, 0, 0, 0};
-      if (i < d.Sq) x = *(const u32x4*)((const uint16_t*)a.q + off + 16 * ks + 8 * g);
+      if (r < rows_kv) x = *(const u32x4*)((const uint16_t*)a.q + off + 16 * ks + 8 * g);
       qf[qb][ks] = __builtin_bit_cast(bf16x8, x);
     }
   }
@@ -391,8 +397,9 @@ fwd_bf16_kernel(FwdArgs a) {
     const float l_tot = xhalf_sum(l_run[qb]);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
     const float lse = l_tot > 0.f ? r[qb] * (1.f / LOG2E) + logf(l_tot) : -INFINITY;
-    const int i = i_wave0 + 32 * qb + ql;
-    if (i >= d.Sq) continue;
+    const int r = r_wave0 + 32 * qb + ql;
+    if (r >= rows_kv) continue;
+    const int hq = hk * G + r / d.Sq, i = r % d.Sq;
     const long row = ((long)b * d.Hq + hq) * d.Sq + i;
     if (a.n_split > 1) {
       float* o = a.o_part + ((long)split * d.B * d.Hq * d.Sq + row) * D;
@@ -469,7 +476,10 @@ int fwd_bf16_pick_split(const Dims& d, int n_cu, bool masked) {
   // one workgroup per CU; split the KV axis until the grid covers the chip.  With a media mask the
   // visible work differs from one query tile to the next (the splits of a tile share its visible
   // key tiles evenly), so four times as many workgroups are made to even the load out.
-  const long base = (long)d.B * d.Hq * ((d.Sq + QM - 1) / QM);
+  // (the dense kernel tiles the rows of a whole group of query heads, the general one each head's)
+  const bool dense = !masked && d.Skv % TN == 0;
+  const long base = dense ? (long)d.B * d.Hkv * (((long)(d.Hq / d.Hkv) * d.Sq + QM - 1) / QM)
+                          : (long)d.B * d.Hq * ((d.Sq + QM - 1) / QM);
   const int n_tiles = (d.Skv + TN - 1) / TN;
   long cap = n_tiles / 16;                // keep at least 16 tiles (1024 keys) per split
   if (cap < 1) cap = 1;
@@ -489,10 +499,9 @@ int fwd_bf16_pick_split(const Dims& d, int n_cu, bool masked) {
 
 hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t s) {
   const Dims& d = a.d;
-  const int G = d.Hq / d.Hkv;
-  const int n_qt = (d.Sq + QM - 1) / QM;
-  const long grid = xcd_grid(d.B * d.Hkv, a.n_split * G * n_qt);
   if (a.mask.allow != nullptr || d.Skv % TN != 0) return launch_fwd_general_bf16(a, s);
+  const int n_qt = (int)(((long)(d.Hq / d.Hkv) * d.Sq + QM - 1) / QM);
+  const long grid = xcd_grid(d.B * d.Hkv, a.n_split * n_qt);
   return d.D == 64 ? launch<64>(a, grid, s) : launch<128>(a, grid, s);
 }
 

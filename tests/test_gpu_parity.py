@@ -132,6 +132,11 @@ FWD_BWD_CASES = [
     # text lengths are arbitrary: a last query tile of 13 rows per head, several heads per group
     small("bf16_ragged_rows_gqa_d64", D=64, Hq=8, Hkv=2, Sq=77, Skv=640, n_blocks=2),
     small("bf16_ragged_rows_one_short_tile", Hq=2, Sq=3, Skv=512),
+    # one text token per head against a long key range: the four heads of a group share a tile,
+    # the key range is split
+    small("bf16_single_token_gqa", Hq=8, Hkv=2, Sq=1, Skv=8192),
+    # a worker's share of the text: 345 rows per head, tiles that straddle the heads of a group
+    small("bf16_short_block_gqa", Hq=8, Hkv=2, Sq=345, Skv=1024),
 ]
 
 
