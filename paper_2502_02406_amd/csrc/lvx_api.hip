@@ -285,6 +285,7 @@ lvx_status lvx_xattn_bwd_stages(const lvx_problem* p, lvx_dtype dtype, const voi
   a.d = make_dims(p);
   a.mask = make_mask(mask);
   a.n_split_dq = bwd_split(a.d, dtype, mask != nullptr);
+  a.dq_pass = 0;
   const size_t need = bwd_ws(a.d, a.n_split_dq);
   if (!workspace || ((uintptr_t)workspace % ALIGN) != 0 || workspace_bytes < need) return LVX_ERR_WORKSPACE;
   a.q = q; a.k = k; a.v = v; a.o = o; a.d_o = d_o; a.lse = lse;

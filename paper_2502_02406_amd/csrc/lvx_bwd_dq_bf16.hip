@@ -35,7 +35,11 @@ template <int D> using DqSmem = KvSmem<D>;
 
 // GENERAL = false: dense attention and Skv a multiple of 64 (no mask code, no ragged tile, so that
 // the steady-state loop is one basic block); GENERAL = true: everything else.
-template <int D, bool GENERAL>
+// LIST (with GENERAL = false): the dense kernel over a list of key tiles -- those that EVERY row
+// of the workgroup sees under a media mask (BwdArgs::dq_pass == 1).  Inside such a tile nothing is
+// masked, so the loop is the dense one; only the tile numbers come from the list.  The other
+// visible tiles are left to a launch of the general kernel (dq_pass == 2).
+template <int D, bool GENERAL, bool LIST = false>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 bwd_dq_bf16_kernel(BwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -48,7 +52,8 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   // G * Sq rows (row r = head r / Sq of the group, its row r % Sq), cut into tiles of 256, so that
   // short query blocks fill tiles instead of leaving one mostly empty tile per head.  The general
   // variant tiles each head's rows (its mask code works on rows of one head).
-  constexpr bool PACK = !GENERAL;
+  static_assert(!(GENERAL && LIST), "the tile list is a variant of the dense kernel");
+  constexpr bool PACK = !GENERAL && !LIST;         // (a mask works on the rows of one head)
   const int rows_lim = PACK ? G * d.Sq : d.Sq;      // rows of the list this workgroup's tiles are cut from
   const int n_qt = (rows_lim + QM - 1) / QM;
   const int per_split = PACK ? n_qt : G * n_qt;
@@ -148,7 +153,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
     };
     uint8_t* const win = (uint8_t*)smem + SM::RING + SM::BITS_BYTES;
     if (plan_masked_tiles<D>(a.mask, b, i_wg0, i_wg1, d.Sq, d.Skv, n_tiles, bits, SM::BITS_BYTES, win,
-                             SM::WIN_BYTES, tid, &mk, &seen)) {
+                             SM::WIN_BYTES, tid, &mk, &seen, a.dq_pass == 2)) {
       // visibility of every tile, and its class (nothing / everything / mixed) for every wave's
       // rows: the loop then reads the bitmap for mixed tiles only
       have_bits = have_cls = true;
@@ -169,6 +174,51 @@ bwd_dq_bf16_kernel(BwdArgs a) {
                        (min(d.Skv, t_end * TN) - 1) / mk.kv_block, win, SM::WIN_BYTES, tid, 256);
     }
   }
+  // LIST: the tiles every row of the workgroup sees, compacted into a list (in the area of the
+  // mask window; its length in the last word), shared evenly by the splits.  From here on
+  // t_begin, t_end and the cursor are POSITIONS in the list; tile_at turns one into a tile.
+  int* const tlist = (int*)(smem + SM::RING + SM::BITS_BYTES);
+  constexpr int LIST_CAP = SM::WIN_BYTES / 4 - 1;
+  if (LIST) {
+    const int c0 = i_wg0 / a.mask.q_chunk, h = i_wg1 / a.mask.q_chunk - c0 + 1;     // chunks of this workgroup's rows
+    const int w = (d.Skv - 1) / a.mask.kv_block + 1;
+    unsigned* const full = bits;                   // full[f]: 1 if all h chunks see key block f; then the tile plane
+    unsigned* const plane = bits + ((w + 1) & ~1);
+    for (int f = tid; f < w; f += 256) {
+      unsigned ok = 1;
+      for (int c = 0; c < h; ++c) ok &= a.mask.allow[b * a.mask.stride_b + (long)(c0 + c) * a.mask.stride_q + f] != 0;
+      full[f] = ok;
+    }
+    __syncthreads();
+    for (int base = 0; base < n_tiles; base += 256) {          // workgroup-uniform trip count
+      const int t = base + tid;
+      bool on = t < n_tiles;
+      if (on) {
+        const int fa = (t * TN) / a.mask.kv_block, fb = (t * TN + TN - 1) / a.mask.kv_block;
+        for (int f = fa; f <= fb; ++f) on = on && full[f] != 0;
+      }
+      const unsigned long long m = __ballot(on);
+      if ((tid & 63) == 0 && t < n_tiles) *(unsigned long long*)(plane + t / 32) = m;
+    }
+    __syncthreads();
+    if (wave == 0) {
+      int count = 0;
+      for (int base = 0; base < n_tiles; base += 64) {         // wave-uniform trip count
+        const unsigned long long m = *(const unsigned long long*)(plane + base / 32);
+        if ((m >> lane) & 1ull) tlist[count + __popcll(m & ((1ull << lane) - 1ull))] = base + lane;
+        count += (int)__popcll(m);
+      }
+      if (lane == 0) tlist[LIST_CAP] = count;
+    }
+    __syncthreads();
+    const int nn = __builtin_amdgcn_readfirstlane(tlist[LIST_CAP]);
+    t_begin = (int)((long)split * nn / a.n_split_dq);
+    t_end = (int)((long)(split + 1) * nn / a.n_split_dq);
+    nt = t_end - t_begin;
+  }
+  auto tile_at = [&](int pos) __attribute__((always_inline)) -> int {
+    return LIST ? __builtin_amdgcn_readfirstlane(tlist[pos]) : pos;
+  };
   int crow[QB] = {};                               // this lane's rows' chunks, relative to the window
   if (GENERAL && have_cls) {
 #pragma unroll
@@ -405,7 +455,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   for (int q = 0; q < NSTG; ++q) {
     if (q < nt) {
       e[q] = cursor;
-      issue_tile(cursor, smem + q * SM::STAGE);
+      issue_tile(tile_at(cursor), smem + q * SM::STAGE);
       cursor = next_tile(cursor + 1);
     }
   }
@@ -422,7 +472,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
     wg_barrier();
     if (issue) {
       e[4] = cursor;
-      issue_tile(cursor, st_copy);
+      issue_tile(tile_at(cursor), st_copy);
       cursor = next_tile(cursor + 1);
     }
   };
@@ -440,6 +490,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
     mask_scores(e[0], 1, s1);
   }
   int T = 0;
+  int id_next = LIST && cursor < t_end ? tlist[cursor] : 0;     // LIST: number of the next tile to copy
   FirstKV fkv;
   bf16x8 fkt = first_kt(smem, 0);                  // handed from phase to phase
   for (; T + 4 < nt; ++T) {                        // full tiles: tile T + 1 is scored, tile T + 4 issued
@@ -454,9 +505,12 @@ bwd_dq_bf16_kernel(BwdArgs a) {
       score_convert(sb, 1, s1, p1, s0, p0, ds0, cy, fkv, [&]() __attribute__((always_inline)) { fkt = first_kt(sb, 0); }, nothing);
     } else {
       mid(std::true_type{}, false, sa);
-      const int t_new = cursor;                    // the copies of tile T + 4 go out during the phase
+      // the copies of tile T + 4 go out during the phase (LIST: its number was fetched a tile ago,
+      // and the operands waited for here were fetched after it)
+      const int t_new = LIST ? __builtin_amdgcn_readfirstlane(id_next) : cursor;
       e[4] = t_new;
       cursor = next_tile(cursor + 1);
+      if (LIST) id_next = tlist[cursor < t_end ? cursor : t_begin];
       constexpr int EVERY = 2 * QB * KS / NDMA;
       static_assert(EVERY >= 1, "more copies than matrix instructions in the score phase");
       score_convert(sb, 1, s1, p1, s0, p0, ds0, cy, fkv, [&]() __attribute__((always_inline)) { fkt = first_kt(sb, 0); },
@@ -527,12 +581,12 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   }
 }
 
-template <int D, bool GENERAL>
+template <int D, bool GENERAL, bool LIST = false>
 hipError_t launch(const BwdArgs& a, long grid, hipStream_t s) {
   static SmemOnce once;
-  hipError_t e = ensure_dynamic_lds((const void*)bwd_dq_bf16_kernel<D, GENERAL>, DqSmem<D>::TOTAL, &once);
+  hipError_t e = ensure_dynamic_lds((const void*)bwd_dq_bf16_kernel<D, GENERAL, LIST>, DqSmem<D>::TOTAL, &once);
   if (e != hipSuccess) return e;
-  bwd_dq_bf16_kernel<D, GENERAL><<<(unsigned)grid, 256, DqSmem<D>::TOTAL, s>>>(a);
+  bwd_dq_bf16_kernel<D, GENERAL, LIST><<<(unsigned)grid, 256, DqSmem<D>::TOTAL, s>>>(a);
   return hipGetLastError();
 }
 
@@ -567,10 +621,12 @@ namespace {
 hipError_t launch_one(const BwdArgs& a, bool general, hipStream_t s) {
   const Dims& d = a.d;
   const int G = d.Hq / d.Hkv;
-  const long per_split = general ? (long)G * ((d.Sq + QM - 1) / QM) : ((long)G * d.Sq + QM - 1) / QM;
+  const bool list = a.dq_pass == 1;                // the dense kernel over a list of tiles: rows tiled per head
+  const long per_split = general || list ? (long)G * ((d.Sq + QM - 1) / QM) : ((long)G * d.Sq + QM - 1) / QM;
   const long grid = xcd_grid(d.B * d.Hkv, (int)(a.n_split_dq * per_split));
   hipError_t e;
-  if (d.D == 64) e = general ? launch<64, true>(a, grid, s) : launch<64, false>(a, grid, s);
+  if (list) e = d.D == 64 ? launch<64, false, true>(a, grid, s) : launch<128, false, true>(a, grid, s);
+  else if (d.D == 64) e = general ? launch<64, true>(a, grid, s) : launch<64, false>(a, grid, s);
   else e = general ? launch<128, true>(a, grid, s) : launch<128, false>(a, grid, s);
   if (e == hipSuccess && a.n_split_dq > 1)
     e = launch_dq_reduce(a.dq_part, a.n_split_dq, (long)d.B * d.Hq * d.Sq * d.D, a.dq_accum, s);
@@ -581,7 +637,22 @@ hipError_t launch_one(const BwdArgs& a, bool general, hipStream_t s) {
 
 hipError_t launch_bwd_dq_bf16(const BwdArgs& a, hipStream_t s) {
   const Dims& d = a.d;
-  if (a.mask.allow != nullptr) return launch_one(a, true, s);
+  if (a.mask.allow != nullptr) {
+    // Two launches when the general kernel's planner is sure to take the mask (it must leave out
+    // exactly the tiles of the first launch) and the tile list fits: the dense kernel on the key
+    // tiles every row of a workgroup sees, then the general kernel on the other visible tiles.
+    // Both add into dq_accum, one after the other on the stream.
+    const int n_tiles = (d.Skv + TN - 1) / TN;
+    const int h_max = (QM - 1) / a.mask.q_chunk + 2, w = (d.Skv - 1) / a.mask.kv_block + 1;
+    const bool two = d.Skv % TN == 0 && plan_fits(h_max, w, n_tiles, DqSmem<128>::BITS_BYTES, DqSmem<128>::WIN_BYTES) &&
+                     n_tiles <= DqSmem<128>::WIN_BYTES / 4 - 1 && ((w + 1) & ~1) + (n_tiles + 63) / 64 * 2 <= DqSmem<128>::BITS_BYTES / 4;
+    if (!two) return launch_one(a, true, s);
+    BwdArgs p1 = a, p2 = a;
+    p1.dq_pass = 1;
+    p2.dq_pass = 2;
+    const hipError_t e = launch_one(p1, false, s);
+    return e != hipSuccess ? e : launch_one(p2, true, s);
+  }
   const int tail = d.Skv % TN;
   if (tail == 0) return launch_one(a, false, s);
   if (d.Skv < 2 * TN) return launch_one(a, true, s);

@@ -52,6 +52,9 @@ struct BwdArgs {
   float* dq_accum;      // [B,Hq,Sq,D] float32, accumulated into
   void *dk, *dv;        // K's strides, input dtype, overwritten
   int n_split_dq;       // KV splits of the dQ kernel
+  int dq_pass;          // media mask, dQ kernel: 0 = one launch over every visible tile; 1 = this launch takes the
+                        // key tiles that EVERY row of a workgroup sees (dense kernel over a list of them),
+                        // 2 = this launch takes the other visible tiles (general kernel)
   float* dq_part;       // workspace, [n_split_dq, B,Hq,Sq,D] float32: the splits' sums (n_split_dq > 1),
                         // added to dq_accum by a reduction that follows the kernel
 };

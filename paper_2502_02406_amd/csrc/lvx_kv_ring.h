@@ -80,18 +80,24 @@ __device__ __forceinline__ void mfma_acc(f32x16& c_acc, bf16x8 a, bf16x8 b) {   
 // Every read of the window and of the words is an LDS read; nothing here goes through the generic
 // pointer of MaskDev, whose every probe costs a round trip of the flat path.
 // Returns false, having done nothing, when the shapes do not fit (more than 32 chunks per
-// workgroup, window and words beyond win_cap bytes, planes beyond bits_cap bytes); on success *mk
+// workgroup, window and words beyond win_cap bytes, planes beyond bits_cap bytes: the test is
+// plan_fits below, which the host can evaluate too); on success *mk
 // addresses the LDS copy of the window and *seen_out the per-block words, which is what the loop
 // probes for mixed tiles: (seen[j / kv_block] >> (i / q_chunk - c0)) & 1 says whether row i sees key j.
+// (h: chunks the rows of a workgroup can touch, w: key blocks, n_tiles: key tiles)
+__host__ __device__ inline bool plan_fits(int h, int w, int n_tiles, int bits_cap, int win_cap) {
+  return h <= 32 && (long)h * w + 4L * w + 4 <= win_cap && (1 + 2 * NWV) * bit_plane_words(n_tiles) * 4 <= bits_cap;
+}
 template <int D>
 __device__ inline bool plan_masked_tiles(const MaskDev& m, int b, int i_wg0, int i_wg1, int Sq, int Skv,
                                          int n_tiles, unsigned* bits, int bits_cap, uint8_t* win,
-                                         int win_cap, int tid, MaskDev* mk, const unsigned** seen_out) {
+                                         int win_cap, int tid, MaskDev* mk, const unsigned** seen_out,
+                                         bool skip_full = false) {
   const int c0 = i_wg0 / m.q_chunk, h = i_wg1 / m.q_chunk - c0 + 1;
   const int w = (Skv - 1) / m.kv_block + 1;
   const int pw = bit_plane_words(n_tiles);
   const int win_bytes = (h * w + 3) & ~3;
-  if (h > 32 || (long)h * w + 4L * w + 4 > win_cap || (1 + 2 * NWV) * pw * 4 > bits_cap) return false;
+  if (!plan_fits(h, w, n_tiles, bits_cap, win_cap)) return false;
   for (int i = tid; i < w * h; i += 256)
     win[i] = m.allow[b * m.stride_b + (long)(c0 + i / w) * m.stride_q + i % w];
   if (tid == 0) bits[0] = 0;
@@ -113,6 +119,8 @@ __device__ inline bool plan_masked_tiles(const MaskDev& m, int b, int i_wg0, int
       wmask[wv] = (z - a == 31 ? ~0u : ((1u << (z - a + 1)) - 1u)) << a;
     }
   }
+  const unsigned wgm = wmask[0] | wmask[1] | wmask[2] | wmask[3];
+  static_assert(NWV == 4, "wgm above names the four waves");
   for (int base = 0; base < n_tiles; base += 256) {          // workgroup-uniform trip count
     const int t = base + tid;
     unsigned any = 0, all = ~0u;
@@ -122,7 +130,8 @@ __device__ inline bool plan_masked_tiles(const MaskDev& m, int b, int i_wg0, int
     } else {
       all = 0;
     }
-    const unsigned long long vis = __ballot(any != 0);
+    // (skip_full: tiles that every row of the workgroup sees are left to another pass)
+    const unsigned long long vis = __ballot(any != 0 && !(skip_full && (all & wgm) == wgm));
     unsigned long long wa[NWV], wl[NWV];
 #pragma unroll
     for (int wv = 0; wv < NWV; ++wv) {

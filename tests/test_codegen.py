@@ -43,7 +43,8 @@ def _blocks(body):
 @pytest.mark.parametrize("src,kernel,loop_mfma", [
     ("lvx_bwd_dkdv_bf16.hip", "bwd_dkdv_bf16_kernelILi128ELb0ELb0E", 128),   # two steps of 64 per trip
     ("lvx_bwd_dkdv_bf16.hip", "bwd_dkdv_bf16_kernelILi128ELb0ELb1E", 128),   # the same loop over a list of steps
-    ("lvx_bwd_dq_bf16.hip", "bwd_dq_bf16_kernelILi128ELb0E", 96),        # one tile = two halves of 48
+    ("lvx_bwd_dq_bf16.hip", "bwd_dq_bf16_kernelILi128ELb0ELb0E", 96),        # one tile = two halves of 48
+    ("lvx_bwd_dq_bf16.hip", "bwd_dq_bf16_kernelILi128ELb0ELb1E", 96),        # the same loop over a list of tiles
 ])
 def test_dense_loop_moves_no_accumulator(src, kernel, loop_mfma):
     body = _kernel(_asm(src), kernel)
@@ -70,7 +71,7 @@ def test_general_dkdv_leaves_half_the_accumulation_file():
 
 @pytest.mark.parametrize("src,kernel", [
     ("lvx_fwd_bf16.hip", "fwd_bf16_kernelILi128EE"),
-    ("lvx_bwd_dq_bf16.hip", "bwd_dq_bf16_kernelILi128ELb1E"),
+    ("lvx_bwd_dq_bf16.hip", "bwd_dq_bf16_kernelILi128ELb1ELb0E"),
 ])
 def test_blocks_with_matrix_instructions_move_no_accumulator(src, kernel):
     """The dense forward's loop has (rare) branches and the general dQ kernel has mask code, so
