@@ -214,7 +214,10 @@ def main():
     out["model"] = {"f_ms": ms_fwd, "note": "per-round max(f, comm) of Equations 2 and 3 with the measured forward visit; "
                                             "one xGMI link, and the paper's two slower interconnects",
                     "rounds": [asdict(RM.predict_forward_round(ms_fwd, w.Sq, blk, w.D, w.Hq, w.Hkv, name, gbs))
-                               for name, gbs in (("xgmi_link", 153.0), ("net_25GBs", 25.0), ("net_1.25GBs", 1.25))]}
+                               for name, gbs in (("xgmi_link", 153.0), ("net_25GBs", 25.0), ("net_1.25GBs", 1.25))],
+                    "f_bwd_ms": ms_dkdv + ms_dq,
+                    "rounds_bwd": [asdict(RM.predict_backward_round(ms_dkdv + ms_dq, w.Sq, blk, w.D, w.Hq, w.Hkv, name, gbs))
+                                   for name, gbs in (("xgmi_link", 153.0), ("net_25GBs", 25.0), ("net_1.25GBs", 1.25))]}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, seed)
     print(json.dumps(out))

@@ -72,3 +72,21 @@ def predict_forward_round(f_ms: float, sq: int, skv_block: int, d: int, h_q: int
     rg = round_time(f, ring_bytes, bw)
     return RoundPrediction(link, bandwidth_gbs, lv_bytes / bw * 1e3, lv * 1e3, ring_bytes / bw * 1e3, rg * 1e3,
                            rg / lv, lv_bytes / bw <= f)
+
+
+def predict_backward_round(f_ms: float, sq: int, skv_block: int, d: int, h_q: int, h_kv: int, link: str,
+                           bandwidth_gbs: float, q_bytes: int = 2, do_bytes: int = 2, dq_bytes: int = 4,
+                           stat_bytes: int = 4, kv_bytes: int = 2, dkv_bytes: int = 4) -> RoundPrediction:
+    """One backward round with the measured backward time f_ms of a visit.  The paper gives the
+    backward pass only through Table 1 (Ring Attention moves 4 units of S_KV/n h d: K, V and their
+    gradients); for LV-XAttn this build's reading is that the query side keeps travelling: Q, dO,
+    the two row statistics (L and rowsum(dO * O)) and the running dQ of the h_q query heads, while
+    K, V, dK and dV stay where they are."""
+    bw = bandwidth_gbs * 1e9
+    lv_bytes = h_q * (sq * d * (q_bytes + do_bytes + dq_bytes) + 2 * sq * stat_bytes)
+    ring_bytes = h_kv * 2 * skv_block * d * (kv_bytes + dkv_bytes)
+    f = f_ms * 1e-3
+    lv = round_time(f, lv_bytes, bw)
+    rg = round_time(f, ring_bytes, bw)
+    return RoundPrediction(link, bandwidth_gbs, lv_bytes / bw * 1e3, lv * 1e3, ring_bytes / bw * 1e3, rg * 1e3,
+                           rg / lv, lv_bytes / bw <= f)

@@ -44,3 +44,14 @@ def test_prediction_for_the_bench_shape():
     assert p.ring_round_ms == pytest.approx(max(0.9, p.ring_comm_ms))
     slow = M.predict_forward_round(0.9, 2048, 32768, 128, 32, 8, "nic", 1.25)
     assert not slow.lvxattn_hidden and slow.speedup == pytest.approx(slow.ring_comm_ms / slow.lvxattn_comm_ms)
+
+
+def test_backward_prediction_counts_the_travelling_tensors():
+    p = M.predict_backward_round(2.8, 2048, 32768, 128, 32, 8, "link", 153.0)
+    assert p.lvxattn_comm_ms == pytest.approx(32 * (2048 * 128 * 8 + 2 * 2048 * 4) / 153e9 * 1e3)
+    assert p.ring_comm_ms == pytest.approx(8 * 2 * 32768 * 128 * 6 / 153e9 * 1e3)
+    assert p.lvxattn_hidden and p.lvxattn_round_ms == pytest.approx(2.8)
+    # with equal element sizes the ratio of the two volumes is Table 1's: 4 units of S_KV against
+    # the query side's 3 tensors of S_Q (plus the statistics)
+    q = M.predict_backward_round(1e-9, 100, 5000, 64, 4, 4, "x", 1.0, 2, 2, 2, 2, 2, 2)
+    assert q.ring_comm_ms / q.lvxattn_comm_ms == pytest.approx(4 * 5000 * 64 / (3 * 100 * 64 + 2 * 100))
