@@ -196,6 +196,52 @@ def test_step_aligned_media_masks(name, kw, per_batch, p_on):
     run_case(w, do_bwd=True, allow=(rng.random(shape) < p_on))
 
 
+def _random_case(it, rng):
+    """A small random problem: head dims, group sizes, query lengths around the tile sizes, key
+    blocks that are and are not tile multiples, block loops, and media masks of three kinds."""
+    D, Hkv, G, B = int(rng.choice([64, 128])), int(rng.choice([1, 2, 3])), int(rng.choice([1, 2, 4])), int(rng.choice([1, 2]))
+    Sq = int(rng.choice([1, 7, 31, 32, 33, 64, 100, 200, 256, 257, 345, 512]))
+    n_blocks = int(rng.choice([1, 1, 2, 3]))
+    masked = rng.random() < 0.5
+    q_chunk = kv_block = 0
+    if masked:
+        q_chunk, kv_block = int(rng.choice([8, 16, 32, 64, 50])), int(rng.choice([64, 128, 256, 512, 100, 729]))
+        blk = kv_block * int(rng.integers(1, 5))              # block boundaries fall on mask blocks
+        if rng.random() < 0.3 and n_blocks == 1:
+            blk += int(rng.integers(1, kv_block))             # ragged last mask block
+    else:
+        blk = int(rng.choice([64, 128, 192, 500, 1000, 1024, 2048, 3000]))
+    Skv = blk * n_blocks
+    if Skv * Sq * B * Hkv * G > 6e7:
+        return None, None
+    w = W.Workload(f"random{it}", B=B, Hq=Hkv * G, Hkv=Hkv, D=D, Sq=Sq, Skv=Skv, dtype="bf16", std=0.5,
+                   n_blocks=n_blocks, q_chunk=q_chunk, kv_block=kv_block)
+    allow = None
+    if masked:
+        nq, nk = -(-Sq // q_chunk), -(-Skv // kv_block)
+        kind = int(rng.integers(0, 3))
+        if kind == 0:
+            allow = rng.random((nq, nk)) < rng.choice([0.2, 0.5, 0.9])
+        elif kind == 1:
+            allow = np.arange(nk)[None, :] <= np.arange(nq)[:, None]
+        else:
+            allow = rng.random((B, nq, nk)) < 0.5
+    return w, allow
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_random_shapes(seed):
+    rng = np.random.Generator(np.random.Philox(seed))
+    done = 0
+    for it in range(16):
+        w, allow = _random_case(it, rng)
+        if w is None:
+            continue
+        run_case(w, seed=seed * 100 + it, do_bwd=True, allow=allow)
+        done += 1
+    assert done >= 8
+
+
 def test_masked_rows_without_keys():
     # block-causal mask whose first chunks see nothing inside the second K/V block
     w = small("bf16_blockcausal_blocks", B=1, Hq=2, Sq=128, Skv=1024, q_chunk=32, kv_block=256,
