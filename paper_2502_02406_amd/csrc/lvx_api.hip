@@ -84,6 +84,33 @@ int bwd_split(const Dims& d, lvx_dtype dtype, bool masked) {
   return dtype == LVX_BF16 ? bwd_bf16_pick_split(d, device_cu_count(), masked) : 1;
 }
 
+// bf16, no mask, a key count that is no multiple of the 64-key tile (and at least two tiles): the
+// dense kernel takes the whole tiles, the general kernel the keys that are left, as one more
+// partial result of the combine.
+constexpr int FWD_TILE = 64;
+bool fwd_has_tail(const Dims& d, lvx_dtype dtype, bool masked) {
+  return dtype == LVX_BF16 && !masked && d.Skv % FWD_TILE != 0 && d.Skv >= 2 * FWD_TILE;
+}
+// launches of the bf16 forward that leave partial results in slices [0, n_split (+ 1)) of
+// o_part / lse_part: every split of the whole tiles, then the tail
+hipError_t launch_fwd_bf16_parts(FwdArgs a, hipStream_t s) {
+  const int tail = a.d.Skv % FWD_TILE;
+  FwdArgs head = a;
+  head.partial = 1;
+  head.part0 = 0;
+  head.d.Skv = a.d.Skv - tail;
+  hipError_t e = launch_fwd_bf16(head, s);
+  if (e != hipSuccess) return e;
+  FwdArgs rest = a;
+  rest.partial = 1;
+  rest.part0 = a.n_split;
+  rest.n_split = 1;
+  rest.k = (const uint16_t*)a.k + (long)head.d.Skv * a.d.kv_ss;
+  rest.v = (const uint16_t*)a.v + (long)head.d.Skv * a.d.kv_ss;
+  rest.d.Skv = tail;
+  return launch_fwd_bf16(rest, s);
+}
+
 size_t fwd_ws(const Dims& d, int n_split) {
   if (n_split <= 1) return ALIGN;   // never zero, so that a valid workspace pointer is always passed
   const size_t rows = (size_t)d.B * d.Hq * d.Sq;
@@ -135,10 +162,12 @@ size_t lvx_xattn_workspace_bytes(const lvx_problem* p, lvx_dtype dtype, int whic
   const Dims d = make_dims(p);
   // (the size does not depend on whether the call will carry a mask: the larger of the two split counts)
   const auto larger = [](int x, int y) { return x > y ? x : y; };
-  if (which == LVX_WS_FWD) return fwd_ws(d, larger(fwd_split(d, dtype, true), fwd_split(d, dtype, false)));
+  const int tail_part = fwd_has_tail(d, dtype, false) ? 1 : 0;        // (one more partial result: the tail's)
+  if (which == LVX_WS_FWD)
+    return fwd_ws(d, larger(fwd_split(d, dtype, true), fwd_split(d, dtype, false) + tail_part));
   if (which == LVX_WS_BWD) return bwd_ws(d, larger(bwd_split(d, dtype, true), bwd_split(d, dtype, false)));
   if (which == LVX_WS_FWD_MERGE)
-    return fwd_merge_ws(d, dtype, larger(fwd_merge_split(d, dtype, true), fwd_merge_split(d, dtype, false)));
+    return fwd_merge_ws(d, dtype, larger(fwd_merge_split(d, dtype, true), fwd_merge_split(d, dtype, false) + tail_part));
   return 0;
 }
 
@@ -156,22 +185,26 @@ lvx_status lvx_xattn_fwd(const lvx_problem* p, lvx_dtype dtype, const void* q, c
   a.mask = make_mask(mask);
   a.q = q; a.k = k; a.v = v; a.o = o; a.o_is_f32 = o_dtype == LVX_F32; a.lse = lse;
   a.merge_into = 0;
+  a.partial = 0; a.part0 = 0;
   a.n_split = fwd_split(a.d, dtype, mask != nullptr);
+  const bool tail = fwd_has_tail(a.d, dtype, mask != nullptr);
+  if (tail && a.n_split > LVX_MAX_PARTS - 1) a.n_split = LVX_MAX_PARTS - 1;
+  const int n_parts = a.n_split + (tail ? 1 : 0);
   a.o_part = nullptr; a.lse_part = nullptr;
-  const size_t need = fwd_ws(a.d, a.n_split);
+  const size_t need = fwd_ws(a.d, n_parts);
   if (!workspace || ((uintptr_t)workspace % ALIGN) != 0 || workspace_bytes < need) return LVX_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)hip_stream;
   const size_t rows = (size_t)a.d.B * a.d.Hq * a.d.Sq;
-  if (a.n_split > 1) {
+  if (n_parts > 1) {
     a.o_part = (float*)workspace;
-    a.lse_part = (float*)((char*)workspace + align_up(rows * a.d.D * sizeof(float) * a.n_split));
+    a.lse_part = (float*)((char*)workspace + align_up(rows * a.d.D * sizeof(float) * n_parts));
   }
-  hipError_t e = dtype == LVX_BF16 ? launch_fwd_bf16(a, s) : launch_fwd_f32(a, s);
+  hipError_t e = tail ? launch_fwd_bf16_parts(a, s) : dtype == LVX_BF16 ? launch_fwd_bf16(a, s) : launch_fwd_f32(a, s);
   if (e != hipSuccess) return LVX_ERR_HIP;
-  if (a.n_split > 1) {
+  if (n_parts > 1) {
     MergeArgs m;
-    m.n_parts = a.n_split;
-    for (int i = 0; i < a.n_split; ++i) {
+    m.n_parts = n_parts;
+    for (int i = 0; i < n_parts; ++i) {
       m.o_parts[i] = a.o_part + (size_t)i * rows * a.d.D;
       m.lse_parts[i] = a.lse_part + (size_t)i * rows;
     }
@@ -198,25 +231,28 @@ lvx_status lvx_xattn_fwd_merge(const lvx_problem* p, lvx_dtype dtype, const void
     return LVX_ERR_STRIDE;      // the float32 kernels write their result with Q's strides
   a.mask = make_mask(mask);
   a.q = q; a.k = k; a.v = v; a.o_is_f32 = 1;
+  a.partial = 0; a.part0 = 0;
   a.n_split = fwd_merge_split(a.d, dtype, mask != nullptr);
+  const bool tail = fwd_has_tail(a.d, dtype, mask != nullptr);
+  if (tail && a.n_split > LVX_MAX_PARTS - 2) a.n_split = LVX_MAX_PARTS - 2;    // (the running state and the tail are parts too)
   a.o_part = nullptr; a.lse_part = nullptr;
-  const size_t need = fwd_merge_ws(a.d, dtype, a.n_split);
+  const size_t need = fwd_merge_ws(a.d, dtype, a.n_split + (tail ? 1 : 0));
   if (!workspace || ((uintptr_t)workspace % ALIGN) != 0 || workspace_bytes < need) return LVX_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)hip_stream;
   const size_t rows = (size_t)a.d.B * a.d.Hq * a.d.Sq;
-  if (dtype == LVX_BF16 && a.n_split == 1) {            // Rescale in the kernel's epilogue
+  if (dtype == LVX_BF16 && a.n_split == 1 && !tail) {   // Rescale in the kernel's epilogue
     a.o = o_acc; a.lse = lse_acc; a.merge_into = 1;
     return launch_fwd_bf16(a, s) == hipSuccess ? LVX_OK : LVX_ERR_HIP;
   }
   // partial result(s) in the workspace, then one combine over the running state and them
   a.merge_into = 0;
-  const int n_parts = dtype == LVX_BF16 ? a.n_split : 1;
+  const int n_parts = dtype == LVX_BF16 ? a.n_split + (tail ? 1 : 0) : 1;
   float* const o_part = (float*)workspace;
   float* const l_part = (float*)((char*)workspace + align_up(rows * a.d.D * sizeof(float) * n_parts));
   hipError_t e;
   if (dtype == LVX_BF16) {
     a.o = nullptr; a.lse = nullptr; a.o_part = o_part; a.lse_part = l_part;
-    e = launch_fwd_bf16(a, s);
+    e = tail ? launch_fwd_bf16_parts(a, s) : launch_fwd_bf16(a, s);
   } else {
     a.o = o_part; a.lse = l_part; a.n_split = 1;
     e = launch_fwd_f32(a, s);

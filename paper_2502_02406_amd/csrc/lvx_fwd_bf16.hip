@@ -401,8 +401,9 @@ fwd_bf16_kernel(FwdArgs a) {
     if (r >= rows_kv) continue;
     const int hq = hk * G + r / d.Sq, i = r % d.Sq;
     const long row = ((long)b * d.Hq + hq) * d.Sq + i;
-    if (a.n_split > 1) {
-      float* o = a.o_part + ((long)split * d.B * d.Hq * d.Sq + row) * D;
+    if (a.n_split > 1 || a.partial) {
+      const long slice = (long)(a.part0 + split) * d.B * d.Hq * d.Sq;
+      float* o = a.o_part + (slice + row) * D;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -411,7 +412,7 @@ fwd_bf16_kernel(FwdArgs a) {
                      oacc[qb][db][4 * q4 + 3] * inv};
           *(f32x4*)(o + 32 * db + 8 * q4 + 4 * g) = y;
         }
-      if (g == 0) a.lse_part[(long)split * d.B * d.Hq * d.Sq + row] = lse;
+      if (g == 0) a.lse_part[slice + row] = lse;
       continue;
     }
     if (a.merge_into) {
@@ -477,7 +478,7 @@ int fwd_bf16_pick_split(const Dims& d, int n_cu, bool masked) {
   // visible work differs from one query tile to the next (the splits of a tile share its visible
   // key tiles evenly), so four times as many workgroups are made to even the load out.
   // (the dense kernel tiles the rows of a whole group of query heads, the general one each head's)
-  const bool dense = !masked && d.Skv % TN == 0;
+  const bool dense = !masked && (d.Skv % TN == 0 || d.Skv >= 2 * TN);   // (a ragged key count: whole tiles on the dense kernel)
   const long base = dense ? (long)d.B * d.Hkv * (((long)(d.Hq / d.Hkv) * d.Sq + QM - 1) / QM)
                           : (long)d.B * d.Hq * ((d.Sq + QM - 1) / QM);
   const int n_tiles = (d.Skv + TN - 1) / TN;

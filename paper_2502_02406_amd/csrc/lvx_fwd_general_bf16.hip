@@ -394,8 +394,9 @@ fwd_general_bf16_kernel(FwdArgs a) {
   const float lse = l_tot > 0.f ? m_ref * d.scale + logf(l_tot) : -INFINITY;
   if (i_lane >= d.Sq) return;
   const long row = ((long)b * d.Hq + hq) * d.Sq + i_lane;
-  if (a.n_split > 1) {
-    float* o = a.o_part + ((long)split * d.B * d.Hq * d.Sq + row) * D;
+  if (a.n_split > 1 || a.partial) {
+    const long slice = (long)(a.part0 + split) * d.B * d.Hq * d.Sq;
+    float* o = a.o_part + (slice + row) * D;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -404,7 +405,7 @@ fwd_general_bf16_kernel(FwdArgs a) {
                    oacc[db][4 * q4 + 3] * inv};
         *(f32x4*)(o + 32 * db + 8 * q4 + 4 * g) = y;
       }
-    if (g == 0) a.lse_part[(long)split * d.B * d.Hq * d.Sq + row] = lse;
+    if (g == 0) a.lse_part[slice + row] = lse;
     return;
   }
   if (a.merge_into) {

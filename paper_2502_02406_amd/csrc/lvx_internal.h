@@ -31,6 +31,9 @@ struct FwdArgs {
                         // result; the kernel leaves in them the Rescale of it with this visit's result
   float* lse;           // [B,Hq,Sq]
   int n_split;          // number of KV splits handled by separate workgroups
+  int partial;          // 1: write partial results even with n_split == 1 (this launch is one of several
+                        // whose results are combined)
+  int part0;            // index of the partial slice that split 0 of this launch writes
   float* o_part;        // [n_split, B,Hq,Sq,D] float32, contiguous (n_split > 1)
   float* lse_part;      // [n_split, B,Hq,Sq]
 };
