@@ -111,6 +111,27 @@ hipError_t launch_fwd_bf16_parts(FwdArgs a, hipStream_t s) {
   return launch_fwd_bf16(rest, s);
 }
 
+// bf16 under a media mask that fits (fwd_bf16_two_pass_fits): the dense kernel over the key tiles
+// that every row of a workgroup sees, then the general kernel on the other visible tiles; each
+// launch leaves n_split partial results (slices [0, n_split) and [n_split, 2 n_split)).
+int fwd_two_pass_split(int n_split, int reserve) {   // each launch's split count: both launches' parts (and
+  const int cap = (LVX_MAX_PARTS - reserve) / 2;      // `reserve` others) go into one combine
+  return n_split < cap ? n_split : cap;
+}
+bool fwd_two_pass(const Dims& d, lvx_dtype dtype, const MaskDev& m) {
+  return dtype == LVX_BF16 && fwd_bf16_two_pass_fits(d, m);
+}
+hipError_t launch_fwd_bf16_two_pass(FwdArgs a, hipStream_t s) {
+  a.partial = 1;
+  a.pass = 1;
+  a.part0 = 0;
+  const hipError_t e = launch_fwd_bf16(a, s);
+  if (e != hipSuccess) return e;
+  a.pass = 2;
+  a.part0 = a.n_split;
+  return launch_fwd_bf16(a, s);
+}
+
 size_t fwd_ws(const Dims& d, int n_split) {
   if (n_split <= 1) return ALIGN;   // never zero, so that a valid workspace pointer is always passed
   const size_t rows = (size_t)d.B * d.Hq * d.Sq;
@@ -163,11 +184,17 @@ size_t lvx_xattn_workspace_bytes(const lvx_problem* p, lvx_dtype dtype, int whic
   // (the size does not depend on whether the call will carry a mask: the larger of the two split counts)
   const auto larger = [](int x, int y) { return x > y ? x : y; };
   const int tail_part = fwd_has_tail(d, dtype, false) ? 1 : 0;        // (one more partial result: the tail's)
+  // (a masked bf16 call may run as two launches that leave their splits' partial results side by side)
+  const int masked_parts = dtype == LVX_BF16 ? 2 * fwd_two_pass_split(fwd_split(d, dtype, true), 0) : fwd_split(d, dtype, true);
   if (which == LVX_WS_FWD)
-    return fwd_ws(d, larger(fwd_split(d, dtype, true), fwd_split(d, dtype, false) + tail_part));
+    return fwd_ws(d, larger(larger(masked_parts, fwd_split(d, dtype, true)), fwd_split(d, dtype, false) + tail_part));
   if (which == LVX_WS_BWD) return bwd_ws(d, larger(bwd_split(d, dtype, true), bwd_split(d, dtype, false)));
   if (which == LVX_WS_FWD_MERGE)
-    return fwd_merge_ws(d, dtype, larger(fwd_merge_split(d, dtype, true), fwd_merge_split(d, dtype, false) + tail_part));
+  {
+    const int masked_merge = dtype == LVX_BF16 ? 2 * fwd_two_pass_split(fwd_merge_split(d, dtype, true), 1) : 1;
+    return fwd_merge_ws(d, dtype, larger(larger(masked_merge, fwd_merge_split(d, dtype, true)),
+                                         fwd_merge_split(d, dtype, false) + tail_part));
+  }
   return 0;
 }
 
@@ -185,11 +212,13 @@ lvx_status lvx_xattn_fwd(const lvx_problem* p, lvx_dtype dtype, const void* q, c
   a.mask = make_mask(mask);
   a.q = q; a.k = k; a.v = v; a.o = o; a.o_is_f32 = o_dtype == LVX_F32; a.lse = lse;
   a.merge_into = 0;
-  a.partial = 0; a.part0 = 0;
+  a.partial = 0; a.part0 = 0; a.pass = 0;
   a.n_split = fwd_split(a.d, dtype, mask != nullptr);
   const bool tail = fwd_has_tail(a.d, dtype, mask != nullptr);
+  const bool two = mask != nullptr && fwd_two_pass(a.d, dtype, a.mask);
   if (tail && a.n_split > LVX_MAX_PARTS - 1) a.n_split = LVX_MAX_PARTS - 1;
-  const int n_parts = a.n_split + (tail ? 1 : 0);
+  if (two) a.n_split = fwd_two_pass_split(a.n_split, 0);
+  const int n_parts = two ? 2 * a.n_split : a.n_split + (tail ? 1 : 0);
   a.o_part = nullptr; a.lse_part = nullptr;
   const size_t need = fwd_ws(a.d, n_parts);
   if (!workspace || ((uintptr_t)workspace % ALIGN) != 0 || workspace_bytes < need) return LVX_ERR_WORKSPACE;
@@ -199,7 +228,9 @@ lvx_status lvx_xattn_fwd(const lvx_problem* p, lvx_dtype dtype, const void* q, c
     a.o_part = (float*)workspace;
     a.lse_part = (float*)((char*)workspace + align_up(rows * a.d.D * sizeof(float) * n_parts));
   }
-  hipError_t e = tail ? launch_fwd_bf16_parts(a, s) : dtype == LVX_BF16 ? launch_fwd_bf16(a, s) : launch_fwd_f32(a, s);
+  hipError_t e = two    ? launch_fwd_bf16_two_pass(a, s)
+                 : tail ? launch_fwd_bf16_parts(a, s)
+                        : dtype == LVX_BF16 ? launch_fwd_bf16(a, s) : launch_fwd_f32(a, s);
   if (e != hipSuccess) return LVX_ERR_HIP;
   if (n_parts > 1) {
     MergeArgs m;
@@ -231,28 +262,31 @@ lvx_status lvx_xattn_fwd_merge(const lvx_problem* p, lvx_dtype dtype, const void
     return LVX_ERR_STRIDE;      // the float32 kernels write their result with Q's strides
   a.mask = make_mask(mask);
   a.q = q; a.k = k; a.v = v; a.o_is_f32 = 1;
-  a.partial = 0; a.part0 = 0;
+  a.partial = 0; a.part0 = 0; a.pass = 0;
   a.n_split = fwd_merge_split(a.d, dtype, mask != nullptr);
   const bool tail = fwd_has_tail(a.d, dtype, mask != nullptr);
+  const bool two = mask != nullptr && fwd_two_pass(a.d, dtype, a.mask);
   if (tail && a.n_split > LVX_MAX_PARTS - 2) a.n_split = LVX_MAX_PARTS - 2;    // (the running state and the tail are parts too)
+  if (two) a.n_split = fwd_two_pass_split(a.n_split, 1);
+  const int n_launch_parts = two ? 2 * a.n_split : a.n_split + (tail ? 1 : 0);
   a.o_part = nullptr; a.lse_part = nullptr;
-  const size_t need = fwd_merge_ws(a.d, dtype, a.n_split + (tail ? 1 : 0));
+  const size_t need = fwd_merge_ws(a.d, dtype, n_launch_parts);
   if (!workspace || ((uintptr_t)workspace % ALIGN) != 0 || workspace_bytes < need) return LVX_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)hip_stream;
   const size_t rows = (size_t)a.d.B * a.d.Hq * a.d.Sq;
-  if (dtype == LVX_BF16 && a.n_split == 1 && !tail) {   // Rescale in the kernel's epilogue
+  if (dtype == LVX_BF16 && a.n_split == 1 && !tail && !two) {   // Rescale in the kernel's epilogue
     a.o = o_acc; a.lse = lse_acc; a.merge_into = 1;
     return launch_fwd_bf16(a, s) == hipSuccess ? LVX_OK : LVX_ERR_HIP;
   }
   // partial result(s) in the workspace, then one combine over the running state and them
   a.merge_into = 0;
-  const int n_parts = dtype == LVX_BF16 ? a.n_split + (tail ? 1 : 0) : 1;
+  const int n_parts = dtype == LVX_BF16 ? n_launch_parts : 1;
   float* const o_part = (float*)workspace;
   float* const l_part = (float*)((char*)workspace + align_up(rows * a.d.D * sizeof(float) * n_parts));
   hipError_t e;
   if (dtype == LVX_BF16) {
     a.o = nullptr; a.lse = nullptr; a.o_part = o_part; a.lse_part = l_part;
-    e = tail ? launch_fwd_bf16_parts(a, s) : launch_fwd_bf16(a, s);
+    e = two ? launch_fwd_bf16_two_pass(a, s) : tail ? launch_fwd_bf16_parts(a, s) : launch_fwd_bf16(a, s);
   } else {
     a.o = o_part; a.lse = l_part; a.n_split = 1;
     e = launch_fwd_f32(a, s);

@@ -44,7 +44,11 @@ constexpr int XE = LVX_FWD_XE;                  // elements of a half converted 
 
 // Dense attention with Skv a multiple of 64 only: no mask code and no ragged tile, so that nothing
 // stands between the phases of the pipeline (masked and ragged problems: lvx_fwd_general_bf16.hip).
-template <int D>
+// LIST: the same kernel over a list of key tiles -- those that EVERY row of the workgroup sees
+// under a media mask (FwdArgs::pass == 1).  Nothing is masked inside such a tile; only the tile
+// numbers come from the list, which the KV splits share evenly.  The other visible tiles are left
+// to a launch of the general kernel (pass == 2), and the partial results of both are combined.
+template <int D, bool LIST = false>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 fwd_bf16_kernel(FwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -57,12 +61,16 @@ fwd_bf16_kernel(FwdArgs a) {
   // r / Sq of the group, its row r % Sq), cut into tiles of 256: short query blocks -- one
   // worker's share of the text, or a single token -- then fill tiles instead of leaving one
   // mostly empty tile per head, and every K/V tile fetched serves all heads of the group.
-  const int rows_kv = G * d.Sq;
+  // (LIST tiles the rows of each head by itself: a mask works on the rows of one head)
+  constexpr bool PACK = !LIST;
+  const int rows_kv = PACK ? G * d.Sq : d.Sq;
   const int n_qt = (rows_kv + QM - 1) / QM;
+  const int per_split = PACK ? n_qt : G * n_qt;
   HeadWork hw;
-  if (!xcd_decode(blockIdx.x, d.B * d.Hkv, a.n_split * n_qt, &hw)) return;
+  if (!xcd_decode(blockIdx.x, d.B * d.Hkv, a.n_split * per_split, &hw)) return;
   const int b = hw.head / d.Hkv, hk = hw.head % d.Hkv;
-  const int split = hw.item / n_qt;
+  const int split = hw.item / per_split;
+  const int hq0 = hk * G + (PACK ? 0 : (hw.item % per_split) / n_qt);   // PACK: the first head of the group
   const int qt = hw.item % n_qt;
 
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ql = lane & 31;
@@ -72,8 +80,8 @@ fwd_bf16_kernel(FwdArgs a) {
   // KV range of this split, in tiles
   const int n_tiles = (d.Skv + TN - 1) / TN;
   const int tps = (n_tiles + a.n_split - 1) / a.n_split;
-  const int t_begin = split * tps;
-  const int t_end = min(n_tiles, t_begin + tps);
+  int t_begin = split * tps;                        // (LIST: re-cut below over the list)
+  int t_end = min(n_tiles, t_begin + tps);
 
   // ---- stationary operands: Q of this lane's rows r_wave0 + 32 qb + ql of the list
   const float c2 = d.scale * LOG2E;
@@ -81,7 +89,7 @@ fwd_bf16_kernel(FwdArgs a) {
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     const int r = r_wave0 + 32 * qb + ql;
-    const int hq = hk * G + r / d.Sq, i = r % d.Sq;
+    const int hq = PACK ? hq0 + r / d.Sq : hq0, i = PACK ? r % d.Sq : r;
     const long off = b * d.q_sb + hq * d.q_sh + (long)i * d.q_ss;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
@@ -97,6 +105,51 @@ fwd_bf16_kernel(FwdArgs a) {
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[qb][ks]));
 
+  // LIST: the tiles every row of the workgroup sees, compacted into a list (in the area of the
+  // mask window; its length in the last word), shared evenly by the splits.  From here on
+  // t_begin, t_end and the cursor are POSITIONS in the list; tile_at turns one into a tile.
+  int* const tlist = (int*)(smem + SM::RING + SM::BITS_BYTES);
+  constexpr int LIST_CAP = SM::WIN_BYTES / 4 - 1;
+  if (LIST) {
+    const int i_wg0 = qt * QM, i_wg1 = min(d.Sq, i_wg0 + QM) - 1;
+    const int c0 = i_wg0 / a.mask.q_chunk, h = i_wg1 / a.mask.q_chunk - c0 + 1;     // chunks of this workgroup's rows
+    const int w = (d.Skv - 1) / a.mask.kv_block + 1;
+    unsigned* const full = (unsigned*)(smem + SM::RING);   // full[f]: all h chunks see key block f; then the tile plane
+    unsigned* const plane = full + ((w + 1) & ~1);
+    for (int f = tid; f < w; f += 256) {
+      unsigned ok = 1;
+      for (int c = 0; c < h; ++c) ok &= a.mask.allow[b * a.mask.stride_b + (long)(c0 + c) * a.mask.stride_q + f] != 0;
+      full[f] = ok;
+    }
+    __syncthreads();
+    for (int base = 0; base < n_tiles; base += 256) {          // workgroup-uniform trip count
+      const int t = base + tid;
+      bool on = t < n_tiles;
+      if (on) {
+        const int fa = (t * TN) / a.mask.kv_block, fb = (t * TN + TN - 1) / a.mask.kv_block;
+        for (int f = fa; f <= fb; ++f) on = on && full[f] != 0;
+      }
+      const unsigned long long m = __ballot(on);
+      if ((tid & 63) == 0 && t < n_tiles) *(unsigned long long*)(plane + t / 32) = m;
+    }
+    __syncthreads();
+    if (wave == 0) {
+      int count = 0;
+      for (int base = 0; base < n_tiles; base += 64) {         // wave-uniform trip count
+        const unsigned long long m = *(const unsigned long long*)(plane + base / 32);
+        if ((m >> lane) & 1ull) tlist[count + __popcll(m & ((1ull << lane) - 1ull))] = base + lane;
+        count += (int)__popcll(m);
+      }
+      if (lane == 0) tlist[LIST_CAP] = count;
+    }
+    __syncthreads();
+    const int nn = __builtin_amdgcn_readfirstlane(tlist[LIST_CAP]);
+    t_begin = (int)((long)split * nn / a.n_split);
+    t_end = (int)((long)(split + 1) * nn / a.n_split);
+  }
+  auto tile_at = [&](int pos) __attribute__((always_inline)) -> int {
+    return LIST ? __builtin_amdgcn_readfirstlane(tlist[pos]) : pos;
+  };
   const int nt = max(t_end - t_begin, 0);          // number of tiles this workgroup performs
   auto next_tile = [&](int t) __attribute__((always_inline)) -> int { return min(t, t_end); };
   int cursor = t_begin;                            // next tile to issue
@@ -320,7 +373,7 @@ fwd_bf16_kernel(FwdArgs a) {
 #pragma unroll
   for (int q = 0; q < NSTG; ++q) {
     if (q < nt) {
-      issue_tile(cursor, smem + q * SM::STAGE);
+      issue_tile(tile_at(cursor), smem + q * SM::STAGE);
       cursor = next_tile(cursor + 1);
     }
   }
@@ -334,7 +387,7 @@ fwd_bf16_kernel(FwdArgs a) {
     else wait_vmcnt<0>();
     wg_barrier();
     if (issue) {
-      issue_tile(cursor, st_copy);
+      issue_tile(tile_at(cursor), st_copy);
       cursor = next_tile(cursor + 1);
     }
   };
@@ -352,6 +405,7 @@ fwd_bf16_kernel(FwdArgs a) {
     score(smem, 1, s1, nothing, first_k(smem, 1), no_tail);
   }
   int T = 0;
+  int id_next = LIST && cursor < t_end ? tlist[cursor] : 0;     // LIST: number of the next tile to copy
   bf16x8 fk;
   bf16x8 fvt = first_vt(smem, 0);                  // handed from phase to phase
   asm volatile("" : "+v"(fvt));                    // (in hand before the loop: both ways into it then agree on what is in flight)
@@ -366,8 +420,10 @@ fwd_bf16_kernel(FwdArgs a) {
     contract_convert(sa, 1, p1, s0, p0, cy, fvt, [&]() __attribute__((always_inline)) { fk = first_k(sb, 1); });
     asm volatile("" : "+v"(fk));
     mid(std::true_type{}, false, sa);
-    const int t_new = cursor;                      // the copies of tile T + 4 go out during the phase
+    // the copies of tile T + 4 go out during the phase (LIST: its number was fetched a tile ago)
+    const int t_new = LIST ? __builtin_amdgcn_readfirstlane(id_next) : cursor;
     cursor = next_tile(cursor + 1);
+    if (LIST) id_next = tlist[cursor < t_end ? cursor : t_begin];
     constexpr int EVERY = QB * KS / NDMA;
     static_assert(EVERY >= 1, "more copies than matrix instructions in the score phase");
     score_convert(sb, 1, s1, s0, p0, cy, fk, [&]() __attribute__((always_inline)) { fvt = first_vt(sb, 0); },
@@ -399,7 +455,7 @@ fwd_bf16_kernel(FwdArgs a) {
     const float lse = l_tot > 0.f ? r[qb] * (1.f / LOG2E) + logf(l_tot) : -INFINITY;
     const int r = r_wave0 + 32 * qb + ql;
     if (r >= rows_kv) continue;
-    const int hq = hk * G + r / d.Sq, i = r % d.Sq;
+    const int hq = PACK ? hq0 + r / d.Sq : hq0, i = PACK ? r % d.Sq : r;
     const long row = ((long)b * d.Hq + hq) * d.Sq + i;
     if (a.n_split > 1 || a.partial) {
       const long slice = (long)(a.part0 + split) * d.B * d.Hq * d.Sq;
@@ -462,12 +518,12 @@ fwd_bf16_kernel(FwdArgs a) {
   }
 }
 
-template <int D>
+template <int D, bool LIST = false>
 hipError_t launch(const FwdArgs& a, long grid, hipStream_t s) {
   static SmemOnce once;
-  const hipError_t e = ensure_dynamic_lds((const void*)fwd_bf16_kernel<D>, KvSmem<D>::TOTAL, &once);
+  const hipError_t e = ensure_dynamic_lds((const void*)fwd_bf16_kernel<D, LIST>, KvSmem<D>::TOTAL, &once);
   if (e != hipSuccess) return e;
-  fwd_bf16_kernel<D><<<(unsigned)grid, 256, KvSmem<D>::TOTAL, s>>>(a);
+  fwd_bf16_kernel<D, LIST><<<(unsigned)grid, 256, KvSmem<D>::TOTAL, s>>>(a);
   return hipGetLastError();
 }
 
@@ -498,8 +554,19 @@ int fwd_bf16_pick_split(const Dims& d, int n_cu, bool masked) {
   return (int)want;
 }
 
+bool fwd_bf16_two_pass_fits(const Dims& d, const MaskDev& m) {
+  // the list and its scratch fit the mask areas of the dense kernel's LDS layout, tiles are whole
+  const int n_tiles = (d.Skv + TN - 1) / TN, w = (d.Skv - 1) / m.kv_block + 1;
+  return m.allow != nullptr && d.Skv % TN == 0 && m.q_chunk >= 8 && n_tiles <= KvSmem<128>::WIN_BYTES / 4 - 1 &&
+         ((w + 1) & ~1) + (n_tiles + 63) / 64 * 2 <= KvSmem<128>::BITS_BYTES / 4;
+}
+
 hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t s) {
   const Dims& d = a.d;
+  if (a.pass == 1) {                               // the dense kernel over the tiles every row of a workgroup sees
+    const long grid = xcd_grid(d.B * d.Hkv, a.n_split * (d.Hq / d.Hkv) * ((d.Sq + QM - 1) / QM));
+    return d.D == 64 ? launch<64, true>(a, grid, s) : launch<128, true>(a, grid, s);
+  }
   if (a.mask.allow != nullptr || d.Skv % TN != 0) return launch_fwd_general_bf16(a, s);
   const int n_qt = (int)(((long)(d.Hq / d.Hkv) * d.Sq + QM - 1) / QM);
   const long grid = xcd_grid(d.B * d.Hkv, a.n_split * n_qt);

@@ -158,7 +158,9 @@ fwd_general_bf16_kernel(FwdArgs a) {
                        (uint8_t*)smem + SM::RING + SM::BITS_BYTES, SM::WIN_BYTES, tid, 64 * NW);
       have_bits = true;
       const int nn = build_bits(bits, n_tiles, tid, 64 * NW, [&](int t) {
-        return mask_rect(mk, b, i_wg0, i_wg1, t * BN, min(d.Skv, t * BN + BN) - 1) != 0;
+        // (pass 2 leaves the tiles that every row of the workgroup sees to the other launch)
+        const int c = mask_rect(mk, b, i_wg0, i_wg1, t * BN, min(d.Skv, t * BN + BN) - 1);
+        return c != 0 && !(a.pass == 2 && c == 1);
       });
       const int k0 = (int)((long)split * nn / a.n_split), k1 = (int)((long)(split + 1) * nn / a.n_split);
       t_begin = nth_bit(bits, k0, n_tiles);
@@ -172,7 +174,10 @@ fwd_general_bf16_kernel(FwdArgs a) {
   auto next_tile = [&](int t) -> int {
     if (mk.allow) {
       if (have_bits) return next_bit(bits, t, t_end);
-      while (t < t_end && mask_rect(mk, b, i_wg0, i_wg1, t * BN, min(d.Skv, t * BN + BN) - 1) == 0) ++t;
+      for (; t < t_end; ++t) {
+        const int c = mask_rect(mk, b, i_wg0, i_wg1, t * BN, min(d.Skv, t * BN + BN) - 1);
+        if (c != 0 && !(a.pass == 2 && c == 1)) break;
+      }
     }
     return __builtin_amdgcn_readfirstlane(min(t, t_end));      // wave-uniform (the bitmap is read through the vector path)
   };

@@ -34,6 +34,9 @@ struct FwdArgs {
   int partial;          // 1: write partial results even with n_split == 1 (this launch is one of several
                         // whose results are combined)
   int part0;            // index of the partial slice that split 0 of this launch writes
+  int pass;             // media mask, bf16: 0 = one launch over every visible tile; 1 = this launch takes the key
+                        // tiles that EVERY row of a workgroup sees (dense kernel over a list of them), 2 = this
+                        // launch takes the other visible tiles (general kernel)
   float* o_part;        // [n_split, B,Hq,Sq,D] float32, contiguous (n_split > 1)
   float* lse_part;      // [n_split, B,Hq,Sq]
 };
@@ -130,6 +133,7 @@ inline int pick_split_balanced(long base, int n_cu, long cap, double t_full, dou
   return best;
 }
 int fwd_bf16_pick_split(const Dims& d, int n_cu, bool masked);
+bool fwd_bf16_two_pass_fits(const Dims& d, const MaskDev& m);   // a masked forward may run as passes 1 and 2
 hipError_t launch_fwd_general_bf16(const FwdArgs& a, hipStream_t s);   // masked or ragged problems
 int bwd_bf16_pick_split(const Dims& d, int n_cu, bool masked);
 // memory-bound helpers

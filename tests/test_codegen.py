@@ -70,7 +70,8 @@ def test_general_dkdv_leaves_half_the_accumulation_file():
 
 
 @pytest.mark.parametrize("src,kernel", [
-    ("lvx_fwd_bf16.hip", "fwd_bf16_kernelILi128EE"),
+    ("lvx_fwd_bf16.hip", "fwd_bf16_kernelILi128ELb0EE"),
+    ("lvx_fwd_bf16.hip", "fwd_bf16_kernelILi128ELb1EE"),     # the same kernel over a list of tiles
     ("lvx_bwd_dq_bf16.hip", "bwd_dq_bf16_kernelILi128ELb1ELb0E"),
 ])
 def test_blocks_with_matrix_instructions_move_no_accumulator(src, kernel):
