@@ -172,7 +172,7 @@ const char* lvx_strerror(lvx_status s) {
     case LVX_ERR_STRIDE: return "invalid or misaligned stride / pointer";
     case LVX_ERR_MASK: return "mask geometry does not cover the problem";
     case LVX_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
-    case LVX_ERR_UNSUPPORTED: return "unsupported head dimension";
+    case LVX_ERR_UNSUPPORTED: return "unsupported head dimension or projection shape";
     case LVX_ERR_HIP: return "HIP launch failed";
   }
   return "unknown status";
