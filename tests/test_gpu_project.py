@@ -73,6 +73,20 @@ def test_project_f32_any_shape():
     check(x, w, outs, 3, "f32", "f32")
 
 
+def test_project_repeats_bit_for_bit():
+    """What the backward pass recomputes must be what the forward pass used: no run-to-run
+    variation (fixed summation order, no atomics)."""
+    from paper_2502_02406_amd import binding as Bn
+    inp = W.projection_inputs(2, 700, 512, 2 * 4 * 128, "bf16", seed=9)
+    x, w = inp["x"].cuda(), inp["w"].cuda()
+    outs = [[torch.empty((2, 4, 700, 128), dtype=torch.bfloat16, device="cuda") for _ in range(2)] for _ in range(2)]
+    Bn.lvx_xattn_project(x, w, outs[0])
+    torch.cuda.synchronize()
+    Bn.lvx_xattn_project(x, w, outs[1])
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+
+
 def test_project_unsupported_shapes_are_refused():
     from paper_2502_02406_amd import binding as Bn
     x = torch.zeros((1, 64, 96), dtype=torch.bfloat16, device="cuda")        # E % 64 != 0
