@@ -226,8 +226,13 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   // They are held as bf16(K * scale * log2 e), so that the accumulation Q K'^T started at -L log2 e
   // is already the exponent of P (Algorithm 2's recomputation P = exp(S - L)) and needs no
   // multiply-add per element; dK uses Q and dS only, so nothing else sees the scaled copy.
+  // Both loads are issued AFTER the first tile copies (load_kv is called there): the three
+  // transfers a workgroup starts with then share one round trip to memory instead of taking one
+  // each.
   const float c2 = d.scale * LOG2E;
   bf16x8 kf[KVB][KS];
+  char* const vres = smem + NSTG * SM::STAGE;
+  auto load_kv = [&]() __attribute__((always_inline)) {
 #pragma unroll
   for (int kb = 0; kb < KVB; ++kb) {
     const int j = j_wave0 + 32 * kb + kl;
@@ -243,7 +248,6 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
     }
   }
   // ---- V rows of the workgroup -> LDS (plain row-major: only read as whole rows)
-  char* const vres = smem + NSTG * SM::STAGE;
   for (int c = tid; c < KN * CPR; c += 256) {
     const int r = c / CPR, col = (c % CPR) * 8, j = j_wg0 + r;
     u32x4 y = {0, 0, 0, 0};
@@ -251,12 +255,13 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
       y = *(const u32x4*)((const uint16_t*)a.v + b * d.kv_sb + hk * d.kv_sh + (long)j * d.kv_ss + col);
     *(u32x4*)(vres + r * SM::P + col * 2) = y;
   }
-  // Finish these loads before the tile copies start: otherwise their first use inside the loop
-  // would make the compiler drain every copy in flight.
+  // Finish these loads here: otherwise their first use inside the loop would make the compiler
+  // drain every copy in flight.
 #pragma unroll
   for (int kb = 0; kb < KVB; ++kb)
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(kf[kb][ks]));
+  };
 
   // ---- tile copies.  In the interleaved tile the logical rows 4 j + w (j = 0..7) of Q occupy the
   // 8 consecutive physical rows 20 w .. 20 w + 7, and those of dO the next 8: a "run" of 8 SPR
@@ -503,6 +508,7 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
       advance(cursor);
     }
   }
+  load_kv();
   wait_vmcnt<0>();
   __syncthreads();                                 // V rows and the first tiles are in LDS
   const char* const vw = vres + (wave * 32 * KVB + kl) * SM::P + g * 16;
