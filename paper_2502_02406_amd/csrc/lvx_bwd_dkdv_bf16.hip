@@ -597,11 +597,17 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
     else
       asm volatile("s_nop 15\n\ts_nop 15" : "+a"(dk[kb][0]), "+a"(dk[kb][1]), "+a"(dv[kb][0]), "+a"(dv[kb][1]));
   }
+  // A lane holds one key row, four columns at a time: stored as they are, every instruction
+  // would touch 32 rows with 16 bytes each.  Each wave turns its rows around through LDS instead
+  // (the ring and the V rows are free once every wave has left the loop) and writes whole
+  // 256-byte rows, 16 bytes per lane.
+  __syncthreads();
+  constexpr int RP = D * 2 + 16;                   // row pitch of the turn-around buffer (padded against bank conflicts)
+  static_assert(NWV * 2 * 32 * KVB * RP <= SM::RING, "the turn-around buffers fit the ring and V area");
+  char* const tk = smem + wave * (2 * 32 * KVB * RP);
+  char* const tv = tk + 32 * KVB * RP;
 #pragma unroll
-  for (int kb = 0; kb < KVB; ++kb) {
-    const int j = j_wave0 + 32 * kb + kl;
-    if (j >= d.Skv) continue;
-    const long off = b * d.kv_sb + hk * d.kv_sh + (long)j * d.kv_ss;
+  for (int kb = 0; kb < KVB; ++kb)
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -611,9 +617,22 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
                     pack2_bf16(dk[kb][db][4 * q4 + 2] * d.scale, dk[kb][db][4 * q4 + 3] * d.scale)};
         u32x2 yv = {pack2_bf16(dv[kb][db][4 * q4], dv[kb][db][4 * q4 + 1]),
                     pack2_bf16(dv[kb][db][4 * q4 + 2], dv[kb][db][4 * q4 + 3])};
-        *(u32x2*)((uint16_t*)a.dk + off + col) = yk;
-        *(u32x2*)((uint16_t*)a.dv + off + col) = yv;
+        *(u32x2*)(tk + (32 * kb + kl) * RP + col * 2) = yk;
+        *(u32x2*)(tv + (32 * kb + kl) * RP + col * 2) = yv;
       }
+  // (each wave reads back only what it wrote itself: no barrier, the LDS queue keeps the order)
+  constexpr int LPR = D / 8;                       // lanes per row, eight bf16 each
+  constexpr int RPI = 64 / LPR;                    // rows per instruction
+  const int rsub = lane / LPR, cb = (lane % LPR) * 16;
+#pragma unroll 4
+  for (int r0 = 0; r0 < 32 * KVB; r0 += RPI) {
+    const int r = r0 + rsub, j = j_wave0 + r;
+    const u32x4 yk = *(const u32x4*)(tk + r * RP + cb);
+    const u32x4 yv = *(const u32x4*)(tv + r * RP + cb);
+    if (j >= d.Skv) continue;
+    const long off = (b * d.kv_sb + hk * d.kv_sh + (long)j * d.kv_ss) * 2 + cb;
+    *(u32x4*)((char*)a.dk + off) = yk;
+    *(u32x4*)((char*)a.dv + off) = yv;
   }
 }
 
