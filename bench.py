@@ -33,7 +33,7 @@ PEAK_HBM_GBS = 8000.0
 # workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file scaled by what the same
 # counters read for a plain copy of known size (profiles/bench_c3_longvideo_256k_hbm_traffic.md).
 # Counters cannot be read from inside this process, so the figures are carried here.
-MEASURED_HBM_BYTES = {"bwd_dkdv": int((258.5 + 142.9) * 2**20), "bwd_dq": int((192.9 + 32.0) * 2**20),
+MEASURED_HBM_BYTES = {"bwd_dkdv": int((258.5 + 128.0) * 2**20), "bwd_dq": int((192.9 + 32.0) * 2**20),
                       "fwd": int((167.0 + 32.3) * 2**20)}
 
 
