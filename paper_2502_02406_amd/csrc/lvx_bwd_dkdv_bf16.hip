@@ -224,7 +224,7 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
 
   // ---- K operands of this wave's keys: lane holds key j_wave0 + 32 kb + kl, columns 16 ks + 8 g ..
   // They are held as bf16(K * scale * log2 e), so that the accumulation Q K'^T started at -L log2 e
-  // is already the exponent of P (Algorithm 2's recomputation P = exp(S - L)) and needs no
+  // is already the exponent of P (Section 3.2's recomputation, P = exp(S - L)) and needs no
   // multiply-add per element; dK uses Q and dS only, so nothing else sees the scaled copy.
   // Both loads are issued AFTER the first tile copies (load_kv is called there): the three
   // transfers a workgroup starts with then share one round trip to memory instead of taking one
@@ -233,28 +233,47 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   bf16x8 kf[KVB][KS];
   char* const vres = smem + NSTG * SM::STAGE;
   auto load_kv = [&]() __attribute__((always_inline)) {
+    // A lane needs ITS key row (16 bytes of it per k-step): fetched directly, every load
+    // instruction would touch 32 rows with 32 bytes each, half a memory line per request.  Each
+    // wave fetches its rows whole instead (16 lanes per 256-byte row), parks them in the part of
+    // the V area that its own rows will occupy, and reads its operands back from there; the V
+    // rows, fetched meanwhile, are stored once every wave has its K operands.
+    constexpr int WR = 32 * KVB;                   // key rows of a wave
+    char* const kst = vres + wave * WR * SM::P;
 #pragma unroll
-  for (int kb = 0; kb < KVB; ++kb) {
-    const int j = j_wave0 + 32 * kb + kl;
-    const long off = b * d.kv_sb + hk * d.kv_sh + (long)j * d.kv_ss;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
+    for (int it = 0; it < WR * CPR / 64; ++it) {
+      const int c = it * 64 + lane, r = c / CPR, col = (c % CPR) * 8, j = j_wave0 + r;
       u32x4 x = {0, 0, 0, 0};
-      if (j < d.Skv) x = *(const u32x4*)((const uint16_t*)a.k + off + 16 * ks + 8 * g);
-#pragma unroll
-      for (int w = 0; w < 4; ++w)
-        x[w] = pack2_bf16(__uint_as_float(x[w] << 16) * c2, __uint_as_float(x[w] & 0xffff0000u) * c2);
-      kf[kb][ks] = __builtin_bit_cast(bf16x8, x);
+      if (j < d.Skv)
+        x = *(const u32x4*)((const uint16_t*)a.k + b * d.kv_sb + hk * d.kv_sh + (long)j * d.kv_ss + col);
+      *(u32x4*)(kst + r * SM::P + col * 2) = x;
     }
-  }
-  // ---- V rows of the workgroup -> LDS (plain row-major: only read as whole rows)
-  for (int c = tid; c < KN * CPR; c += 256) {
-    const int r = c / CPR, col = (c % CPR) * 8, j = j_wg0 + r;
-    u32x4 y = {0, 0, 0, 0};
-    if (j < d.Skv)
-      y = *(const u32x4*)((const uint16_t*)a.v + b * d.kv_sb + hk * d.kv_sh + (long)j * d.kv_ss + col);
-    *(u32x4*)(vres + r * SM::P + col * 2) = y;
-  }
+    // ---- V rows of the workgroup -> LDS (plain row-major: only read as whole rows)
+    constexpr int VIT = KN * CPR / 256;
+    u32x4 vy[VIT];
+#pragma unroll
+    for (int it = 0; it < VIT; ++it) {
+      const int c = it * 256 + tid, r = c / CPR, col = (c % CPR) * 8, j = j_wg0 + r;
+      vy[it] = u32x4{0, 0, 0, 0};
+      if (j < d.Skv)
+        vy[it] = *(const u32x4*)((const uint16_t*)a.v + b * d.kv_sb + hk * d.kv_sh + (long)j * d.kv_ss + col);
+    }
+#pragma unroll
+    for (int kb = 0; kb < KVB; ++kb)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        u32x4 x = *(const u32x4*)(kst + (32 * kb + kl) * SM::P + (16 * ks + 8 * g) * 2);
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+          x[w] = pack2_bf16(__uint_as_float(x[w] << 16) * c2, __uint_as_float(x[w] & 0xffff0000u) * c2);
+        kf[kb][ks] = __builtin_bit_cast(bf16x8, x);
+      }
+    __syncthreads();                               // every wave has read its K rows back
+#pragma unroll
+    for (int it = 0; it < VIT; ++it) {
+      const int c = it * 256 + tid, r = c / CPR, col = (c % CPR) * 8;
+      *(u32x4*)(vres + r * SM::P + col * 2) = vy[it];
+    }
   // Finish these loads here: otherwise their first use inside the loop would make the compiler
   // drain every copy in flight.
 #pragma unroll
