@@ -80,6 +80,10 @@ WORKLOADS: Dict[str, Workload] = {
                                 dtype="bf16", std=0.5, note="text side as long as half the visual side"),
     "x2_d64_sq8k_skv256k": Workload("x2_d64_sq8k_skv256k", B=1, Hq=32, Hkv=8, D=64, Sq=8192, Skv=262144,
                                     dtype="bf16", std=0.5, n_blocks=4, note="64-wide heads, 4 blocks of 65536"),
+    "x4_ragged_5514x64040": Workload("x4_ragged_5514x64040", B=1, Hq=32, Hkv=8, D=128, Sq=5514, Skv=64040,
+                                     dtype="bf16", std=0.5, n_blocks=2,
+                                     note="sizes that are no tile multiples: the paper's Video-MME text length, "
+                                          "ten frames of 6404 visual tokens in two blocks"),
     "x3_sq65k_skv8k": Workload("x3_sq65k_skv8k", B=1, Hq=32, Hkv=8, D=128, Sq=65536, Skv=8192,
                                dtype="bf16", std=0.5, note="text side longer than the visual side"),
 }

@@ -26,7 +26,7 @@ def rel(x, ref):
 
 
 @pytest.mark.parametrize("name", ["c2_llama_64k", "c3_longvideo_256k", "c4_flamingo_masked",
-                                  "c5_extreme_1m"])
+                                  "c5_extreme_1m", "x4_ragged_5514x64040"])
 def test_full_size_sampled_parity(name):
     from paper_2502_02406_amd.blockloop import BlockLoop, MediaMask
     w = W.WORKLOADS[name]
