@@ -19,8 +19,11 @@
  *     live in HOST memory and are read before the call returns.
  *   - Errors are returned as negative lvx_status values; argument errors are
  *     detected on the host before anything is launched.  No exceptions, no aborts.
- *   - No global state; calls on different streams may run concurrently as long
- *     as their buffers do not overlap.
+ *   - The library keeps no state between calls that a result depends on (it only
+ *     caches, per device, the number of compute units and which kernels have had
+ *     their LDS limit raised; lvx_xattn_fwd_static is the one exception and says
+ *     so).  Calls on different streams may run concurrently as long as their
+ *     buffers do not overlap.
  *
  * Tensor layout (all strides in ELEMENTS, innermost dimension D contiguous)
  *   Q, O, dO, dQ : [B, Hq,  Sq,  D]   strides q_sb, q_sh, q_ss
@@ -93,6 +96,19 @@ size_t lvx_xattn_workspace_bytes(const lvx_problem* p, lvx_dtype dtype, int whic
 lvx_status lvx_xattn_fwd(const lvx_problem* p, lvx_dtype dtype, const void* q, const void* k,
                          const void* v, const lvx_mask* mask, void* o, lvx_dtype o_dtype,
                          float* lse, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* lvx_xattn_fwd for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, result and kernels as
+ * lvx_xattn_fwd, but no workspace: the KV splits' partial results go into a device array of
+ * LVX_STATIC_SCRATCH_BYTES that the library holds on every GPU it runs on until the process ends.
+ * Problems whose lvx_xattn_workspace_bytes(p, dtype, LVX_WS_FWD) exceeds that size are refused with
+ * LVX_ERR_WORKSPACE before anything is launched.  Allocates nothing.  The stream must belong to
+ * the current device.  Every call on a GPU shares that GPU's array: two calls that overlap in
+ * time on one GPU (different streams, or different host threads) race; calls on one stream do not. */
+enum { LVX_STATIC_SCRATCH_BYTES = 64 << 20 };
+lvx_status lvx_xattn_fwd_static(const lvx_problem* p, lvx_dtype dtype, const void* q, const void* k,
+                                const void* v, const lvx_mask* mask, void* o, lvx_dtype o_dtype,
+                                float* lse, void* hip_stream);
 
 /* Rescale of Algorithm 1, for n_parts >= 1 partial results of the same query block:
  *   L' = ln sum_k exp(L_k),   O' = sum_k exp(L_k - L') O_k        (all L_k = -inf -> O' = 0, L' = -inf)

@@ -21,7 +21,9 @@ LVX_MAX_PARTS = 64
 
 LVX_BWD_DELTA, LVX_BWD_DKDV, LVX_BWD_DQ, LVX_BWD_ALL = 1, 2, 4, 7
 
-EXPORTS = ("lvx_xattn_workspace_bytes", "lvx_xattn_fwd", "lvx_xattn_fwd_merge", "lvx_xattn_merge", "lvx_xattn_bwd",
+LVX_STATIC_SCRATCH_BYTES = 64 << 20
+
+EXPORTS = ("lvx_xattn_workspace_bytes", "lvx_xattn_fwd", "lvx_xattn_fwd_static", "lvx_xattn_fwd_merge", "lvx_xattn_merge", "lvx_xattn_bwd",
            "lvx_xattn_bwd_stages", "lvx_xattn_dq_finalize", "lvx_xattn_project", "lvx_strerror")
 
 
@@ -67,6 +69,8 @@ def load() -> C.CDLL:
         lib.lvx_xattn_fwd.argtypes = [C.POINTER(lvx_problem), C.c_int, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.POINTER(lvx_mask), C.c_void_p, C.c_int,
                                       C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.lvx_xattn_fwd_static.restype = C.c_int
+        lib.lvx_xattn_fwd_static.argtypes = lib.lvx_xattn_fwd.argtypes[:9] + [C.c_void_p]
         lib.lvx_xattn_fwd_merge.restype = C.c_int
         lib.lvx_xattn_fwd_merge.argtypes = [C.POINTER(lvx_problem), C.c_int, C.c_void_p, C.c_void_p,
                                             C.c_void_p, C.POINTER(lvx_mask), C.c_void_p, C.c_void_p,
@@ -156,6 +160,16 @@ def lvx_xattn_fwd(p: lvx_problem, q, k, v, mask: Optional[lvx_mask], o, lse, wor
                                 workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                 _stream())
     _check(code, "lvx_xattn_fwd")
+
+
+def lvx_xattn_fwd_static(p: lvx_problem, q, k, v, mask: Optional[lvx_mask], o, lse) -> None:
+    """lvx_xattn_fwd without a workspace: scratch is the library's own fixed device array."""
+    if not q.is_cuda:
+        raise RuntimeError("lvx_xattn_fwd_static needs device tensors")
+    code = load().lvx_xattn_fwd_static(C.byref(p), dtype_code(q.dtype), q.data_ptr(), k.data_ptr(),
+                                       v.data_ptr(), C.byref(mask) if mask is not None else None,
+                                       o.data_ptr(), dtype_code(o.dtype), lse.data_ptr(), _stream())
+    _check(code, "lvx_xattn_fwd_static")
 
 
 def lvx_xattn_fwd_merge(p: lvx_problem, q, k, v, mask: Optional[lvx_mask], o_acc, lse_acc, workspace) -> None:

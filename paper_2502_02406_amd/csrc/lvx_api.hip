@@ -132,6 +132,21 @@ hipError_t launch_fwd_bf16_two_pass(FwdArgs a, hipStream_t s) {
   return launch_fwd_bf16(a, s);
 }
 
+// How lvx_xattn_fwd runs a problem: the KV splits of each launch, whether a ragged tail or a media
+// mask makes it two launches, and the partial results the combine then reads.
+struct FwdPlan { int n_split; bool tail, two; int n_parts; };
+FwdPlan fwd_plan(const Dims& d, lvx_dtype dtype, const MaskDev& m) {
+  const bool masked = m.allow != nullptr;
+  FwdPlan f;
+  f.n_split = fwd_split(d, dtype, masked);
+  f.tail = fwd_has_tail(d, dtype, masked);
+  f.two = masked && fwd_two_pass(d, dtype, m);
+  if (f.tail && f.n_split > LVX_MAX_PARTS - 1) f.n_split = LVX_MAX_PARTS - 1;
+  if (f.two) f.n_split = fwd_two_pass_split(f.n_split, 0);
+  f.n_parts = f.two ? 2 * f.n_split : f.n_split + (f.tail ? 1 : 0);
+  return f;
+}
+
 size_t fwd_ws(const Dims& d, int n_split) {
   if (n_split <= 1) return ALIGN;   // never zero, so that a valid workspace pointer is always passed
   const size_t rows = (size_t)d.B * d.Hq * d.Sq;
@@ -160,6 +175,14 @@ size_t bwd_ws(const Dims& d, int n_split) {   // ... + the dQ kernel's partial s
 }
 
 }  // namespace
+
+namespace lvx {
+size_t fwd_workspace_need(const lvx_problem* p, lvx_dtype dtype, const lvx_mask* mask) {
+  if (check_problem(p, dtype) != LVX_OK || check_mask(p, mask) != LVX_OK) return 0;
+  const Dims d = make_dims(p);
+  return fwd_ws(d, fwd_plan(d, dtype, make_mask(mask)).n_parts);
+}
+}  // namespace lvx
 
 extern "C" {
 
@@ -213,12 +236,10 @@ lvx_status lvx_xattn_fwd(const lvx_problem* p, lvx_dtype dtype, const void* q, c
   a.q = q; a.k = k; a.v = v; a.o = o; a.o_is_f32 = o_dtype == LVX_F32; a.lse = lse;
   a.merge_into = 0;
   a.partial = 0; a.part0 = 0; a.pass = 0;
-  a.n_split = fwd_split(a.d, dtype, mask != nullptr);
-  const bool tail = fwd_has_tail(a.d, dtype, mask != nullptr);
-  const bool two = mask != nullptr && fwd_two_pass(a.d, dtype, a.mask);
-  if (tail && a.n_split > LVX_MAX_PARTS - 1) a.n_split = LVX_MAX_PARTS - 1;
-  if (two) a.n_split = fwd_two_pass_split(a.n_split, 0);
-  const int n_parts = two ? 2 * a.n_split : a.n_split + (tail ? 1 : 0);
+  const FwdPlan plan = fwd_plan(a.d, dtype, a.mask);
+  a.n_split = plan.n_split;
+  const bool tail = plan.tail, two = plan.two;
+  const int n_parts = plan.n_parts;
   a.o_part = nullptr; a.lse_part = nullptr;
   const size_t need = fwd_ws(a.d, n_parts);
   if (!workspace || ((uintptr_t)workspace % ALIGN) != 0 || workspace_bytes < need) return LVX_ERR_WORKSPACE;
@@ -345,7 +366,6 @@ lvx_status lvx_xattn_bwd_stages(const lvx_problem* p, lvx_dtype dtype, const voi
   lvx_status st = check_problem(p, dtype);
   if (st != LVX_OK) return st;
   if (stages == 0 || (stages & ~(unsigned)LVX_BWD_ALL)) return LVX_ERR_SHAPE;
-  if (st != LVX_OK) return st;
   if (!q || !k || !v || !o || !lse || !d_o || !dq_accum || !dk || !dv) return LVX_ERR_NULL;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) ||
       !aligned16(dq_accum) || !aligned16(dk) || !aligned16(dv))

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "../../include/lvx.h"
+
 namespace lvx {
 
 // Media mask as the kernels see it (allow == nullptr means dense attention).
@@ -88,6 +90,10 @@ struct ProjArgs {
 };
 bool project_bf16_supported(const ProjArgs& a);   // shapes the matrix-core kernel takes
 hipError_t launch_project(const ProjArgs& a, int is_f32, hipStream_t s);
+
+// Bytes of workspace that lvx_xattn_fwd needs for exactly this call (with this mask or without
+// one; lvx_xattn_workspace_bytes returns the larger of the two cases); 0 for invalid arguments.
+size_t fwd_workspace_need(const lvx_problem* p, lvx_dtype dtype, const lvx_mask* mask);
 
 // kernels for float32 tensors (plain FMA, correctness-grade)
 hipError_t launch_fwd_f32(const FwdArgs& a, hipStream_t s);

@@ -187,3 +187,15 @@ def test_binding_refuses_cpu_tensors():
     from paper_2502_02406_amd.blockloop import BlockLoop
     with pytest.raises(RuntimeError):
         BlockLoop((1, 2, 8, 128), (1, 2, 64, 128), torch.bfloat16)
+
+
+def test_static_scratch_forward_refuses_what_does_not_fit(lib):
+    """lvx_xattn_fwd_static turns down, before any HIP call, a problem whose split-KV partial results
+    exceed its fixed array; bad arguments get the same codes as from lvx_xattn_fwd."""
+    p = problem(Hq=64, Hkv=8, Sq=700, Skv=1 << 20)
+    assert B.lvx_xattn_workspace_bytes(p, B.LVX_BF16, B.LVX_WS_FWD) > B.LVX_STATIC_SCRATCH_BYTES
+    call = lambda pp, q=FAKE: lib.lvx_xattn_fwd_static(C.byref(pp), B.LVX_BF16, q, FAKE, FAKE, None, FAKE,
+                                                       B.LVX_BF16, FAKE, None)
+    assert call(p) == -6
+    text = open(os.path.join(ROOT, "include", "lvx.h")).read()
+    assert re.search(r"LVX_STATIC_SCRATCH_BYTES\s*=\s*64\s*<<\s*20", text) and B.LVX_STATIC_SCRATCH_BYTES == 64 << 20
