@@ -211,7 +211,7 @@ def main():
     # with the transfers of LV-XAttn (Q, running O, L) or of Ring Attention (K, V) on one link
     from dataclasses import asdict
     from paper_2502_02406_amd import runtime_model as RM
-    out["model"] = {"f_ms": ms_fwd, "note": "per-round max(f, comm) of Equations 2 and 3 with the measured forward visit; "
+    out["model"] = {"f_ms": ms_fwd, "note": "per-round max(f, comm) of Equations 1 and 2 with the measured forward visit; "
                                             "one xGMI link, and the paper's two slower interconnects",
                     "rounds": [asdict(RM.predict_forward_round(ms_fwd, w.Sq, blk, w.D, w.Hq, w.Hkv, name, gbs))
                                for name, gbs in (("xgmi_link", 153.0), ("net_25GBs", 25.0), ("net_1.25GBs", 1.25))],

@@ -149,7 +149,8 @@ lvx_status lvx_xattn_bwd(const lvx_problem* p, lvx_dtype dtype, const void* q, c
                          const lvx_mask* mask, float* dq_accum, void* dk, void* dv,
                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* The same call restricted to some of its kernels, for measurement: `stages` is a bit set of
+/* MEASUREMENT ONLY (not part of the method's interface; bench.py times single kernels with it):
+ * the same call restricted to some of its kernels.  `stages` is a bit set of
  * LVX_BWD_DELTA (delta = rowsum(dO * O) into the workspace), LVX_BWD_DKDV (dK and dV) and
  * LVX_BWD_DQ (dQ accumulation).  DKDV and DQ read the delta a previous DELTA stage left in the
  * same workspace.  lvx_xattn_bwd is this call with LVX_BWD_ALL. */

@@ -1,4 +1,4 @@
-"""The paper's analytic runtime model (Section 3.1, "Runtime Analysis"; Equations 2 and 3; Table 1),
+"""The paper's analytic runtime model (Section 3.1, "Runtime Analysis"; Equations 1 and 2; Table 1),
 as plain host arithmetic.  Nothing here touches the GPU: bench.py feeds it the measured time of
 one visit (the kernel on one worker's K/V share) and prints what the model predicts per round
 for a given link bandwidth.
@@ -15,13 +15,13 @@ from dataclasses import dataclass
 
 
 def lvxattn_round_elements(sq_per_worker: int, d: int, h: int = 1) -> int:
-    """Elements a worker of LV-XAttn sends per round (Equation 2): Q_j and O_j, S_Q/n x d each,
+    """Elements a worker of LV-XAttn sends per round (Equation 1): Q_j and O_j, S_Q/n x d each,
     and L_j, S_Q/n, for each of the h heads."""
     return h * (2 * sq_per_worker * d + sq_per_worker)
 
 
 def ring_round_elements(skv_per_worker: int, d: int, h: int = 1) -> int:
-    """Elements a worker of Ring Attention sends per round (Equation 3): K_i and V_i, S_KV/n x d
+    """Elements a worker of Ring Attention sends per round (Equation 2): K_i and V_i, S_KV/n x d
     each, for each of the h heads."""
     return h * 2 * skv_per_worker * d
 
@@ -33,7 +33,7 @@ def volume_ratio(sq: int, skv: int, d: int) -> float:
 
 
 def round_time(f_seconds: float, comm_bytes: float, bandwidth_bytes_per_s: float) -> float:
-    """max(f, comm): the transfer of a round overlaps its attention (Equations 2 and 3)."""
+    """max(f, comm): the transfer of a round overlaps its attention (Equations 1 and 2)."""
     return max(f_seconds, comm_bytes / bandwidth_bytes_per_s)
 
 

@@ -1,4 +1,4 @@
-"""The analytic runtime model (Section 3.1: Equations 2 and 3, Table 1) against what the paper
+"""The analytic runtime model (Section 3.1: Equations 1 and 2, Table 1) against what the paper
 prints and against the table's own algebra."""
 import os
 
