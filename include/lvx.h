@@ -154,12 +154,25 @@ lvx_status lvx_xattn_bwd(const lvx_problem* p, lvx_dtype dtype, const void* q, c
  * LVX_BWD_DELTA (delta = rowsum(dO * O) into the workspace), LVX_BWD_DKDV (dK and dV) and
  * LVX_BWD_DQ (dQ accumulation).  DKDV and DQ read the delta a previous DELTA stage left in the
  * same workspace.  lvx_xattn_bwd is this call with LVX_BWD_ALL. */
-enum { LVX_BWD_DELTA = 1, LVX_BWD_DKDV = 2, LVX_BWD_DQ = 4, LVX_BWD_ALL = 7 };
+enum { LVX_BWD_DELTA = 1, LVX_BWD_DKDV = 2, LVX_BWD_DQ = 4, LVX_BWD_ALL = 7,
+       /* with DKDV and DQ both set: form all five products in ONE kernel where the problem allows it
+        * (dense bf16, D = 128, at least 256 keys and 32 query rows), or never; neither = the library's choice */
+       LVX_BWD_FUSED = 8, LVX_BWD_SPLIT = 16 };
 lvx_status lvx_xattn_bwd_stages(const lvx_problem* p, lvx_dtype dtype, const void* q, const void* k,
                                 const void* v, const void* o, const float* lse, const void* d_o,
                                 const lvx_mask* mask, float* dq_accum, void* dk, void* dv,
                                 void* workspace, size_t workspace_bytes, void* hip_stream,
                                 unsigned stages);
+
+/* Where lvx_xattn_bwd reports that it could not finish dQ.  For dense bf16 problems with D = 128 the
+ * backward forms all five products of Table 1 in one kernel whose workgroups add their dQ tiles
+ * into one array under per-tile locks; a wave that cannot get a lock within a bounded number of
+ * tries (which takes another wave that never releases one: a fault, not load) gives up, so that
+ * the kernel always ends, and sets a word in the workspace.  *word receives the DEVICE address of
+ * that word for a call with these arguments and this workspace (NULL when the call uses no such
+ * kernel); it is 0 after a call whose dQ is complete.  Read it after synchronising the stream. */
+lvx_status lvx_xattn_bwd_error_word(const lvx_problem* p, lvx_dtype dtype, const lvx_mask* mask,
+                                    void* workspace, size_t workspace_bytes, const int** word);
 
 /* dq (type `dtype`, Q's strides) = dq_accum (float32, contiguous) rounded to `dtype`. */
 lvx_status lvx_xattn_dq_finalize(const lvx_problem* p, const float* dq_accum, void* dq,

@@ -20,11 +20,12 @@ LVX_WS_FWD, LVX_WS_BWD, LVX_WS_FWD_MERGE = 0, 1, 2
 LVX_MAX_PARTS = 64
 
 LVX_BWD_DELTA, LVX_BWD_DKDV, LVX_BWD_DQ, LVX_BWD_ALL = 1, 2, 4, 7
+LVX_BWD_FUSED, LVX_BWD_SPLIT = 8, 16
 
 LVX_STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = ("lvx_xattn_workspace_bytes", "lvx_xattn_fwd", "lvx_xattn_fwd_static", "lvx_xattn_fwd_merge", "lvx_xattn_merge", "lvx_xattn_bwd",
-           "lvx_xattn_bwd_stages", "lvx_xattn_dq_finalize", "lvx_xattn_project", "lvx_strerror")
+           "lvx_xattn_bwd_stages", "lvx_xattn_bwd_error_word", "lvx_xattn_dq_finalize", "lvx_xattn_project", "lvx_strerror")
 
 
 class LvxError(RuntimeError):
@@ -86,6 +87,9 @@ def load() -> C.CDLL:
                                       C.c_void_p, C.c_size_t, C.c_void_p]
         lib.lvx_xattn_bwd_stages.restype = C.c_int
         lib.lvx_xattn_bwd_stages.argtypes = lib.lvx_xattn_bwd.argtypes + [C.c_uint]
+        lib.lvx_xattn_bwd_error_word.restype = C.c_int
+        lib.lvx_xattn_bwd_error_word.argtypes = [C.POINTER(lvx_problem), C.c_int, C.POINTER(lvx_mask), C.c_void_p,
+                                                 C.c_size_t, C.POINTER(C.c_void_p)]
         lib.lvx_xattn_dq_finalize.restype = C.c_int
         lib.lvx_xattn_dq_finalize.argtypes = [C.POINTER(lvx_problem), C.c_void_p, C.c_void_p,
                                               C.c_int, C.c_void_p]
@@ -220,6 +224,17 @@ def lvx_xattn_bwd(p: lvx_problem, q, k, v, o, lse, d_o, mask: Optional[lvx_mask]
         _check(load().lvx_xattn_bwd(*args), "lvx_xattn_bwd")
     else:
         _check(load().lvx_xattn_bwd_stages(*args, stages), "lvx_xattn_bwd_stages")
+
+
+def lvx_xattn_bwd_error_word(p: lvx_problem, dtype: int, mask: Optional[lvx_mask], workspace) -> int:
+    """Device address (0 if none) of the word that a backward call with these arguments sets when
+    it could not finish dQ."""
+    out = C.c_void_p()
+    code = load().lvx_xattn_bwd_error_word(C.byref(p), dtype, C.byref(mask) if mask is not None else None,
+                                           workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                           C.byref(out))
+    _check(code, "lvx_xattn_bwd_error_word")
+    return int(out.value or 0)
 
 
 def lvx_xattn_dq_finalize(p: lvx_problem, dq_accum, dq) -> None:

@@ -33,7 +33,7 @@ class MediaMask:
 class BlockLoop:
     def __init__(self, q_shape, kv_shape, dtype: torch.dtype, n_blocks: int = 1,
                  mask: Optional[MediaMask] = None, softmax_scale: float = 0.0,
-                 device: str = "cuda"):
+                 device: str = "cuda", bwd_flags: int = 0):
         if not torch.cuda.is_available():
             raise RuntimeError("BlockLoop needs a GPU: there is no CPU fallback")
         B.load()
@@ -41,6 +41,7 @@ class BlockLoop:
         _, self.Hkv, self.Skv, _ = kv_shape
         assert self.Skv % n_blocks == 0, "blocks must be equal (the paper's Skv/n)"
         self.n_blocks = n_blocks
+        self.bwd_flags = bwd_flags      # B.LVX_BWD_FUSED / B.LVX_BWD_SPLIT: which backward kernels (0: the library's choice)
         self.blk = self.Skv // n_blocks
         if mask is not None and n_blocks > 1:
             assert self.blk % mask.kv_block == 0, "block boundaries must fall on mask blocks"
@@ -100,7 +101,7 @@ class BlockLoop:
             p = B.make_problem(q, kb, self.scale)
             # delta = rowsum(dO * O) depends on the query block only: the first visit computes it
             # into the workspace, the others reuse it
-            stages = B.LVX_BWD_ALL if n == 0 else (B.LVX_BWD_DKDV | B.LVX_BWD_DQ)
+            stages = (B.LVX_BWD_ALL if n == 0 else (B.LVX_BWD_DKDV | B.LVX_BWD_DQ)) | self.bwd_flags
             B.lvx_xattn_bwd(p, q, kb, vb, o, lse, d_o, self._mask_for(n), self.dq_accum,
                             dk[:, :, sl], dv[:, :, sl], self.ws, stages)
         p = B.make_problem(q, k, self.scale)

@@ -33,7 +33,11 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
 # register file; there the compiler would by default put every matrix-instruction result into the
 # accumulation registers, including the scores that the vector ALU consumes next.  Its own
 # accumulators are pinned to that file in the source, everything else stays in ordinary registers.
-FILE_FLAGS = {"lvx_bwd_dkdv_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+FILE_FLAGS = {"lvx_bwd_dkdv_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+              # (its contraction phase is one unrolled run of 48 matrix instructions with the vector work
+              # of a step between them: larger than what the unroll pragma accepts by default)
+              "lvx_bwd_fused_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1",
+                                         "-mllvm", "-pragma-unroll-threshold=200000"]}
 
 
 def _compile(src: str, force: bool, extra) -> str:

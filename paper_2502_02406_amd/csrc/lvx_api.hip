@@ -11,6 +11,7 @@ using namespace lvx;
 namespace {
 
 constexpr size_t ALIGN = 256;
+constexpr bool FUSED_BY_DEFAULT = false;   // lvx_xattn_bwd: one fused kernel where it applies, else dK/dV + dQ kernels
 inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
 int device_cu_count() {
@@ -169,9 +170,11 @@ size_t bwd_ws_fixed(const Dims& d) {   // delta [B,Hq,Sq] + padded statistics [B
   return align_up((size_t)d.B * d.Hq * d.Sq * sizeof(float)) +
          align_up((stats_floats(d) + (has_stats_ovl(d) ? (size_t)d.B * d.Hq * 64 : 0)) * sizeof(float));
 }
-size_t bwd_ws(const Dims& d, int n_split) {   // ... + the dQ kernel's partial sums [n_split, B,Hq,Sq,D] when it splits
-  const size_t part = n_split > 1 ? align_up((size_t)n_split * d.B * d.Hq * d.Sq * d.D * sizeof(float)) : 0;
-  return bwd_ws_fixed(d) + part;
+size_t bwd_ws_part(const Dims& d, int n_split) {   // the dQ kernel's partial sums [n_split, B,Hq,Sq,D] when it splits
+  return n_split > 1 ? align_up((size_t)n_split * d.B * d.Hq * d.Sq * d.D * sizeof(float)) : 0;
+}
+size_t bwd_ws(const Dims& d, int n_split, bool fused) {   // ... + the fused kernel's dQ tiles and locks
+  return bwd_ws_fixed(d) + bwd_ws_part(d, n_split) + (fused ? align_up(bwd_fused_ws_bytes(d)) : 0);
 }
 
 }  // namespace
@@ -211,7 +214,9 @@ size_t lvx_xattn_workspace_bytes(const lvx_problem* p, lvx_dtype dtype, int whic
   const int masked_parts = dtype == LVX_BF16 ? 2 * fwd_two_pass_split(fwd_split(d, dtype, true), 0) : fwd_split(d, dtype, true);
   if (which == LVX_WS_FWD)
     return fwd_ws(d, larger(larger(masked_parts, fwd_split(d, dtype, true)), fwd_split(d, dtype, false) + tail_part));
-  if (which == LVX_WS_BWD) return bwd_ws(d, larger(bwd_split(d, dtype, true), bwd_split(d, dtype, false)));
+  if (which == LVX_WS_BWD)
+    return bwd_ws(d, larger(bwd_split(d, dtype, true), bwd_split(d, dtype, false)),
+                  dtype == LVX_BF16 && bwd_fused_bf16_supported(d, false));
   if (which == LVX_WS_FWD_MERGE)
   {
     const int masked_merge = dtype == LVX_BF16 ? 2 * fwd_two_pass_split(fwd_merge_split(d, dtype, true), 1) : 1;
@@ -365,7 +370,8 @@ lvx_status lvx_xattn_bwd_stages(const lvx_problem* p, lvx_dtype dtype, const voi
                                 unsigned stages) {
   lvx_status st = check_problem(p, dtype);
   if (st != LVX_OK) return st;
-  if (stages == 0 || (stages & ~(unsigned)LVX_BWD_ALL)) return LVX_ERR_SHAPE;
+  if ((stages & LVX_BWD_ALL) == 0 || (stages & ~(unsigned)(LVX_BWD_ALL | LVX_BWD_FUSED | LVX_BWD_SPLIT))) return LVX_ERR_SHAPE;
+  if ((stages & LVX_BWD_FUSED) && (stages & LVX_BWD_SPLIT)) return LVX_ERR_SHAPE;
   if (!q || !k || !v || !o || !lse || !d_o || !dq_accum || !dk || !dv) return LVX_ERR_NULL;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) ||
       !aligned16(dq_accum) || !aligned16(dk) || !aligned16(dv))
@@ -376,7 +382,12 @@ lvx_status lvx_xattn_bwd_stages(const lvx_problem* p, lvx_dtype dtype, const voi
   a.mask = make_mask(mask);
   a.n_split_dq = bwd_split(a.d, dtype, mask != nullptr);
   a.dq_pass = 0;
-  const size_t need = bwd_ws(a.d, a.n_split_dq);
+  // the kernel that forms all five products at once: where it applies, unless the caller asks for
+  // the two-kernel form (or only for one of the two kernels)
+  const bool can_fuse = dtype == LVX_BF16 && bwd_fused_bf16_supported(a.d, mask != nullptr);
+  const bool want_fuse = (stages & LVX_BWD_FUSED) || (FUSED_BY_DEFAULT && !(stages & LVX_BWD_SPLIT));
+  const bool fused = can_fuse && want_fuse && (stages & (LVX_BWD_DKDV | LVX_BWD_DQ)) == (LVX_BWD_DKDV | LVX_BWD_DQ);
+  const size_t need = bwd_ws(a.d, a.n_split_dq, can_fuse);
   if (!workspace || ((uintptr_t)workspace % ALIGN) != 0 || workspace_bytes < need) return LVX_ERR_WORKSPACE;
   a.q = q; a.k = k; a.v = v; a.o = o; a.d_o = d_o; a.lse = lse;
   a.delta = (float*)workspace;
@@ -385,13 +396,30 @@ lvx_status lvx_xattn_bwd_stages(const lvx_problem* p, lvx_dtype dtype, const voi
   a.stats_ovl = has_stats_ovl(a.d) ? a.stats + stats_floats(a.d) : nullptr;
   a.dq_accum = dq_accum; a.dk = dk; a.dv = dv;
   a.dq_part = a.n_split_dq > 1 ? (float*)((char*)workspace + bwd_ws_fixed(a.d)) : nullptr;
+  a.dq_tiles = fused ? (float*)((char*)workspace + bwd_ws_fixed(a.d) + bwd_ws_part(a.d, a.n_split_dq)) : nullptr;
+  a.dq_locks = nullptr; a.dq_err = nullptr; a.dq_stagger = 0;
   hipStream_t s = (hipStream_t)hip_stream;
   hipError_t e = hipSuccess;
   if (stages & LVX_BWD_DELTA) e = launch_delta(a.d, o, d_o, dtype == LVX_F32, lse, a.delta, a.stats, a.sq_pad, a.stats_ovl, s);
   if (e != hipSuccess) return LVX_ERR_HIP;
   if (stages & (LVX_BWD_DKDV | LVX_BWD_DQ))
-    e = dtype == LVX_BF16 ? launch_bwd_bf16(a, stages, s) : launch_bwd_f32(a, stages, s);
+    e = dtype == LVX_BF16 ? launch_bwd_bf16(a, stages & LVX_BWD_ALL, s) : launch_bwd_f32(a, stages & LVX_BWD_ALL, s);
   return e == hipSuccess ? LVX_OK : LVX_ERR_HIP;
+}
+
+lvx_status lvx_xattn_bwd_error_word(const lvx_problem* p, lvx_dtype dtype, const lvx_mask* mask,
+                                    void* workspace, size_t workspace_bytes, const int** word) {
+  lvx_status st = check_problem(p, dtype);
+  if (st != LVX_OK) return st;
+  if (!word) return LVX_ERR_NULL;
+  if ((st = check_mask(p, mask)) != LVX_OK) return st;
+  const Dims d = make_dims(p);
+  const int n_split = bwd_split(d, dtype, mask != nullptr);
+  const bool fused = dtype == LVX_BF16 && bwd_fused_bf16_supported(d, mask != nullptr);
+  if (!workspace || ((uintptr_t)workspace % ALIGN) != 0 || workspace_bytes < bwd_ws(d, n_split, fused)) return LVX_ERR_WORKSPACE;
+  *word = fused ? (const int*)((char*)workspace + bwd_ws_fixed(d) + bwd_ws_part(d, n_split) + bwd_fused_ws_bytes(d) - 256)
+                : nullptr;
+  return LVX_OK;
 }
 
 lvx_status lvx_xattn_dq_finalize(const lvx_problem* p, const float* dq_accum, void* dq,

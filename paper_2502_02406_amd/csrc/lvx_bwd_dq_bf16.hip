@@ -674,6 +674,23 @@ hipError_t launch_bwd_dq_bf16(const BwdArgs& a, hipStream_t s) {
 
 hipError_t launch_bwd_bf16(const BwdArgs& a, unsigned stages, hipStream_t s) {
   hipError_t e = hipSuccess;
+  if ((stages & 6) == 6 && a.dq_tiles != nullptr) {
+    // One pass over the whole tiles of 256 keys with the fused kernel; the keys that are left go
+    // through the two kernels below (dQ is a sum over keys, dK and dV rows are independent).
+    e = launch_bwd_fused_bf16(a, s);
+    const int done = a.d.Skv / 256 * 256;
+    if (e != hipSuccess || done == a.d.Skv) return e;
+    BwdArgs rest = a;
+    rest.k = (const uint16_t*)a.k + (long)done * a.d.kv_ss;
+    rest.v = (const uint16_t*)a.v + (long)done * a.d.kv_ss;
+    rest.dk = (uint16_t*)a.dk + (long)done * a.d.kv_ss;
+    rest.dv = (uint16_t*)a.dv + (long)done * a.d.kv_ss;
+    rest.d.Skv = a.d.Skv - done;
+    rest.n_split_dq = 1;
+    rest.dq_part = nullptr;
+    rest.dq_tiles = nullptr;
+    return launch_bwd_bf16(rest, stages, s);
+  }
   if (stages & 2) e = launch_bwd_dkdv_bf16(a, s);
   if (e == hipSuccess && (stages & 4)) e = launch_bwd_dq_bf16(a, s);
   return e;

@@ -65,6 +65,11 @@ struct BwdArgs {
                         // 2 = this launch takes the other visible tiles (general kernel)
   float* dq_part;       // workspace, [n_split_dq, B,Hq,Sq,D] float32: the splits' sums (n_split_dq > 1),
                         // added to dq_accum by a reduction that follows the kernel
+  // fused kernel (all five products in one pass): workspace of bwd_fused_ws_bytes, zeroed by the launch
+  float* dq_tiles;      // [B,Hq,ceil(Sq/32)] tiles of 32 rows x 128 columns in matrix-register order
+  int* dq_locks;        // one word per (tile, wave): 0 = free          (set by the launch)
+  int* dq_err;          // nonzero after the kernel: a wave gave up on a lock, dQ is invalid   (set by the launch)
+  int dq_stagger;       // steps by which consecutive key tiles start apart   (set by the launch)
 };
 
 struct MergeArgs {
@@ -103,6 +108,11 @@ hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t s);
 hipError_t launch_bwd_bf16(const BwdArgs& a, unsigned stages, hipStream_t s);
 hipError_t launch_bwd_dkdv_bf16(const BwdArgs& a, hipStream_t s);
 hipError_t launch_bwd_dq_bf16(const BwdArgs& a, hipStream_t s);
+// all five products in one kernel (dense, head dim 128, at least 256 keys and 32 query rows):
+// handles the first Skv / 256 * 256 keys; needs BwdArgs::dq_tiles
+bool bwd_fused_bf16_supported(const Dims& d, bool masked);
+size_t bwd_fused_ws_bytes(const Dims& d);
+hipError_t launch_bwd_fused_bf16(const BwdArgs& a, hipStream_t s);
 // Raises a kernel's dynamic LDS limit once per device (the attribute belongs to the device's copy
 // of the kernel).  `done` is the caller's per-kernel table; a race between host threads only
 // repeats a harmless call.

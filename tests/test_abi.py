@@ -103,7 +103,9 @@ def test_merge_and_bwd_errors(lib):
     bad = list(args); bad[13] = 16                               # workspace too small
     assert lib.lvx_xattn_bwd(*bad) == -6
     assert lib.lvx_xattn_bwd_stages(*args, 0) == -2
-    assert lib.lvx_xattn_bwd_stages(*args, 8) == -2
+    assert lib.lvx_xattn_bwd_stages(*args, 8) == -2          # a kernel choice without a stage
+    assert lib.lvx_xattn_bwd_stages(*args, 32 | 7) == -2     # unknown bit
+    assert lib.lvx_xattn_bwd_stages(*args, 7 | 8 | 16) == -2  # both kernel choices
     assert lib.lvx_xattn_dq_finalize(C.byref(p), None, FAKE, B.LVX_BF16, None) == -1
 
 
@@ -160,8 +162,15 @@ def test_workspace_sizes_and_strerror(lib):
     rows = 32 * 2048
     # delta + 2 padded stats, + the dQ kernel's partial sums for the most it may split this problem
     # (a masked call on 256 compute units, the count assumed without a device: 4 splits)
+    # + for the fused kernel (dense, D = 128): dQ tiles of 32 rows x 128 float32, a lock word per tile
+    # (rounded up to 256 bytes) and 256 bytes that hold the error word
     ws_bwd = B.lvx_xattn_workspace_bytes(p, B.LVX_BF16, B.LVX_WS_BWD)
-    assert ws_bwd >= 3 * rows * 4 and (ws_bwd - 3 * rows * 4) % (rows * 128 * 4) == 0
+    tiles = 32 * (2048 // 32)
+    fused = tiles * 32 * 128 * 4 + (tiles * 4 + 255) // 256 * 256 + 256
+    assert ws_bwd >= 3 * rows * 4 + fused and (ws_bwd - 3 * rows * 4 - fused) % (rows * 128 * 4) == 0
+    # 64-wide heads use the two-kernel backward: no tiles
+    p64 = problem(B=1, Hq=32, Hkv=8, Sq=2048, Skv=32768, D=64)
+    assert (B.lvx_xattn_workspace_bytes(p64, B.LVX_BF16, B.LVX_WS_BWD) - 3 * rows * 4) % (rows * 64 * 4) == 0
     assert B.lvx_xattn_workspace_bytes(p, B.LVX_F32, B.LVX_WS_BWD) == 3 * rows * 4
     assert B.lvx_xattn_workspace_bytes(p, B.LVX_BF16, B.LVX_WS_FWD) >= 256
     assert B.lvx_xattn_workspace_bytes(p, B.LVX_F32, B.LVX_WS_FWD) == 256

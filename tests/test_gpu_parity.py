@@ -60,7 +60,7 @@ def check_grad(g, ref, tol, tag, cancel_atol=0.0):
     assert rel_max(g, ref) <= tol["grad"], f"{tag}: max-abs rel err {rel_max(g, ref)}"
 
 
-def run_case(w: W.Workload, seed=W.BASE_SEED, do_bwd=True, v_mean=0.0, k_ramp=0.0, allow=None):
+def run_case(w: W.Workload, seed=W.BASE_SEED, do_bwd=True, v_mean=0.0, k_ramp=0.0, allow=None, bwd_flags=0):
     x = W.make_inputs(w, seed)
     if allow is not None:                # a bitmap other than the workload's block-causal one
         x["allow"] = torch.from_numpy(np.ascontiguousarray(allow, dtype=np.uint8))
@@ -77,7 +77,8 @@ def run_case(w: W.Workload, seed=W.BASE_SEED, do_bwd=True, v_mean=0.0, k_ramp=0.
         from paper_2502_02406_amd.blockloop import MediaMask
         dmask = MediaMask(dev["allow"], w.q_chunk, w.kv_block)
     tol = TOL[w.dtype]
-    loop = _loop(tuple(x["q"].shape), tuple(x["k"].shape), W.torch_dtype(w.dtype), w.n_blocks, dmask)
+    loop = _loop(tuple(x["q"].shape), tuple(x["k"].shape), W.torch_dtype(w.dtype), w.n_blocks, dmask,
+                 bwd_flags=bwd_flags)
     O, L = loop.forward(dev["q"], dev["k"], dev["v"])
     torch.cuda.synchronize()
     Oref, Lref = oracle.fwd(qn, kn, vn, mask=omask)
@@ -96,6 +97,16 @@ def run_case(w: W.Workload, seed=W.BASE_SEED, do_bwd=True, v_mean=0.0, k_ramp=0.
     check_grad(dq, dQr, tol, w.name + " dQ", atol)
     check_grad(dk, dKr, tol, w.name + " dK", atol)
     check_grad(dv, dVr, tol, w.name + " dV")
+    if bwd_flags:       # the fused kernel reports a lock it could not get; there must be none
+        from paper_2502_02406_amd import binding as B
+        kb = dev["k"][:, :, :loop.blk]
+        ew = B.lvx_xattn_bwd_error_word(B.make_problem(dev["q"], kb), B.dtype_code(dev["q"].dtype), None, loop.ws)
+        if ew and (bwd_flags & B.LVX_BWD_FUSED):
+            import ctypes
+            word = torch.ones(1, dtype=torch.int32, device="cuda")
+            assert ctypes.CDLL("libamdhip64.so").hipMemcpy(ctypes.c_void_p(word.data_ptr()), ctypes.c_void_p(ew), 4, 3) == 0
+            torch.cuda.synchronize()
+            assert int(word.item()) == 0, f"{w.name}: a workgroup gave up on a dQ tile lock"
 
 
 def small(name, **kw):
@@ -138,6 +149,30 @@ FWD_BWD_CASES = [
     # a worker's share of the text: 345 rows per head, tiles that straddle the heads of a group
     small("bf16_short_block_gqa", Hq=8, Hkv=2, Sq=345, Skv=1024),
 ]
+
+
+# Both forms of the bf16 backward on the shapes the fused kernel takes (dense, D = 128, >= 256 keys,
+# >= 32 query rows): one kernel for all five products (dQ tiles added under locks by every key
+# tile's workgroup), and the dK/dV + dQ kernel pair.  Shapes: many key tiles against few steps (every
+# workgroup meets every other on the same dQ tiles), walks cut into segments of one, two and three
+# steps, a ragged Sq (overlapping last step) and a ragged Skv (tail on the kernel pair), GQA 8:1,
+# K/V blocks (dQ accumulated over calls), two batches.
+FUSED_CASES = [
+    small("fz_contended", Hq=2, Sq=32, Skv=8192),
+    small("fz_two_steps", Hq=2, Sq=64, Skv=4096),
+    small("fz_segments", Hq=4, Sq=128, Skv=2048),
+    small("fz_ragged", Hq=4, Sq=200, Skv=2048 + 100),
+    small("fz_gqa8_blocks", B=2, Hq=8, Hkv=1, Sq=96, Skv=3072, n_blocks=3),
+    small("fz_outliers", Hq=4, Sq=160, Skv=4096, outlier_frac=0.01, outlier_scale=8.0, n_blocks=2),
+    small("fz_long_q", Hq=2, Sq=1100, Skv=512),
+]
+
+
+@pytest.mark.parametrize("mode", ["fused", "split"])
+@pytest.mark.parametrize("w", FUSED_CASES, ids=lambda w: w.name)
+def test_backward_forms(w, mode):
+    from paper_2502_02406_amd import binding as B
+    run_case(w, bwd_flags=B.LVX_BWD_FUSED if mode == "fused" else B.LVX_BWD_SPLIT)
 
 
 @pytest.mark.parametrize("w", FWD_BWD_CASES, ids=lambda w: w.name)
