@@ -34,6 +34,10 @@
 
 #include <type_traits>
 
+#ifndef LVX_PROBE
+#define LVX_PROBE 0
+#endif
+
 namespace lvx {
 
 namespace {
@@ -70,13 +74,19 @@ template <int D> struct FusedSmem {
   // K' of the workgroup's 256 keys, the same interleaving with groups of 64 rows
   static constexpr int KGS = 64 * P + 64;
   static constexpr int K_BYTES = 4 * KGS;
-  // dS of one step: unit (key, c) = the 4 query rows 4 c .. 4 c + 3 of a key, 8 bytes, at
-  // key * 64 + ((c + key / 4) % 8) * 8: writes (32 keys, one c per instruction) and transposing
-  // reads (4 keys x all c) both touch every bank once
+  // dS of one step: 64 bytes per key, as four chunks of 16.  Query row r = 8 q4 + 4 gw + e (the
+  // registers of a score block: q4 = 0..3, gw the half-wave, e = 0..3) lives in chunk 2 gw + q4 / 2,
+  // at byte 8 (q4 % 2) + 2 e: a lane's eight values of one half of the rows (its B operand of dK)
+  // are one chunk, written and read back whole.  Chunk h of key j is stored at slot h ^ (j / 4 % 4):
+  // b128 accesses of 16 consecutive keys and transposing reads of 4 keys x 64 bytes then touch
+  // every bank once.
   static constexpr int DS_BYTES = KN * 64;
-  static constexpr int OFF_K = NSTG * STAGE;
-  static constexpr int OFF_DS = OFF_K + K_BYTES;
-  static constexpr int TOTAL = OFF_DS + 2 * DS_BYTES;
+  // the two dS buffers come first, so that one address bit tells them apart
+  static constexpr int OFF_DS = 0;
+  static constexpr int OFF_RING = 2 * DS_BYTES;
+  static constexpr int OFF_K = OFF_RING + NSTG * STAGE;
+  static constexpr int TOTAL = OFF_K + K_BYTES;
+  static_assert((DS_BYTES & (DS_BYTES - 1)) == 0, "the buffers are told apart by one address bit");
   static_assert(GS % 256 == 64 && KGS % 256 == 64, "groups must sit 64 bytes apart modulo 256");
   static_assert(TOTAL <= 160 * 1024, "LDS of one compute unit");
 };
@@ -98,9 +108,11 @@ __device__ __forceinline__ bf16x8 join8(s16x4 lo, s16x4 hi) {
 // policy, and the order of data accesses against lock accesses is kept with explicit waits.
 typedef int __attribute__((address_space(1))) gint;
 __device__ __forceinline__ int lock_try(int* lk) {          // 0 = taken by this call
+  if (LVX_PROBE & (1 | 4)) return 0;
   return __hip_atomic_exchange((gint*)lk, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void lock_release(int* lk) {
+  if (LVX_PROBE & (1 | 4)) return;
   __hip_atomic_store((gint*)lk, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
@@ -133,7 +145,6 @@ bwd_fused_bf16_kernel(BwdArgs a) {
   const int s_start = (int)(((long)hw.item * a.dq_stagger) % n_all);
 
   char* const kres = smem + SM::OFF_K;
-  char* const dsb = smem + SM::OFF_DS;
 
   // ---- tile copies (the layout of the copies follows the interleaved tile: the logical rows
   // 4 j + w, j = 0..7, of Q occupy 8 consecutive rows of group w and those of dO the next 8: a
@@ -151,8 +162,7 @@ bwd_fused_bf16_kernel(BwdArgs a) {
   }
   constexpr int NDMA = 2 * NCR + 1;                // copies per wave and step
   struct Tile { const char *qb, *gb, *lb; char* dst; };
-  auto tile_of = [&](int s, char* st) __attribute__((always_inline)) -> Tile {
-    const int h = s / spH, t = s - h * spH;
+  auto tile_of = [&](int h, int t, char* st) __attribute__((always_inline)) -> Tile {   // row tile t of head h of the group
     const int hq = hk * G + h, i0 = t * KM;
     const int i0_eff = min(i0, d.Sq - KM);
     Tile tl;
@@ -172,8 +182,8 @@ bwd_fused_bf16_kernel(BwdArgs a) {
     else if (k % 2 == 0) dma16s(t.qb, cp_off[k / 2], qdst + run_start(k / 2) * 16);
     else dma16s(t.gb, cp_off[k / 2], qdst + 8 * SM::P + run_start(k / 2) * 16);
   };
-  auto issue_tile = [&](int s, char* st) __attribute__((always_inline)) {
-    const Tile t = tile_of(s, st);
+  auto issue_tile = [&](int s, char* st) __attribute__((always_inline)) {     // (divides: not for the steady state)
+    const Tile t = tile_of(s / spH, s % spH, st);
 #pragma unroll
     for (int k = 0; k < NDMA; ++k) issue_part(t, k);
   };
@@ -186,25 +196,42 @@ bwd_fused_bf16_kernel(BwdArgs a) {
   int* const lock0 = a.dq_locks + tile0;            // one lock per tile, handled by wave 0 for the workgroup
   auto lock_of = [&](int s) __attribute__((always_inline)) -> int* { return lock0 + s; };
   constexpr int AGENT = 16;                        // cache policy of the buffer accesses: sc1
-  f32x16 dq;                                       // this wave's block of dQ^T: lane = query row, registers = columns
+  // This wave's block of dQ^T (lane = query row, registers = columns): `dq` is the accumulator of
+  // the step being contracted and what is stored afterwards; `dq_old` receives the old values of
+  // the NEXT step's tile, which that step's first dQ instruction takes as its starting value.  Two
+  // sets, because the loads must be issued BEFORE the stores: vector-memory operations retire in
+  // issue order, so whatever is waited for after a store waits for the store, and an agent-scope
+  // store takes far longer than a load.
+  f32x16 dq, dq_old;
+  unsigned long long pr_wait = 0, pr_bar = 0;
+  const unsigned long long pr_t0 = (LVX_PROBE & 0x400) ? __builtin_readcyclecounter() : 0;
+  bool probe_final = false;
+  if (LVX_PROBE & 0x100) dq_old = zero16();
+  const int dq_voff = lane * 16;
+  auto dq_load_part = [&](int s, int q4) __attribute__((always_inline)) {
+    if (LVX_PROBE & (1 | 8 | 0x100)) return;
+    const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(dq_rsrc, dq_voff, s * 16384 + q4 * 1024, AGENT);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) dq_old[4 * q4 + e] = __uint_as_float(x[e]);
+  };
+  auto dq_store_part = [&](int s, int q4) __attribute__((always_inline)) {
+    if ((LVX_PROBE & (1 | 16)) || ((LVX_PROBE & 0x200) && !probe_final)) return;
+    const u32x4 x = {__float_as_uint(dq[4 * q4]), __float_as_uint(dq[4 * q4 + 1]), __float_as_uint(dq[4 * q4 + 2]),
+                     __float_as_uint(dq[4 * q4 + 3])};
+    __builtin_amdgcn_raw_buffer_store_b128(x, dq_rsrc, dq_voff, ((LVX_PROBE & 64) ? (int)(blockIdx.x & 255) : s) * 16384 + q4 * 1024,
+                                           (LVX_PROBE & 32) ? 0 : AGENT);
+  };
   auto dq_load = [&](int s) __attribute__((always_inline)) {
 #pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {
-      const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(dq_rsrc, lane * 16 + q4 * 1024, s * 16384, AGENT);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) dq[4 * q4 + e] = __uint_as_float(x[e]);
-    }
+    for (int q4 = 0; q4 < 4; ++q4) dq_load_part(s, q4);
   };
   auto dq_store = [&](int s) __attribute__((always_inline)) {
 #pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {
-      const u32x4 x = {__float_as_uint(dq[4 * q4]), __float_as_uint(dq[4 * q4 + 1]), __float_as_uint(dq[4 * q4 + 2]),
-                       __float_as_uint(dq[4 * q4 + 3])};
-      __builtin_amdgcn_raw_buffer_store_b128(x, dq_rsrc, lane * 16 + q4 * 1024, s * 16384, AGENT);
-    }
+    for (int q4 = 0; q4 < 4; ++q4) dq_store_part(s, q4);
   };
   // lane 0 tries until it has the lock; a wave that gives up reports it and goes on
   auto lock_spin = [&](int* lk) __attribute__((always_inline)) {
+    if (LVX_PROBE & (1 | 4)) return;
     if (lane == 0) {
       int tries = 0;
       while (lock_try(lk) != 0) {
@@ -224,7 +251,7 @@ bwd_fused_bf16_kernel(BwdArgs a) {
   const int n_seg0 = n_all - s_start;              // steps of the first segment (>= 1)
 #pragma unroll
   for (int q = 0; q < NSTG; ++q)
-    if (q < n_seg0) issue_tile(s_start + q, smem + q * SM::STAGE);
+    if (q < n_seg0) issue_tile(s_start + q, smem + SM::OFF_RING + q * SM::STAGE);
 
   const float c2 = d.scale * LOG2E;
   bf16x8 vf[KVB][KS];
@@ -275,25 +302,31 @@ bwd_fused_bf16_kernel(BwdArgs a) {
 
   // ---- lane constants of the LDS accesses
   // K' rows of this lane's keys (B operand of S): key 64 wave + 32 kb + kl, columns 16 ks + 8 g
-  const char* const krow = kres + kres_off<D>(kl, 64 * wave, 16 * g);
+  const int krow_off = SM::OFF_K + kres_off<D>(kl, 64 * wave, 16 * g);
   // K'^T (A operand of dQ): rows = this wave's 32 columns, k = keys
   const int jj = lane & 15, half = (lane >> 4) & 1;
-  const char* const ktb = kres + kres_off<D>(4 * g + (jj >> 2), 0, (32 * wave + 16 * half + 4 * (jj & 3)) * 2);
-  // dS units this lane writes (and reads back for dK): key 64 wave + 32 kb + kl, c = 2 q4 + g
-  int ds_w[4];
+  const int ktb_off = SM::OFF_K + kres_off<D>(4 * g + (jj >> 2), 0, (32 * wave + 16 * half + 4 * (jj & 3)) * 2);
+  // dS chunks this lane writes (and reads back for dK): key 64 wave + 32 kb + kl, chunk 2 g + t2, at
+  // ds_w0 ^ (16 t2) (+ 2048 kb).  ds_w0 addresses the buffer being written, ds_o the same chunks in
+  // the buffer being read; both (and ds_r) change buffers every iteration by flipping one address bit.
+  static_assert(SM::OFF_DS == 0, "the offsets below are LDS addresses");
+  int ds_w0 = (64 * wave + kl) * 64 + (((2 * g) ^ (kl >> 2)) & 3) * 16;
+  int ds_o = ds_w0;
+  // dS^T (B operand of dQ): lane = query row 16 half + i of the transposing read's group, k = keys
+  // 16 kk + 8 h + 4 g + (jj >> 2); the lane supplies rows 16 half + 4 (jj & 3) .. + 3 of its key:
+  // chunk 2 (jj & 1) + half, byte 8 ((jj >> 1) & 1); key / 4 % 4 = (2 h + g) % 4, so h flips bit 5
+  int ds_r[2];
+  ds_r[0] = (4 * g + (jj >> 2)) * 64 + (((2 * (jj & 1) + half) ^ g) & 3) * 16 + ((jj >> 1) & 1) * 8;
+  ds_r[1] = ds_r[0] ^ 32;
+  auto ds_flip = [&]() __attribute__((always_inline)) {
+    ds_w0 ^= SM::DS_BYTES;
+    ds_o ^= SM::DS_BYTES;
 #pragma unroll
-  for (int q4 = 0; q4 < 4; ++q4) ds_w[q4] = (64 * wave + kl) * 64 + ((2 * q4 + g + (kl >> 2)) & 7) * 8;
-  // dS^T (B operand of dQ): lane = query row 16 half + i, k = keys 16 kk + 8 h + 4 g + (jj >> 2):
-  // unit (key, c = 4 half + (jj & 3)); key / 4 = 4 kk + 2 h + g, so the rotation is one of four
-  int ds_r[4];
-#pragma unroll
-  for (int v = 0; v < 4; ++v)
-    ds_r[v] = (4 * g + (jj >> 2)) * 64 + ((4 * half + (jj & 3) + g + 2 * v) & 7) * 8;
+    for (int v = 0; v < 2; ++v) ds_r[v] ^= SM::DS_BYTES;
+  };
 
   // ---- building blocks ------------------------------------------------------------------------
   f32x16 s[KVB], p[KVB];                           // S and dP of the step being scored / converted
-#pragma unroll
-  for (int kb = 0; kb < KVB; ++kb) { s[kb] = zero16(); p[kb] = zero16(); }
   u32x4 pf[KVB][2] = {};                           // packed P of the step being contracted
 
   // S = Q K'^T and dP = dO V^T of the step in stage t (lane = key, registers = query rows); both
@@ -302,33 +335,45 @@ bwd_fused_bf16_kernel(BwdArgs a) {
   auto score = [&](const char* __restrict__ t, auto&& hook) __attribute__((always_inline)) {
     const char* qrow = t + qg_off<D>(kl, 0, 16 * g);
     const char* grow = t + qg_off<D>(kl, KM, 16 * g);
-    f32x16 nl, nd;
+    int krow_v = krow_off;
+    asm volatile("" : "+v"(krow_v));                // (see the contraction phase)
+    const char* const krow = smem + krow_v;
+    // (the statistics are read once per accumulator, straight into its registers: a separate copy
+    // would be 32 more registers alive at the point where the kernel has the fewest to spare)
 #pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {
-      const f32x4 x = *(const f32x4*)(t + SM::STAT_OFF + (8 * q4 + 4 * g) * 4);
-      const f32x4 y = *(const f32x4*)(t + SM::STAT_OFF + 128 + (8 * q4 + 4 * g) * 4);
+    for (int kb = 0; kb < KVB; ++kb) {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) { nl[4 * q4 + e] = x[e]; nd[4 * q4 + e] = y[e]; }
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const f32x4 x = *(const f32x4*)(t + SM::STAT_OFF + (8 * q4 + 4 * g) * 4);
+        const f32x4 y = *(const f32x4*)(t + SM::STAT_OFF + 128 + (8 * q4 + 4 * g) * 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { s[kb][4 * q4 + e] = x[e]; p[kb][4 * q4 + e] = y[e]; }
+      }
+      asm volatile("" ::: "memory");               // (keeps the two reads apart: merged, they would need the copy)
     }
-    bf16x8 qa[2], ga[2], ka[2][KVB];
-    qa[0] = *(const bf16x8*)qrow;
-    ga[0] = *(const bf16x8*)grow;
+    // One set of operand registers: an operand of the next k-step is fetched as soon as the last
+    // matrix instruction that reads the current one has been issued (three instructions ahead of
+    // its first use).
+    bf16x8 qa, ga, ka[KVB];
+    qa = *(const bf16x8*)qrow;
 #pragma unroll
-    for (int kb = 0; kb < KVB; ++kb) ka[0][kb] = *(const bf16x8*)(krow + kb * 8 * SM::P);
+    for (int kb = 0; kb < KVB; ++kb) ka[kb] = *(const bf16x8*)(krow + kb * 8 * SM::P);
+    ga = *(const bf16x8*)grow;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      const int cu = ks & 1, nx = cu ^ 1;
-      if (ks + 1 < KS) {
-        qa[nx] = *(const bf16x8*)(qrow + (ks + 1) * 32);
-        ga[nx] = *(const bf16x8*)(grow + (ks + 1) * 32);
-#pragma unroll
-        for (int kb = 0; kb < KVB; ++kb) ka[nx][kb] = *(const bf16x8*)(krow + kb * 8 * SM::P + (ks + 1) * 32);
-      }
 #pragma unroll
       for (int j = 0; j < 2 * KVB; ++j) {
         const int kb = j % KVB;
-        if (j < KVB) s[kb] = mfma32(qa[cu], ka[cu][kb], ks == 0 ? nl : s[kb]);
-        else p[kb] = mfma32(ga[cu], vf[kb][ks], ks == 0 ? nd : p[kb]);
+        if (j < KVB) s[kb] = mfma32(qa, ka[kb], s[kb]);
+        else p[kb] = mfma32(ga, vf[kb][ks], p[kb]);
+        if (ks + 1 < KS) {
+          if (j == KVB - 1) {
+            qa = *(const bf16x8*)(qrow + (ks + 1) * 32);
+#pragma unroll
+            for (int k2 = 0; k2 < KVB; ++k2) ka[k2] = *(const bf16x8*)(krow + k2 * 8 * SM::P + (ks + 1) * 32);
+          }
+          if (j == 2 * KVB - 1) ga = *(const bf16x8*)(grow + (ks + 1) * 32);
+        }
         hook(ks * 2 * KVB + j);
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -338,9 +383,9 @@ bwd_fused_bf16_kernel(BwdArgs a) {
 
   // Conversion of element x of a step (x = 0 .. 31: query rows q4 = x / 8 of key block kb =
   // (x / 4) % 2, row e = x % 4 of the four): p = exp2(s), dS = p dP, packed in pairs as bf16.  P goes
-  // into the operand registers; dS of four rows goes to LDS (buffer `dsw`) as one unit.
-  struct Carry { float pr, ds; unsigned w0; };
-  auto conv_elem = [&](int x, Carry& cy, char* dsw) __attribute__((always_inline)) {
+  // into the operand registers; dS of four rows goes to LDS (the buffer ds_w0 addresses) as one unit.
+  struct Carry { float pr, ds; unsigned w0; unsigned u[KVB][2]; };
+  auto conv_elem = [&](int x, Carry& cy) __attribute__((always_inline)) {
     const int q4 = x / (4 * KVB), kb = (x / 4) % KVB, e = x % 4, v = 4 * q4 + e;
     const float pr = __builtin_amdgcn_exp2f(s[kb][v]);
     const float ds = pr * p[kb][v];
@@ -348,56 +393,64 @@ bwd_fused_bf16_kernel(BwdArgs a) {
     pf[kb][q4 >> 1][2 * (q4 & 1) + e / 2] = pack2_bf16(cy.pr, pr);
     const unsigned w = pack2_bf16(cy.ds, ds);
     if (e == 1) { cy.w0 = w; return; }
-    const u32x2 u = {cy.w0, w};
-    *(u32x2*)(dsw + ds_w[q4] + kb * 32 * 64) = u;
+    if (q4 % 2 == 0) { cy.u[kb][0] = cy.w0; cy.u[kb][1] = w; return; }
+    const u32x4 u = {cy.u[kb][0], cy.u[kb][1], cy.w0, w};      // rows 16 t2 + 4 g .., then 16 t2 + 8 + 4 g ..
+    const int t2 = q4 >> 1;
+    *(u32x4*)(smem + (t2 == 0 ? ds_w0 : ds_w0 ^ 16) + kb * 32 * 64) = u;
   };
 
-  // The contraction phase of step i (stage t, dS buffer dsr) with the conversion of step i + 1 (dS
-  // buffer dsw) in its shadow: dV^T += dO^T P (16 matrix instructions), dK^T += Q^T dS (16), then
+  // The contraction phase of step i (stage t, dS in the buffer ds_o and ds_r address) with the
+  // conversion of step i + 1 (dS into the buffer ds_w0 addresses) in its shadow: dV^T += dO^T P (16 matrix instructions), dK^T += Q^T dS (16), then
   // this wave's block of dQ^T += K'^T dS^T over the 256 keys (16).  P of step i + 1 replaces P of
   // step i in the same registers, which is why dV goes first and the conversion starts at the
   // ninth instruction.  (After the last step of a segment the conversion works on stale scores;
   // nothing reads what it leaves.)
-  auto contract = [&](const char* __restrict__ t, const char* __restrict__ dsr, char* dsw) __attribute__((always_inline)) {
+  auto contract = [&](const char* __restrict__ t) __attribute__((always_inline)) {
     constexpr int NV = 2 * DB * KVB;               // matrix instructions of dV (and of dK)
     constexpr int NQ = KN / 16;                    // of dQ
     constexpr int NM = 2 * NV + NQ, C0 = NV / 2, XE = 16 * KVB;
     const char* const trb = t + qg_off<D>(4 * g + (jj >> 2), 0, (16 * half + 4 * (jj & 3)) * 2);
+    // (Lane constants pass through an empty statement inside the loop: otherwise every address
+    // "constant + offset" is itself loop-invariant, gets hoisted, and comes back as an addition in
+    // front of each access instead of the instruction's own offset field.)
+    int ktb_v = ktb_off, dsr0 = ds_r[0], dsr1 = ds_r[1], dso = ds_o;
+    asm volatile("" : "+v"(ktb_v), "+v"(dsr0), "+v"(dsr1), "+v"(dso));
+    const char* const ktb_ = smem + ktb_v;
     auto tr_op = [&](int rbase, int n0) __attribute__((always_inline)) -> bf16x8 {
       return join8(lds_read_tr(trb + qg_off<D>(0, rbase, n0 * 2)), lds_read_tr(trb + qg_off<D>(0, rbase + 8, n0 * 2)));
     };
     auto ds_own = [&](int kb, int t2) __attribute__((always_inline)) -> bf16x8 {   // B operand of dK: this lane's key, rows 16 t2 ..
-      const u32x2 lo = *(const u32x2*)(dsr + ds_w[2 * t2] + kb * 32 * 64);
-      const u32x2 hi = *(const u32x2*)(dsr + ds_w[2 * t2 + 1] + kb * 32 * 64);
-      const u32x4 r = {lo[0], lo[1], hi[0], hi[1]};
-      return __builtin_bit_cast(bf16x8, r);
+      return *(const bf16x8*)(smem + (t2 == 0 ? dso : dso ^ 16) + kb * 32 * 64);
     };
     auto kt_op = [&](int kk) __attribute__((always_inline)) -> bf16x8 {
-      return join8(lds_read_tr(ktb + kres_off<D>(0, 16 * kk, 0)), lds_read_tr(ktb + kres_off<D>(0, 16 * kk + 8, 0)));
+      return join8(lds_read_tr(ktb_ + kres_off<D>(0, 16 * kk, 0)), lds_read_tr(ktb_ + kres_off<D>(0, 16 * kk + 8, 0)));
     };
     auto dst_op = [&](int kk) __attribute__((always_inline)) -> bf16x8 {
-      return join8(lds_read_tr(dsr + ds_r[(2 * kk) & 3] + (16 * kk) * 64),
-                   lds_read_tr(dsr + ds_r[(2 * kk + 1) & 3] + (16 * kk + 8) * 64));
+      return join8(lds_read_tr(smem + dsr0 + (16 * kk) * 64), lds_read_tr(smem + dsr1 + (16 * kk + 8) * 64));
     };
-    bf16x8 at[2];                                  // transposed operands, used alternately
+    // Instruction m of the phase: 0 .. NV - 1 are dV; from NV on dK (even) and dQ (odd) alternate.
+    // The sixteen dQ instructions accumulate into one block, each waiting for the one before it:
+    // with an independent instruction between two of them the matrix pipe never idles.
+    bf16x8 at[2];                                  // transposed operands of dV / dK, used alternately
     bf16x8 sb[KVB];                                // dS operands of dK for the current half of the rows
-    bf16x8 kt[2], dt[2];
+    bf16x8 kt[2], dt[2];                           // operands of dQ, used alternately
     at[0] = tr_op(KM, 0);
     Carry cy;
 #pragma unroll
     for (int m = 0; m < NM; ++m) {
-      if (m < 2 * NV) {
-        const bool is_dk = m >= NV;
-        const int c = (m % NV) / KVB, t2 = c / DB, db = c % DB, kb = m % KVB, cu = (m / KVB) & 1;
-        if (kb == 0) {                             // the operand of the next pair of instructions
-          const int mn = m + KVB;
-          if (mn < 2 * NV) {
-            const int cn = (mn % NV) / KVB;
-            at[cu ^ 1] = tr_op((mn >= NV ? 0 : KM) + 16 * (cn / DB), 32 * (cn % DB));
-          } else {
-            kt[0] = kt_op(0);
-            dt[0] = dst_op(0);
-          }
+      const bool is_dq = m >= NV && ((m - NV) & 1) != 0 && !(LVX_PROBE & 2);
+      if (!is_dq) {
+        // u: number of this instruction among the 2 NV of dV and dK
+        const int u = m < NV ? m : NV + (m - NV) / 2;
+        const bool is_dk = u >= NV;
+        const int c = (u % NV) / KVB, t2 = c / DB, db = c % DB, kb = u % KVB, cu = (u / KVB) & 1;
+        if (kb == 0 && u + KVB < 2 * NV) {         // the operand of the next pair of these instructions
+          const int un = u + KVB, cn = (un % NV) / KVB;
+          at[cu ^ 1] = tr_op((un >= NV ? 0 : KM) + 16 * (cn / DB), 32 * (cn % DB));
+        }
+        if (u == NV - 2) {                         // ... and of the first dQ instruction
+          kt[0] = kt_op(0);
+          dt[0] = dst_op(0);
         }
         if (is_dk && kb == 0 && db == 0) {
 #pragma unroll
@@ -406,33 +459,32 @@ bwd_fused_bf16_kernel(BwdArgs a) {
         if (!is_dk) mfma32_acc(dv[kb][db], at[cu], __builtin_bit_cast(bf16x8, pf[kb][t2]));
         else mfma32_acc(dk[kb][db], at[cu], sb[kb]);
       } else {
-        const int kk = m - 2 * NV, cu = kk & 1;
+        const int kk = (m - NV) / 2, cu = kk & 1;
         if (kk + 1 < NQ) {
           kt[cu ^ 1] = kt_op(kk + 1);
           dt[cu ^ 1] = dst_op(kk + 1);
         }
-        dq = mfma32(kt[cu], dt[cu], dq);
+        dq = mfma32(kt[cu], dt[cu], kk == 0 ? dq_old : dq);
       }
       if (m >= C0) {
 #pragma unroll
-        for (int x = (m - C0) * XE / (NM - C0); x < (m - C0 + 1) * XE / (NM - C0); ++x) conv_elem(x, cy, dsw);
+        for (int x = (m - C0) * XE / (NM - C0); x < (m - C0 + 1) * XE / (NM - C0); ++x) conv_elem(x, cy);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  auto convert_all = [&](char* dsw) __attribute__((always_inline)) {
+  auto convert_all = [&]() __attribute__((always_inline)) {
     Carry cy;
 #pragma unroll
-    for (int x = 0; x < 16 * KVB; ++x) conv_elem(x, cy, dsw);
+    for (int x = 0; x < 16 * KVB; ++x) conv_elem(x, cy);
   };
 
   // ---- the two segments of the walk --------------------------------------------------------
   // Within a segment of n steps, step q (q = 0 .. n - 1, step id s0 + q) lives in ring stage q % 3
-  // and its dS in buffer q % 2.  Iteration i: contraction of step i with the conversion of step
+  // and its dS in buffer q % 2.  Per step i: contraction of step i with the conversion of step
   // i + 1; the one barrier; then the locks (the try of step i + 2 goes out, that of step i + 1 is
-  // looked at, that of step i - 1 is released), the copies of step i + 3, the dQ block of step i is
-  // stored and the old values of step i + 1 are loaded into the same registers, and step i + 2 is
-  // scored.
+  // looked at, that of step i - 2 is released), the old values of step i + 1's dQ block are loaded,
+  // the copies of step i + 3 go out, the dQ block of step i is stored, and step i + 2 is scored.
 #pragma nounroll
   for (int seg = 0; seg < 2; ++seg) {
     const int s0 = seg == 0 ? s_start : 0;
@@ -441,7 +493,7 @@ bwd_fused_bf16_kernel(BwdArgs a) {
     if (seg == 1) {
 #pragma unroll
       for (int q = 0; q < NSTG; ++q)
-        if (q < n) issue_tile(s0 + q, smem + q * SM::STAGE);
+        if (q < n) issue_tile(s0 + q, smem + SM::OFF_RING + q * SM::STAGE);
     }
     // lock of the first step (wave 0 takes the locks for the workgroup: per-wave locks would let
     // two workgroups wait for each other through their barriers); the try for the second step
@@ -455,49 +507,103 @@ bwd_fused_bf16_kernel(BwdArgs a) {
     __syncthreads();                               // tiles, K', everything in LDS; the first lock is held
     asm volatile("" ::: "memory");
     dq_load(s0);
-    char* st_a = smem;                             // stages of steps i, i + 1, i + 2
-    char* st_b = smem + SM::STAGE;
-    char* st_c = smem + 2 * SM::STAGE;
-    char* ds_a = dsb;                              // dS buffers of steps i, i + 1
-    char* ds_b = dsb + SM::DS_BYTES;
+    char* st_a = smem + SM::OFF_RING;              // stages of steps i, i + 1, i + 2
+    char* st_b = st_a + SM::STAGE;
+    char* st_c = st_a + 2 * SM::STAGE;
+    // dS of the first step goes into buffer 0 and is read from there
+    ds_w0 &= SM::DS_BYTES - 1;
+    ds_o &= SM::DS_BYTES - 1;
+#pragma unroll
+    for (int v = 0; v < 2; ++v) ds_r[v] &= SM::DS_BYTES - 1;
     score(st_a, nothing);
-    convert_all(ds_a);
+    convert_all();
+    ds_w0 ^= SM::DS_BYTES;                         // from here on: read from one buffer, write the other
     if (n > 1) score(st_b, nothing);
     __syncthreads();                               // dS of the first step is in LDS
 
-    for (int i = 0; i < n; ++i) {
-      const bool more1 = i + 1 < n, more2 = i + 2 < n, more3 = i + 3 < n;
-      contract(st_a, ds_a, ds_b);
-      // The workgroup owns the lock of step i + 1 before it passes the barrier (the try went out an
-      // iteration ago).  A workgroup waits for a lock only while the locks it holds are of earlier
-      // steps, and the try for step i + 2 goes out only after step i + 1 is owned.
-      if (wave == 0 && more1) {
-        if (__builtin_expect(__builtin_amdgcn_readfirstlane(got_next) != 0, 0)) lock_spin(lock_of(s0 + i + 1));
+    // The contraction phase of step j, then the workgroup makes sure it owns the lock of step
+    // j + 1 (the try went out an iteration ago) and meets at the step's one barrier.  A workgroup
+    // waits for a lock only while the locks it holds are of earlier steps, and the try for step
+    // j + 2 goes out only after step j + 1 is owned.
+    // Vector-memory operations retire in issue order, and the steady state issues the stores of a
+    // step's dQ block last: leaving four operations outstanding (stores_last) waits for the tile
+    // copies and the loads, not for the stores.
+    auto contract_and_meet = [&](int j, bool stores_last) __attribute__((always_inline)) {
+      contract(st_a);
+      if (wave == 0 && j + 1 < n) {
+        if (__builtin_expect(__builtin_amdgcn_readfirstlane(got_next) != 0, 0)) lock_spin(lock_of(s0 + j + 1));
       }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      wait_vmcnt<0>();
+      unsigned long long t0 = 0, t1 = 0;
+      if (LVX_PROBE & 0x400) t0 = __builtin_readcyclecounter();
+      if (stores_last) wait_vmcnt<4>();
+      else wait_vmcnt<0>();
+      if (LVX_PROBE & 0x400) t1 = __builtin_readcyclecounter();
       wg_barrier();
+      if (LVX_PROBE & 0x400) { const unsigned long long t2 = __builtin_readcyclecounter(); pr_wait += t1 - t0; pr_bar += t2 - t1; }
       asm volatile("" ::: "memory");
-      // every wave's stores of step i - 1 completed before the barrier (vmcnt was 0): release it
+    };
+    // What follows the barrier of step i, and then the contraction of step i + 1.  full: steps
+    // i + 1 .. i + 3 all exist (the steady state: nothing is conditional, the memory operations go
+    // out one at a time between the matrix instructions of the scoring, and the loads of the old dQ
+    // values sit in the same basic block as their first use, so that the wait the compiler puts
+    // before it counts the stores behind them instead of waiting for everything).
+    int h3 = (s0 + 3) / spH, t3 = (s0 + 3) % spH;   // head and row tile of step i + 3
+    auto iteration = [&](auto full_t, int i) __attribute__((always_inline)) {
+      constexpr bool FULL = decltype(full_t)::value;
+      const bool more1 = FULL || i + 1 < n, more2 = FULL || i + 2 < n, more3 = FULL || i + 3 < n;
+      // The stores of step i - 2 were issued two iterations ago, before everything the wait before
+      // the barrier covered: they have completed in every wave, and its lock can go.
+      // (Iterations 0 and 1 have nothing to release and write a spare word instead.)
       if (wave == 0 && lane == 0) {
-        if (i > 0) lock_release(lock_of(s0 + i - 1));
+        lock_release(i > 1 ? lock_of(s0 + i - 2) : a.dq_err + 1);
         if (more2) got_next = lock_try(lock_of(s0 + i + 2));
       }
       asm volatile("" ::: "memory");
-      if (more3) issue_tile(s0 + i + 3, st_a);
-      dq_store(s0 + i);
-      if (more1) dq_load(s0 + i + 1);
-      if (more2) score(st_c, nothing);
+      const int sc = __builtin_amdgcn_readfirstlane(s0 + i);   // (wave-uniform; said explicitly for the buffer accesses)
+      if (FULL) {
+        const Tile tl = tile_of(h3, t3, st_a);
+        score(st_c, [&](int m) __attribute__((always_inline)) {
+          if (m < NDMA) issue_part(tl, m);
+          else if (m < 4 + NDMA) dq_load_part(sc + 1, m - NDMA);
+          else if (m < 8 + NDMA) dq_store_part(sc, m - 4 - NDMA);
+        });
+      } else {
+        if (more1) dq_load(sc + 1);
+        if (more3) {
+          const Tile tl = tile_of(h3, t3, st_a);
+#pragma unroll
+          for (int k = 0; k < NDMA; ++k) issue_part(tl, k);
+        }
+        dq_store(sc);
+        if (more2) score(st_c, nothing);
+      }
+      if (++t3 == spH) { t3 = 0; ++h3; }
       char* const t_ = st_a; st_a = st_b; st_b = st_c; st_c = t_;
-      char* const u_ = ds_a; ds_a = ds_b; ds_b = u_;
-    }
+      ds_flip();
+      if (more1) contract_and_meet(i + 1, FULL);
+    };
+    contract_and_meet(0, false);
+    int i = 0;
+    for (; i + 3 < n; ++i) iteration(std::true_type{}, i);
+    for (; i < n; ++i) iteration(std::false_type{}, i);
     // every wave's stores of the last block must have completed before its lock is released
     wait_vmcnt<0>();
     __syncthreads();                               // (also: the next segment's copies overwrite the stages)
     asm volatile("" ::: "memory");
-    if (wave == 0 && lane == 0) lock_release(lock_of(s0 + n - 1));
+    if (wave == 0 && lane == 0) {
+      if (n > 1) lock_release(lock_of(s0 + n - 2));
+      lock_release(lock_of(s0 + n - 1));
+    }
   }
 
+  if (LVX_PROBE & 0x200) { probe_final = true; dq_store(0); }
+  if ((LVX_PROBE & 0x400) && lane == 0) {
+    atomicAdd((unsigned long long*)(a.dq_err + 2), pr_wait);
+    atomicAdd((unsigned long long*)(a.dq_err + 4), pr_bar);
+    atomicAdd((unsigned long long*)(a.dq_err + 6), __builtin_readcyclecounter() - pr_t0);
+    atomicAdd((unsigned long long*)(a.dq_err + 8), 1ull);
+  }
   // ---- write dK = scale * acc, dV = acc (transposed accumulators: lane = key row).  The last matrix instructions must have retired before their registers are read.
 #pragma unroll
   for (int kb = 0; kb < KVB; ++kb) {
