@@ -152,7 +152,12 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   // cursor over the steps in issue order: step id s = head * spH + tile, kept with its head and
   // first row so that no division is needed per step (STEPS: k = position in the list, tp = the
   // list entry after it, fetched a step ahead so that nothing waits for it)
-  struct Cursor { int s, h, i0, k, tp; };
+  // (dense variant: hb, lb and lo are running addresses of the cursor's step -- the byte offset of
+  // this wave's first row of the head, the step's statistics, the head's overlay statistics -- so
+  // that a step costs a handful of scalar additions instead of the 64-bit products of its tile
+  // address: with one wave per SIMD every scalar instruction takes an issue slot from the loop)
+  struct Cursor { int s, h, i0, k, tp; long hb, lb, lo; };
+  constexpr bool RUNNING = !GENERAL && !STEPS;
   auto step_needed = [&](const Cursor& c) __attribute__((always_inline)) -> bool {
     if (!GENERAL || !mk.allow) return true;
     return mask_rect(mk, b, c.i0, min(d.Sq, c.i0 + KM) - 1, j_wg0, j_wg1) != 0;
@@ -177,6 +182,17 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
       c.s = (c.h < G && t < spH) ? c.h * spH + t : n_all;
       return;
     }
+    if (RUNNING) {
+      ++c.s;
+      c.i0 += KM;
+      c.lb += 256;
+      const bool wrap = c.i0 >= d.Sq;
+      c.i0 = wrap ? 0 : c.i0;
+      c.h += wrap ? 1 : 0;
+      c.hb += wrap ? d.q_sh * 2 : 0;
+      c.lo += wrap ? 256 : 0;
+      return;
+    }
     do {
       ++c.s;
       c.i0 += KM;
@@ -188,7 +204,7 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
       c.i0 = __builtin_amdgcn_readfirstlane(c.i0);
     }
   };
-  Cursor cursor = {0, 0, 0, 0, 0};
+  Cursor cursor = {0, 0, 0, 0, 0, 0, 0, 0};
   if (STEPS) {
     if (per_head > 0) {
       cursor.i0 = __builtin_amdgcn_readfirstlane(tl[0]) * KM;
@@ -305,7 +321,26 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   // 0 .. NDMA - 1 so that the dense loop can spread them over the matrix instructions of a phase.
   constexpr int NDMA = 2 * NCR + 1;                // copies per wave and step
   struct Tile { const char *qb, *gb, *lb; char* dst; int rows; long tile; };
+  if (RUNNING) {                                   // (the dense cursor still stands at step 0)
+    cursor.hb = (long)(hk * G) * d.q_sh * 2 + (long)wave * row_bytes;
+    cursor.lb = (long)(uintptr_t)l0 + (long)(hk * G) * a.sq_pad * 8;
+    cursor.lo = (long)(uintptr_t)a.stats_ovl + ((long)b * d.Hq + hk * G) * 256;
+  }
   auto tile_of = [&](const Cursor& c, char* st) __attribute__((always_inline)) -> Tile {
+    if constexpr (RUNNING) {
+      // the short last step of a head takes rows Sq-32 .. Sq-1 and their own statistics (selected
+      // without a branch: one would cut the steady-state loop into pieces)
+      const int i0_eff = min(c.i0, d.Sq - KM);
+      const long tile = c.hb + (long)((unsigned long long)(unsigned)i0_eff * row_bytes);
+      Tile t;
+      t.rows = KM;
+      t.tile = tile;
+      t.qb = q0 + tile;
+      t.gb = g0 + tile;
+      t.lb = (const char*)(uintptr_t)(c.i0 != i0_eff ? c.lo : c.lb);
+      t.dst = st;
+      return t;
+    }
     // (wave-uniform by construction; said explicitly because with a media mask the cursor derives
     // from bitmap words read through the vector path)
     const int hq = __builtin_amdgcn_readfirstlane(hk * G + c.h), i0 = __builtin_amdgcn_readfirstlane(c.i0);
@@ -328,11 +363,12 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
     t.dst = st;
     return t;
   };
+  const unsigned smem_u = lds_base(smem);
   auto issue_part = [&](const Tile& t, int k) __attribute__((always_inline)) {   // full tiles only
-    char* const qdst = t.dst + 20 * wave * SM::P;
-    if (k == NDMA - 1) dma4s(t.lb, lane * 4, t.dst + SM::STAT_OFF);
-    else if (k % 2 == 0) dma16s(t.qb, cp_off[k / 2], qdst + run_start(k / 2) * 16);
-    else dma16s(t.gb, cp_off[k / 2], qdst + 8 * SM::P + run_start(k / 2) * 16);
+    const unsigned dst = smem_u + (unsigned)(t.dst - smem), qdst = dst + 20 * wave * SM::P;
+    if (k == NDMA - 1) dma4u(t.lb, lane * 4, dst + SM::STAT_OFF);
+    else if (k % 2 == 0) dma16u(t.qb, cp_off[k / 2], qdst + run_start(k / 2) * 16);
+    else dma16u(t.gb, cp_off[k / 2], qdst + 8 * SM::P + run_start(k / 2) * 16);
   };
   auto issue_tile = [&](const Cursor& c, char* st) __attribute__((always_inline)) {
     const Tile t = tile_of(c, st);
@@ -445,15 +481,27 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   // q4 = x / (4 KVB) of key block kb = (x / 4) % KVB, row e = x % 4 of the four): p = exp2(s), dS = p dP,
   // both differences already formed by the accumulation, packed in pairs as bf16 into word
   // 2 (q4 % 2) + e / 2 of operand q4 / 2 of the key block.
-  struct Carry { float pr, ds; };
-  auto conv_elem = [&](int x, Carry& cy, const f32x16 (&s)[KVB], const f32x16 (&p)[KVB],
-                       u32x4 (&pwo)[KVB][2], u32x4 (&swo)[KVB][2]) __attribute__((always_inline)) {
+  // In two halves -- the exponential, then everything that uses it -- so that the pipelined loop
+  // can start an element under one matrix instruction and finish it under the next: a
+  // transcendental result read by the very next instruction costs an idle issue slot.
+  struct Carry { float pr, ds, ex; };
+  auto conv_start = [&](int x, const f32x16 (&s)[KVB]) __attribute__((always_inline)) -> float {
     const int q4 = x / (4 * KVB), kb = (x / 4) % KVB, e = x % 4, v = 4 * q4 + e;
-    const float pr = __builtin_amdgcn_exp2f(s[kb][v]);
+    return __builtin_amdgcn_exp2f(s[kb][v]);
+  };
+  auto conv_finish = [&](int x, Carry& cy, const f32x16 (&p)[KVB],
+                         u32x4 (&pwo)[KVB][2], u32x4 (&swo)[KVB][2]) __attribute__((always_inline)) {
+    const int q4 = x / (4 * KVB), kb = (x / 4) % KVB, e = x % 4, v = 4 * q4 + e;
+    const float pr = cy.ex;
     const float ds = pr * p[kb][v];
     if (e % 2 == 0) { cy.pr = pr; cy.ds = ds; return; }
     pwo[kb][q4 >> 1][2 * (q4 & 1) + e / 2] = pack2_bf16(cy.pr, pr);
     swo[kb][q4 >> 1][2 * (q4 & 1) + e / 2] = pack2_bf16(cy.ds, ds);
+  };
+  auto conv_elem = [&](int x, Carry& cy, const f32x16 (&s)[KVB], const f32x16 (&p)[KVB],
+                       u32x4 (&pwo)[KVB][2], u32x4 (&swo)[KVB][2]) __attribute__((always_inline)) {
+    cy.ex = conv_start(x, s);
+    conv_finish(x, cy, p, pwo, swo);
   };
   auto convert = [&](const f32x16 (&s)[KVB], const f32x16 (&p)[KVB],
                      u32x4 (&pwo)[KVB][2], u32x4 (&swo)[KVB][2]) __attribute__((always_inline)) {
@@ -505,7 +553,12 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
       if (j % 2 == 0) mfma32_acc<GENERAL>(dv[j / 2][db], gt[cu], __builtin_bit_cast(bf16x8, pwi[j / 2][t2]));
       else mfma32_acc<GENERAL>(dk[j / 2][db], qt[cu], __builtin_bit_cast(bf16x8, swi[j / 2][t2]));
 #pragma unroll
-      for (int x = m * EPM; x < (m + 1) * EPM && x < XE; ++x) conv_elem(x, cy, s, p, pwo, swo);
+      for (int x = m * EPM; x < (m + 1) * EPM && x < XE; ++x) {
+        const float ex = conv_start(x, s);         // (first: the instruction after it must not read it)
+        if (x > 0) conv_finish(x - 1, cy, p, pwo, swo);
+        cy.ex = ex;
+        if (x == XE - 1) conv_finish(x, cy, p, pwo, swo);
+      }
       hook(m);
       __builtin_amdgcn_sched_barrier(0);
     }

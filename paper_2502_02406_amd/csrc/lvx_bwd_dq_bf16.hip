@@ -264,11 +264,12 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   // A tile's copies are numbered 0 .. NDMA - 1, so that the dense loop can spread them over the
   // matrix instructions of a phase: issued back to back, each waits for the one before it to be
   // accepted by the memory pipeline, and the wave would stand still for hundreds of cycles.
+  const unsigned smem_u = lds_base(smem);
   auto issue_part = [&](int t, char* st, int k) __attribute__((always_inline)) {   // full tiles only
     const long tile = (long)t * TN * row_bytes + (long)wave * row_bytes;           // this wave's first row: tile row w
-    char* const kdst = st + wave * SM::GS;
-    if (k % 2 == 0) dma16s(k0 + tile, cp_off[k / 2], kdst + run_start(k / 2) * 16);
-    else dma16s(v0 + tile, cp_off[k / 2], kdst + SM::TILE + run_start(k / 2) * 16);
+    const unsigned kdst = smem_u + (unsigned)(st - smem) + wave * SM::GS;
+    if (k % 2 == 0) dma16u(k0 + tile, cp_off[k / 2], kdst + run_start(k / 2) * 16);
+    else dma16u(v0 + tile, cp_off[k / 2], kdst + SM::TILE + run_start(k / 2) * 16);
   };
   auto issue_tile = [&](int t, char* st) __attribute__((always_inline)) {
     const int rows = min(TN, d.Skv - t * TN);

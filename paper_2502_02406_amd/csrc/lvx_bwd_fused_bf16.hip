@@ -176,11 +176,12 @@ bwd_fused_bf16_kernel(BwdArgs a) {
     tl.dst = st;
     return tl;
   };
+  const unsigned smem_u = lds_base(smem);
   auto issue_part = [&](const Tile& t, int k) __attribute__((always_inline)) {
-    char* const qdst = t.dst + wave * SM::GS;
-    if (k == NDMA - 1) dma4s(t.lb, lane * 4, t.dst + SM::STAT_OFF);
-    else if (k % 2 == 0) dma16s(t.qb, cp_off[k / 2], qdst + run_start(k / 2) * 16);
-    else dma16s(t.gb, cp_off[k / 2], qdst + 8 * SM::P + run_start(k / 2) * 16);
+    const unsigned dst = smem_u + (unsigned)(t.dst - smem), qdst = dst + wave * SM::GS;
+    if (k == NDMA - 1) dma4u(t.lb, lane * 4, dst + SM::STAT_OFF);
+    else if (k % 2 == 0) dma16u(t.qb, cp_off[k / 2], qdst + run_start(k / 2) * 16);
+    else dma16u(t.gb, cp_off[k / 2], qdst + 8 * SM::P + run_start(k / 2) * 16);
   };
   auto issue_tile = [&](int s, char* st) __attribute__((always_inline)) {     // (divides: not for the steady state)
     const Tile t = tile_of(s / spH, s % spH, st);

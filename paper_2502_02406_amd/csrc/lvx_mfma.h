@@ -111,6 +111,22 @@ __device__ __forceinline__ const void* ptr_uniform(const void* p) {
   const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(x >> 32));
   return (const void*)(uintptr_t)(((unsigned long long)hi << 32) | lo);
 }
+// (the forms that take an LDS byte address save the null test that a cast from a generic pointer
+// carries -- two scalar instructions per copy, which a kernel with one wave per SIMD pays for in
+// issue slots; lds_base gives the address of the dynamic LDS array once per kernel)
+__device__ __forceinline__ unsigned lds_base(void* smem) { return lds_addr_uniform(smem); }
+__device__ __forceinline__ void dma16u(const void* base, unsigned voff, unsigned lds_addr) {
+  base = ptr_uniform(base);
+  const unsigned l = (unsigned)__builtin_amdgcn_readfirstlane((int)lds_addr);
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(voff), "s"(base), "s"(l) : "memory", "m0");
+}
+__device__ __forceinline__ void dma4u(const void* base, unsigned voff, unsigned lds_addr) {
+  base = ptr_uniform(base);
+  const unsigned l = (unsigned)__builtin_amdgcn_readfirstlane((int)lds_addr);
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+               :: "v"(voff), "s"(base), "s"(l) : "memory", "m0");
+}
 __device__ __forceinline__ void dma16s(const void* base, unsigned voff, void* lds_dst) {
   base = ptr_uniform(base);
   const unsigned l = lds_addr_uniform(lds_dst);
