@@ -13,7 +13,8 @@ Functions follow the paper as stated in the header of ``lvx_oracle.c``:
 the attention definition of Section 2, the Rescale step of Algorithm 1, the
 derivative of the definition (Table 1 counts its FLOPs, Section 3.2 names
 what is saved for it), and the projections x W_Q, y W_K, y W_V of Section 2
-that Section 3.2 recomputes in the backward pass.
+that Section 3.2 recomputes in the backward pass, with the chain rule through
+them (gradients of the weights and of the tokens).
 """
 from __future__ import annotations
 
@@ -222,3 +223,33 @@ def project(x, w, n_heads: int, rows=None) -> np.ndarray:
     _load().lvx_oracle_project(C.c_int(B), C.c_int(S), C.c_int(E), C.c_int(n_heads), C.c_int(D),
                                _ptr(x), _ptr(w), C.c_int(rows.shape[0]), _ptr(rows), _ptr(out))
     return out
+
+
+def project_bwd(x, w, g, n_heads: int, cols=None, rows=None):
+    """The chain rule through project (Section 2's linear maps, which Section 3.2 evaluates again
+    in the backward pass): x [B,S,E], w [n_heads*D, E], g = d loss / d out [B, n_heads, S, D] ->
+    (dw [n_heads*D, E], dx [B,S,E]).  With cols (output columns h*D + c) only those rows of dw,
+    [n, E]; with rows ([n,2] of (b, s)) only those tokens of dx, [n, E]."""
+    x, w, g = _f32(x), _f32(w), _f32(g)
+    B, S, E = x.shape
+    N, Ew = w.shape
+    assert Ew == E and N % n_heads == 0
+    D = N // n_heads
+    assert g.shape == (B, n_heads, S, D)
+    dims = (C.c_int(B), C.c_int(S), C.c_int(E), C.c_int(n_heads), C.c_int(D))
+    if cols is None:
+        dw = np.empty((N, E), dtype=np.float64)
+        _load().lvx_oracle_project_bwd_w(*dims, _ptr(x), _ptr(g), C.c_int(0), None, _ptr(dw))
+    else:
+        cols = np.ascontiguousarray(cols, dtype=np.int32).reshape(-1)
+        assert cols.size == 0 or (cols.min() >= 0 and cols.max() < N)
+        dw = np.empty((cols.size, E), dtype=np.float64)
+        _load().lvx_oracle_project_bwd_w(*dims, _ptr(x), _ptr(g), C.c_int(cols.size), _ptr(cols), _ptr(dw))
+    if rows is None:
+        dx = np.empty((B, S, E), dtype=np.float64)
+        _load().lvx_oracle_project_bwd_x(*dims, _ptr(w), _ptr(g), C.c_int(0), None, _ptr(dx))
+    else:
+        rows = np.ascontiguousarray(rows, dtype=np.int32).reshape(-1, 2)
+        dx = np.empty((rows.shape[0], E), dtype=np.float64)
+        _load().lvx_oracle_project_bwd_x(*dims, _ptr(w), _ptr(g), C.c_int(rows.shape[0]), _ptr(rows), _ptr(dx))
+    return dw, dx

@@ -29,6 +29,10 @@
  *     backward pass compute again instead of keeping Q, K and V.  Written
  *     out as the definition of a matrix product, one dot product per output
  *     element, with the d columns of the result cut into heads.
+ *   - projection gradients: the paper prints no formula for them either; they
+ *     are the chain rule through those same linear maps (what the recomputed
+ *     K and V of Section 3.2 are for: carrying dK, dV back to the visual
+ *     tokens and to W_K, W_V), one sum per element of dW and of dx.
  *
  * Conventions:
  *   Q, dO      [B, Hq,  Sq,  D]  float32, contiguous, values already rounded
@@ -485,5 +489,56 @@ void lvx_oracle_project(int B, int S, int E, int H, int D, const float *x, const
                 else
                     out[(((long)b * H + h) * S + s) * D + c] = acc;
             }
+    }
+}
+
+/* ---------------------------------------------------------------------------
+ * Gradients of the projection.  Section 3.2 has the backward pass form K and V
+ * again from the saved visual tokens; what it then owes the rest of the network
+ * is the chain rule through out = project(x, w) (Section 2's linear maps):
+ * with g = d loss / d out, [B, H, S, D] like out,
+ *     dw[h * D + c, e] = sum_{b, s} g[b, h, s, c] * x[b, s, e]
+ *     dx[b, s, e]      = sum_{h, c} g[b, h, s, c] * w[h * D + c, e].
+ * One double-precision sum per element, in the order written.
+ * cols == NULL: every row of dw, [H * D, E]; otherwise cols lists n_cols output
+ * columns n = h * D + c and dw is [n_cols, E].
+ * rows == NULL: every token, dx is [B, S, E]; otherwise rows holds n_rows pairs
+ * (b, s) and dx is [n_rows, E].
+ * ------------------------------------------------------------------------- */
+void lvx_oracle_project_bwd_w(int B, int S, int E, int H, int D, const float *x, const float *g,
+                              int n_cols, const int32_t *cols, double *dw)
+{
+    const long n = cols ? n_cols : (long)H * D;
+#pragma omp parallel for schedule(static)
+    for (long r = 0; r < n; ++r) {
+        const int col = cols ? cols[r] : (int)r;
+        const int h = col / D, c = col % D;
+        for (int e = 0; e < E; ++e) {
+            double acc = 0.0;
+            for (int b = 0; b < B; ++b)
+                for (int s = 0; s < S; ++s)
+                    acc += (double)g[(((long)b * H + h) * S + s) * D + c] *
+                           (double)x[((long)b * S + s) * E + e];
+            dw[r * E + e] = acc;
+        }
+    }
+}
+
+void lvx_oracle_project_bwd_x(int B, int S, int E, int H, int D, const float *w, const float *g,
+                              int n_rows, const int32_t *rows, double *dx)
+{
+    const long n = rows ? n_rows : (long)B * S;
+#pragma omp parallel for schedule(static)
+    for (long r = 0; r < n; ++r) {
+        const int b = rows ? rows[2 * r] : (int)(r / S);
+        const int s = rows ? rows[2 * r + 1] : (int)(r % S);
+        for (int e = 0; e < E; ++e) {
+            double acc = 0.0;
+            for (int h = 0; h < H; ++h)
+                for (int c = 0; c < D; ++c)
+                    acc += (double)g[(((long)b * H + h) * S + s) * D + c] *
+                           (double)w[((long)h * D + c) * E + e];
+            dx[r * E + e] = acc;
+        }
     }
 }
