@@ -31,10 +31,12 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch (read + written) of the three matrix kernels on one K/V block of the bench
 # workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file scaled by what the same
-# counters read for a plain copy of known size (profiles/bench_c3_longvideo_256k_hbm_traffic.md).
-# Counters cannot be read from inside this process, so the figures are carried here.
-MEASURED_HBM_BYTES = {"bwd_dkdv": int((258.5 + 128.0) * 2**20), "bwd_dq": int((192.9 + 32.0) * 2**20),
-                      "fwd": int((167.0 + 32.3) * 2**20)}
+# counters read for a plain copy of known size.  Counters cannot be read from inside this process,
+# so the figures are carried here together with where and when they were measured; they describe
+# the kernels of that commit and are refreshed with the profile.
+MEASURED_HBM = {"profile": "profiles/bench_c3_longvideo_256k_hbm_traffic.md", "kernels_of_commit": "936e3e3",
+                "bytes": {"bwd_dkdv": int((258.5 + 128.0) * 2**20), "bwd_dq": int((192.9 + 32.0) * 2**20),
+                          "fwd": int((167.0 + 32.3) * 2**20)}}
 
 
 def cpu_baseline(w, seed):
@@ -151,13 +153,35 @@ def main():
     ms_merge = timed(lambda: B.lvx_xattn_merge([o_acc, o_part], [l_acc, l_part], o_acc, l_acc), reps)
     rows = w.B * w.Hq * w.Sq
     merge_bytes = 3 * rows * w.D * 4 + 3 * rows * 4
+    # the N-way form of Rescale: one partial result per K/V block (at least two), combined in one
+    # launch into an output of the input dtype: reads N * (O + L) float32, writes O (bf16) + L
+    n_way = max(2, w.n_blocks)
+    o_parts = [torch.randn_like(o_part) for _ in range(n_way)]
+    l_parts = [torch.randn_like(l_part) for _ in range(n_way)]
+    o_fin, l_fin = torch.empty_like(q), torch.empty_like(l_part)
+    ms_merge_n = timed(lambda: B.lvx_xattn_merge(o_parts, l_parts, o_fin, l_fin), reps)
+    merge_n_bytes = n_way * (rows * w.D * 4 + rows * 4) + rows * w.D * o_fin.element_size() + rows * 4
+    del o_parts, l_parts, o_fin, l_fin
+    # the backward in its one-kernel form (all five products in one pass), where the problem allows it
+    ms_fused = None
+    if w.dtype == "bf16" and not w.masked and w.D == 128 and blk >= 256 and w.Sq >= 32:
+        fused = B.LVX_BWD_DKDV | B.LVX_BWD_DQ | B.LVX_BWD_FUSED
+        ms_fused = timed(lambda: B.lvx_xattn_bwd(p, q, kb, vb, o, lse, g, m0, loop.dq_accum,
+                                                 dk[:, :, :blk], dv[:, :, :blk], loop.ws, fused), reps)
     kernels = {
         "bwd_dkdv": {"ms": ms_dkdv, "flops": 8 * unit, "tflops": 8 * unit / ms_dkdv * 1e-9},
         "bwd_dq": {"ms": ms_dq, "flops": 6 * unit, "tflops": 6 * unit / ms_dq * 1e-9},
         "fwd": {"ms": ms_fwd, "flops": 4 * unit, "tflops": 4 * unit / ms_fwd * 1e-9},
         "merge": {"ms": ms_merge, "bytes": merge_bytes, "gbs": merge_bytes / ms_merge * 1e-6,
                   "frac_hbm": merge_bytes / ms_merge * 1e-6 / PEAK_HBM_GBS},
+        "merge_nway": {"parts": n_way, "ms": ms_merge_n, "bytes": merge_n_bytes,
+                       "gbs": merge_n_bytes / ms_merge_n * 1e-6,
+                       "frac_hbm": merge_n_bytes / ms_merge_n * 1e-6 / PEAK_HBM_GBS},
     }
+    if ms_fused is not None:
+        kernels["bwd_fused"] = {"ms": ms_fused, "flops": 10 * unit, "tflops": 10 * unit / ms_fused * 1e-9,
+                                "note": "the optional one-kernel backward (LVX_BWD_FUSED) on the same block; "
+                                        "compare with bwd_dkdv + bwd_dq, which lvx_xattn_bwd runs by default"}
     # ---- the recomputation of Section 3.2 beside it (not part of `value`): K and V of one block
     # from that block's visual tokens, and Q from the text tokens, with an embedding width of
     # Hq * D (the width of the language model the shapes stand for) and seeded synthetic weights
@@ -188,13 +212,14 @@ def main():
     roofline = {"bound": "mfma", "kernel": dom, "achieved": kernels[dom]["tflops"],
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": kernels[dom]["tflops"] / PEAK_BF16_TFLOPS,
-                "traffic": MEASURED_HBM_BYTES[dom] if args.workload == "c3_longvideo_256k" else None,
+                "traffic": MEASURED_HBM["bytes"][dom] if args.workload == "c3_longvideo_256k" else None,
+                "traffic_source": {k: MEASURED_HBM[k] for k in ("profile", "kernels_of_commit")},
                 "launch_ms": kernels[dom]["ms"],
                 "note": "flops = the matrix products this kernel itself performs per launch "
                         "(one K/V block of the workload)"}
 
     out = {
-        "metric": "cross-attn fwd+bwd TFLOP/s, Sq=2048 Skv=256K, 1 GPU",
+        "metric": f"cross-attn fwd+bwd TFLOP/s, Sq={w.Sq} Skv={w.Skv // 1024}K, 1 GPU",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",

@@ -77,6 +77,9 @@ class BlockLoop:
 
     def forward(self, q, k, v) -> Tuple[torch.Tensor, torch.Tensor]:
         """Returns (O in the input dtype, L float32); both are buffers owned by this object."""
+        # (the running O of the block loop is written with Q's strides by the first visit and read as
+        # a contiguous tensor by the others)
+        assert self.n_blocks == 1 or q.is_contiguous(), "the block loop needs a contiguous Q"
         if self.n_blocks == 1:
             p = B.make_problem(q, k, self.scale)
             B.lvx_xattn_fwd(p, q, k, v, self._mask_for(0), self.o, self.lse, self.ws)

@@ -68,4 +68,7 @@ def build(force: bool = True, extra_flags=()) -> str:
 
 
 if __name__ == "__main__":
-    print(build(force="--incremental" not in sys.argv))
+    # --define NAME=VALUE (repeatable): extra preprocessor definitions, e.g. the measurement switches
+    # of the fused backward kernel
+    defs = [f"-D{sys.argv[i + 1]}" for i, a in enumerate(sys.argv[:-1]) if a == "--define"]
+    print(build(force="--incremental" not in sys.argv or bool(defs), extra_flags=defs))

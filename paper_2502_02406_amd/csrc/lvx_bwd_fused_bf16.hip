@@ -34,6 +34,14 @@
 
 #include <type_traits>
 
+// Measurement builds only (python -m paper_2502_02406_amd.build --define LVX_PROBE=<bits>): parts of
+// the kernel switched off to see what each costs.  RESULTS ARE WRONG with any bit set.
+//   1  no dQ product (its matrix instructions and operand reads)
+//   2  no loads of old dQ tiles (the accumulation starts from zero)
+//   4  no stores of dQ tiles inside the loop (one store at the very end keeps the product alive)
+//   8  no locks
+//  16  cycle counters per wave, added up in the words after the error word: cycles waited for
+//      memory before a step's barrier, cycles inside the barrier, cycles of the whole kernel, waves
 #ifndef LVX_PROBE
 #define LVX_PROBE 0
 #endif
@@ -108,11 +116,11 @@ __device__ __forceinline__ bf16x8 join8(s16x4 lo, s16x4 hi) {
 // policy, and the order of data accesses against lock accesses is kept with explicit waits.
 typedef int __attribute__((address_space(1))) gint;
 __device__ __forceinline__ int lock_try(int* lk) {          // 0 = taken by this call
-  if (LVX_PROBE & (1 | 4)) return 0;
+  if (LVX_PROBE & 8) return 0;
   return __hip_atomic_exchange((gint*)lk, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void lock_release(int* lk) {
-  if (LVX_PROBE & (1 | 4)) return;
+  if (LVX_PROBE & 8) return;
   __hip_atomic_store((gint*)lk, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
@@ -205,22 +213,21 @@ bwd_fused_bf16_kernel(BwdArgs a) {
   // store takes far longer than a load.
   f32x16 dq, dq_old;
   unsigned long long pr_wait = 0, pr_bar = 0;
-  const unsigned long long pr_t0 = (LVX_PROBE & 0x400) ? __builtin_readcyclecounter() : 0;
+  const unsigned long long pr_t0 = (LVX_PROBE & 16) ? __builtin_readcyclecounter() : 0;
   bool probe_final = false;
-  if (LVX_PROBE & 0x100) dq_old = zero16();
+  if (LVX_PROBE & 2) dq_old = zero16();
   const int dq_voff = lane * 16;
   auto dq_load_part = [&](int s, int q4) __attribute__((always_inline)) {
-    if (LVX_PROBE & (1 | 8 | 0x100)) return;
+    if (LVX_PROBE & 2) return;
     const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(dq_rsrc, dq_voff, s * 16384 + q4 * 1024, AGENT);
 #pragma unroll
     for (int e = 0; e < 4; ++e) dq_old[4 * q4 + e] = __uint_as_float(x[e]);
   };
   auto dq_store_part = [&](int s, int q4) __attribute__((always_inline)) {
-    if ((LVX_PROBE & (1 | 16)) || ((LVX_PROBE & 0x200) && !probe_final)) return;
+    if ((LVX_PROBE & 4) && !probe_final) return;
     const u32x4 x = {__float_as_uint(dq[4 * q4]), __float_as_uint(dq[4 * q4 + 1]), __float_as_uint(dq[4 * q4 + 2]),
                      __float_as_uint(dq[4 * q4 + 3])};
-    __builtin_amdgcn_raw_buffer_store_b128(x, dq_rsrc, dq_voff, ((LVX_PROBE & 64) ? (int)(blockIdx.x & 255) : s) * 16384 + q4 * 1024,
-                                           (LVX_PROBE & 32) ? 0 : AGENT);
+    __builtin_amdgcn_raw_buffer_store_b128(x, dq_rsrc, dq_voff, s * 16384 + q4 * 1024, AGENT);
   };
   auto dq_load = [&](int s) __attribute__((always_inline)) {
 #pragma unroll
@@ -232,7 +239,7 @@ bwd_fused_bf16_kernel(BwdArgs a) {
   };
   // lane 0 tries until it has the lock; a wave that gives up reports it and goes on
   auto lock_spin = [&](int* lk) __attribute__((always_inline)) {
-    if (LVX_PROBE & (1 | 4)) return;
+    if (LVX_PROBE & 8) return;
     if (lane == 0) {
       int tries = 0;
       while (lock_try(lk) != 0) {
@@ -439,8 +446,9 @@ bwd_fused_bf16_kernel(BwdArgs a) {
     Carry cy;
 #pragma unroll
     for (int m = 0; m < NM; ++m) {
-      const bool is_dq = m >= NV && ((m - NV) & 1) != 0 && !(LVX_PROBE & 2);
-      if (!is_dq) {
+      const bool is_dq = m >= NV && ((m - NV) & 1) != 0;
+      if (is_dq && (LVX_PROBE & 1)) {
+      } else if (!is_dq) {
         // u: number of this instruction among the 2 NV of dV and dK
         const int u = m < NV ? m : NV + (m - NV) / 2;
         const bool is_dk = u >= NV;
@@ -536,12 +544,12 @@ bwd_fused_bf16_kernel(BwdArgs a) {
       }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       unsigned long long t0 = 0, t1 = 0;
-      if (LVX_PROBE & 0x400) t0 = __builtin_readcyclecounter();
+      if (LVX_PROBE & 16) t0 = __builtin_readcyclecounter();
       if (stores_last) wait_vmcnt<4>();
       else wait_vmcnt<0>();
-      if (LVX_PROBE & 0x400) t1 = __builtin_readcyclecounter();
+      if (LVX_PROBE & 16) t1 = __builtin_readcyclecounter();
       wg_barrier();
-      if (LVX_PROBE & 0x400) { const unsigned long long t2 = __builtin_readcyclecounter(); pr_wait += t1 - t0; pr_bar += t2 - t1; }
+      if (LVX_PROBE & 16) { const unsigned long long t2 = __builtin_readcyclecounter(); pr_wait += t1 - t0; pr_bar += t2 - t1; }
       asm volatile("" ::: "memory");
     };
     // What follows the barrier of step i, and then the contraction of step i + 1.  full: steps
@@ -598,8 +606,8 @@ bwd_fused_bf16_kernel(BwdArgs a) {
     }
   }
 
-  if (LVX_PROBE & 0x200) { probe_final = true; dq_store(0); }
-  if ((LVX_PROBE & 0x400) && lane == 0) {
+  if (LVX_PROBE & 4) { probe_final = true; dq_store(0); }
+  if ((LVX_PROBE & 16) && lane == 0) {
     atomicAdd((unsigned long long*)(a.dq_err + 2), pr_wait);
     atomicAdd((unsigned long long*)(a.dq_err + 4), pr_bar);
     atomicAdd((unsigned long long*)(a.dq_err + 6), __builtin_readcyclecounter() - pr_t0);

@@ -45,6 +45,13 @@ def _blocks(body):
     ("lvx_bwd_dkdv_bf16.hip", "bwd_dkdv_bf16_kernelILi128ELb0ELb1E", 128),   # the same loop over a list of steps
     ("lvx_bwd_dq_bf16.hip", "bwd_dq_bf16_kernelILi128ELb0ELb0E", 96),        # one tile = two halves of 48
     ("lvx_bwd_dq_bf16.hip", "bwd_dq_bf16_kernelILi128ELb0ELb1E", 96),        # the same loop over a list of tiles
+    # the instantiations for 64-wide heads: half the matrix instructions per step or tile
+    ("lvx_bwd_dkdv_bf16.hip", "bwd_dkdv_bf16_kernelILi64ELb0ELb0E", 64),
+    ("lvx_bwd_dkdv_bf16.hip", "bwd_dkdv_bf16_kernelILi64ELb0ELb1E", 64),
+    ("lvx_bwd_dq_bf16.hip", "bwd_dq_bf16_kernelILi64ELb0ELb0E", 48),
+    ("lvx_bwd_dq_bf16.hip", "bwd_dq_bf16_kernelILi64ELb0ELb1E", 48),
+    # the fused backward: scoring of one step and contraction of the next in one block
+    ("lvx_bwd_fused_bf16.hip", "bwd_fused_bf16_kernelILi128E", 80),
 ])
 def test_dense_loop_moves_no_accumulator(src, kernel, loop_mfma):
     body = _kernel(_asm(src), kernel)
@@ -73,6 +80,10 @@ def test_general_dkdv_leaves_half_the_accumulation_file():
     ("lvx_fwd_bf16.hip", "fwd_bf16_kernelILi128ELb0EE"),
     ("lvx_fwd_bf16.hip", "fwd_bf16_kernelILi128ELb1EE"),     # the same kernel over a list of tiles
     ("lvx_bwd_dq_bf16.hip", "bwd_dq_bf16_kernelILi128ELb1ELb0E"),
+    ("lvx_fwd_bf16.hip", "fwd_bf16_kernelILi64ELb0EE"),      # 64-wide heads
+    ("lvx_fwd_bf16.hip", "fwd_bf16_kernelILi64ELb1EE"),
+    ("lvx_bwd_dq_bf16.hip", "bwd_dq_bf16_kernelILi64ELb1ELb0E"),
+    ("lvx_bwd_dkdv_bf16.hip", "bwd_dkdv_bf16_kernelILi64ELb1ELb0E"),
 ])
 def test_blocks_with_matrix_instructions_move_no_accumulator(src, kernel):
     """The dense forward's loop has (rare) branches and the general dQ kernel has mask code, so
@@ -86,4 +97,18 @@ def test_blocks_with_matrix_instructions_move_no_accumulator(src, kernel):
             n += 1
             assert "v_accvgpr" not in blk, "accumulator moved next to matrix instructions"
             assert "scratch_" not in blk, "register spill next to matrix instructions"
+    assert n > 0
+
+
+def test_fused_backward_accumulators_stay_put():
+    """The fused backward writes only its dK / dV accumulations by hand (into the accumulation file);
+    S, dP and dQ are matrix instructions the compiler knows.  Wherever a hand-written one is issued,
+    no accumulator may move.  (Spills of ordinary registers are the compiler's own business: it knows
+    every instruction that wrote them; the steady-state block, checked above, has none.)"""
+    body = _kernel(_asm("lvx_bwd_fused_bf16.hip"), "bwd_fused_bf16_kernelILi128E")
+    n = 0
+    for blk in _blocks(body):
+        if re.search(r"v_mfma_f32_32x32x16_bf16 a\[", blk):
+            n += 1
+            assert "v_accvgpr" not in blk, "accumulator moved next to hand-written matrix instructions"
     assert n > 0

@@ -134,6 +134,12 @@ FWD_BWD_CASES = [
     small("bf16_fused_rescale", B=4, Hq=64, Hkv=8, D=64, Sq=32, Skv=512, n_blocks=4),
     small("bf16_long_q", Sq=1100, Skv=384),                                    # five query tiles, six key tiles
     small("bf16_gqa8_d64_blocks", D=64, Hq=8, Hkv=1, Sq=96, Skv=1536, n_blocks=3),
+    # 64-wide heads through every kind of kernel, six or more tiles / steps each: dense; a mask
+    # that selects whole steps and whole key tiles (step lists in dK/dV, tile lists plus the general
+    # kernels on the partly visible tiles in the forward and dQ); a mask that cuts through tiles
+    small("bf16_d64_dense_long", D=64, Hq=2, Sq=224, Skv=1024),
+    small("bf16_d64_blockcausal_lists", D=64, Hq=4, Hkv=2, Sq=256, Skv=4096, q_chunk=32, kv_block=512),
+    small("bf16_d64_mixed_mask", D=64, Hq=4, Hkv=2, Sq=200, Skv=1500, q_chunk=5, kv_block=24),
     # the structure of the masked bench workload at a size the oracle does in seconds: 32-row
     # chunks, 1024-key frames, chunk i sees frames <= i -- every wave meets tiles that are
     # visible to one of its two row blocks only, inside the pipelined loop
@@ -304,9 +310,16 @@ def test_merge_matches_oracle(dtype):
         l_out = torch.empty(shape[:3], dtype=torch.float32, device="cuda")
         B.lvx_xattn_merge(parts, lses, o_out, l_out)
         torch.cuda.synchronize()
-        tol = 1e-5 if out_dtype == torch.float32 and dtype == "f32" else 2e-2
+        # The parts are exact in float32 (the oracle reads their rounded values), the weights and
+        # sums are float32 arithmetic (1e-5 of the largest value is far above its noise), and a
+        # bf16 output adds ONE rounding: half a unit in the last of 8 mantissa bits, at most 2^-8 |O|
+            # (reached just above a power of two).
         got = o_out.float().cpu().numpy().astype(np.float64)
-        assert np.abs(got - Oref).max() <= tol * max(1.0, np.abs(Oref).max())
+        bound = 1e-5 * max(1.0, np.abs(Oref).max())
+        if out_dtype == torch.bfloat16:
+            bound = bound + 2.0 ** -8 * np.abs(Oref)
+        assert np.all(np.abs(got - Oref) <= bound), f"merge error {np.abs(got - Oref).max()}"
+
         Lg = l_out.cpu().numpy().astype(np.float64)
         assert np.array_equal(np.isneginf(Lg), np.isneginf(Lref))
         fin = np.isfinite(Lref)
