@@ -201,6 +201,28 @@ typedef struct {
 lvx_status lvx_xattn_project(const lvx_projection* p, lvx_dtype dtype, const void* x, const void* w,
                              int n_out, void* const* out, void* hip_stream);
 
+/* The chain rule through those projections (Section 2's linear maps; Section 3.2 evaluates them
+ * again in the backward pass precisely so that dK and dV can be carried back to the visual tokens
+ * and to W_K, W_V without K and V having been kept).  With d_out[o] = d loss / d out[o]:
+ *     dx[b, s, e]              = sum_{o, h, c} d_out[o][b, h, s, c] * w[(o * H + h) * D + c, e]
+ *     dw[(o * H + h) * D + c, e] += sum_{b, s} d_out[o][b, h, s, c] * x[b, s, e].
+ * p, x, w, n_out as for lvx_xattn_project (same layouts, same stride rules).
+ * d_out  host array of n_out (1 or 2) device pointers, each [B, H, S, D] of `dtype`, contiguous
+ *        (what lvx_xattn_bwd writes as dK, dV, and lvx_xattn_dq_finalize as dQ).
+ * dx     device, [B, S, E] of `dtype` with x's strides, OVERWRITTEN (one rounding of a float32
+ *        sum); NULL = not wanted.
+ * dw     device, [n_out * H * D, E] float32, contiguous, ACCUMULATED INTO: the caller zeroes it
+ *        before the first K/V block of a step, and each block's call adds its tokens' part
+ *        (the order of the additions is the order of the calls: results repeat bit for bit);
+ *        NULL = not wanted.  At least one of dx, dw must be given.
+ * LVX_BF16 runs on the matrix cores when E % 256 == 0, (H * D) % 256 == 0, D % 64 == 0,
+ * B * S < 2^24 and B * S * H * D < 2^30; other shapes, and LVX_F32, take a plain kernel (one
+ * float32 sum per element in the order of the definition: correctness-grade, slow).
+ * LVX_BF16: pointers and x's row stride must be 16-byte aligned.  No workspace. */
+lvx_status lvx_xattn_project_bwd(const lvx_projection* p, lvx_dtype dtype, const void* x, const void* w,
+                                 int n_out, const void* const* d_out, void* dx, float* dw,
+                                 void* hip_stream);
+
 /* Human-readable name of a status code (static storage). */
 const char* lvx_strerror(lvx_status s);
 

@@ -25,7 +25,7 @@ LVX_BWD_FUSED, LVX_BWD_SPLIT = 8, 16
 LVX_STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = ("lvx_xattn_workspace_bytes", "lvx_xattn_fwd", "lvx_xattn_fwd_static", "lvx_xattn_fwd_merge", "lvx_xattn_merge", "lvx_xattn_bwd",
-           "lvx_xattn_bwd_stages", "lvx_xattn_bwd_error_word", "lvx_xattn_dq_finalize", "lvx_xattn_project", "lvx_strerror")
+           "lvx_xattn_bwd_stages", "lvx_xattn_bwd_error_word", "lvx_xattn_dq_finalize", "lvx_xattn_project", "lvx_xattn_project_bwd", "lvx_strerror")
 
 
 class LvxError(RuntimeError):
@@ -96,6 +96,10 @@ def load() -> C.CDLL:
         lib.lvx_xattn_project.restype = C.c_int
         lib.lvx_xattn_project.argtypes = [C.POINTER(lvx_projection), C.c_int, C.c_void_p, C.c_void_p,
                                           C.c_int, C.POINTER(C.c_void_p), C.c_void_p]
+        lib.lvx_xattn_project_bwd.restype = C.c_int
+        lib.lvx_xattn_project_bwd.argtypes = [C.POINTER(lvx_projection), C.c_int, C.c_void_p, C.c_void_p,
+                                              C.c_int, C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p,
+                                              C.c_void_p]
         lib.lvx_strerror.restype = C.c_char_p
         lib.lvx_strerror.argtypes = [C.c_int]
         _lib = lib
@@ -259,3 +263,30 @@ def lvx_xattn_project(x, w, outs) -> None:
     code = load().lvx_xattn_project(C.byref(p), dtype_code(x.dtype), x.data_ptr(), w.data_ptr(),
                                     len(outs), arr, _stream())
     _check(code, "lvx_xattn_project")
+
+
+def lvx_xattn_project_bwd(x, w, d_outs, dx=None, dw=None) -> None:
+    """d_outs: one or two tensors [B, H, S, D] (contiguous, dtype of x), the gradients of the heads
+    that lvx_xattn_project made from x [B, S, E] and w [len(d_outs) * H * D, E].  dx (x's shape,
+    strides and dtype) is overwritten with the gradient of x; dw (w's shape, float32) has the
+    gradient of w added to it."""
+    if not x.is_cuda:
+        raise RuntimeError("lvx_xattn_project_bwd needs device tensors")
+    assert x.dim() == 3 and x.stride(2) == 1 and w.dim() == 2 and w.is_contiguous() and w.dtype == x.dtype
+    assert all(g.dim() == 4 and g.is_contiguous() and g.dtype == x.dtype for g in d_outs)
+    assert dx is not None or dw is not None
+    p = lvx_projection()
+    p.B, p.S, p.E = x.shape
+    _, p.H, _, p.D = d_outs[0].shape
+    assert all(tuple(g.shape) == (p.B, p.H, p.S, p.D) for g in d_outs)
+    assert tuple(w.shape) == (len(d_outs) * p.H * p.D, p.E)
+    p.x_sb, p.x_ss = x.stride(0), x.stride(1)
+    if dx is not None:
+        assert dx.shape == x.shape and dx.stride() == x.stride() and dx.dtype == x.dtype and dx.is_cuda
+    if dw is not None:
+        assert dw.shape == w.shape and dw.is_contiguous() and dw.dtype == torch.float32 and dw.is_cuda
+    arr = (C.c_void_p * len(d_outs))(*[g.data_ptr() for g in d_outs])
+    code = load().lvx_xattn_project_bwd(C.byref(p), dtype_code(x.dtype), x.data_ptr(), w.data_ptr(),
+                                        len(d_outs), arr, dx.data_ptr() if dx is not None else None,
+                                        dw.data_ptr() if dw is not None else None, _stream())
+    _check(code, "lvx_xattn_project_bwd")

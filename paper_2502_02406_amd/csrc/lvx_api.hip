@@ -466,4 +466,40 @@ lvx_status lvx_xattn_project(const lvx_projection* p, lvx_dtype dtype, const voi
   return e == hipSuccess ? LVX_OK : LVX_ERR_HIP;
 }
 
+lvx_status lvx_xattn_project_bwd(const lvx_projection* p, lvx_dtype dtype, const void* x, const void* w,
+                                 int n_out, const void* const* d_out, void* dx, float* dw,
+                                 void* hip_stream) {
+  if (!p || !x || !w || !d_out) return LVX_ERR_NULL;
+  if (n_out < 1 || n_out > 2) return LVX_ERR_SHAPE;
+  for (int o = 0; o < n_out; ++o)
+    if (!d_out[o]) return LVX_ERR_NULL;
+  if (!dx && !dw) return LVX_ERR_NULL;
+  if (p->B <= 0 || p->S <= 0 || p->E <= 0 || p->H <= 0 || p->D <= 0) return LVX_ERR_SHAPE;
+  if ((long)n_out * p->H * p->D > INT32_MAX) return LVX_ERR_SHAPE;
+  if (dtype != LVX_F32 && dtype != LVX_BF16) return LVX_ERR_DTYPE;
+  const int esz = dtype == LVX_F32 ? 4 : 2;
+  if (p->x_ss < p->E || p->x_sb != (int64_t)p->S * p->x_ss) return LVX_ERR_STRIDE;
+  if (dtype == LVX_BF16) {                           // 16-byte copies and stores
+    if ((p->x_ss * esz) % 16 != 0 || !aligned16(x) || !aligned16(w)) return LVX_ERR_STRIDE;
+    if ((dx && !aligned16(dx)) || (dw && !aligned16(dw))) return LVX_ERR_STRIDE;
+    for (int o = 0; o < n_out; ++o)
+      if (!aligned16(d_out[o])) return LVX_ERR_STRIDE;
+  }
+  ProjBwdArgs a{};
+  a.x = x;
+  a.w = w;
+  for (int o = 0; o < n_out; ++o) a.g[o] = d_out[o];
+  a.dx = dx;
+  a.dw = dw;
+  a.M = (long)p->B * p->S;
+  a.ldx = p->x_ss;
+  a.S = p->S;
+  a.E = p->E;
+  a.N = n_out * p->H * p->D;
+  a.H = p->H;
+  a.D = p->D;
+  const hipError_t e = launch_project_bwd(a, dtype == LVX_F32, (hipStream_t)hip_stream);
+  return e == hipSuccess ? LVX_OK : LVX_ERR_HIP;
+}
+
 }  // extern "C"

@@ -96,6 +96,20 @@ struct ProjArgs {
 bool project_bf16_supported(const ProjArgs& a);   // shapes the matrix-core kernel takes
 hipError_t launch_project(const ProjArgs& a, int is_f32, hipStream_t s);
 
+// Gradients of the projection: dx[m, e] = sum_n g[m, n] w[n, e] (rounded to the tensors' type),
+// dw[n, e] += sum_m g[m, n] x[m, e] (float32), g given head-major per output like ProjArgs::out.
+struct ProjBwdArgs {
+  const void* x;        // [M, E], row stride ldx elements
+  const void* w;        // [N, E] contiguous
+  const void* g[2];     // each [B, H, S, D] contiguous
+  void* dx;             // [M, E], row stride ldx, or null
+  float* dw;            // [N, E] contiguous, or null
+  long M, ldx;
+  int S, E, N, H, D;
+};
+bool project_bwd_bf16_supported(const ProjBwdArgs& a);   // shapes the matrix-core kernels take
+hipError_t launch_project_bwd(const ProjBwdArgs& a, int is_f32, hipStream_t s);
+
 // Bytes of workspace that lvx_xattn_fwd needs for exactly this call (with this mask or without
 // one; lvx_xattn_workspace_bytes returns the larger of the two cases); 0 for invalid arguments.
 size_t fwd_workspace_need(const lvx_problem* p, lvx_dtype dtype, const lvx_mask* mask);

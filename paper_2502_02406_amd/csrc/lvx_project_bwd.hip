@@ -1,0 +1,401 @@
+// Gradients of the projections: the chain rule through the linear maps of Section 2 that Section
+// 3.2 has the backward pass evaluate again.  With g[o] = d loss / d out[o], head-major like out,
+//     dx[b, s, e]            = sum_{o, h, c} g[o][b, h, s, c] * w[(o H + h) D + c, e]
+//     dw[(o H + h) D + c, e] += sum_{b, s}   g[o][b, h, s, c] * x[b, s, e]
+// dx is rounded once to the tensors' type; dw is float32 and ACCUMULATED, because the weights of
+// K and V meet one gradient per K/V block and those add up.
+//
+// bf16: both products run on the matrix cores with the tiling of the forward projection: one
+// workgroup = 4 wavefronts (one per SIMD) makes a 256 x 256 tile of the result, a wave owns
+// 128 x 128 of it as 4 x 4 blocks of 32 x 32 in the accumulation registers, tile pairs of 64
+// contraction steps travel HBM -> LDS by direct copies into two 64 KB slots that alternate.
+// What differs is where the contraction index lies in memory:
+//   dx = G W    contraction over the columns n of the projection.  G is read like x in the
+//               forward (rows = tokens, the 64 columns of a step contiguous: a 128-byte line
+//               inside one head); W has n along its ROWS, so its tile is kept as [n][e] and
+//               its operand taken with the transposing LDS read.
+//   dw = G^T X  contraction over the tokens.  Both G ([token][n]) and x ([token][e]) have the
+//               contraction index along their rows: both tiles are [token][256 columns] and both
+//               operands come from transposing reads.
+// A [k][256] tile has rows of 512 bytes; chunk c (16 bytes) of row r sits at position
+// c ^ 4 (r % 4): the four rows that a transposing read of 16 lanes touches then lie in four
+// different 64-byte bank groups.  The transposing read delivers the 16 contraction steps of a
+// matrix instruction in the order 0-3, 8-11 (lanes 0-31) / 4-7, 12-15 (lanes 32-63); the G
+// operand of dx, read with plain 8-byte reads, takes the same order.
+// Rows past the last token are never stored (dx) and are cleared in LDS before they are
+// multiplied (dw, where they would otherwise enter every sum).
+#include "lvx_internal.h"
+#include "lvx_mfma.h"
+#include "lvx_kv_ring.h"
+
+#include <type_traits>
+
+namespace lvx {
+
+namespace {
+
+constexpr int T = 256;                 // edge of a workgroup's tile of the result
+constexpr int BK = 64;                 // contraction steps per tile pair
+constexpr int NSLOT = 2;
+constexpr int KR_ROWB = T * 2;         // [k][256] tile: bytes of a row
+constexpr int RK_ROWB = BK * 2;        // [256][k] tile: bytes of a row (one 128-byte line)
+constexpr int TILE_B = BK * KR_ROWB;   // either kind: 32 KB
+static_assert(TILE_B == T * RK_ROWB, "both tile kinds take the same room");
+constexpr int SLOT_B = 2 * TILE_B;     // A-side tile ([k][256 columns e]), then B-side tile
+constexpr int RING_B = NSLOT * SLOT_B;
+constexpr int TB_PITCH = 128 * 2 + 16; // dx epilogue: a wave's 128 tokens x 128 columns of bf16, padded rows
+constexpr int TB_WAVE = 128 * TB_PITCH;
+constexpr int SMEM_B = RING_B > 4 * TB_WAVE ? RING_B : 4 * TB_WAVE;
+constexpr int NPART = 16;              // copies per wave and tile pair: 8 per tile
+
+__device__ __forceinline__ int perm_of(int r) { return (r & 7) ^ ((r >> 3) & 1); }
+
+// floor(m / S) and the remainder for 0 <= m < 2^24 (exact: the float quotient is off by at most one)
+__device__ __forceinline__ void div_tokens(int m, int S, float inv_S, int* b, int* s) {
+  int q = (int)((float)m * inv_S);
+  int r = m - q * S;
+  if (r < 0) { --q; r += S; }
+  if (r >= S) { ++q; r -= S; }
+  *b = q;
+  *s = r;
+}
+
+// MODE 0: dx = G W (rows = tokens, columns = features e, contraction over n)
+// MODE 1: dw += G^T X (rows = columns n of the projection, columns = e, contraction over tokens)
+template <int MODE>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+project_bwd_bf16_kernel(ProjBwdArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int n_rt = MODE == 0 ? (int)((a.M + T - 1) / T) : a.N / T;   // row tiles of the result
+  const int n_ct = a.E / T;
+  HeadWork hw;                                       // the column tiles of a row tile share an XCD
+  if (!xcd_decode(blockIdx.x, n_rt, n_ct, &hw)) return;
+  const long r0 = (long)hw.head * T;                 // first token (MODE 0) / first column n (MODE 1)
+  const int e0 = hw.item * T;
+  const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, l31 = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;           // this wave's 128 rows / 128 columns of the tile
+  const int nk = MODE == 0 ? a.N / BK : (int)((a.M + BK - 1) / BK);
+  const int HD = a.H * a.D;
+  const float inv_S = 1.0f / (float)a.S;
+  const long head_b = (long)a.S * a.D * 2;           // bytes of one head of one batch in g
+
+  // ---- copies into a [k][256] tile: one instruction moves 2 rows x 512 bytes; lane l fills
+  // position l % 32 of row l / 32, which holds chunk (l % 32) ^ 4 (row % 4).  A wave copies rows
+  // 16 wave + 2 j + l / 32, j = 0 .. 7; (row % 4) = 2 (j % 2) + l / 32.
+  const int lh = lane >> 5, pos = lane & 31;
+  unsigned kr_chunk[2];                              // byte offset of the lane's chunk inside a row, j even / odd
+#pragma unroll
+  for (int par = 0; par < 2; ++par) kr_chunk[par] = 16u * (unsigned)(pos ^ (4 * ((2 * par + lh) & 3)));
+
+  // MODE 0: rows of the G tile ([256 tokens][64 n], the forward's x layout): one instruction
+  // moves 8 rows x 128 bytes; a wave copies rows 64 wave + 8 j + l / 8.  Tokens past the last
+  // one re-read it (their results are never stored).
+  unsigned g_row[8];
+  // MODE 1: the lane's column part of a G address, j even / odd (the 256 columns of the tile lie
+  // in one output, in 256 / D heads)
+  unsigned g_col[2];
+  const char* g_tile_base = nullptr;                 // MODE 1: the output's gradient
+  if (MODE == 0) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int r = 64 * wave + 8 * j + (lane >> 3);
+      const long m = r0 + r < a.M ? r0 + r : a.M - 1;
+      int b, s;
+      div_tokens((int)m, a.S, inv_S, &b, &s);
+      g_row[j] = (unsigned)(((long)b * a.H * a.S + s) * a.D * 2) +
+                 16u * (unsigned)((lane & 7) ^ perm_of(8 * j + (lane >> 3)));
+    }
+  } else {
+    const int o = (int)(r0 / HD), nn0 = (int)(r0 % HD);
+    g_tile_base = (const char*)a.g[o];
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+      const int n = nn0 + (int)(kr_chunk[par] / 2);
+      g_col[par] = (unsigned)((long)(n / a.D) * head_b + (long)(n % a.D) * 2);
+    }
+  }
+  const unsigned wrow_b = (unsigned)(a.E * 2), xrow_b = (unsigned)(a.ldx * 2);
+  const unsigned smem_u = lds_base(smem);
+
+  // MODE 0: the head and column that tile pair kt of G starts at, advanced pair by pair (the G
+  // copies of the pairs are issued in ascending order, copy 8 of a pair first)
+  int g_o = 0, g_h = 0, g_c = 0;
+  const char* g_pair_base = nullptr;
+
+  auto issue_part = [&](int kt, int part) __attribute__((always_inline)) {
+    const unsigned st = smem_u + (unsigned)((kt % NSLOT) * SLOT_B);
+    const int j = part & 7;
+    if (part < 8) {                                  // A side: rows kt * 64 + 16 wave + 2 j + lh of w (MODE 0) or x (MODE 1)
+      const unsigned dst = st + (unsigned)((16 * wave + 2 * j) * KR_ROWB);
+      if (MODE == 0) {
+        const char* base = (const char*)a.w + ((long)(kt * BK + 16 * wave + 2 * j) * a.E + e0) * 2;
+        dma16u(base, (unsigned)lh * wrow_b + kr_chunk[j & 1], dst);
+      } else {
+        const long m_first = (long)kt * BK;
+        const int last = (int)(a.M - 1 - m_first);   // rows past it re-read it, and are cleared in LDS
+        const int r = 16 * wave + 2 * j + lh;
+        const char* base = (const char*)a.x + (m_first * a.ldx + e0) * 2;
+        dma16u(base, (unsigned)(r < last ? r : last) * xrow_b + kr_chunk[j & 1], dst);
+      }
+    } else if (MODE == 0) {                          // B side: G, 256 tokens x 64 columns
+      if (part == 8) {
+        g_pair_base = (const char*)a.g[g_o] + (long)g_h * head_b + (long)g_c * 2;
+        g_c += BK;
+        if (g_c == a.D) { g_c = 0; if (++g_h == a.H) { g_h = 0; ++g_o; } }
+      }
+      dma16u(g_pair_base, g_row[j], st + (unsigned)(TILE_B + (64 * wave + 8 * j) * RK_ROWB));
+    } else {                                         // B side: G, 64 tokens x 256 columns
+      const long m_first = (long)kt * BK;
+      const int r = 16 * wave + 2 * j + lh;
+      const long m = m_first + r < a.M ? m_first + r : a.M - 1;
+      int b, s;
+      div_tokens((int)m, a.S, inv_S, &b, &s);
+      const unsigned row = (unsigned)(((long)b * a.H * a.S + s) * a.D * 2);
+      dma16u(g_tile_base, row + g_col[j & 1], st + (unsigned)(TILE_B + (16 * wave + 2 * j) * KR_ROWB));
+    }
+  };
+
+  // ---- operands.  From a [k][256] tile: block jj of the wave's 128 columns, k-step q (16 rows);
+  // lane l supplies the address of 8 bytes of row 4 g + (l % 16) / 4 (+ 16 q, + 8 for the second
+  // read), byte column 64 jj' + 32 ((l / 16) % 2) + 8 (l % 4), where jj' is the block's position
+  // after the permutation: (4 wcol + jj) ^ (row % 4).
+  const int j16 = lane & 15, jr = j16 >> 2;
+  const int tr_lane = (4 * g + jr) * KR_ROWB + 32 * ((lane >> 4) & 1) + 8 * (j16 & 3);
+  int ka[4], kb[4];
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj) {
+    ka[jj] = tr_lane + 64 * ((4 * wn + jj) ^ jr);
+    kb[jj] = TILE_B + tr_lane + 64 * ((4 * wm + jj) ^ jr);
+  }
+  auto tr_op = [&](const char* p) __attribute__((always_inline)) -> bf16x8 {
+    const s16x4 lo = lds_read_tr(p), hi = lds_read_tr(p + 8 * KR_ROWB);
+    typedef __attribute__((ext_vector_type(8))) short s16x8;
+    const s16x8 r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, r);
+  };
+  // From the [256][64] tile (MODE 0): row 32 i + l % 32 of the wave's tokens, k-step q: bytes
+  // 8 g .. 8 g + 7 of chunks 2 q and 2 q + 1 (steps 4 g .. 4 g + 3 and 8 + 4 g .. 8 + 4 g + 3)
+  int rk[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+    rk[q] = TILE_B + (wm * 128 + l31) * RK_ROWB + 16 * ((2 * q) ^ perm_of(l31)) + 8 * g;
+  auto a_op = [&](const char* st, int q, int jj) __attribute__((always_inline)) -> bf16x8 {
+    return tr_op(st + ka[jj] + 16 * q * KR_ROWB);
+  };
+  auto b_op = [&](const char* st, int q, int i) __attribute__((always_inline)) -> bf16x8 {
+    if (MODE == 1) return tr_op(st + kb[i] + 16 * q * KR_ROWB);
+    const char* p = st + rk[q] + 32 * i * RK_ROWB;
+    const u32x2 lo = *(const u32x2*)p;
+    const u32x2 hi = *(const u32x2*)(st + (rk[q] ^ 16) + 32 * i * RK_ROWB);
+    const u32x4 r = {lo[0], lo[1], hi[0], hi[1]};
+    return __builtin_bit_cast(bf16x8, r);
+  };
+
+  f32x16 acc[4][4];                                  // [column block jj][row block i]: lane = row, registers = columns
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { acc[j][i] = zero16(); asm volatile("" : "+a"(acc[j][i])); }
+
+  auto mma16 = [&](const bf16x8 (&bv)[4], const bf16x8 (&av)[4], auto&& hook) __attribute__((always_inline)) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        kvring::mfma_acc(acc[j][i], av[j], bv[i]);
+        hook(4 * j + i);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+  };
+
+  // dw: the rows of the last tile pair that lie past the last token are cleared, in both tiles,
+  // once the pair has landed (every thread calls this behind the barrier that says so)
+  const int tail_rows = (int)(a.M - (long)(nk - 1) * BK);      // rows of the last pair that exist
+  auto settle = [&](int kt) __attribute__((always_inline)) {
+    if (MODE == 1 && kt == nk - 1 && tail_rows < BK) {
+      char* const st = smem + (kt % NSLOT) * SLOT_B;
+      const int n16 = (BK - tail_rows) * (KR_ROWB / 16);
+      const u32x4 z = {0u, 0u, 0u, 0u};
+      for (int c = tid; c < n16; c += 256) {
+        *(u32x4*)(st + tail_rows * KR_ROWB + c * 16) = z;
+        *(u32x4*)(st + TILE_B + tail_rows * KR_ROWB + c * 16) = z;
+      }
+      __builtin_amdgcn_s_waitcnt(0xc07f);            // lgkmcnt(0)
+      wg_barrier();
+    }
+  };
+
+  // ---- pipeline (the forward projection's): pairs 0 and 1 go out whole; later, pair P + 2 goes
+  // out in two batches, the first during the last k-step of pair P (right behind the barrier
+  // that frees its slot), the second during the first k-step of pair P + 1
+#pragma unroll
+  for (int q = 0; q < NSLOT; ++q)
+    if (q < nk) {
+#pragma unroll
+      for (int part = 0; part < NPART; ++part) issue_part(q, part);
+    }
+  if (nk > 1) wait_vmcnt<NPART>();
+  else wait_vmcnt<0>();
+  wg_barrier();
+  settle(0);
+  bf16x8 ba[4], aa[4], bb[4], ab[4];                 // operands of even / odd k-steps
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { ba[i] = b_op(smem, 0, i); aa[i] = a_op(smem, 0, i); }
+
+  auto fetch = [&](const char* st, int q, int u, bf16x8 (&bv)[4], bf16x8 (&av)[4]) __attribute__((always_inline)) {
+    if (u < 4) bv[u] = b_op(st, q, u);
+    else if (u < 8) av[u - 4] = a_op(st, q, u - 4);
+  };
+  auto pair = [&](int P, auto steady, bool send2, bool send1, bool more) __attribute__((always_inline)) {
+    constexpr bool STEADY = decltype(steady)::value;   // send2, send1 and more are all true
+    const char* const st = smem + (P % NSLOT) * SLOT_B;
+    const char* const sn = smem + ((P + 1) % NSLOT) * SLOT_B;
+    mma16(ba, aa, [&](int u) __attribute__((always_inline)) {
+      fetch(st, 1, u, bb, ab);
+      if ((STEADY || send2) && u % 2 == 1) issue_part(P + 1, 8 + u / 2);
+    });
+    mma16(bb, ab, [&](int u) __attribute__((always_inline)) { fetch(st, 2, u, ba, aa); });
+    mma16(ba, aa, [&](int u) __attribute__((always_inline)) { fetch(st, 3, u, bb, ab); });
+    // Pair P + 1 has landed when none of this wave's copies is outstanding, and this wave's last
+    // reads of pair P have returned; behind the barrier that holds for every wave.
+    if (STEADY || more) {
+      __builtin_amdgcn_s_waitcnt(0x0070);              // vmcnt(0) and lgkmcnt(0)
+      wg_barrier();
+      settle(P + 1);
+    }
+    mma16(bb, ab, [&](int u) __attribute__((always_inline)) {
+      if (STEADY || more) fetch(sn, 0, u, ba, aa);
+      if ((STEADY || send1) && u % 2 == 1) issue_part(P + 2, u / 2);
+    });
+  };
+  int P = 0;
+  if (nk > 0) { pair(0, std::false_type{}, false, 2 < nk, 1 < nk); P = 1; }
+  for (; P + 2 < nk; ++P) pair(P, std::true_type{}, true, true, true);
+  for (; P < nk; ++P) pair(P, std::false_type{}, P + 1 < nk, false, P + 1 < nk);
+
+  // ---- epilogue.  Every wave has left the ring and the last matrix instructions have retired
+  // before their registers are read.
+  wg_barrier();
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    asm volatile("s_nop 15\n\ts_nop 15" : "+a"(acc[j][0]), "+a"(acc[j][1]), "+a"(acc[j][2]), "+a"(acc[j][3]));
+  if (MODE == 0) {
+    // turn the tile around in LDS (rounded to bf16) and write whole 256-byte row segments
+    char* const tb = smem + wave * TB_WAVE;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {                // registers 4 q .. 4 q + 3: columns 32 j + 8 q + 4 g + (0..3)
+          const u32x2 y = {pack2_bf16(acc[j][i][4 * q], acc[j][i][4 * q + 1]),
+                           pack2_bf16(acc[j][i][4 * q + 2], acc[j][i][4 * q + 3])};
+          *(u32x2*)(tb + (32 * i + l31) * TB_PITCH + (32 * j + 8 * q + 4 * g) * 2) = y;
+        }
+    uint16_t* const out = (uint16_t*)a.dx + e0 + wn * 128;
+#pragma unroll 4
+    for (int it = 0; it < 32; ++it) {
+      const int row = 4 * it + (lane >> 4), ch = lane & 15;
+      const long m = r0 + wm * 128 + row;
+      const u32x4 y = *(const u32x4*)(tb + row * TB_PITCH + ch * 16);
+      if (m < a.M) *(u32x4*)(out + m * a.ldx + 8 * ch) = y;
+    }
+  } else {
+    // this workgroup alone owns its tile of dw: add in place, 16 bytes per lane and register group
+    float* const out = a.dw + (r0 + wm * 128 + l31) * (long)a.E + e0 + wn * 128 + 4 * g;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          f32x4* const p = (f32x4*)(out + (long)(32 * i) * a.E + 32 * j + 8 * q);
+          f32x4 v = *p;
+#pragma unroll
+          for (int t = 0; t < 4; ++t) v[t] += acc[j][i][4 * q + t];
+          *p = v;
+        }
+  }
+}
+
+// Any shape and both types: one thread per element of the result, the sum in float32 in the order
+// of the definition.
+template <typename TIn> __device__ __forceinline__ float to_f32(TIn v);
+template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f32<__bf16>(__bf16 v) { return (float)v; }
+
+template <typename TIn>
+__global__ void __launch_bounds__(256) project_bwd_x_plain_kernel(ProjBwdArgs a) {
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= a.M * a.E) return;
+  const long m = idx / a.E;
+  const int e = (int)(idx % a.E);
+  const long b = m / a.S, s = m % a.S;
+  const int HD = a.H * a.D;
+  float acc = 0.f;
+  for (int n = 0; n < a.N; ++n) {
+    const int nn = n % HD;
+    const TIn* gp = (const TIn*)a.g[n / HD] + ((b * a.H + nn / a.D) * a.S + s) * a.D + nn % a.D;
+    acc = fmaf(to_f32<TIn>(*gp), to_f32<TIn>(((const TIn*)a.w)[(long)n * a.E + e]), acc);
+  }
+  ((TIn*)a.dx)[m * a.ldx + e] = (TIn)acc;
+}
+
+template <typename TIn>
+__global__ void __launch_bounds__(256) project_bwd_w_plain_kernel(ProjBwdArgs a) {
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long)a.N * a.E) return;
+  const int n = (int)(idx / a.E), e = (int)(idx % a.E);
+  const int HD = a.H * a.D, nn = n % HD;
+  const TIn* gh = (const TIn*)a.g[n / HD] + (long)(nn / a.D) * a.S * a.D + nn % a.D;
+  float acc = 0.f;
+  for (long m = 0; m < a.M; ++m) {
+    const long b = m / a.S, s = m % a.S;
+    acc = fmaf(to_f32<TIn>(gh[(b * a.H * a.S + s) * a.D]), to_f32<TIn>(((const TIn*)a.x)[m * a.ldx + e]), acc);
+  }
+  a.dw[idx] += acc;
+}
+
+}  // namespace
+
+bool project_bwd_bf16_supported(const ProjBwdArgs& a) {
+  // 16-byte chunks inside one head, a tile of 256 columns inside one output, tokens countable in
+  // a float, and every G offset inside 32 bits
+  return a.E % T == 0 && a.N % T == 0 && (a.H * a.D) % T == 0 && a.D % BK == 0 &&
+         a.M < (1L << 24) && a.M * a.H * a.D * 2 < (1L << 31) && 64 * a.ldx * 2 < (1L << 31) &&
+         2L * a.E * 2 < (1L << 31);
+}
+
+hipError_t launch_project_bwd(const ProjBwdArgs& a, int is_f32, hipStream_t s) {
+  const bool mfma = !is_f32 && project_bwd_bf16_supported(a);
+  if (mfma) {
+    static SmemOnce once_x, once_w;
+    if (a.dx) {
+      const hipError_t e = ensure_dynamic_lds((const void*)project_bwd_bf16_kernel<0>, SMEM_B, &once_x);
+      if (e != hipSuccess) return e;
+      const long grid = xcd_grid((int)((a.M + T - 1) / T), a.E / T);
+      project_bwd_bf16_kernel<0><<<(unsigned)grid, 256, SMEM_B, s>>>(a);
+    }
+    if (a.dw) {
+      const hipError_t e = ensure_dynamic_lds((const void*)project_bwd_bf16_kernel<1>, SMEM_B, &once_w);
+      if (e != hipSuccess) return e;
+      const long grid = xcd_grid(a.N / T, a.E / T);
+      project_bwd_bf16_kernel<1><<<(unsigned)grid, 256, SMEM_B, s>>>(a);
+    }
+    return hipGetLastError();
+  }
+  if (a.dx) {
+    const unsigned grid = (unsigned)((a.M * a.E + 255) / 256);
+    if (is_f32) project_bwd_x_plain_kernel<float><<<grid, 256, 0, s>>>(a);
+    else project_bwd_x_plain_kernel<__bf16><<<grid, 256, 0, s>>>(a);
+  }
+  if (a.dw) {
+    const unsigned grid = (unsigned)(((long)a.N * a.E + 255) / 256);
+    if (is_f32) project_bwd_w_plain_kernel<float><<<grid, 256, 0, s>>>(a);
+    else project_bwd_w_plain_kernel<__bf16><<<grid, 256, 0, s>>>(a);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace lvx

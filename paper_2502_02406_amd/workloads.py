@@ -19,7 +19,7 @@ import numpy as np
 import torch
 
 BASE_SEED = 20250204
-_TENSOR_ID = {"q": 0, "k": 1, "v": 2, "do": 3, "outliers": 4, "tokens": 5, "weights": 6}
+_TENSOR_ID = {"q": 0, "k": 1, "v": 2, "do": 3, "outliers": 4, "tokens": 5, "weights": 6, "head_grads": 7}
 
 
 @dataclass(frozen=True)
@@ -172,3 +172,17 @@ def projection_inputs(B: int, S: int, E: int, N: int, dtype: str, seed: int = BA
     g.manual_seed(seed + _TENSOR_ID["weights"])
     w = torch.empty((N, E), dtype=torch.float32).normal_(0.0, std_out / float(E) ** 0.5, generator=g)
     return {"x": x.to(dt), "w": w.to(dt)}
+
+
+def projection_grad_inputs(B: int, S: int, H: int, D: int, n_out: int, dtype: str,
+                           seed: int = BASE_SEED, std: float = 0.05) -> list:
+    """CPU tensors standing in for the gradients of the projected heads (what the attention
+    backward hands over as dQ, or as dK and dV): n_out tensors [B, H, S, D] ~ N(0, std^2), rounded
+    to the storage type here, once."""
+    dt = torch_dtype(dtype)
+    g = torch.Generator(device="cpu")
+    outs = []
+    for o in range(n_out):
+        g.manual_seed(seed + _TENSOR_ID["head_grads"] + 16 * o)
+        outs.append(torch.empty((B, H, S, D), dtype=torch.float32).normal_(0.0, std, generator=g).to(dt))
+    return outs

@@ -108,3 +108,120 @@ def test_project_full_size_block_sampled():
     check(x, w, outs, H, "bf16", "full", rows=rows.astype(np.int32))
     # projected keys feed the attention: their spread is the attention workloads'
     assert 0.4 < outs[0].std() < 0.6
+
+
+# ---- gradients of the projection -----------------------------------------------------------------
+# Tolerance, from the arithmetic: exact bf16 x bf16 products added in float32.  dx is a sum of
+# N = n_out H D terms rounded once to the tensors' type: 2^-8 |ref| + 2^-20 A with A the sum of the
+# terms' magnitudes, as for the forward.  dw stays float32 and is a sum over the M tokens, taken 16
+# at a time by a matrix instruction and then added to a running float32 value: M / 16 roundings of
+# at most 2^-24 A each in the worst case, i.e. 2^-28 M A, and never less than 2^-20 A allowed.
+
+
+def run_bwd(B, S, E, H, D, n_out, dtype, seed, x_pad=0, want=("dx", "dw"), dw0=None):
+    from paper_2502_02406_amd import binding as Bn
+    inp = W.projection_inputs(B, S, E, n_out * H * D, dtype, seed=seed)
+    gs = W.projection_grad_inputs(B, S, H, D, n_out, dtype, seed=seed)
+    x, w = inp["x"], inp["w"]
+    if x_pad:
+        buf = torch.zeros((B, S, E + x_pad), dtype=x.dtype)
+        buf[:, :, :E] = x
+        xd = buf.cuda()[:, :, :E]
+        dxd = torch.full((B, S, E + x_pad), float("nan"), dtype=x.dtype, device="cuda")[:, :, :E]
+    else:
+        xd = x.cuda()
+        dxd = torch.full((B, S, E), float("nan"), dtype=x.dtype, device="cuda")
+    dwd = (torch.zeros((n_out * H * D, E), dtype=torch.float32) if dw0 is None else dw0.clone()).cuda()
+    Bn.lvx_xattn_project_bwd(xd, w.cuda(), [g.cuda() for g in gs],
+                             dx=dxd if "dx" in want else None, dw=dwd if "dw" in want else None)
+    torch.cuda.synchronize()
+    return x, w, gs, dxd.float().cpu().numpy().astype(np.float64), dwd.cpu().numpy().astype(np.float64)
+
+
+def check_bwd(x, w, gs, dx, dw, H, dtype, tag, cols=None, rows=None, dw0=None, want=("dx", "dw")):
+    xf, wf = x.float().numpy(), w.float().numpy()
+    gf = np.concatenate([g.float().numpy() for g in gs], axis=1)          # heads of all outputs stacked
+    Ht = H * len(gs)
+    M = xf.shape[0] * xf.shape[1]
+    ref_w, ref_x = oracle.project_bwd(xf, wf, gf, Ht, cols=cols, rows=rows)
+    mag_w, mag_x = oracle.project_bwd(np.abs(xf), np.abs(wf), np.abs(gf), Ht, cols=cols, rows=rows)
+    if "dx" in want:
+        got = dx if rows is None else np.stack([dx[b, s] for b, s in rows])
+        assert np.isfinite(got).all(), f"{tag}: non-finite dx"
+        bound = (2.0 ** -8 * np.abs(ref_x) if dtype == "bf16" else 0.0) + 2.0 ** -20 * mag_x
+        worst = (np.abs(got - ref_x) / bound).max()
+        assert worst <= 1.0, f"{tag}: dx off by {worst:.2f} of the bound"
+    if "dw" in want:
+        got = dw if cols is None else dw[cols]
+        if dw0 is not None:
+            base = dw0.numpy().astype(np.float64)
+            base = base if cols is None else base[cols]
+            ref_w = ref_w + base
+            mag_w = mag_w + np.abs(base)
+        assert np.isfinite(got).all(), f"{tag}: non-finite dw"
+        bound = max(2.0 ** -20, 2.0 ** -28 * M) * mag_w
+        worst = (np.abs(got - ref_w) / bound).max()
+        assert worst <= 1.0, f"{tag}: dw off by {worst:.2f} of the bound"
+
+
+BWD_CASES = [
+    # B, S, E, H, D, n_out, x_pad
+    ("one_tile_four_pairs", 1, 256, 256, 2, 128, 1, 0),
+    ("less_than_one_pair_of_tokens", 1, 40, 256, 2, 128, 1, 0),
+    ("two_pairs", 1, 128, 256, 2, 128, 1, 0),
+    ("ragged_tokens_two_outputs", 1, 300, 256, 2, 128, 2, 0),
+    ("d64_batches_fold", 2, 333, 512, 4, 64, 2, 0),
+    ("short_batches_inside_a_pair", 3, 70, 256, 2, 128, 1, 0),
+    ("llama_like_kv", 1, 1000, 1024, 8, 128, 2, 0),
+    ("strided_tokens", 1, 515, 256, 2, 128, 1, 64),
+    ("q_like_many_column_tiles", 1, 257, 512, 16, 64, 1, 0),
+    # shapes the matrix-core kernels do not take: the plain kernels
+    ("plain_heads_of_96", 1, 130, 64, 2, 96, 2, 0),
+    ("plain_narrow_output", 2, 65, 128, 1, 128, 1, 0),
+]
+
+
+@pytest.mark.parametrize("case", BWD_CASES, ids=[c[0] for c in BWD_CASES])
+def test_project_bwd_bf16(case):
+    tag, B, S, E, H, D, n_out, x_pad = case
+    print(f"[project_bwd] {tag}", flush=True)
+    x, w, gs, dx, dw = run_bwd(B, S, E, H, D, n_out, "bf16", seed=31 + len(tag), x_pad=x_pad)
+    check_bwd(x, w, gs, dx, dw, H, "bf16", tag)
+
+
+def test_project_bwd_f32_any_shape():
+    x, w, gs, dx, dw = run_bwd(2, 37, 50, 3, 20, 2, "f32", seed=6)
+    check_bwd(x, w, gs, dx, dw, 3, "f32", "f32")
+
+
+def test_project_bwd_accumulates_into_dw_and_takes_either_output_alone():
+    B, S, E, H, D, n_out = 1, 200, 256, 2, 128, 2
+    dw0 = torch.empty((n_out * H * D, E), dtype=torch.float32).normal_(0.0, 1.0, generator=torch.Generator().manual_seed(4))
+    x, w, gs, dx, dw = run_bwd(B, S, E, H, D, n_out, "bf16", seed=12, dw0=dw0)
+    check_bwd(x, w, gs, dx, dw, H, "bf16", "accumulate", dw0=dw0)
+    x, w, gs, dx1, dw1 = run_bwd(B, S, E, H, D, n_out, "bf16", seed=12, want=("dx",), dw0=dw0)
+    assert np.array_equal(dx1, dx) and np.array_equal(dw1, dw0.numpy().astype(np.float64))   # dw untouched
+    x, w, gs, dx2, dw2 = run_bwd(B, S, E, H, D, n_out, "bf16", seed=12, want=("dw",), dw0=dw0)
+    assert np.array_equal(dw2, dw) and np.isnan(dx2).all()                                     # dx untouched
+
+
+def test_project_bwd_repeats_bit_for_bit():
+    a = run_bwd(2, 700, 512, 4, 128, 2, "bf16", seed=9)
+    b = run_bwd(2, 700, 512, 4, 128, 2, "bf16", seed=9)
+    assert np.array_equal(a[3], b[3]) and np.array_equal(a[4], b[4])
+
+
+def test_project_bwd_full_size_block_sampled():
+    """The gradients of one K/V block of the long-video workload: 32768 tokens of width 4096, 8 K
+    heads and 8 V heads of 128 -- the launch bench.py times -- on sampled tokens (dx) and sampled
+    columns of the projection (dw)."""
+    B, S, E, H, D = 1, 32768, 4096, 8, 128
+    print("[project_bwd] full size: GPU", flush=True)
+    x, w, gs, dx, dw = run_bwd(B, S, E, H, D, 2, "bf16", seed=W.BASE_SEED)
+    rng = np.random.default_rng(5)
+    rows = np.stack([np.zeros(24, dtype=np.int64), np.sort(rng.choice(S, 24, replace=False))], axis=1)
+    rows[0, 1], rows[-1, 1] = 0, S - 1
+    cols = np.sort(rng.choice(2 * H * D, 12, replace=False))
+    cols[0], cols[-1] = 0, 2 * H * D - 1
+    print("[project_bwd] full size: oracle on sampled tokens and columns", flush=True)
+    check_bwd(x, w, gs, dx, dw, H, "bf16", "full", cols=cols.astype(np.int32), rows=rows.astype(np.int32))
