@@ -200,11 +200,29 @@ def main():
         f_kv = 2.0 * w.B * blk * E * 2 * w.Hkv * w.D
         f_q = 2.0 * w.B * w.Sq * E * w.Hq * w.D
         extra_ms = w.n_blocks * ms_kv + ms_q
+        # the chain rule through the same projections (lvx_xattn_project_bwd): dy and dW_K, dW_V of a
+        # block from its dK, dV (stood in for by the recomputed heads: timing only), dx and dW_Q from dQ
+        dy_d, dwkv_d = torch.empty_like(y_d), torch.zeros(wkv_d.shape, dtype=torch.float32, device="cuda")
+        dxq_d, dwq_d = torch.empty_like(x_d), torch.zeros(wq_d.shape, dtype=torch.float32, device="cuda")
+        ms_gkv_x = timed(lambda: B.lvx_xattn_project_bwd(y_d, wkv_d, [k_re, v_re], dx=dy_d), reps)
+        ms_gkv_w = timed(lambda: B.lvx_xattn_project_bwd(y_d, wkv_d, [k_re, v_re], dw=dwkv_d), reps)
+        ms_gq = timed(lambda: B.lvx_xattn_project_bwd(x_d, wq_d, [q_re], dx=dxq_d, dw=dwq_d), reps)
+        grad_ms = w.n_blocks * (ms_gkv_x + ms_gkv_w) + ms_gq
+        del dy_d, dwkv_d, dxq_d, dwq_d
         recompute = {"embed": E,
                      "kv_block": {"ms": ms_kv, "flops": f_kv, "tflops": f_kv / ms_kv * 1e-9,
                                   "frac": f_kv / ms_kv * 1e-9 / PEAK_BF16_TFLOPS},
                      "q": {"ms": ms_q, "flops": f_q, "tflops": f_q / ms_q * 1e-9},
                      "ms_per_step": extra_ms, "overhead_of_step": extra_ms / (sec * 1e3),
+                     "gradients": {
+                         "kv_block_dx": {"ms": ms_gkv_x, "flops": f_kv, "tflops": f_kv / ms_gkv_x * 1e-9,
+                                         "frac": f_kv / ms_gkv_x * 1e-9 / PEAK_BF16_TFLOPS},
+                         "kv_block_dw": {"ms": ms_gkv_w, "flops": f_kv, "tflops": f_kv / ms_gkv_w * 1e-9,
+                                         "frac": f_kv / ms_gkv_w * 1e-9 / PEAK_BF16_TFLOPS},
+                         "q": {"ms": ms_gq, "flops": 2 * f_q, "tflops": 2 * f_q / ms_gq * 1e-9},
+                         "ms_per_step": grad_ms,
+                         "note": "lvx_xattn_project_bwd: dy, dW_K, dW_V of every block and dx, dW_Q; work any "
+                                 "training step does with or without recomputation, not an overhead of it"},
                      "note": "lvx_xattn_project: K and V of every block and Q made again in the backward "
                              "pass; overhead = that time over the attention forward + backward above"}
         del y_d, wkv_d, x_d, wq_d, k_re, v_re, q_re

@@ -498,6 +498,7 @@ lvx_status lvx_xattn_project_bwd(const lvx_projection* p, lvx_dtype dtype, const
   a.N = n_out * p->H * p->D;
   a.H = p->H;
   a.D = p->D;
+  a.n_cu = device_cu_count();
   const hipError_t e = launch_project_bwd(a, dtype == LVX_F32, (hipStream_t)hip_stream);
   return e == hipSuccess ? LVX_OK : LVX_ERR_HIP;
 }

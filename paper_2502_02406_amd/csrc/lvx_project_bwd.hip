@@ -24,6 +24,9 @@
 // operand of dx, read with plain 8-byte reads, takes the same order.
 // Rows past the last token are never stored (dx) and are cleared in LDS before they are
 // multiplied (dw, where they would otherwise enter every sum).
+// dw of a narrow projection (K and V of a model with few K/V heads) has fewer 256 x 256 tiles
+// than the chip has compute units; its tiles are then 128 rows high (a wave owns 64 x 128, the G
+// tile is [token][128 columns] with rows of 256 bytes, same permutation).
 #include "lvx_internal.h"
 #include "lvx_mfma.h"
 #include "lvx_kv_ring.h"
@@ -41,12 +44,11 @@ constexpr int KR_ROWB = T * 2;         // [k][256] tile: bytes of a row
 constexpr int RK_ROWB = BK * 2;        // [256][k] tile: bytes of a row (one 128-byte line)
 constexpr int TILE_B = BK * KR_ROWB;   // either kind: 32 KB
 static_assert(TILE_B == T * RK_ROWB, "both tile kinds take the same room");
-constexpr int SLOT_B = 2 * TILE_B;     // A-side tile ([k][256 columns e]), then B-side tile
+constexpr int SLOT_B = 2 * TILE_B;     // A-side tile ([k][256 columns e]), then B-side tile (up to as large)
 constexpr int RING_B = NSLOT * SLOT_B;
 constexpr int TB_PITCH = 128 * 2 + 16; // dx epilogue: a wave's 128 tokens x 128 columns of bf16, padded rows
 constexpr int TB_WAVE = 128 * TB_PITCH;
 constexpr int SMEM_B = RING_B > 4 * TB_WAVE ? RING_B : 4 * TB_WAVE;
-constexpr int NPART = 16;              // copies per wave and tile pair: 8 per tile
 
 __device__ __forceinline__ int perm_of(int r) { return (r & 7) ^ ((r >> 3) & 1); }
 
@@ -62,15 +64,22 @@ __device__ __forceinline__ void div_tokens(int m, int S, float inv_S, int* b, in
 
 // MODE 0: dx = G W (rows = tokens, columns = features e, contraction over n)
 // MODE 1: dw += G^T X (rows = columns n of the projection, columns = e, contraction over tokens)
-template <int MODE>
+// RB: 32-row blocks of the result per wave (4: tiles of 256 rows; 2: of 128 rows, MODE 1 only)
+template <int MODE, int RB>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 project_bwd_bf16_kernel(ProjBwdArgs a) {
+  static_assert(RB == 4 || (RB == 2 && MODE == 1), "tile heights");
+  constexpr int TR = 64 * RB;                        // rows of a workgroup's tile
+  constexpr int BROWB = TR * 2;                      // MODE 1: bytes of a row of the G tile [k][TR]
+  constexpr int RPI = 1024 / BROWB;                  // ... rows that one copy instruction moves (2 or 4)
+  constexpr int NB = MODE == 0 ? 8 : 16 / RPI;       // copies per wave and tile pair: B side,
+  constexpr int NPART = 8 + NB;                      // and with the 8 of the A side
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int n_rt = MODE == 0 ? (int)((a.M + T - 1) / T) : a.N / T;   // row tiles of the result
+  const int n_rt = MODE == 0 ? (int)((a.M + TR - 1) / TR) : a.N / TR;   // row tiles of the result
   const int n_ct = a.E / T;
   HeadWork hw;                                       // the column tiles of a row tile share an XCD
   if (!xcd_decode(blockIdx.x, n_rt, n_ct, &hw)) return;
-  const long r0 = (long)hw.head * T;                 // first token (MODE 0) / first column n (MODE 1)
+  const long r0 = (long)hw.head * TR;                // first token (MODE 0) / first column n (MODE 1)
   const int e0 = hw.item * T;
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, l31 = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -92,8 +101,11 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
   // moves 8 rows x 128 bytes; a wave copies rows 64 wave + 8 j + l / 8.  Tokens past the last
   // one re-read it (their results are never stored).
   unsigned g_row[8];
-  // MODE 1: the lane's column part of a G address, j even / odd (the 256 columns of the tile lie
-  // in one output, in 256 / D heads)
+  // MODE 1: the G tile [64 tokens][TR columns]: one instruction moves RPI rows; lane l fills
+  // position l % (64 / RPI) of row l / (64 / RPI); a wave copies rows 16 wave + RPI j + that.
+  // g_col: the lane's column part of a G address, j even / odd (the columns of the tile lie in
+  // one output)
+  const int b_rin = lane / (64 / RPI), b_pos = lane % (64 / RPI);
   unsigned g_col[2];
   const char* g_tile_base = nullptr;                 // MODE 1: the output's gradient
   if (MODE == 0) {
@@ -111,7 +123,7 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
     g_tile_base = (const char*)a.g[o];
 #pragma unroll
     for (int par = 0; par < 2; ++par) {
-      const int n = nn0 + (int)(kr_chunk[par] / 2);
+      const int n = nn0 + 8 * (b_pos ^ (4 * ((RPI * par + b_rin) & 3)));
       g_col[par] = (unsigned)((long)(n / a.D) * head_b + (long)(n % a.D) * 2);
     }
   }
@@ -145,14 +157,15 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
         if (g_c == a.D) { g_c = 0; if (++g_h == a.H) { g_h = 0; ++g_o; } }
       }
       dma16u(g_pair_base, g_row[j], st + (unsigned)(TILE_B + (64 * wave + 8 * j) * RK_ROWB));
-    } else {                                         // B side: G, 64 tokens x 256 columns
+    } else {                                         // B side: G, 64 tokens x TR columns
+      const int jb = part - 8;
       const long m_first = (long)kt * BK;
-      const int r = 16 * wave + 2 * j + lh;
+      const int r = 16 * wave + RPI * jb + b_rin;
       const long m = m_first + r < a.M ? m_first + r : a.M - 1;
       int b, s;
       div_tokens((int)m, a.S, inv_S, &b, &s);
       const unsigned row = (unsigned)(((long)b * a.H * a.S + s) * a.D * 2);
-      dma16u(g_tile_base, row + g_col[j & 1], st + (unsigned)(TILE_B + (16 * wave + 2 * j) * KR_ROWB));
+      dma16u(g_tile_base, row + g_col[jb & 1], st + (unsigned)(TILE_B + (16 * wave + RPI * jb) * BROWB));
     }
   };
 
@@ -161,15 +174,14 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
   // read), byte column 64 jj' + 32 ((l / 16) % 2) + 8 (l % 4), where jj' is the block's position
   // after the permutation: (4 wcol + jj) ^ (row % 4).
   const int j16 = lane & 15, jr = j16 >> 2;
-  const int tr_lane = (4 * g + jr) * KR_ROWB + 32 * ((lane >> 4) & 1) + 8 * (j16 & 3);
-  int ka[4], kb[4];
+  const int tr_col = 32 * ((lane >> 4) & 1) + 8 * (j16 & 3);
+  int ka[4], kb[RB];
 #pragma unroll
-  for (int jj = 0; jj < 4; ++jj) {
-    ka[jj] = tr_lane + 64 * ((4 * wn + jj) ^ jr);
-    kb[jj] = TILE_B + tr_lane + 64 * ((4 * wm + jj) ^ jr);
-  }
-  auto tr_op = [&](const char* p) __attribute__((always_inline)) -> bf16x8 {
-    const s16x4 lo = lds_read_tr(p), hi = lds_read_tr(p + 8 * KR_ROWB);
+  for (int jj = 0; jj < 4; ++jj) ka[jj] = (4 * g + jr) * KR_ROWB + tr_col + 64 * ((4 * wn + jj) ^ jr);
+#pragma unroll
+  for (int i = 0; i < RB; ++i) kb[i] = TILE_B + (4 * g + jr) * BROWB + tr_col + 64 * ((RB * wm + i) ^ jr);
+  auto tr_op = [&](const char* p, auto pitch) __attribute__((always_inline)) -> bf16x8 {
+    const s16x4 lo = lds_read_tr(p), hi = lds_read_tr(p + 8 * decltype(pitch)::value);
     typedef __attribute__((ext_vector_type(8))) short s16x8;
     const s16x8 r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     return __builtin_bit_cast(bf16x8, r);
@@ -181,10 +193,10 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
   for (int q = 0; q < 4; ++q)
     rk[q] = TILE_B + (wm * 128 + l31) * RK_ROWB + 16 * ((2 * q) ^ perm_of(l31)) + 8 * g;
   auto a_op = [&](const char* st, int q, int jj) __attribute__((always_inline)) -> bf16x8 {
-    return tr_op(st + ka[jj] + 16 * q * KR_ROWB);
+    return tr_op(st + ka[jj] + 16 * q * KR_ROWB, std::integral_constant<int, KR_ROWB>{});
   };
   auto b_op = [&](const char* st, int q, int i) __attribute__((always_inline)) -> bf16x8 {
-    if (MODE == 1) return tr_op(st + kb[i] + 16 * q * KR_ROWB);
+    if (MODE == 1) return tr_op(st + kb[i] + 16 * q * BROWB, std::integral_constant<int, BROWB>{});
     const char* p = st + rk[q] + 32 * i * RK_ROWB;
     const u32x2 lo = *(const u32x2*)p;
     const u32x2 hi = *(const u32x2*)(st + (rk[q] ^ 16) + 32 * i * RK_ROWB);
@@ -192,19 +204,21 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
     return __builtin_bit_cast(bf16x8, r);
   };
 
-  f32x16 acc[4][4];                                  // [column block jj][row block i]: lane = row, registers = columns
+  f32x16 acc[4][RB];                                 // [column block jj][row block i]: lane = row, registers = columns
 #pragma unroll
   for (int j = 0; j < 4; ++j)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { acc[j][i] = zero16(); asm volatile("" : "+a"(acc[j][i])); }
+    for (int i = 0; i < RB; ++i) { acc[j][i] = zero16(); asm volatile("" : "+a"(acc[j][i])); }
 
-  auto mma16 = [&](const bf16x8 (&bv)[4], const bf16x8 (&av)[4], auto&& hook) __attribute__((always_inline)) {
+  // the 4 RB matrix instructions of one k-step; hook(u) is other work issued after instruction u
+  constexpr int NU = 4 * RB;
+  auto mma16 = [&](const bf16x8 (&bv)[RB], const bf16x8 (&av)[4], auto&& hook) __attribute__((always_inline)) {
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < RB; ++i) {
         kvring::mfma_acc(acc[j][i], av[j], bv[i]);
-        hook(4 * j + i);
+        hook(RB * j + i);
         __builtin_amdgcn_sched_barrier(0);
       }
   };
@@ -215,12 +229,11 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
   auto settle = [&](int kt) __attribute__((always_inline)) {
     if (MODE == 1 && kt == nk - 1 && tail_rows < BK) {
       char* const st = smem + (kt % NSLOT) * SLOT_B;
-      const int n16 = (BK - tail_rows) * (KR_ROWB / 16);
       const u32x4 z = {0u, 0u, 0u, 0u};
-      for (int c = tid; c < n16; c += 256) {
+      for (int c = tid; c < (BK - tail_rows) * (KR_ROWB / 16); c += 256)
         *(u32x4*)(st + tail_rows * KR_ROWB + c * 16) = z;
-        *(u32x4*)(st + TILE_B + tail_rows * KR_ROWB + c * 16) = z;
-      }
+      for (int c = tid; c < (BK - tail_rows) * (BROWB / 16); c += 256)
+        *(u32x4*)(st + TILE_B + tail_rows * BROWB + c * 16) = z;
       __builtin_amdgcn_s_waitcnt(0xc07f);            // lgkmcnt(0)
       wg_barrier();
     }
@@ -239,21 +252,26 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
   else wait_vmcnt<0>();
   wg_barrier();
   settle(0);
-  bf16x8 ba[4], aa[4], bb[4], ab[4];                 // operands of even / odd k-steps
+  bf16x8 ba[RB], aa[4], bb[RB], ab[4];               // operands of even / odd k-steps
 #pragma unroll
-  for (int i = 0; i < 4; ++i) { ba[i] = b_op(smem, 0, i); aa[i] = a_op(smem, 0, i); }
+  for (int i = 0; i < RB; ++i) ba[i] = b_op(smem, 0, i);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) aa[i] = a_op(smem, 0, i);
 
-  auto fetch = [&](const char* st, int q, int u, bf16x8 (&bv)[4], bf16x8 (&av)[4]) __attribute__((always_inline)) {
-    if (u < 4) bv[u] = b_op(st, q, u);
-    else if (u < 8) av[u - 4] = a_op(st, q, u - 4);
+  auto fetch = [&](const char* st, int q, int u, bf16x8 (&bv)[RB], bf16x8 (&av)[4]) __attribute__((always_inline)) {
+    if (u < RB) bv[u] = b_op(st, q, u);
+    else if (u < RB + 4) av[u - RB] = a_op(st, q, u - RB);
   };
+  // the B-side copies of a pair go out during one k-step, the A-side copies during another: one
+  // every NU / NB (NU / 8) matrix instructions
+  constexpr int EB = NU / NB, EA = NU / 8;
   auto pair = [&](int P, auto steady, bool send2, bool send1, bool more) __attribute__((always_inline)) {
     constexpr bool STEADY = decltype(steady)::value;   // send2, send1 and more are all true
     const char* const st = smem + (P % NSLOT) * SLOT_B;
     const char* const sn = smem + ((P + 1) % NSLOT) * SLOT_B;
     mma16(ba, aa, [&](int u) __attribute__((always_inline)) {
       fetch(st, 1, u, bb, ab);
-      if ((STEADY || send2) && u % 2 == 1) issue_part(P + 1, 8 + u / 2);
+      if ((STEADY || send2) && u % EB == EB - 1) issue_part(P + 1, 8 + u / EB);
     });
     mma16(bb, ab, [&](int u) __attribute__((always_inline)) { fetch(st, 2, u, ba, aa); });
     mma16(ba, aa, [&](int u) __attribute__((always_inline)) { fetch(st, 3, u, bb, ab); });
@@ -266,7 +284,7 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
     }
     mma16(bb, ab, [&](int u) __attribute__((always_inline)) {
       if (STEADY || more) fetch(sn, 0, u, ba, aa);
-      if ((STEADY || send1) && u % 2 == 1) issue_part(P + 2, u / 2);
+      if ((STEADY || send1) && u % EA == EA - 1) issue_part(P + 2, u / EA);
     });
   };
   int P = 0;
@@ -279,8 +297,10 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
   wg_barrier();
 #pragma unroll
   for (int j = 0; j < 4; ++j)
-    asm volatile("s_nop 15\n\ts_nop 15" : "+a"(acc[j][0]), "+a"(acc[j][1]), "+a"(acc[j][2]), "+a"(acc[j][3]));
-  if (MODE == 0) {
+#pragma unroll
+    for (int i = 0; i < RB; i += 2)
+      asm volatile("s_nop 15\n\ts_nop 15" : "+a"(acc[j][i]), "+a"(acc[j][i + 1]));
+  if constexpr (MODE == 0) {
     // turn the tile around in LDS (rounded to bf16) and write whole 256-byte row segments
     char* const tb = smem + wave * TB_WAVE;
 #pragma unroll
@@ -303,9 +323,9 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
     }
   } else {
     // this workgroup alone owns its tile of dw: add in place, 16 bytes per lane and register group
-    float* const out = a.dw + (r0 + wm * 128 + l31) * (long)a.E + e0 + wn * 128 + 4 * g;
+    float* const out = a.dw + (r0 + wm * (32 * RB) + l31) * (long)a.E + e0 + wn * 128 + 4 * g;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < RB; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -362,7 +382,7 @@ __global__ void __launch_bounds__(256) project_bwd_w_plain_kernel(ProjBwdArgs a)
 bool project_bwd_bf16_supported(const ProjBwdArgs& a) {
   // 16-byte chunks inside one head, a tile of 256 columns inside one output, tokens countable in
   // a float, and every G offset inside 32 bits
-  return a.E % T == 0 && a.N % T == 0 && (a.H * a.D) % T == 0 && a.D % BK == 0 &&
+  return a.E % T == 0 && (a.H * a.D) % T == 0 && a.D % BK == 0 &&
          a.M < (1L << 24) && a.M * a.H * a.D * 2 < (1L << 31) && 64 * a.ldx * 2 < (1L << 31) &&
          2L * a.E * 2 < (1L << 31);
 }
@@ -370,18 +390,25 @@ bool project_bwd_bf16_supported(const ProjBwdArgs& a) {
 hipError_t launch_project_bwd(const ProjBwdArgs& a, int is_f32, hipStream_t s) {
   const bool mfma = !is_f32 && project_bwd_bf16_supported(a);
   if (mfma) {
-    static SmemOnce once_x, once_w;
+    static SmemOnce once_x, once_w, once_w2;
     if (a.dx) {
-      const hipError_t e = ensure_dynamic_lds((const void*)project_bwd_bf16_kernel<0>, SMEM_B, &once_x);
+      const hipError_t e = ensure_dynamic_lds((const void*)project_bwd_bf16_kernel<0, 4>, SMEM_B, &once_x);
       if (e != hipSuccess) return e;
       const long grid = xcd_grid((int)((a.M + T - 1) / T), a.E / T);
-      project_bwd_bf16_kernel<0><<<(unsigned)grid, 256, SMEM_B, s>>>(a);
+      project_bwd_bf16_kernel<0, 4><<<(unsigned)grid, 256, SMEM_B, s>>>(a);
     }
     if (a.dw) {
-      const hipError_t e = ensure_dynamic_lds((const void*)project_bwd_bf16_kernel<1>, SMEM_B, &once_w);
-      if (e != hipSuccess) return e;
-      const long grid = xcd_grid(a.N / T, a.E / T);
-      project_bwd_bf16_kernel<1><<<(unsigned)grid, 256, SMEM_B, s>>>(a);
+      // tiles of 128 rows when tiles of 256 would leave a quarter of the compute units idle
+      const long tiles = (long)(a.N / T) * (a.E / T);
+      if (tiles * 4 > (long)a.n_cu * 3) {
+        const hipError_t e = ensure_dynamic_lds((const void*)project_bwd_bf16_kernel<1, 4>, SMEM_B, &once_w);
+        if (e != hipSuccess) return e;
+        project_bwd_bf16_kernel<1, 4><<<(unsigned)xcd_grid(a.N / T, a.E / T), 256, SMEM_B, s>>>(a);
+      } else {
+        const hipError_t e = ensure_dynamic_lds((const void*)project_bwd_bf16_kernel<1, 2>, SMEM_B, &once_w2);
+        if (e != hipSuccess) return e;
+        project_bwd_bf16_kernel<1, 2><<<(unsigned)xcd_grid(a.N / 128, a.E / T), 256, SMEM_B, s>>>(a);
+      }
     }
     return hipGetLastError();
   }

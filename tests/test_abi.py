@@ -157,6 +157,31 @@ def test_project_errors(lib):
     assert call(pp=bad, n_out=1) == -7                                        # ... but one output of 128 columns is not a tile
 
 
+def test_project_bwd_errors(lib):
+    p = B.lvx_projection()
+    p.B, p.S, p.E, p.H, p.D = 1, 100, 256, 2, 128
+    p.x_ss, p.x_sb = p.E, p.S * p.E
+    gs = (C.c_void_p * 2)(FAKE, FAKE)
+    one = (C.c_void_p * 2)(FAKE, None)
+
+    def call(pp=p, dtype=B.LVX_BF16, x=FAKE, w=FAKE, n_out=2, g=gs, dx=FAKE, dw=FAKE):
+        return lib.lvx_xattn_project_bwd(C.byref(pp) if pp is not None else None, dtype, x, w, n_out, g,
+                                         dx, dw, None)
+
+    assert call(pp=None) == -1
+    assert call(w=None) == -1
+    assert call(g=one) == -1
+    assert call(dx=None, dw=None) == -1            # nothing asked for
+    assert call(n_out=0) == -2
+    assert call(dtype=5) == -3
+    assert call(dw=FAKE + 4) == -4
+    assert call(dx=FAKE + 2) == -4
+    bad = B.lvx_projection.from_buffer_copy(p); bad.H = 0
+    assert call(pp=bad) == -2
+    bad = B.lvx_projection.from_buffer_copy(p); bad.x_sb = p.S * p.E + 64
+    assert call(pp=bad) == -4
+
+
 def test_workspace_sizes_and_strerror(lib):
     p = problem(B=1, Hq=32, Hkv=8, Sq=2048, Skv=32768)
     rows = 32 * 2048

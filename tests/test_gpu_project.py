@@ -211,6 +211,20 @@ def test_project_bwd_repeats_bit_for_bit():
     assert np.array_equal(a[3], b[3]) and np.array_equal(a[4], b[4])
 
 
+def test_project_bwd_wide_projection_takes_tall_tiles_sampled():
+    """A projection with at least as many 256 x 256 tiles of dw as three quarters of the chip's
+    compute units (the query projection of the bench model: 4096 columns from 4096 features) runs
+    the 256-row tiles; narrower ones, every other case here, the 128-row tiles."""
+    B, S, E, H, D = 1, 200, 4096, 32, 128
+    x, w, gs, dx, dw = run_bwd(B, S, E, H, D, 1, "bf16", seed=44)
+    rng = np.random.default_rng(6)
+    rows = np.stack([np.zeros(6, dtype=np.int64), np.sort(rng.choice(S, 6, replace=False))], axis=1)
+    cols = np.sort(rng.choice(H * D, 24, replace=False))
+    cols[0], cols[-1] = 0, H * D - 1
+    check_bwd(x, w, gs, dx, dw, H, "bf16", "wide", cols=cols.astype(np.int32), rows=rows.astype(np.int32))
+    assert np.isfinite(dw).all() and np.isfinite(dx).all()
+
+
 def test_project_bwd_full_size_block_sampled():
     """The gradients of one K/V block of the long-video workload: 32768 tokens of width 4096, 8 K
     heads and 8 V heads of 128 -- the launch bench.py times -- on sampled tokens (dx) and sampled
