@@ -33,7 +33,7 @@
  *     -inf for a query row that sees no key.
  *   Grouped-query attention: query head hq reads K/V head hq / (Hq / Hkv)
  *     (contiguous groups); dK/dV sum over the heads of a group.
- *   Supported head dims D: 64, 128.  Sq, Skv >= 1, no multiple-of-tile rule.
+ *   Supported head dims D: 64, 96, 128.  Sq, Skv >= 1, no multiple-of-tile rule.
  */
 #ifndef LVX_H
 #define LVX_H
@@ -53,7 +53,7 @@ typedef enum {
   LVX_ERR_STRIDE = -4,      /* stride too small for the shape, or misaligned for vector access */
   LVX_ERR_MASK = -5,        /* mask geometry does not cover Sq x Skv */
   LVX_ERR_WORKSPACE = -6,   /* workspace NULL, misaligned or smaller than required */
-  LVX_ERR_UNSUPPORTED = -7, /* head dim other than 64 / 128; projection shape the bf16 kernel does not take */
+  LVX_ERR_UNSUPPORTED = -7, /* head dim other than 64 / 96 / 128; projection shape the bf16 kernel does not take */
   LVX_ERR_HIP = -8          /* a kernel launch failed (hipGetLastError) */
 } lvx_status;
 

@@ -33,7 +33,7 @@ lvx_status check_problem(const lvx_problem* p, lvx_dtype dtype) {
   if (p->B < 1 || p->Hq < 1 || p->Hkv < 1 || p->Sq < 1 || p->Skv < 1 || p->D < 1) return LVX_ERR_SHAPE;
   if (p->Hq % p->Hkv != 0) return LVX_ERR_SHAPE;
   if (p->B > 65535 || p->Hq > 65535) return LVX_ERR_SHAPE;
-  if (p->D != 64 && p->D != 128) return LVX_ERR_UNSUPPORTED;
+  if (p->D != 64 && p->D != 96 && p->D != 128) return LVX_ERR_UNSUPPORTED;
   // rows are read with 16-byte vector accesses: strides must keep that alignment
   const int64_t vec = dtype == LVX_F32 ? 4 : 8;
   const int64_t qs[3] = {p->q_sb, p->q_sh, p->q_ss}, ks[3] = {p->kv_sb, p->kv_sh, p->kv_ss};
@@ -337,7 +337,7 @@ lvx_status lvx_xattn_merge(int32_t B, int32_t Hq, int32_t Sq, int32_t D, int32_t
                            void* hip_stream) {
   if (!o_parts || !lse_parts || !o_out || !lse_out) return LVX_ERR_NULL;
   if (B < 1 || Hq < 1 || Sq < 1 || n_parts < 1 || n_parts > LVX_MAX_PARTS) return LVX_ERR_SHAPE;
-  if (D != 64 && D != 128) return LVX_ERR_UNSUPPORTED;
+  if (D != 64 && D != 96 && D != 128) return LVX_ERR_UNSUPPORTED;
   if ((part_dtype != LVX_F32 && part_dtype != LVX_BF16) || (out_dtype != LVX_F32 && out_dtype != LVX_BF16))
     return LVX_ERR_DTYPE;
   if (!aligned16(o_out)) return LVX_ERR_STRIDE;

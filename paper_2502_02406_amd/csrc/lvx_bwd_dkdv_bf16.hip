@@ -666,6 +666,9 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
     if constexpr (DB == 4)
       asm volatile("s_nop 15\n\ts_nop 15" : "+a"(dk[kb][0]), "+a"(dk[kb][1]), "+a"(dk[kb][2]), "+a"(dk[kb][3]),
                    "+a"(dv[kb][0]), "+a"(dv[kb][1]), "+a"(dv[kb][2]), "+a"(dv[kb][3]));
+    else if constexpr (DB == 3)
+      asm volatile("s_nop 15\n\ts_nop 15" : "+a"(dk[kb][0]), "+a"(dk[kb][1]), "+a"(dk[kb][2]),
+                   "+a"(dv[kb][0]), "+a"(dv[kb][1]), "+a"(dv[kb][2]));
     else
       asm volatile("s_nop 15\n\ts_nop 15" : "+a"(dk[kb][0]), "+a"(dk[kb][1]), "+a"(dv[kb][0]), "+a"(dv[kb][1]));
   }
@@ -695,10 +698,12 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   // (each wave reads back only what it wrote itself: no barrier, the LDS queue keeps the order)
   constexpr int LPR = D / 8;                       // lanes per row, eight bf16 each
   constexpr int RPI = 64 / LPR;                    // rows per instruction
+  constexpr bool EVEN = 64 % LPR == 0 && (32 * KVB) % RPI == 0;   // else: idle lanes, and a last instruction with fewer rows
   const int rsub = lane / LPR, cb = (lane % LPR) * 16;
 #pragma unroll 4
   for (int r0 = 0; r0 < 32 * KVB; r0 += RPI) {
     const int r = r0 + rsub, j = j_wave0 + r;
+    if (!EVEN && (rsub >= RPI || r >= 32 * KVB)) continue;
     const u32x4 yk = *(const u32x4*)(tk + r * RP + cb);
     const u32x4 yv = *(const u32x4*)(tv + r * RP + cb);
     if (j >= d.Skv) continue;
@@ -727,11 +732,13 @@ hipError_t launch_bwd_dkdv_bf16(const BwdArgs& a, hipStream_t s) {
   const bool rows_ok = d.Sq % KM == 0 || d.Sq >= KM;           // (a ragged Sq needs 32 rows to overlap)
   const bool steps = a.mask.allow != nullptr && rows_ok && a.mask.q_chunk % KM == 0 &&
                      a.mask.kv_block % DkvSmem<128, 2>::KN == 0 && (d.Sq + KM - 1) / KM <= dkdv_step_list_cap<128>();
-  static_assert(DkvSmem<64, 2>::KN == DkvSmem<128, 2>::KN && dkdv_step_list_cap<64>() == dkdv_step_list_cap<128>(),
+  static_assert(DkvSmem<64, 2>::KN == DkvSmem<128, 2>::KN && dkdv_step_list_cap<64>() == dkdv_step_list_cap<128>() &&
+                DkvSmem<96, 2>::KN == DkvSmem<128, 2>::KN && dkdv_step_list_cap<96>() == dkdv_step_list_cap<128>(),
                 "the test above is the same for both head dims");
-  if (steps) return d.D == 64 ? launch<64, false, true>(a, s) : launch<128, false, true>(a, s);
+  if (steps) return d.D == 64 ? launch<64, false, true>(a, s) : d.D == 96 ? launch<96, false, true>(a, s) : launch<128, false, true>(a, s);
   const bool general = a.mask.allow != nullptr || !rows_ok;
   if (d.D == 64) return general ? launch<64, true>(a, s) : launch<64, false>(a, s);
+  if (d.D == 96) return general ? launch<96, true>(a, s) : launch<96, false>(a, s);
   return general ? launch<128, true>(a, s) : launch<128, false>(a, s);
 }
 

@@ -546,6 +546,9 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   if constexpr (DB == 4) {
     asm volatile("s_nop 15\n\ts_nop 15" : "+a"(dq[0][0]), "+a"(dq[0][1]), "+a"(dq[0][2]), "+a"(dq[0][3]),
                  "+a"(dq[1][0]), "+a"(dq[1][1]), "+a"(dq[1][2]), "+a"(dq[1][3]));
+  } else if constexpr (DB == 3) {
+    asm volatile("s_nop 15\n\ts_nop 15" : "+a"(dq[0][0]), "+a"(dq[0][1]), "+a"(dq[0][2]),
+                 "+a"(dq[1][0]), "+a"(dq[1][1]), "+a"(dq[1][2]));
   } else {
     asm volatile("s_nop 15\n\ts_nop 15" : "+a"(dq[0][0]), "+a"(dq[0][1]), "+a"(dq[1][0]), "+a"(dq[1][1]));
   }
@@ -566,6 +569,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   // (each wave reads back only what it wrote itself: no barrier, the LDS queue keeps the order)
   constexpr int LPR = D / 4;                       // lanes per row, four floats each
   constexpr int RPI = 64 / LPR;                    // rows per instruction
+  constexpr bool EVEN = 64 % LPR == 0 && (32 * QB) % RPI == 0;    // else: idle lanes, and a last instruction with fewer rows
   const int rsub = lane / LPR, col = (lane % LPR) * 4;
   const bool whole = a.n_split_dq == 1;            // else: this split's own slice of the partial sums
   float* const out0 = (whole ? a.dq_accum : a.dq_part + (long)split * d.B * d.Hq * d.Sq * D) +
@@ -575,6 +579,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   for (int r0 = 0; r0 < 32 * QB; r0 += RPI) {
     const int r = r0 + rsub, i = i_wave0 + r;
     if (i >= rows_lim) continue;
+    if (!EVEN && (rsub >= RPI || r >= 32 * QB)) continue;
     f32x4 y = *(const f32x4*)(tbuf + r * RP + col * 4);
     float* const out = out0 + (long)i * D + col;
     if (whole) y += *(const f32x4*)out;
@@ -626,8 +631,9 @@ hipError_t launch_one(const BwdArgs& a, bool general, hipStream_t s) {
   const long per_split = general || list ? (long)G * ((d.Sq + QM - 1) / QM) : ((long)G * d.Sq + QM - 1) / QM;
   const long grid = xcd_grid(d.B * d.Hkv, (int)(a.n_split_dq * per_split));
   hipError_t e;
-  if (list) e = d.D == 64 ? launch<64, false, true>(a, grid, s) : launch<128, false, true>(a, grid, s);
+  if (list) e = d.D == 64 ? launch<64, false, true>(a, grid, s) : d.D == 96 ? launch<96, false, true>(a, grid, s) : launch<128, false, true>(a, grid, s);
   else if (d.D == 64) e = general ? launch<64, true>(a, grid, s) : launch<64, false>(a, grid, s);
+  else if (d.D == 96) e = general ? launch<96, true>(a, grid, s) : launch<96, false>(a, grid, s);
   else e = general ? launch<128, true>(a, grid, s) : launch<128, false>(a, grid, s);
   if (e == hipSuccess && a.n_split_dq > 1)
     e = launch_dq_reduce(a.dq_part, a.n_split_dq, (long)d.B * d.Hq * d.Sq * d.D, a.dq_accum, s);

@@ -20,17 +20,25 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
 // One thread owns VEC consecutive elements of one (b,h,i) row: VEC = 4 floats or 8 bf16 (16 bytes).
 // L' = ln sum_k exp(L_k), O' = sum_k exp(L_k - L') O_k.  A row's threads sit in one wavefront, so
 // every lane has read lse_parts[*][row] before lane 0 of the row stores lse_out[row]; this is
-// what makes lse_out == lse_parts[0] (in-place update of the running state) safe.
+// what makes lse_out == lse_parts[0] (in-place update of the running state) safe.  (A row takes a
+// power-of-two number of lanes, the next one up when D / VEC is none: the spare lanes idle.)
+__host__ __device__ inline int merge_lanes_per_row(int n) {   // smallest power of two >= n (n <= 64)
+  int p = 1;
+  while (p < n) p <<= 1;
+  return p;
+}
+
 template <bool PART_F32, bool OUT_F32>
 __global__ void __launch_bounds__(256) merge_kernel(MergeArgs a) {
   constexpr int VEC_IN = PART_F32 ? 4 : 8;
   constexpr int VEC_OUT = OUT_F32 ? 4 : 8;
   constexpr int VEC = VEC_IN < VEC_OUT ? VEC_IN : VEC_OUT;   // elements per thread
-  const int vpr = a.D / VEC;                                  // threads per row
+  const int vpr = merge_lanes_per_row(a.D / VEC);             // threads per row
   const long t = (long)blockIdx.x * 256 + threadIdx.x;
   const long row = t / vpr;
   if (row >= a.rows) return;
   const int c = (int)(t % vpr) * VEC;
+  if (c >= a.D) return;
 
   float M = -INFINITY;
   for (int k = 0; k < a.n_parts; ++k) M = fmaxf(M, a.lse_parts[k][row]);
@@ -92,7 +100,7 @@ __global__ void __launch_bounds__(256) merge_kernel(MergeArgs a) {
 
 hipError_t launch_merge(const MergeArgs& a, int part_is_f32, int out_is_f32, hipStream_t s) {
   const int vec = (part_is_f32 || out_is_f32) ? 4 : 8;
-  const long threads = a.rows * (a.D / vec);
+  const long threads = a.rows * merge_lanes_per_row(a.D / vec);
   const unsigned blocks = (unsigned)((threads + 255) / 256);
   if (part_is_f32 && out_is_f32) merge_kernel<true, true><<<blocks, 256, 0, s>>>(a);
   else if (part_is_f32) merge_kernel<true, false><<<blocks, 256, 0, s>>>(a);

@@ -244,6 +244,7 @@ __global__ void __launch_bounds__(256) bwd_dkdv_f32_kernel(BwdArgs a) {
 hipError_t launch_fwd_f32(const FwdArgs& a, hipStream_t s) {
   dim3 grid((a.d.Sq + R - 1) / R, a.d.Hq, a.d.B);
   if (a.d.D == 64) fwd_f32_kernel<64><<<grid, 256, 0, s>>>(a);
+  else if (a.d.D == 96) fwd_f32_kernel<96><<<grid, 256, 0, s>>>(a);
   else fwd_f32_kernel<128><<<grid, 256, 0, s>>>(a);
   return hipGetLastError();
 }
@@ -254,6 +255,9 @@ hipError_t launch_bwd_f32(const BwdArgs& a, unsigned stages, hipStream_t s) {
   if (a.d.D == 64) {
     if (stages & 4) bwd_dq_f32_kernel<64><<<gq, 256, 0, s>>>(a);
     if (stages & 2) bwd_dkdv_f32_kernel<64><<<gk, 256, 0, s>>>(a);
+  } else if (a.d.D == 96) {
+    if (stages & 4) bwd_dq_f32_kernel<96><<<gq, 256, 0, s>>>(a);
+    if (stages & 2) bwd_dkdv_f32_kernel<96><<<gk, 256, 0, s>>>(a);
   } else {
     if (stages & 4) bwd_dq_f32_kernel<128><<<gq, 256, 0, s>>>(a);
     if (stages & 2) bwd_dkdv_f32_kernel<128><<<gk, 256, 0, s>>>(a);

@@ -245,6 +245,8 @@ fwd_bf16_kernel(FwdArgs a) {
     for (int qb = 0; qb < QB; ++qb) {
       if constexpr (DB == 4)
         asm volatile("s_nop 15\n\ts_nop 15" : "+a"(oacc[qb][0]), "+a"(oacc[qb][1]), "+a"(oacc[qb][2]), "+a"(oacc[qb][3]));
+      else if constexpr (DB == 3)
+        asm volatile("s_nop 15\n\ts_nop 15" : "+a"(oacc[qb][0]), "+a"(oacc[qb][1]), "+a"(oacc[qb][2]));
       else
         asm volatile("s_nop 15\n\ts_nop 15" : "+a"(oacc[qb][0]), "+a"(oacc[qb][1]));
     }
@@ -304,6 +306,8 @@ fwd_bf16_kernel(FwdArgs a) {
       for (int qb = 0; qb < QB; ++qb) {            // the new values settle before a matrix instruction reads them
         if constexpr (DB == 4)
           asm volatile("s_nop 7" : "+a"(oacc[qb][0]), "+a"(oacc[qb][1]), "+a"(oacc[qb][2]), "+a"(oacc[qb][3]));
+        else if constexpr (DB == 3)
+          asm volatile("s_nop 7" : "+a"(oacc[qb][0]), "+a"(oacc[qb][1]), "+a"(oacc[qb][2]));
         else
           asm volatile("s_nop 7" : "+a"(oacc[qb][0]), "+a"(oacc[qb][1]));
       }
@@ -566,12 +570,12 @@ hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t s) {
   const Dims& d = a.d;
   if (a.pass == 1) {                               // the dense kernel over the tiles every row of a workgroup sees
     const long grid = xcd_grid(d.B * d.Hkv, a.n_split * (d.Hq / d.Hkv) * ((d.Sq + QM - 1) / QM));
-    return d.D == 64 ? launch<64, true>(a, grid, s) : launch<128, true>(a, grid, s);
+    return d.D == 64 ? launch<64, true>(a, grid, s) : d.D == 96 ? launch<96, true>(a, grid, s) : launch<128, true>(a, grid, s);
   }
   if (a.mask.allow != nullptr || d.Skv % TN != 0) return launch_fwd_general_bf16(a, s);
   const int n_qt = (int)(((long)(d.Hq / d.Hkv) * d.Sq + QM - 1) / QM);
   const long grid = xcd_grid(d.B * d.Hkv, a.n_split * n_qt);
-  return d.D == 64 ? launch<64>(a, grid, s) : launch<128>(a, grid, s);
+  return d.D == 64 ? launch<64>(a, grid, s) : d.D == 96 ? launch<96>(a, grid, s) : launch<128>(a, grid, s);
 }
 
 }  // namespace lvx

@@ -475,7 +475,7 @@ hipError_t launch_fwd_general_bf16(const FwdArgs& a, hipStream_t s) {
   const int G = d.Hq / d.Hkv;
   const int n_qt = (d.Sq + BM - 1) / BM;
   const long grid = xcd_grid(d.B * d.Hkv, a.n_split * G * n_qt);
-  return d.D == 64 ? launch<64>(a, grid, s) : launch<128>(a, grid, s);
+  return d.D == 64 ? launch<64>(a, grid, s) : d.D == 96 ? launch<96>(a, grid, s) : launch<128>(a, grid, s);
 }
 
 }  // namespace lvx

@@ -34,8 +34,9 @@ class Workload:
     dtype: str                 # "f32" or "bf16": storage type of Q, K, V, dO
     std: float                 # Q, K, V, dO ~ N(0,1) * std
     n_blocks: int = 1          # K/V blocks the query block visits in turn (Algorithm 1 on one GPU)
-    q_chunk: int = 0           # >0: block-causal media mask, text chunk i sees visual blocks <= i
+    q_chunk: int = 0           # >0: media mask over text chunks of q_chunk rows and visual blocks of kv_block keys
     kv_block: int = 0
+    mask_kind: str = "causal"  # "causal": text chunk i sees visual blocks <= i; "recent": only block i
     outlier_frac: float = 0.0  # fraction of key tokens whose K row is scaled
     outlier_scale: float = 1.0
     note: str = ""
@@ -55,8 +56,11 @@ class Workload:
     def visible_pairs(self) -> float:
         if not self.masked:
             return float(self.Sq) * float(self.Skv)
-        allow = block_causal_mask(self)
-        return float(allow.sum()) * self.q_chunk * self.kv_block
+        allow = media_mask(self)
+        # (ragged last chunk / block: count the rows and keys that exist)
+        rows = np.minimum(self.q_chunk, self.Sq - np.arange(allow.shape[0]) * self.q_chunk)
+        keys = np.minimum(self.kv_block, self.Skv - np.arange(allow.shape[1]) * self.kv_block)
+        return float(rows.astype(np.float64) @ allow.astype(np.float64) @ keys.astype(np.float64))
 
 
 WORKLOADS: Dict[str, Workload] = {
@@ -86,6 +90,22 @@ WORKLOADS: Dict[str, Workload] = {
                                           "ten frames of 6404 visual tokens in two blocks"),
     "x3_sq65k_skv8k": Workload("x3_sq65k_skv8k", B=1, Hq=32, Hkv=8, D=128, Sq=65536, Skv=8192,
                                dtype="bf16", std=0.5, note="text side longer than the visual side"),
+    "x5_d96_skv256k": Workload("x5_d96_skv256k", B=1, Hq=32, Hkv=8, D=96, Sq=2048, Skv=262144,
+                               dtype="bf16", std=0.5, n_blocks=8, note="96-wide heads on the shape of c3"),
+    # One worker's share of rows of the paper's comparison table (Section 4.2, 16 workers: the
+    # worker keeps 1/16 of the text and meets all 16 K/V blocks), with the models' visual tokens
+    # per frame (Section 4.1): 729 and 64
+    "m1_owl7b_729": Workload("m1_owl7b_729", B=1, Hq=28, Hkv=4, D=128, Sq=512, Skv=1458000,
+                             dtype="bf16", std=0.5, n_blocks=16,
+                             note="8K text, 2000 frames of 729 tokens: 512 text rows, 16 blocks of 125 frames "
+                                  "(91125 keys, no tile multiple), head groups of 7"),
+    "m2_flamingo9b_64": Workload("m2_flamingo9b_64", B=1, Hq=8, Hkv=8, D=64, Sq=4096, Skv=2097152,
+                                 dtype="bf16", std=0.5, n_blocks=16,
+                                 note="64K text, 32K frames of 64 tokens: 4096 text rows, 16 blocks of 2048 frames"),
+    "m3_flamingo_recent_frame": Workload("m3_flamingo_recent_frame", B=1, Hq=8, Hkv=8, D=64, Sq=4096, Skv=131072,
+                                         dtype="bf16", std=0.5, q_chunk=2, kv_block=64, mask_kind="recent",
+                                         note="the same worker's text against its own 2048 frames when every "
+                                              "text chunk (2 tokens per frame) sees only the frame before it"),
 }
 
 
@@ -131,6 +151,21 @@ def block_causal_mask(w: Workload) -> np.ndarray:
     return (f <= i).astype(np.uint8)
 
 
+def recent_frame_mask(w: Workload) -> np.ndarray:
+    """allow[i, f] = 1 iff f == i: a text chunk sees only the visual block inserted right before it
+    (the most recent frame); chunks past the last block see the last one."""
+    nq = (w.Sq + w.q_chunk - 1) // w.q_chunk
+    nk = (w.Skv + w.kv_block - 1) // w.kv_block
+    i = np.minimum(np.arange(nq), nk - 1)[:, None]
+    f = np.arange(nk)[None, :]
+    return (f == i).astype(np.uint8)
+
+
+def media_mask(w: Workload) -> np.ndarray:
+    """The workload's mask bitmap [n_q_chunks, n_kv_blocks] (shared across the batch)."""
+    return {"causal": block_causal_mask, "recent": recent_frame_mask}[w.mask_kind](w)
+
+
 def make_inputs(w: Workload, seed: int = BASE_SEED, with_do: bool = True) -> Dict[str, torch.Tensor]:
     """CPU tensors in the workload's storage dtype: q, k, v, (do), plus 'allow' (uint8) if masked.
 
@@ -150,7 +185,7 @@ def make_inputs(w: Workload, seed: int = BASE_SEED, with_do: bool = True) -> Dic
     if with_do:
         out["do"] = _normal((w.B, w.Hq, w.Sq, w.D), seed + _TENSOR_ID["do"], w.std).to(dt)
     if w.masked:
-        out["allow"] = torch.from_numpy(block_causal_mask(w))
+        out["allow"] = torch.from_numpy(media_mask(w))
     return out
 
 

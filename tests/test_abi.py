@@ -64,7 +64,7 @@ def test_fwd_argument_errors(lib):
     assert fwd(lib, problem(Hq=3)) == -2                       # Hq % Hkv != 0
     assert fwd(lib, problem(), dtype=7) == -3
     assert fwd(lib, problem(), dtype=B.LVX_F32, o_dtype=B.LVX_BF16) == -3
-    assert fwd(lib, problem(D=96)) == -7
+    assert fwd(lib, problem(D=80)) == -7
     assert fwd(lib, problem(kv_ss=64)) == -4                   # row stride smaller than D
     assert fwd(lib, problem(kv_ss=132)) == -4                  # breaks 16-byte row alignment
     assert fwd(lib, problem(), k=FAKE + 2) == -4               # misaligned pointer
@@ -123,7 +123,7 @@ def test_fwd_merge_errors(lib):
     strided = problem()
     strided.q_ss = 2 * strided.D                                 # float32 kernels need a contiguous Q here
     assert lib.lvx_xattn_fwd_merge(C.byref(strided), B.LVX_F32, *args[2:]) == -4
-    assert lib.lvx_xattn_fwd_merge(C.byref(problem(D=96)), B.LVX_BF16, *args[2:]) == -7
+    assert lib.lvx_xattn_fwd_merge(C.byref(problem(D=80)), B.LVX_BF16, *args[2:]) == -7
     n = B.lvx_xattn_workspace_bytes(p, B.LVX_F32, B.LVX_WS_FWD_MERGE)
     assert n >= p.B * p.Hq * p.Sq * (p.D + 1) * 4                # one float32 partial result and its L
     assert B.lvx_xattn_workspace_bytes(p, B.LVX_BF16, B.LVX_WS_FWD_MERGE) >= 256
@@ -199,7 +199,7 @@ def test_workspace_sizes_and_strerror(lib):
     assert B.lvx_xattn_workspace_bytes(p, B.LVX_F32, B.LVX_WS_BWD) == 3 * rows * 4
     assert B.lvx_xattn_workspace_bytes(p, B.LVX_BF16, B.LVX_WS_FWD) >= 256
     assert B.lvx_xattn_workspace_bytes(p, B.LVX_F32, B.LVX_WS_FWD) == 256
-    assert B.lvx_xattn_workspace_bytes(problem(D=96), B.LVX_BF16, B.LVX_WS_FWD) == 0
+    assert B.lvx_xattn_workspace_bytes(problem(D=80), B.LVX_BF16, B.LVX_WS_FWD) == 0
     assert B.lvx_xattn_workspace_bytes(p, B.LVX_BF16, 9) == 0
     small = problem(B=1, Hq=2, Hkv=2, Sq=64, Skv=1 << 20)       # few query tiles: split-KV
     n = B.lvx_xattn_workspace_bytes(small, B.LVX_BF16, B.LVX_WS_FWD)

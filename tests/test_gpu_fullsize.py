@@ -37,7 +37,8 @@ def rel(x, ref):
 
 @pytest.mark.parametrize("name", ["c2_llama_64k", "c3_longvideo_256k", "c4_flamingo_masked", "c5_extreme_1m",
                                   "x1_sq32k_skv64k", "x2_d64_sq8k_skv256k", "x3_sq65k_skv8k",
-                                  "x4_ragged_5514x64040"])
+                                  "x4_ragged_5514x64040", "x5_d96_skv256k", "m1_owl7b_729", "m2_flamingo9b_64",
+                                  "m3_flamingo_recent_frame"])
 def test_full_size_sampled_parity(name):
     from paper_2502_02406_amd.blockloop import BlockLoop, MediaMask
     w = W.WORKLOADS[name]
@@ -79,7 +80,11 @@ def test_full_size_sampled_parity(name):
     # (the oracle needs the statistics of the whole head group for them)
     pick = zlib.crc32(name.encode())
     b0, hk0 = pick % w.B, (pick // 7) % w.Hkv
-    hi = w.Skv if not w.masked else 32 * w.kv_block          # masked workload: only these keys are visible
+    hi = w.Skv                                               # masked workloads: only a prefix of the keys is visible
+    if w.masked:
+        seen = np.flatnonzero(x["allow"].numpy().any(axis=0))
+        assert np.array_equal(seen, np.arange(len(seen)))
+        hi = min(w.Skv, len(seen) * w.kv_block)
     js = np.unique(np.concatenate([rng.integers(0, hi, 40), [0, hi - 1]]))
     kr = np.stack([np.full_like(js, b0), np.full_like(js, hk0), js], axis=1).astype(np.int32)
     print(f"[fullsize] {name}: oracle on {len(kr)} key rows of head ({b0},{hk0})", flush=True)

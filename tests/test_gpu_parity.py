@@ -154,6 +154,21 @@ FWD_BWD_CASES = [
     small("bf16_single_token_gqa", Hq=8, Hkv=2, Sq=1, Skv=8192),
     # a worker's share of the text: 345 rows per head, tiles that straddle the heads of a group
     small("bf16_short_block_gqa", Hq=8, Hkv=2, Sq=345, Skv=1024),
+    # 96-wide heads (three 32-column blocks, six k-steps, rows of 192 bytes: 12 chunks per row,
+    # so copies and row-wise stores have idle lanes) through every kind of kernel
+    small("f32_d96_gqa_ragged", dtype="f32", std=1.0, D=96, Hq=4, Sq=37, Skv=203),
+    small("bf16_d96_one_tile", D=96, Sq=32, Skv=64),
+    small("bf16_d96_dense_long", D=96, Hq=2, Sq=224, Skv=1024),
+    small("bf16_d96_ragged", D=96, Hq=4, Sq=200, Skv=1037),
+    small("bf16_d96_gqa4_blocks", D=96, B=2, Hq=8, Hkv=2, Sq=192, Skv=2048, n_blocks=4),
+    small("bf16_d96_blockcausal_lists", D=96, Hq=4, Hkv=2, Sq=256, Skv=4096, q_chunk=32, kv_block=512),
+    small("bf16_d96_mixed_mask", D=96, Hq=4, Hkv=2, Sq=200, Skv=1500, q_chunk=5, kv_block=24),
+    small("bf16_d96_splitkv", D=96, Hq=2, Sq=64, Skv=16384),
+    small("bf16_d96_single_token_gqa", D=96, Hq=8, Hkv=2, Sq=1, Skv=8192),
+    small("bf16_d96_fused_rescale", D=96, B=4, Hq=64, Hkv=8, Sq=32, Skv=512, n_blocks=4),
+    # a head group of seven (28 query heads on 4 K/V heads), 729 keys per frame: tiles straddle
+    # the heads of a group and the frames
+    small("bf16_gqa7_frames_of_729", Hq=14, Hkv=2, Sq=150, Skv=4 * 729, n_blocks=2),
 ]
 
 
@@ -237,10 +252,12 @@ def test_step_aligned_media_masks(name, kw, per_batch, p_on):
     run_case(w, do_bwd=True, allow=(rng.random(shape) < p_on))
 
 
-def _random_case(it, rng):
+def _random_case(it, rng, wide=False):
     """A small random problem: head dims, group sizes, query lengths around the tile sizes, key
-    blocks that are and are not tile multiples, block loops, and media masks of three kinds."""
-    D, Hkv, G, B = int(rng.choice([64, 128])), int(rng.choice([1, 2, 3])), int(rng.choice([1, 2, 4])), int(rng.choice([1, 2]))
+    blocks that are and are not tile multiples, block loops, and media masks of three kinds
+    (wide: also 96-wide heads, head groups of 7, and masks that show each text chunk one frame)."""
+    D, Hkv, G, B = int(rng.choice([64, 96, 96, 128] if wide else [64, 128])), int(rng.choice([1, 2, 3])), \
+        int(rng.choice([1, 2, 4, 7] if wide else [1, 2, 4])), int(rng.choice([1, 2]))
     Sq = int(rng.choice([1, 7, 31, 32, 33, 64, 100, 200, 256, 257, 345, 512]))
     n_blocks = int(rng.choice([1, 1, 2, 3]))
     masked = rng.random() < 0.5
@@ -260,8 +277,10 @@ def _random_case(it, rng):
     allow = None
     if masked:
         nq, nk = -(-Sq // q_chunk), -(-Skv // kv_block)
-        kind = int(rng.integers(0, 3))
-        if kind == 0:
+        kind = int(rng.integers(0, 4 if wide else 3))
+        if kind == 3:        # each text chunk sees one frame, the most recent one
+            allow = np.arange(nk)[None, :] == np.minimum(np.arange(nq)[:, None], nk - 1)
+        elif kind == 0:
             allow = rng.random((nq, nk)) < rng.choice([0.2, 0.5, 0.9])
         elif kind == 1:
             allow = np.arange(nk)[None, :] <= np.arange(nq)[:, None]
@@ -270,12 +289,12 @@ def _random_case(it, rng):
     return w, allow
 
 
-@pytest.mark.parametrize("seed", [11, 12, 13])
+@pytest.mark.parametrize("seed", [11, 12, 13, 21, 22])
 def test_random_shapes(seed):
     rng = np.random.Generator(np.random.Philox(seed))
     done = 0
     for it in range(16):
-        w, allow = _random_case(it, rng)
+        w, allow = _random_case(it, rng, wide=seed > 20)
         if w is None:
             continue
         run_case(w, seed=seed * 100 + it, do_bwd=True, allow=allow)
@@ -290,11 +309,12 @@ def test_masked_rows_without_keys():
     run_case(w, do_bwd=True)
 
 
+@pytest.mark.parametrize("D", [128, 96])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_merge_matches_oracle(dtype):
+def test_merge_matches_oracle(dtype, D):
     from paper_2502_02406_amd import binding as B
     rng = np.random.default_rng(5)
-    n, shape = 5, (2, 3, 50, 128)
+    n, shape = 5, (2, 3, 50, D)
     O = rng.standard_normal((n,) + shape)
     L = rng.standard_normal((n,) + shape[:3]) * 4
     L[1, :, :, :7] = -np.inf
@@ -313,7 +333,7 @@ def test_merge_matches_oracle(dtype):
         # The parts are exact in float32 (the oracle reads their rounded values), the weights and
         # sums are float32 arithmetic (1e-5 of the largest value is far above its noise), and a
         # bf16 output adds ONE rounding: half a unit in the last of 8 mantissa bits, at most 2^-8 |O|
-            # (reached just above a power of two).
+        # (reached just above a power of two).
         got = o_out.float().cpu().numpy().astype(np.float64)
         bound = 1e-5 * max(1.0, np.abs(Oref).max())
         if out_dtype == torch.bfloat16:

@@ -52,3 +52,21 @@ def test_block_causal_mask_and_flop_counts():
     assert c3.Skv // c3.n_blocks == 32768
     c1 = W.WORKLOADS["c1_tiny"]
     assert c1.dtype == "f32" and W.make_inputs(c1)["q"].dtype == torch.float32
+
+
+def test_recent_frame_mask_and_model_shaped_workloads():
+    w = W.WORKLOADS["m3_flamingo_recent_frame"]
+    allow = W.media_mask(w)
+    assert allow.shape == (2048, 2048) and np.array_equal(allow, np.eye(2048, dtype=np.uint8))
+    assert w.visible_pairs() == w.Sq * 64                      # every text row sees one frame of 64 tokens
+    # more text chunks than frames: the late chunks keep the last frame
+    late = W.scaled(w, Sq=16, Skv=3 * 64)
+    assert np.array_equal(W.media_mask(late).argmax(axis=1), [0, 1, 2, 2, 2, 2, 2, 2])
+    # ragged last chunk and block are counted by the rows and keys that exist
+    rag = W.scaled(w, Sq=5, Skv=100, mask_kind="causal")       # chunks of 2,2,1 rows; blocks of 64, 36 keys
+    assert rag.visible_pairs() == 2 * 64 + 2 * 100 + 1 * 100
+    m1 = W.WORKLOADS["m1_owl7b_729"]
+    assert m1.Skv == 2000 * 729 and m1.Skv % m1.n_blocks == 0 and (m1.Skv // m1.n_blocks) % 729 == 0
+    m2 = W.WORKLOADS["m2_flamingo9b_64"]
+    assert m2.Skv == 32768 * 64 and m2.Sq * 16 == 65536
+    assert W.WORKLOADS["x5_d96_skv256k"].D == 96
