@@ -268,7 +268,8 @@ fwd_general_bf16_kernel(FwdArgs a) {
   // with them the register pressure) as written.  Returns this lane's maximum of nxt.
   auto fused_half = [&](const char* k_pre, int kb_pre, const char* vs_, int kb, f32x16& cur,
                         f32x16& nxt, bf16x8 (&kop)[KS]) -> float {
-    constexpr int EPC = 16 / KS;                  // probabilities produced per score k-step
+    // (the 16 probabilities of a lane are produced KS-th by KS-th under the score k-steps:
+    // elements [16 c / KS, 16 (c + 1) / KS) under step c, which is 2 or 3 of them when KS = 6)
     const float mc = (m_ref == -INFINITY) ? 0.f : m_ref * c2;
     float psum = 0.f;
     bf16x8 pfrag[2], vop[KS];                     // KS == 2 * DB V operands per half
@@ -278,14 +279,13 @@ fwd_general_bf16_kernel(FwdArgs a) {
       vop[c] = load_tr_operand(vs_, SM::VP, 32 * kb + 16 * (c / DB), 32 * (c % DB), lane);
       nxt = mfma32(kop[c], qf[c], nxt);
 #pragma unroll
-      for (int i = 0; i < EPC; ++i) {
-        const int e = c * EPC + i;
+      for (int e = 16 * c / KS; e < 16 * (c + 1) / KS; ++e) {
         const float pr = __builtin_amdgcn_exp2f(fmaf(cur[e], c2, -mc));
         cur[e] = pr;
         psum += pr;
       }
-      if ((c + 1) * EPC == 8) pfrag[0] = cvt_operand(cur, 0);
-      if ((c + 1) * EPC == 16) pfrag[1] = cvt_operand(cur, 8);
+      if (16 * c / KS < 8 && 16 * (c + 1) / KS >= 8) pfrag[0] = cvt_operand(cur, 0);
+      if (c == KS - 1) pfrag[1] = cvt_operand(cur, 8);
       __builtin_amdgcn_sched_barrier(0);
     }
     l_run += psum;
