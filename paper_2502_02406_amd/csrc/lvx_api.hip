@@ -144,6 +144,9 @@ FwdPlan fwd_plan(const Dims& d, lvx_dtype dtype, const MaskDev& m) {
   f.two = masked && fwd_two_pass(d, dtype, m);
   if (f.tail && f.n_split > LVX_MAX_PARTS - 1) f.n_split = LVX_MAX_PARTS - 1;
   if (f.two) f.n_split = fwd_two_pass_split(f.n_split, 0);
+  // (one launch over tile lists: its workgroups start longest first, which evens the load out
+  // with half the splits the other masked forms want)
+  if (masked && dtype == LVX_BF16 && fwd_bf16_one_pass_fits(d, m) && f.n_split > 1) f.n_split /= 2;
   f.n_parts = f.two ? 2 * f.n_split : f.n_split + (f.tail ? 1 : 0);
   return f;
 }
@@ -294,6 +297,7 @@ lvx_status lvx_xattn_fwd_merge(const lvx_problem* p, lvx_dtype dtype, const void
   const bool two = mask != nullptr && fwd_two_pass(a.d, dtype, a.mask);
   if (tail && a.n_split > LVX_MAX_PARTS - 2) a.n_split = LVX_MAX_PARTS - 2;    // (the running state and the tail are parts too)
   if (two) a.n_split = fwd_two_pass_split(a.n_split, 1);
+  if (mask != nullptr && dtype == LVX_BF16 && fwd_bf16_one_pass_fits(a.d, a.mask) && a.n_split > 1) a.n_split /= 2;
   const int n_launch_parts = two ? 2 * a.n_split : a.n_split + (tail ? 1 : 0);
   a.o_part = nullptr; a.lse_part = nullptr;
   const size_t need = fwd_merge_ws(a.d, dtype, n_launch_parts);

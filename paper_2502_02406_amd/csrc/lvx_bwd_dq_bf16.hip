@@ -39,7 +39,12 @@ template <int D> using DqSmem = KvSmem<D>;
 // of the workgroup sees under a media mask (BwdArgs::dq_pass == 1).  Inside such a tile nothing is
 // masked, so the loop is the dense one; only the tile numbers come from the list.  The other
 // visible tiles are left to a launch of the general kernel (dq_pass == 2).
-template <int D, bool GENERAL, bool LIST = false>
+// LIST = 2: a mask whose text chunks are multiples of 32 rows and whose key blocks are multiples
+// of 64 keys never cuts through a (32-row block, key tile) pair: the list then holds the tiles
+// that ANY row of the workgroup sees, each with one bit per 32-row block of the workgroup; the
+// dS operands of a row block that does not see a tile are replaced by zeros as they are packed
+// (whatever its scores gave, nothing of it reaches a matrix instruction).  One launch does it all.
+template <int D, bool GENERAL, int LIST = 0>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 bwd_dq_bf16_kernel(BwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -57,12 +62,27 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   const int rows_lim = PACK ? G * d.Sq : d.Sq;      // rows of the list this workgroup's tiles are cut from
   const int n_qt = (rows_lim + QM - 1) / QM;
   const int per_split = PACK ? n_qt : G * n_qt;
-  HeadWork hw;
-  if (!xcd_decode(blockIdx.x, d.B * d.Hkv, a.n_split_dq * per_split, &hw)) return;
-  const int b = hw.head / d.Hkv, hk = hw.head % d.Hkv;
-  const int split = hw.item / per_split;
-  const int hq = hk * G + (PACK ? 0 : (hw.item % per_split) / n_qt);   // PACK: the first head of the group
-  const int qt = hw.item % n_qt;
+  int b, hk, split, hq, qt;
+  if constexpr (LIST == 2) {
+    // (as in the forward: the later query tiles, which under a causal mask see the most key tiles,
+    // start first; the head varies fastest)
+    const int n_hq = d.B * d.Hq;
+    const int head = (int)(blockIdx.x % n_hq), rest = (int)(blockIdx.x / n_hq);
+    split = rest % a.n_split_dq;
+    qt = n_qt - 1 - rest / a.n_split_dq;
+    if (qt < 0) return;
+    b = head / d.Hq;
+    hq = head % d.Hq;
+    hk = hq / G;
+  } else {
+    HeadWork hw;
+    if (!xcd_decode(blockIdx.x, d.B * d.Hkv, a.n_split_dq * per_split, &hw)) return;
+    b = hw.head / d.Hkv;
+    hk = hw.head % d.Hkv;
+    split = hw.item / per_split;
+    hq = hk * G + (PACK ? 0 : (hw.item % per_split) / n_qt);   // PACK: the first head of the group
+    qt = hw.item % n_qt;
+  }
 
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ql = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -179,14 +199,26 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   // t_begin, t_end and the cursor are POSITIONS in the list; tile_at turns one into a tile.
   int* const tlist = (int*)(smem + SM::RING + SM::BITS_BYTES);
   constexpr int LIST_CAP = SM::WIN_BYTES / 4 - 1;
+  constexpr int VIS_SHIFT = 24;                    // LIST = 2: a list entry is tile | row-block bits << 24
   if (LIST) {
     const int c0 = i_wg0 / a.mask.q_chunk, h = i_wg1 / a.mask.q_chunk - c0 + 1;     // chunks of this workgroup's rows
     const int w = (d.Skv - 1) / a.mask.kv_block + 1;
-    unsigned* const full = bits;                   // full[f]: 1 if all h chunks see key block f; then the tile plane
+    // full[f]: 1 if all h chunks see key block f (LIST = 2: bit k = the k-th 32-row block of the
+    // workgroup, which lies in one chunk, sees it); then the tile plane
+    unsigned* const full = bits;
     unsigned* const plane = bits + ((w + 1) & ~1);
     for (int f = tid; f < w; f += 256) {
-      unsigned ok = 1;
-      for (int c = 0; c < h; ++c) ok &= a.mask.allow[b * a.mask.stride_b + (long)(c0 + c) * a.mask.stride_q + f] != 0;
+      unsigned ok;
+      if (LIST == 2) {
+        ok = 0;
+        for (int k = 0; k < QM / 32; ++k) {
+          const int i = i_wg0 + 32 * k;
+          if (i < d.Sq && a.mask.allow[b * a.mask.stride_b + (long)(i / a.mask.q_chunk) * a.mask.stride_q + f] != 0) ok |= 1u << k;
+        }
+      } else {
+        ok = 1;
+        for (int c = 0; c < h; ++c) ok &= a.mask.allow[b * a.mask.stride_b + (long)(c0 + c) * a.mask.stride_q + f] != 0;
+      }
       full[f] = ok;
     }
     __syncthreads();
@@ -205,7 +237,11 @@ bwd_dq_bf16_kernel(BwdArgs a) {
       int count = 0;
       for (int base = 0; base < n_tiles; base += 64) {         // wave-uniform trip count
         const unsigned long long m = *(const unsigned long long*)(plane + base / 32);
-        if ((m >> lane) & 1ull) tlist[count + __popcll(m & ((1ull << lane) - 1ull))] = base + lane;
+        if ((m >> lane) & 1ull) {
+          int entry = base + lane;
+          if (LIST == 2) entry |= (int)(bits[((base + lane) * TN) / a.mask.kv_block] << VIS_SHIFT);
+          tlist[count + __popcll(m & ((1ull << lane) - 1ull))] = entry;
+        }
         count += (int)__popcll(m);
       }
       if (lane == 0) tlist[LIST_CAP] = count;
@@ -216,9 +252,21 @@ bwd_dq_bf16_kernel(BwdArgs a) {
     t_end = (int)((long)(split + 1) * nn / a.n_split_dq);
     nt = t_end - t_begin;
   }
-  auto tile_at = [&](int pos) __attribute__((always_inline)) -> int {
-    return LIST ? __builtin_amdgcn_readfirstlane(tlist[pos]) : pos;
+  auto tile_of = [&](int entry) __attribute__((always_inline)) -> int {
+    return LIST == 2 ? entry & ((1 << VIS_SHIFT) - 1) : entry;
   };
+  auto tile_at = [&](int pos) __attribute__((always_inline)) -> int {
+    return LIST ? tile_of(__builtin_amdgcn_readfirstlane(tlist[pos])) : pos;
+  };
+  // LIST = 2: which of this wave's QB row blocks see tile number T_ of this workgroup's share of
+  // the list (bit qb); vcur holds that for the tile whose scores are being converted
+  auto vis_at = [&](int T_) __attribute__((always_inline)) -> int {
+    if constexpr (LIST == 2)
+      return (__builtin_amdgcn_readfirstlane(tlist[t_begin + T_]) >> (VIS_SHIFT + QB * wave)) & ((1 << QB) - 1);
+    else
+      return (1 << QB) - 1;
+  };
+  int vcur = (1 << QB) - 1;
   int crow[QB] = {};                               // this lane's rows' chunks, relative to the window
   if (GENERAL && have_cls) {
 #pragma unroll
@@ -394,7 +442,8 @@ bwd_dq_bf16_kernel(BwdArgs a) {
     const float pr = __builtin_amdgcn_exp2f(FOLD ? s[qb][v] : fmaf(s[qb][v], c2, nl2[qb]));
     const float ds = pr * (FOLD ? p[qb][v] : p[qb][v] + nd[qb]);
     if (v % 2 == 0) { cy.ds = ds; return; }
-    dsw[qb][v / 8][(v % 8) / 2] = pack2_bf16(cy.ds, ds);
+    const unsigned w2 = pack2_bf16(cy.ds, ds);
+    dsw[qb][v / 8][(v % 8) / 2] = (LIST != 2 || ((vcur >> qb) & 1)) ? w2 : 0u;
   };
   auto convert = [&](const f32x16 (&s)[QB], const f32x16 (&p)[QB], u32x4 (&dsw)[QB][2]) __attribute__((always_inline)) {
     Carry cy;
@@ -482,6 +531,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   u32x4 ds0[QB][2] = {}, ds1[QB][2] = {};          // packed dS operands of even / odd halves
   Carry cy;
   if (nt > 0) {
+    vcur = vis_at(0);
     score(smem, 0, s0, p0, nothing, first_kv(smem, 0), no_tail);
     mask_scores(e[0], 0, s0);
     settle_scores(s0);
@@ -497,9 +547,11 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   for (; T + 4 < nt; ++T) {                        // full tiles: tile T + 1 is scored, tile T + 4 issued
     char* const sa = stage(T);
     char* const sb = stage(T + 1);
+    const int vnext = vis_at(T + 1);               // (the conversions under way are tile T's)
     contract_convert(sa, 0, ds0, s1, p1, ds1, cy, fkt, [&]() __attribute__((always_inline)) { fkv = first_kv(sb, 0); });
     score_convert(sb, 0, s0, p0, s1, p1, ds1, cy, fkv, [&]() __attribute__((always_inline)) { fkt = first_kt(sa, 1); }, nothing);
     mask_scores(e[1], 0, s0);
+    vcur = vnext;                                  // from here on: scores of tile T + 1
     contract_convert(sa, 1, ds1, s0, p0, ds0, cy, fkt, [&]() __attribute__((always_inline)) { fkv = first_kv(sb, 1); });
     if constexpr (GENERAL) {
       mid(std::false_type{}, true, sa);
@@ -508,7 +560,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
       mid(std::true_type{}, false, sa);
       // the copies of tile T + 4 go out during the phase (LIST: its number was fetched a tile ago,
       // and the operands waited for here were fetched after it)
-      const int t_new = LIST ? __builtin_amdgcn_readfirstlane(id_next) : cursor;
+      const int t_new = LIST ? tile_of(__builtin_amdgcn_readfirstlane(id_next)) : cursor;
       e[4] = t_new;
       cursor = next_tile(cursor + 1);
       if (LIST) id_next = tlist[cursor < t_end ? cursor : t_begin];
@@ -526,6 +578,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
     const bool more = T + 1 < nt;
     contract(stage(T), 0, ds0);
     convert(s1, p1, ds1);
+    if (more) vcur = vis_at(T + 1);
     if (more) { score(stage(T + 1), 0, s0, p0, nothing, first_kv(stage(T + 1), 0), no_tail); mask_scores(e[1], 0, s0); }
     contract(stage(T), 1, ds1);
     if (more) convert(s0, p0, ds0);
@@ -587,7 +640,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   }
 }
 
-template <int D, bool GENERAL, bool LIST = false>
+template <int D, bool GENERAL, int LIST = 0>
 hipError_t launch(const BwdArgs& a, long grid, hipStream_t s) {
   static SmemOnce once;
   hipError_t e = ensure_dynamic_lds((const void*)bwd_dq_bf16_kernel<D, GENERAL, LIST>, DqSmem<D>::TOTAL, &once);
@@ -627,11 +680,13 @@ namespace {
 hipError_t launch_one(const BwdArgs& a, bool general, hipStream_t s) {
   const Dims& d = a.d;
   const int G = d.Hq / d.Hkv;
-  const bool list = a.dq_pass == 1;                // the dense kernel over a list of tiles: rows tiled per head
+  const bool list = a.dq_pass == 1 || a.dq_pass == 3;   // the dense kernel over a list of tiles: rows tiled per head
   const long per_split = general || list ? (long)G * ((d.Sq + QM - 1) / QM) : ((long)G * d.Sq + QM - 1) / QM;
-  const long grid = xcd_grid(d.B * d.Hkv, (int)(a.n_split_dq * per_split));
+  const long grid = a.dq_pass == 3 ? (long)d.B * d.Hq * a.n_split_dq * ((d.Sq + QM - 1) / QM)
+                                   : xcd_grid(d.B * d.Hkv, (int)(a.n_split_dq * per_split));
   hipError_t e;
-  if (list) e = d.D == 64 ? launch<64, false, true>(a, grid, s) : d.D == 96 ? launch<96, false, true>(a, grid, s) : launch<128, false, true>(a, grid, s);
+  if (a.dq_pass == 3) e = d.D == 64 ? launch<64, false, 2>(a, grid, s) : d.D == 96 ? launch<96, false, 2>(a, grid, s) : launch<128, false, 2>(a, grid, s);
+  else if (list) e = d.D == 64 ? launch<64, false, 1>(a, grid, s) : d.D == 96 ? launch<96, false, 1>(a, grid, s) : launch<128, false, 1>(a, grid, s);
   else if (d.D == 64) e = general ? launch<64, true>(a, grid, s) : launch<64, false>(a, grid, s);
   else if (d.D == 96) e = general ? launch<96, true>(a, grid, s) : launch<96, false>(a, grid, s);
   else e = general ? launch<128, true>(a, grid, s) : launch<128, false>(a, grid, s);
@@ -651,6 +706,16 @@ hipError_t launch_bwd_dq_bf16(const BwdArgs& a, hipStream_t s) {
     // Both add into dq_accum, one after the other on the stream.
     const int n_tiles = (d.Skv + TN - 1) / TN;
     const int h_max = (QM - 1) / a.mask.q_chunk + 2, w = (d.Skv - 1) / a.mask.kv_block + 1;
+    // One launch of the dense kernel over the tiles any row of a workgroup sees, when the mask
+    // never cuts through a 32-row block or a key tile and the list fits.
+    const bool fits = d.Skv % TN == 0 && n_tiles <= DqSmem<128>::WIN_BYTES / 4 - 1 &&
+                      ((w + 1) & ~1) + (n_tiles + 63) / 64 * 2 <= DqSmem<128>::BITS_BYTES / 4;
+    if (fits && a.mask.q_chunk % 32 == 0 && a.mask.kv_block % TN == 0) {
+      BwdArgs p3 = a;
+      p3.dq_pass = 3;
+      if (p3.n_split_dq > 1) p3.n_split_dq /= 2;    // (its workgroups start longest first: half the splits even the load out)
+      return launch_one(p3, false, s);
+    }
     const bool two = d.Skv % TN == 0 && plan_fits(h_max, w, n_tiles, DqSmem<128>::BITS_BYTES, DqSmem<128>::WIN_BYTES) &&
                      n_tiles <= DqSmem<128>::WIN_BYTES / 4 - 1 && ((w + 1) & ~1) + (n_tiles + 63) / 64 * 2 <= DqSmem<128>::BITS_BYTES / 4;
     if (!two) return launch_one(a, true, s);

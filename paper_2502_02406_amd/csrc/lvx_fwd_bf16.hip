@@ -40,15 +40,25 @@ constexpr float LAZY_SUM = 64.0f;      // a lane's 16 probabilities of a half ma
 #ifndef LVX_FWD_XE
 #define LVX_FWD_XE 8
 #endif
+#ifndef LVX_MASKED_WG_FACTOR
+#define LVX_MASKED_WG_FACTOR 4L
+#endif
 constexpr int XE = LVX_FWD_XE;                  // elements of a half converted during the contraction (of 32)
 
 // Dense attention with Skv a multiple of 64 only: no mask code and no ragged tile, so that nothing
 // stands between the phases of the pipeline (masked and ragged problems: lvx_fwd_general_bf16.hip).
-// LIST: the same kernel over a list of key tiles -- those that EVERY row of the workgroup sees
+// LIST = 1: the same kernel over a list of key tiles -- those that EVERY row of the workgroup sees
 // under a media mask (FwdArgs::pass == 1).  Nothing is masked inside such a tile; only the tile
 // numbers come from the list, which the KV splits share evenly.  The other visible tiles are left
 // to a launch of the general kernel (pass == 2), and the partial results of both are combined.
-template <int D, bool LIST = false>
+// LIST = 2: a mask whose text chunks are multiples of 32 rows and whose key blocks are multiples
+// of 64 keys never cuts through a (32-row block, key tile) pair: the list then holds the tiles
+// that ANY row of the workgroup sees, each with one bit per 32-row block of the workgroup, and a
+// row block that does not see a tile converts its scores against a reference of +infinity --
+// every probability is exp2(-inf) = 0 -- so that the whole mask costs two selects per half tile
+// and one launch does it all.  (A workgroup moves at the pace of its busiest wave anyway: a wave
+// that skipped the tile would wait at the barrier.)
+template <int D, int LIST = 0>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 fwd_bf16_kernel(FwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -66,12 +76,30 @@ fwd_bf16_kernel(FwdArgs a) {
   const int rows_kv = PACK ? G * d.Sq : d.Sq;
   const int n_qt = (rows_kv + QM - 1) / QM;
   const int per_split = PACK ? n_qt : G * n_qt;
-  HeadWork hw;
-  if (!xcd_decode(blockIdx.x, d.B * d.Hkv, a.n_split * per_split, &hw)) return;
-  const int b = hw.head / d.Hkv, hk = hw.head % d.Hkv;
-  const int split = hw.item / per_split;
-  const int hq0 = hk * G + (PACK ? 0 : (hw.item % per_split) / n_qt);   // PACK: the first head of the group
-  const int qt = hw.item % n_qt;
+  int b, hk, split, hq0, qt;
+  if constexpr (LIST == 2) {
+    // Under a mask the query tiles of a head differ in how many key tiles they see (under a causal
+    // one, the later the tile the more).  Workgroups start in the order of their numbers: the later
+    // query tiles go first, so that the short ones fill the gaps the long ones leave at the end;
+    // the head varies fastest, which keeps a head's workgroups on one XCD (number mod 8) whenever
+    // the head count is a multiple of 8.
+    const int n_hq = d.B * d.Hq;
+    const int head = (int)(blockIdx.x % n_hq), rest = (int)(blockIdx.x / n_hq);
+    split = rest % a.n_split;
+    qt = n_qt - 1 - rest / a.n_split;
+    if (qt < 0) return;
+    b = head / d.Hq;
+    hq0 = head % d.Hq;
+    hk = hq0 / G;
+  } else {
+    HeadWork hw;
+    if (!xcd_decode(blockIdx.x, d.B * d.Hkv, a.n_split * per_split, &hw)) return;
+    b = hw.head / d.Hkv;
+    hk = hw.head % d.Hkv;
+    split = hw.item / per_split;
+    hq0 = hk * G + (PACK ? 0 : (hw.item % per_split) / n_qt);   // PACK: the first head of the group
+    qt = hw.item % n_qt;
+  }
 
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ql = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -110,15 +138,27 @@ fwd_bf16_kernel(FwdArgs a) {
   // t_begin, t_end and the cursor are POSITIONS in the list; tile_at turns one into a tile.
   int* const tlist = (int*)(smem + SM::RING + SM::BITS_BYTES);
   constexpr int LIST_CAP = SM::WIN_BYTES / 4 - 1;
+  constexpr int VIS_SHIFT = 24;                     // LIST = 2: a list entry is tile | row-block bits << 24
   if (LIST) {
     const int i_wg0 = qt * QM, i_wg1 = min(d.Sq, i_wg0 + QM) - 1;
     const int c0 = i_wg0 / a.mask.q_chunk, h = i_wg1 / a.mask.q_chunk - c0 + 1;     // chunks of this workgroup's rows
     const int w = (d.Skv - 1) / a.mask.kv_block + 1;
-    unsigned* const full = (unsigned*)(smem + SM::RING);   // full[f]: all h chunks see key block f; then the tile plane
+    // full[f]: all h chunks see key block f (LIST = 2: bit k = the k-th 32-row block of the
+    // workgroup, which lies in one chunk, sees it); then the tile plane
+    unsigned* const full = (unsigned*)(smem + SM::RING);
     unsigned* const plane = full + ((w + 1) & ~1);
     for (int f = tid; f < w; f += 256) {
-      unsigned ok = 1;
-      for (int c = 0; c < h; ++c) ok &= a.mask.allow[b * a.mask.stride_b + (long)(c0 + c) * a.mask.stride_q + f] != 0;
+      unsigned ok;
+      if (LIST == 2) {
+        ok = 0;
+        for (int k = 0; k < QM / 32; ++k) {
+          const int i = i_wg0 + 32 * k;
+          if (i < d.Sq && a.mask.allow[b * a.mask.stride_b + (long)(i / a.mask.q_chunk) * a.mask.stride_q + f] != 0) ok |= 1u << k;
+        }
+      } else {
+        ok = 1;
+        for (int c = 0; c < h; ++c) ok &= a.mask.allow[b * a.mask.stride_b + (long)(c0 + c) * a.mask.stride_q + f] != 0;
+      }
       full[f] = ok;
     }
     __syncthreads();
@@ -137,7 +177,11 @@ fwd_bf16_kernel(FwdArgs a) {
       int count = 0;
       for (int base = 0; base < n_tiles; base += 64) {         // wave-uniform trip count
         const unsigned long long m = *(const unsigned long long*)(plane + base / 32);
-        if ((m >> lane) & 1ull) tlist[count + __popcll(m & ((1ull << lane) - 1ull))] = base + lane;
+        if ((m >> lane) & 1ull) {
+          int entry = base + lane;
+          if (LIST == 2) entry |= (int)(full[((base + lane) * TN) / a.mask.kv_block] << VIS_SHIFT);
+          tlist[count + __popcll(m & ((1ull << lane) - 1ull))] = entry;
+        }
         count += (int)__popcll(m);
       }
       if (lane == 0) tlist[LIST_CAP] = count;
@@ -147,8 +191,19 @@ fwd_bf16_kernel(FwdArgs a) {
     t_begin = (int)((long)split * nn / a.n_split);
     t_end = (int)((long)(split + 1) * nn / a.n_split);
   }
+  auto tile_of = [&](int entry) __attribute__((always_inline)) -> int {
+    return LIST == 2 ? entry & ((1 << VIS_SHIFT) - 1) : entry;
+  };
   auto tile_at = [&](int pos) __attribute__((always_inline)) -> int {
-    return LIST ? __builtin_amdgcn_readfirstlane(tlist[pos]) : pos;
+    return LIST ? tile_of(__builtin_amdgcn_readfirstlane(tlist[pos])) : pos;
+  };
+  // LIST = 2: which of this wave's QB row blocks see tile number T_ of this workgroup's share of
+  // the list (bit qb); everything otherwise
+  auto vis_at = [&](int T_) __attribute__((always_inline)) -> int {
+    if constexpr (LIST == 2)
+      return (__builtin_amdgcn_readfirstlane(tlist[t_begin + T_]) >> (VIS_SHIFT + QB * wave)) & ((1 << QB) - 1);
+    else
+      return (1 << QB) - 1;
   };
   const int nt = max(t_end - t_begin, 0);          // number of tiles this workgroup performs
   auto next_tile = [&](int t) __attribute__((always_inline)) -> int { return min(t, t_end); };
@@ -189,6 +244,16 @@ fwd_bf16_kernel(FwdArgs a) {
   f32x16 oacc[QB][DB];                 // O^T, relative to the reference
   float r[QB], l_run[QB], l_half[QB];  // reference, this lane's share of the sum of p over the halves
                                        // accepted so far, and over the half being converted
+  // the reference that conversions subtract: r itself, or (LIST = 2) +infinity for a row block
+  // that does not see the tile whose scores are being converted
+  float rq_own[QB];
+  float (&rq)[QB] = *(LIST == 2 ? &rq_own : &r);
+  auto set_rq = [&](int vb) __attribute__((always_inline)) {
+    if constexpr (LIST == 2) {
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) rq[qb] = ((vb >> qb) & 1) ? r[qb] : INFINITY;
+    }
+  };
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
 #pragma unroll
@@ -257,7 +322,7 @@ fwd_bf16_kernel(FwdArgs a) {
   struct Carry { float p; };
   auto conv_elem = [&](int x, Carry& cy, const f32x16 (&s)[QB], u32x4 (&pw)[QB][2]) __attribute__((always_inline)) {
     const int qb = x / 16, v = x % 16;
-    const float pr = __builtin_amdgcn_exp2f(fmaf(s[qb][v], c2, -r[qb]));
+    const float pr = __builtin_amdgcn_exp2f(fmaf(s[qb][v], c2, -rq[qb]));
     if (v == 0) l_half[qb] = pr;
     else l_half[qb] += pr;
     if (v % 2 == 0) { cy.p = pr; return; }
@@ -283,7 +348,7 @@ fwd_bf16_kernel(FwdArgs a) {
   // -- and the accepted sums shrink by alpha = 2^(old - new), and the half is converted again
   // from its scores, which are still in their registers.  Rows that keep their reference get
   // identical values again.
-  auto commit = [&](const f32x16 (&s)[QB], u32x4 (&pw)[QB][2]) __attribute__((always_inline)) {
+  auto commit = [&](const f32x16 (&s)[QB], u32x4 (&pw)[QB][2], int vb) __attribute__((always_inline)) {
     bool need = false;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) need |= !(l_half[qb] <= LAZY_SUM);
@@ -292,6 +357,7 @@ fwd_bf16_kernel(FwdArgs a) {
       drain_oacc();
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
+        if (LIST == 2 && !((vb >> qb) & 1)) continue;          // (scores the rows do not see raise nothing)
         const float r_new = fmaxf(r[qb], row_max(s[qb]));
         const float alpha = __builtin_amdgcn_exp2f(r[qb] - r_new);
         r[qb] = r_new;
@@ -311,6 +377,7 @@ fwd_bf16_kernel(FwdArgs a) {
         else
           asm volatile("s_nop 7" : "+a"(oacc[qb][0]), "+a"(oacc[qb][1]));
       }
+      set_rq(vb);
       convert(s, pw);
     }
 #pragma unroll
@@ -405,8 +472,11 @@ fwd_bf16_kernel(FwdArgs a) {
     settle_scores(s0);
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) r[qb] = row_max(s0[qb]);     // no probability of the first half exceeds 1
+    // (LIST = 2: rows that do not see the first tile start from a reference that means nothing
+    // yet; any finite one will do, their first visible tile raises it if it has to)
+    set_rq(vis_at(0));
     convert(s0, p0);
-    commit(s0, p0);
+    commit(s0, p0, vis_at(0));
     score(smem, 1, s1, nothing, first_k(smem, 1), no_tail);
   }
   int T = 0;
@@ -417,16 +487,18 @@ fwd_bf16_kernel(FwdArgs a) {
   for (; T + 4 < nt; ++T) {                        // full tiles: tile T + 1 is scored, tile T + 4 issued
     char* const sa = stage(T);
     char* const sb = stage(T + 1);
+    const int vb_t = vis_at(T), vb_n = vis_at(T + 1);          // (the conversions under way are tile T's)
     contract_convert(sa, 0, p0, s1, p1, cy, fvt, [&]() __attribute__((always_inline)) { fk = first_k(sb, 0); });
     asm volatile("" : "+v"(fk));                   // (waited for here, where the compiler still knows what is in flight)
     score_convert(sb, 0, s0, s1, p1, cy, fk, [&]() __attribute__((always_inline)) { fvt = first_vt(sa, 1); }, nothing);
     asm volatile("" : "+v"(fvt));
-    commit(s1, p1);
+    commit(s1, p1, vb_t);
+    set_rq(vb_n);                                  // from here on: scores of tile T + 1
     contract_convert(sa, 1, p1, s0, p0, cy, fvt, [&]() __attribute__((always_inline)) { fk = first_k(sb, 1); });
     asm volatile("" : "+v"(fk));
     mid(std::true_type{}, false, sa);
     // the copies of tile T + 4 go out during the phase (LIST: its number was fetched a tile ago)
-    const int t_new = LIST ? __builtin_amdgcn_readfirstlane(id_next) : cursor;
+    const int t_new = LIST ? tile_of(__builtin_amdgcn_readfirstlane(id_next)) : cursor;
     cursor = next_tile(cursor + 1);
     if (LIST) id_next = tlist[cursor < t_end ? cursor : t_begin];
     constexpr int EVERY = QB * KS / NDMA;
@@ -436,16 +508,17 @@ fwd_bf16_kernel(FwdArgs a) {
                     if (m % EVERY == EVERY - 1 && m / EVERY < NDMA) issue_part(t_new, sa, m / EVERY);
                   });
     asm volatile("" : "+v"(fvt));
-    commit(s0, p0);
+    commit(s0, p0, vb_n);
   }
   for (; T < nt; ++T) {                            // the last (at most four) tiles, phase after phase
     const bool more = T + 1 < nt;
+    const int vb_t = vis_at(T), vb_n = more ? vis_at(T + 1) : 0;
     contract(stage(T), 0, p0);
     convert(s1, p1);
-    commit(s1, p1);                                // (a raise comes before anything relative to the new reference is added)
+    commit(s1, p1, vb_t);                          // (a raise comes before anything relative to the new reference is added)
     if (more) { score(stage(T + 1), 0, s0, nothing, first_k(stage(T + 1), 0), no_tail); }
     contract(stage(T), 1, p1);
-    if (more) { convert(s0, p0); commit(s0, p0); }
+    if (more) { set_rq(vb_n); convert(s0, p0); commit(s0, p0, vb_n); }
     mid(std::false_type{}, T + 4 < nt, stage(T));
     if (more) { score(stage(T + 1), 1, s1, nothing, first_k(stage(T + 1), 1), no_tail); }
   }
@@ -523,7 +596,7 @@ fwd_bf16_kernel(FwdArgs a) {
   }
 }
 
-template <int D, bool LIST = false>
+template <int D, int LIST = 0>
 hipError_t launch(const FwdArgs& a, long grid, hipStream_t s) {
   static SmemOnce once;
   const hipError_t e = ensure_dynamic_lds((const void*)fwd_bf16_kernel<D, LIST>, KvSmem<D>::TOTAL, &once);
@@ -552,25 +625,39 @@ int fwd_bf16_pick_split(const Dims& d, int n_cu, bool masked) {
     const double t_part = 2.0 * (double)d.B * d.Hq * d.Sq * d.D * 4.0 / 3e12;
     return pick_split_balanced(base, n_cu, cap, t_full, t_part);
   }
-  long want = (4L * n_cu + base - 1) / base;
+  long want = (LVX_MASKED_WG_FACTOR * n_cu + base - 1) / base;
   if (want < 1) want = 1;
   if (want > cap) want = cap;
   if (want > 64) want = 64;
   return (int)want;
 }
 
-bool fwd_bf16_two_pass_fits(const Dims& d, const MaskDev& m) {
+namespace {
+bool list_fits(const Dims& d, const MaskDev& m) {
   // the list and its scratch fit the mask areas of the dense kernel's LDS layout, tiles are whole
   const int n_tiles = (d.Skv + TN - 1) / TN, w = (d.Skv - 1) / m.kv_block + 1;
-  return m.allow != nullptr && d.Skv % TN == 0 && m.q_chunk >= 8 && n_tiles <= KvSmem<128>::WIN_BYTES / 4 - 1 &&
+  return m.allow != nullptr && d.Skv % TN == 0 && n_tiles <= KvSmem<128>::WIN_BYTES / 4 - 1 &&
          ((w + 1) & ~1) + (n_tiles + 63) / 64 * 2 <= KvSmem<128>::BITS_BYTES / 4;
+}
+}  // namespace
+// one launch of the dense kernel over the tiles any row of a workgroup sees: the mask never cuts
+// through a 32-row block or a key tile
+bool fwd_bf16_one_pass_fits(const Dims& d, const MaskDev& m) {
+  return list_fits(d, m) && m.q_chunk % 32 == 0 && m.kv_block % TN == 0;
+}
+bool fwd_bf16_two_pass_fits(const Dims& d, const MaskDev& m) {
+  return list_fits(d, m) && m.q_chunk >= 8 && !fwd_bf16_one_pass_fits(d, m);
 }
 
 hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t s) {
   const Dims& d = a.d;
   if (a.pass == 1) {                               // the dense kernel over the tiles every row of a workgroup sees
     const long grid = xcd_grid(d.B * d.Hkv, a.n_split * (d.Hq / d.Hkv) * ((d.Sq + QM - 1) / QM));
-    return d.D == 64 ? launch<64, true>(a, grid, s) : d.D == 96 ? launch<96, true>(a, grid, s) : launch<128, true>(a, grid, s);
+    return d.D == 64 ? launch<64, 1>(a, grid, s) : d.D == 96 ? launch<96, 1>(a, grid, s) : launch<128, 1>(a, grid, s);
+  }
+  if (a.pass == 0 && fwd_bf16_one_pass_fits(d, a.mask)) {
+    const long grid = (long)d.B * d.Hq * a.n_split * ((d.Sq + QM - 1) / QM);
+    return d.D == 64 ? launch<64, 2>(a, grid, s) : d.D == 96 ? launch<96, 2>(a, grid, s) : launch<128, 2>(a, grid, s);
   }
   if (a.mask.allow != nullptr || d.Skv % TN != 0) return launch_fwd_general_bf16(a, s);
   const int n_qt = (int)(((long)(d.Hq / d.Hkv) * d.Sq + QM - 1) / QM);

@@ -165,6 +165,7 @@ inline int pick_split_balanced(long base, int n_cu, long cap, double t_full, dou
 }
 int fwd_bf16_pick_split(const Dims& d, int n_cu, bool masked);
 bool fwd_bf16_two_pass_fits(const Dims& d, const MaskDev& m);   // a masked forward may run as passes 1 and 2
+bool fwd_bf16_one_pass_fits(const Dims& d, const MaskDev& m);   // ... or as one launch of the dense kernel over tile lists
 hipError_t launch_fwd_general_bf16(const FwdArgs& a, hipStream_t s);   // masked or ragged problems
 int bwd_bf16_pick_split(const Dims& d, int n_cu, bool masked);
 // memory-bound helpers
