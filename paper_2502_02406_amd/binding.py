@@ -13,7 +13,8 @@ from typing import Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "liblvx.so")
+# (LVX_LIB: another build of the same library, e.g. one with measurement switches compiled in)
+LIB_PATH = os.environ.get("LVX_LIB") or os.path.join(_HERE, "liblvx.so")
 
 LVX_F32, LVX_BF16 = 0, 1
 LVX_WS_FWD, LVX_WS_BWD, LVX_WS_FWD_MERGE = 0, 1, 2

@@ -56,19 +56,32 @@ def _compile(src: str, force: bool, extra) -> str:
     return obj
 
 
-def build(force: bool = True, extra_flags=()) -> str:
-    """Compile every csrc/*.hip for gfx950 and link liblvx.so; returns its path."""
-    os.makedirs(OBJ, exist_ok=True)
-    srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
-    with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
-        objs = list(ex.map(lambda s: _compile(s, force, extra_flags), srcs))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
+def build(force: bool = True, extra_flags=(), output: str = None) -> str:
+    """Compile every csrc/*.hip for gfx950 and link liblvx.so; returns its path.  With `output`
+    the library goes to that path instead (a variant built with other definitions, to be loaded
+    through the LVX_LIB environment variable), its objects into a directory of their own."""
+    global OBJ
+    lib, obj_dir = LIB, OBJ
+    if output:
+        lib = os.path.abspath(output)
+        OBJ = os.path.join(obj_dir, "variant_" + os.path.basename(lib).replace(".", "_"))
+    try:
+        os.makedirs(OBJ, exist_ok=True)
+        srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+        with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
+            objs = list(ex.map(lambda s: _compile(s, force, extra_flags), srcs))
+    finally:
+        OBJ = obj_dir
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + objs
     subprocess.run(cmd, check=True)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":
     # --define NAME=VALUE (repeatable): extra preprocessor definitions, e.g. the measurement switches
     # of the fused backward kernel
+    # --output PATH: link the library there instead of replacing liblvx.so
     defs = [f"-D{sys.argv[i + 1]}" for i, a in enumerate(sys.argv[:-1]) if a == "--define"]
-    print(build(force="--incremental" not in sys.argv or bool(defs), extra_flags=defs))
+    outs = [sys.argv[i + 1] for i, a in enumerate(sys.argv[:-1]) if a == "--output"]
+    print(build(force="--incremental" not in sys.argv or bool(defs), extra_flags=defs,
+                output=outs[-1] if outs else None))
