@@ -215,7 +215,7 @@ lvx_status lvx_xattn_project(const lvx_projection* p, lvx_dtype dtype, const voi
  *        before the first K/V block of a step, and each block's call adds its tokens' part
  *        (the order of the additions is the order of the calls: results repeat bit for bit);
  *        NULL = not wanted.  At least one of dx, dw must be given.
- * LVX_BF16 runs on the matrix cores when E % 256 == 0, (H * D) % 256 == 0, D % 64 == 0,
+ * LVX_BF16 runs on the matrix cores when E % 256 == 0, (H * D) % 256 == 0, D % 8 == 0,
  * B * S < 2^24 and B * S * H * D < 2^30; other shapes, and LVX_F32, take a plain kernel (one
  * float32 sum per element in the order of the definition: correctness-grade, slow).
  * LVX_BF16: pointers and x's row stride must be 16-byte aligned.  No workspace. */

@@ -65,7 +65,8 @@ __device__ __forceinline__ void div_tokens(int m, int S, float inv_S, int* b, in
 // MODE 0: dx = G W (rows = tokens, columns = features e, contraction over n)
 // MODE 1: dw += G^T X (rows = columns n of the projection, columns = e, contraction over tokens)
 // RB: 32-row blocks of the result per wave (4: tiles of 256 rows; 2: of 128 rows, MODE 1 only)
-template <int MODE, int RB>
+// GA (MODE 0): heads are multiples of 64 wide, so that a tile pair's 64 columns of G are one line
+template <int MODE, int RB, bool GA = true>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 project_bwd_bf16_kernel(ProjBwdArgs a) {
   static_assert(RB == 4 || (RB == 2 && MODE == 1), "tile heights");
@@ -77,8 +78,19 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int n_rt = MODE == 0 ? (int)((a.M + TR - 1) / TR) : a.N / TR;   // row tiles of the result
   const int n_ct = a.E / T;
-  HeadWork hw;                                       // the column tiles of a row tile share an XCD
-  if (!xcd_decode(blockIdx.x, n_rt, n_ct, &hw)) return;
+  HeadWork hw;
+  if (MODE == 1 && n_rt % 2 == 0 && n_ct % 4 == 0) {
+    // dw streams a [tokens][TR] panel of G per row tile and a [tokens][256] panel of x per column
+    // tile, and each XCD has an L2 of its own: the XCDs (workgroup number mod 8) are laid out 2 x 4
+    // over the tile grid, so that each reads half of G and a quarter of x instead of an eighth of
+    // G and all of x.
+    const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8, pc = n_ct / 4;
+    hw.head = (xcd / 4) * (n_rt / 2) + slot / pc;
+    hw.item = (xcd % 4) * pc + slot % pc;
+    if (hw.head >= ((xcd / 4) + 1) * (n_rt / 2)) return;
+  } else if (!xcd_decode(blockIdx.x, n_rt, n_ct, &hw)) {   // the column tiles of a row tile share an XCD
+    return;
+  }
   const long r0 = (long)hw.head * TR;                // first token (MODE 0) / first column n (MODE 1)
   const int e0 = hw.item * T;
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, l31 = lane & 31;
@@ -115,8 +127,10 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
       const long m = r0 + r < a.M ? r0 + r : a.M - 1;
       int b, s;
       div_tokens((int)m, a.S, inv_S, &b, &s);
-      g_row[j] = (unsigned)(((long)b * a.H * a.S + s) * a.D * 2) +
-                 16u * (unsigned)((lane & 7) ^ perm_of(8 * j + (lane >> 3)));
+      g_row[j] = (unsigned)(((long)b * a.H * a.S + s) * a.D * 2);
+      // (heads that are multiples of 64 wide: the 64 columns of a tile pair are one 128-byte line,
+      // and the lane's chunk of it is a fixed offset; otherwise see g_lane below)
+      if (GA) g_row[j] += 16u * (unsigned)((lane & 7) ^ perm_of(8 * j + (lane >> 3)));
     }
   } else {
     const int o = (int)(r0 / HD), nn0 = (int)(r0 % HD);
@@ -134,6 +148,11 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
   // copies of the pairs are issued in ascending order, copy 8 of a pair first)
   int g_o = 0, g_h = 0, g_c = 0;
   const char* g_pair_base = nullptr;
+  // ... and for heads that are no multiple of 64 wide (96): a tile pair's 64 columns may lie in two
+  // heads, so each lane works out where ITS 8 columns are: chunk (l % 8) ^ (l / 8) ^ (j % 2) of
+  // the pair, i.e. column g_c + 8 chunk of the output, in head / at column (that / D, that % D)
+  unsigned g_lane0 = 0u, g_lane1 = 0u;               // (j even / odd)
+  const float inv_D = 1.0f / (float)a.D;
 
   auto issue_part = [&](int kt, int part) __attribute__((always_inline)) {
     const unsigned st = smem_u + (unsigned)((kt % NSLOT) * SLOT_B);
@@ -152,11 +171,23 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
       }
     } else if (MODE == 0) {                          // B side: G, 256 tokens x 64 columns
       if (part == 8) {
-        g_pair_base = (const char*)a.g[g_o] + (long)g_h * head_b + (long)g_c * 2;
-        g_c += BK;
-        if (g_c == a.D) { g_c = 0; if (++g_h == a.H) { g_h = 0; ++g_o; } }
+        if constexpr (GA) {
+          g_pair_base = (const char*)a.g[g_o] + (long)g_h * head_b + (long)g_c * 2;
+          g_c += BK;
+          if (g_c == a.D) { g_c = 0; if (++g_h == a.H) { g_h = 0; ++g_o; } }
+        } else {                                     // g_c counts the columns of the output here
+          g_pair_base = (const char*)a.g[g_o];
+          int h, cc;
+          div_tokens(g_c + 8 * ((lane & 7) ^ (lane >> 3)), a.D, inv_D, &h, &cc);
+          g_lane0 = (unsigned)((long)h * head_b + (long)cc * 2);
+          div_tokens(g_c + 8 * ((lane & 7) ^ (lane >> 3) ^ 1), a.D, inv_D, &h, &cc);
+          g_lane1 = (unsigned)((long)h * head_b + (long)cc * 2);
+          g_c += BK;
+          if (g_c == HD) { g_c = 0; ++g_o; }
+        }
       }
-      dma16u(g_pair_base, g_row[j], st + (unsigned)(TILE_B + (64 * wave + 8 * j) * RK_ROWB));
+      dma16u(g_pair_base, g_row[j] + (GA ? 0u : (j & 1) ? g_lane1 : g_lane0),
+             st + (unsigned)(TILE_B + (64 * wave + 8 * j) * RK_ROWB));
     } else {                                         // B side: G, 64 tokens x TR columns
       const int jb = part - 8;
       const long m_first = (long)kt * BK;
@@ -379,23 +410,35 @@ __global__ void __launch_bounds__(256) project_bwd_w_plain_kernel(ProjBwdArgs a)
 
 }  // namespace
 
-bool project_bwd_bf16_supported(const ProjBwdArgs& a) {
-  // 16-byte chunks inside one head, a tile of 256 columns inside one output, tokens countable in
-  // a float, and every G offset inside 32 bits
-  return a.E % T == 0 && (a.H * a.D) % T == 0 && a.D % BK == 0 &&
+namespace {
+// what both matrix-core kernels need: 16-byte chunks inside one head, a tile of 256 columns inside
+// one output, tokens countable in a float, and every G offset inside 32 bits
+bool mfma_common(const ProjBwdArgs& a) {
+  return a.E % T == 0 && (a.H * a.D) % T == 0 && a.D % 8 == 0 &&
          a.M < (1L << 24) && a.M * a.H * a.D * 2 < (1L << 31) && 64 * a.ldx * 2 < (1L << 31) &&
          2L * a.E * 2 < (1L << 31);
 }
+}  // namespace
+bool project_bwd_bf16_supported(const ProjBwdArgs& a) { return mfma_common(a); }
 
 hipError_t launch_project_bwd(const ProjBwdArgs& a, int is_f32, hipStream_t s) {
-  const bool mfma = !is_f32 && project_bwd_bf16_supported(a);
-  if (mfma) {
-    static SmemOnce once_x, once_w, once_w2;
-    if (a.dx) {
-      const hipError_t e = ensure_dynamic_lds((const void*)project_bwd_bf16_kernel<0, 4>, SMEM_B, &once_x);
-      if (e != hipSuccess) return e;
+  const bool mfma_w = !is_f32 && mfma_common(a), mfma_x = mfma_w;
+  static SmemOnce once_x, once_xu, once_w, once_w2;
+  ProjBwdArgs rest = a;                              // what is left for the plain kernels
+  if (mfma_x) rest.dx = nullptr;
+  if (mfma_w) rest.dw = nullptr;
+  if (mfma_w) {
+    if (a.dx && mfma_x) {
       const long grid = xcd_grid((int)((a.M + T - 1) / T), a.E / T);
-      project_bwd_bf16_kernel<0, 4><<<(unsigned)grid, 256, SMEM_B, s>>>(a);
+      if (a.D % BK == 0) {
+        const hipError_t e = ensure_dynamic_lds((const void*)project_bwd_bf16_kernel<0, 4, true>, SMEM_B, &once_x);
+        if (e != hipSuccess) return e;
+        project_bwd_bf16_kernel<0, 4, true><<<(unsigned)grid, 256, SMEM_B, s>>>(a);
+      } else {
+        const hipError_t e = ensure_dynamic_lds((const void*)project_bwd_bf16_kernel<0, 4, false>, SMEM_B, &once_xu);
+        if (e != hipSuccess) return e;
+        project_bwd_bf16_kernel<0, 4, false><<<(unsigned)grid, 256, SMEM_B, s>>>(a);
+      }
     }
     if (a.dw) {
       // tiles of 128 rows when tiles of 256 would leave a quarter of the compute units idle
@@ -410,17 +453,18 @@ hipError_t launch_project_bwd(const ProjBwdArgs& a, int is_f32, hipStream_t s) {
         project_bwd_bf16_kernel<1, 2><<<(unsigned)xcd_grid(a.N / 128, a.E / T), 256, SMEM_B, s>>>(a);
       }
     }
-    return hipGetLastError();
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
   }
-  if (a.dx) {
+  if (rest.dx) {
     const unsigned grid = (unsigned)((a.M * a.E + 255) / 256);
-    if (is_f32) project_bwd_x_plain_kernel<float><<<grid, 256, 0, s>>>(a);
-    else project_bwd_x_plain_kernel<__bf16><<<grid, 256, 0, s>>>(a);
+    if (is_f32) project_bwd_x_plain_kernel<float><<<grid, 256, 0, s>>>(rest);
+    else project_bwd_x_plain_kernel<__bf16><<<grid, 256, 0, s>>>(rest);
   }
-  if (a.dw) {
+  if (rest.dw) {
     const unsigned grid = (unsigned)(((long)a.N * a.E + 255) / 256);
-    if (is_f32) project_bwd_w_plain_kernel<float><<<grid, 256, 0, s>>>(a);
-    else project_bwd_w_plain_kernel<__bf16><<<grid, 256, 0, s>>>(a);
+    if (is_f32) project_bwd_w_plain_kernel<float><<<grid, 256, 0, s>>>(rest);
+    else project_bwd_w_plain_kernel<__bf16><<<grid, 256, 0, s>>>(rest);
   }
   return hipGetLastError();
 }

@@ -175,6 +175,8 @@ BWD_CASES = [
     ("llama_like_kv", 1, 1000, 1024, 8, 128, 2, 0),
     ("strided_tokens", 1, 515, 256, 2, 128, 1, 64),
     ("q_like_many_column_tiles", 1, 257, 512, 16, 64, 1, 0),
+    # 96-wide heads: a tile pair's 64 columns straddle two heads, eight heads fill three column tiles
+    ("d96_heads_straddle_tile_pairs", 2, 150, 256, 8, 96, 2, 0),
     # shapes the matrix-core kernels do not take: the plain kernels
     ("plain_heads_of_96", 1, 130, 64, 2, 96, 2, 0),
     ("plain_narrow_output", 2, 65, 128, 1, 128, 1, 0),
