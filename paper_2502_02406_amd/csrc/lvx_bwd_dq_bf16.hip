@@ -594,7 +594,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   // is the only one on its rows in this launch (launches follow each other in stream order);
   // when the key range is split over several workgroups, each stores its sums in its own slice
   // of the workspace and a reduction follows the kernel (float atomics from every split would
-  // be bounded by the L2 atomic rate, about 50 G per second).
+  // be bounded by the L2 atomic rate, about 80 G elements per second).
   // The last matrix instructions must have retired before their registers are read.
   if constexpr (DB == 4) {
     asm volatile("s_nop 15\n\ts_nop 15" : "+a"(dq[0][0]), "+a"(dq[0][1]), "+a"(dq[0][2]), "+a"(dq[0][3]),
