@@ -225,7 +225,27 @@ def main():
                                  "training step does with or without recomputation, not an overhead of it"},
                      "note": "lvx_xattn_project: K and V of every block and Q made again in the backward "
                              "pass; overhead = that time over the attention forward + backward above"}
-        del y_d, wkv_d, x_d, wq_d, k_re, v_re, q_re
+        del y_d, k_re, v_re, q_re
+        # the whole layer with recomputation (RecomputeLayer: keeps x, y, O, L; makes Q, and K, V block by
+        # block, again in the backward pass and carries the gradients through the projections), timed as
+        # a sequence of C-ABI calls like the attention step above
+        if not w.masked and w.B == 1 and w.Skv * E * 2 <= 8 << 30:
+            from paper_2502_02406_amd.blockloop import RecomputeLayer
+            layer = RecomputeLayer(w.B, w.Sq, w.Skv, E, w.Hq, w.Hkv, w.D, q.dtype, w.n_blocks)
+            y_all = W.projection_inputs(w.B, w.Skv, E, 8, w.dtype, seed + 200)["x"].cuda()
+            lo, ll = layer.forward(x_d, y_all, wq_d, wkv_d)
+            ms_lf = timed(lambda: layer.forward(x_d, y_all, wq_d, wkv_d), max(1, reps // 2))
+            ms_lb = timed(lambda: layer.backward(x_d, y_all, wq_d, wkv_d, lo, ll, g), max(1, reps // 2))
+            recompute["layer"] = {
+                "fwd_ms": ms_lf, "bwd_ms": ms_lb,
+                "attention_only_ms": sec * 1e3,
+                "bwd_share_recompute": extra_ms / ms_lb,
+                "note": "projections + attention forward; backward with Q, K, V made again and the projections' "
+                        "gradients: a whole cross-attention layer's share of a training step (no output "
+                        "projection, no residual path); bwd_share_recompute = the recomputed projections' "
+                        "time over the layer's backward"}
+            del layer, y_all, lo, ll
+        del wkv_d, x_d, wq_d
     dom = max(("bwd_dkdv", "bwd_dq", "fwd"), key=lambda n: kernels[n]["ms"])
     roofline = {"bound": "mfma", "kernel": dom, "achieved": kernels[dom]["tflops"],
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",

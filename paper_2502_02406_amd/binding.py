@@ -248,6 +248,13 @@ def lvx_xattn_dq_finalize(p: lvx_problem, dq_accum, dq) -> None:
     _check(code, "lvx_xattn_dq_finalize")
 
 
+def _token_strides(x):
+    """(batch stride, token stride) of x [B, S, E]; with one batch the batch stride means nothing (a
+    window of a longer token sequence reports the whole sequence's), so it is set to what the
+    entry points ask for: batches that follow each other."""
+    return (x.stride(0) if x.shape[0] > 1 else x.shape[1] * x.stride(1)), x.stride(1)
+
+
 def lvx_xattn_project(x, w, outs) -> None:
     """outs: one or two tensors [B, H, S, D] (contiguous, dtype of x), overwritten with the heads of
     x [B, S, E] times the rows of w [len(outs) * H * D, E]."""
@@ -259,7 +266,7 @@ def lvx_xattn_project(x, w, outs) -> None:
     p.B, p.S, p.E = x.shape
     _, p.H, _, p.D = outs[0].shape
     assert all(tuple(o.shape) == (p.B, p.H, p.S, p.D) for o in outs) and tuple(w.shape) == (len(outs) * p.H * p.D, p.E)
-    p.x_sb, p.x_ss = x.stride(0), x.stride(1)
+    p.x_sb, p.x_ss = _token_strides(x)
     arr = (C.c_void_p * len(outs))(*[o.data_ptr() for o in outs])
     code = load().lvx_xattn_project(C.byref(p), dtype_code(x.dtype), x.data_ptr(), w.data_ptr(),
                                     len(outs), arr, _stream())
@@ -281,7 +288,7 @@ def lvx_xattn_project_bwd(x, w, d_outs, dx=None, dw=None) -> None:
     _, p.H, _, p.D = d_outs[0].shape
     assert all(tuple(g.shape) == (p.B, p.H, p.S, p.D) for g in d_outs)
     assert tuple(w.shape) == (len(d_outs) * p.H * p.D, p.E)
-    p.x_sb, p.x_ss = x.stride(0), x.stride(1)
+    p.x_sb, p.x_ss = _token_strides(x)
     if dx is not None:
         assert dx.shape == x.shape and dx.stride() == x.stride() and dx.dtype == x.dtype and dx.is_cuda
     if dw is not None:

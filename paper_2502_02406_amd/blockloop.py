@@ -110,3 +110,71 @@ class BlockLoop:
         p = B.make_problem(q, k, self.scale)
         B.lvx_xattn_dq_finalize(p, self.dq_accum, self.dq)
         return self.dq
+
+
+class RecomputeLayer:
+    """One cross-attention layer under the activation recomputation of Section 3.2, on one GPU: the
+    forward pass keeps the token features x, y and (O, L) and nothing else; the backward pass makes
+    Q again from x and, block by block, K and V again from the block's visual tokens, runs the
+    attention backward on them, and carries dQ, dK, dV on through the projections to dx, dy and the
+    weights' gradients.  K and V exist for one block at a time.
+
+    x [B, Sq, E] text tokens, y [B, Skv, E] visual tokens (B > 1: n_blocks must be 1, the
+    projection entry points want the batches of a call to follow each other), wq [Hq D, E],
+    wkv [2 Hkv D, E] (W_K^T on top of W_V^T).  Only sequences C-ABI calls."""
+
+    def __init__(self, Bsz, Sq, Skv, E, Hq, Hkv, D, dtype: torch.dtype, n_blocks: int = 1,
+                 softmax_scale: float = 0.0, device: str = "cuda"):
+        assert Skv % n_blocks == 0 and (Bsz == 1 or n_blocks == 1)
+        self.n_blocks, self.blk = n_blocks, Skv // n_blocks
+        self.loop = BlockLoop((Bsz, Hq, Sq, D), (Bsz, Hkv, self.blk, D), dtype, 1, None, softmax_scale, device)
+        kw = dict(dtype=dtype, device=device)
+        self.q = torch.empty((Bsz, Hq, Sq, D), **kw)
+        self.k = torch.empty((Bsz, Hkv, self.blk, D), **kw)
+        self.v = torch.empty_like(self.k)
+        self.dk, self.dv = torch.empty_like(self.k), torch.empty_like(self.k)
+        self.o_acc = torch.empty((Bsz, Hq, Sq, D), dtype=torch.float32, device=device)
+        self.dx = torch.empty((Bsz, Sq, E), **kw)
+        self.dy = torch.empty((Bsz, Skv, E), **kw)
+        self.dwq = torch.empty((Hq * D, E), dtype=torch.float32, device=device)
+        self.dwkv = torch.empty((2 * Hkv * D, E), dtype=torch.float32, device=device)
+
+    def _kv_of_block(self, y, wkv, n):
+        yb = y[:, n * self.blk:(n + 1) * self.blk]
+        B.lvx_xattn_project(yb, wkv, [self.k, self.v])
+        return yb
+
+    def forward(self, x, y, wq, wkv) -> Tuple[torch.Tensor, torch.Tensor]:
+        """(O in the input dtype, L float32); Q, K, V are not kept."""
+        lp = self.loop
+        B.lvx_xattn_project(x, wq, [self.q])
+        p = B.make_problem(self.q, self.k, lp.scale)
+        for n in range(self.n_blocks):
+            self._kv_of_block(y, wkv, n)
+            if self.n_blocks == 1:
+                B.lvx_xattn_fwd(p, self.q, self.k, self.v, None, lp.o, lp.lse, lp.ws)
+                return lp.o, lp.lse
+            if n == 0:
+                B.lvx_xattn_fwd(p, self.q, self.k, self.v, None, self.o_acc, lp.lse, lp.ws)
+            else:
+                B.lvx_xattn_fwd_merge(p, self.q, self.k, self.v, None, self.o_acc, lp.lse, lp.ws)
+        B.lvx_xattn_merge([self.o_acc], [lp.lse], lp.o, lp.lse)
+        return lp.o, lp.lse
+
+    def backward(self, x, y, wq, wkv, o, lse, d_o):
+        """(dx, dy in the input dtype, dW_Q, dW_KV float32) from x, y, (O, L) and dO alone."""
+        lp = self.loop
+        B.lvx_xattn_project(x, wq, [self.q])                       # Q again
+        lp.dq_accum.zero_()
+        self.dwq.zero_()
+        self.dwkv.zero_()
+        p = B.make_problem(self.q, self.k, lp.scale)
+        for n in range(self.n_blocks):
+            yb = self._kv_of_block(y, wkv, n)                       # K, V of the block again
+            stages = B.LVX_BWD_ALL if n == 0 else (B.LVX_BWD_DKDV | B.LVX_BWD_DQ)
+            B.lvx_xattn_bwd(p, self.q, self.k, self.v, o, lse, d_o, None, lp.dq_accum, self.dk, self.dv, lp.ws, stages)
+            B.lvx_xattn_project_bwd(yb, wkv, [self.dk, self.dv],
+                                    dx=self.dy[:, n * self.blk:(n + 1) * self.blk], dw=self.dwkv)
+        B.lvx_xattn_dq_finalize(p, lp.dq_accum, lp.dq)
+        B.lvx_xattn_project_bwd(x, wq, [lp.dq], dx=self.dx, dw=self.dwq)
+        return self.dx, self.dy, self.dwq, self.dwkv

@@ -577,11 +577,13 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   for (; T < nt; ++T) {                            // the last (at most four) tiles
     const bool more = T + 1 < nt;
     contract(stage(T), 0, ds0);
+    settle_scores(s1);                             // (outside the pipelined loop the wait comes first, as a real dependence)
+    settle_scores(p1);
     convert(s1, p1, ds1);
     if (more) vcur = vis_at(T + 1);
     if (more) { score(stage(T + 1), 0, s0, p0, nothing, first_kv(stage(T + 1), 0), no_tail); mask_scores(e[1], 0, s0); }
     contract(stage(T), 1, ds1);
-    if (more) convert(s0, p0, ds0);
+    if (more) { settle_scores(s0); settle_scores(p0); convert(s0, p0, ds0); }
     mid(std::false_type{}, T + 4 < nt, stage(T));
     if (more) { score(stage(T + 1), 1, s1, p1, nothing, first_kv(stage(T + 1), 1), no_tail); mask_scores(e[1], 1, s1); }
     e[0] = e[1]; e[1] = e[2]; e[2] = e[3]; e[3] = e[4];

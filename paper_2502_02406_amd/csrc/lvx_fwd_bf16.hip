@@ -514,11 +514,12 @@ fwd_bf16_kernel(FwdArgs a) {
     const bool more = T + 1 < nt;
     const int vb_t = vis_at(T), vb_n = more ? vis_at(T + 1) : 0;
     contract(stage(T), 0, p0);
+    settle_scores(s1);                             // (outside the pipelined loop the wait comes first, as a real dependence)
     convert(s1, p1);
     commit(s1, p1, vb_t);                          // (a raise comes before anything relative to the new reference is added)
     if (more) { score(stage(T + 1), 0, s0, nothing, first_k(stage(T + 1), 0), no_tail); }
     contract(stage(T), 1, p1);
-    if (more) { set_rq(vb_n); convert(s0, p0); commit(s0, p0, vb_n); }
+    if (more) { settle_scores(s0); set_rq(vb_n); convert(s0, p0); commit(s0, p0, vb_n); }
     mid(std::false_type{}, T + 4 < nt, stage(T));
     if (more) { score(stage(T + 1), 1, s1, nothing, first_k(stage(T + 1), 1), no_tail); }
   }
