@@ -106,7 +106,9 @@ struct ProjBwdArgs {
   float* dw;            // [N, E] contiguous, or null
   long M, ldx;
   int S, E, N, H, D;
-  int n_cu;             // compute units of the device (picks dw's tile height)
+  int n_cu;             // compute units of the device (picks dw's tile height and token split)
+  int dw_parts;         // set by launch_project_bwd: parts the token range of dw is cut into, and the
+  unsigned dw_tiles_grid;   // workgroups of one part
 };
 bool project_bwd_bf16_supported(const ProjBwdArgs& a);   // shapes the matrix-core kernels take
 hipError_t launch_project_bwd(const ProjBwdArgs& a, int is_f32, hipStream_t s);

@@ -25,8 +25,15 @@
 // Rows past the last token are never stored (dx) and are cleared in LDS before they are
 // multiplied (dw, where they would otherwise enter every sum).
 // dw of a narrow projection (K and V of a model with few K/V heads) has fewer 256 x 256 tiles
-// than the chip has compute units; its tiles are then 128 rows high (a wave owns 64 x 128, the G
-// tile is [token][128 columns] with rows of 256 bytes, same permutation).
+// than the chip has compute units.  Its token range is then cut into parts, one workgroup per
+// (tile, part), and the parts of a tile add their sums to dw ONE AFTER THE OTHER in the order of
+// their numbers: a turn word per tile says whose turn it is, the data travels with agent-scope
+// loads and stores (the L2 caches of the XCDs are not coherent with each other), and the last part
+// sets the word back to zero.  The order is fixed, so results repeat bit for bit; a part only ever
+// waits for a workgroup with a lower number, which was started before it, so the waits end (they
+// are bounded all the same).  Calls that overlap in time on one GPU would share the turn words and
+// must not be made.  (Without that, tiles 128 rows high: a wave owns 64 x 128, the G tile is
+// [token][128 columns] with rows of 256 bytes, same permutation.)
 #include "lvx_internal.h"
 #include "lvx_mfma.h"
 #include "lvx_kv_ring.h"
@@ -46,20 +53,27 @@ constexpr int TILE_B = BK * KR_ROWB;   // either kind: 32 KB
 static_assert(TILE_B == T * RK_ROWB, "both tile kinds take the same room");
 constexpr int SLOT_B = 2 * TILE_B;     // A-side tile ([k][256 columns e]), then B-side tile (up to as large)
 constexpr int RING_B = NSLOT * SLOT_B;
+constexpr int MAX_TURNS = 4096;        // tiles of dw that can take turns
+constexpr int SPIN_LIMIT = 1 << 22;    // tries (with a short sleep each) before a part stops waiting for its turn
 constexpr int TB_PITCH = 128 * 2 + 16; // dx epilogue: a wave's 128 tokens x 128 columns of bf16, padded rows
 constexpr int TB_WAVE = 128 * TB_PITCH;
 constexpr int SMEM_B = RING_B > 4 * TB_WAVE ? RING_B : 4 * TB_WAVE;
 
 __device__ __forceinline__ int perm_of(int r) { return (r & 7) ^ ((r >> 3) & 1); }
 
+// whose turn it is to add to tile t of dw (0 between launches)
+__device__ int dw_turn[MAX_TURNS];
+typedef int __attribute__((address_space(1))) gint;
+
 // floor(m / S) and the remainder for 0 <= m < 2^24 (exact: the float quotient is off by at most one)
 __device__ __forceinline__ void div_tokens(int m, int S, float inv_S, int* b, int* s) {
-  int q = (int)((float)m * inv_S);
-  int r = m - q * S;
-  if (r < 0) { --q; r += S; }
-  if (r >= S) { ++q; r -= S; }
-  *b = q;
-  *s = r;
+  // (without branches: this runs between the matrix instructions of the dw kernel's loop, which
+  // a conditional would cut into pieces)
+  const int q = (int)((float)m * inv_S);
+  const int r = m - q * S;
+  const int fix = (r >= S ? 1 : 0) - (r < 0 ? 1 : 0);
+  *b = q + fix;
+  *s = r - fix * S;
 }
 
 // MODE 0: dx = G W (rows = tokens, columns = features e, contraction over n)
@@ -79,16 +93,19 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
   const int n_rt = MODE == 0 ? (int)((a.M + TR - 1) / TR) : a.N / TR;   // row tiles of the result
   const int n_ct = a.E / T;
   HeadWork hw;
+  // (dw: workgroups part * dw_tiles_grid + i, i = 0 .. dw_tiles_grid - 1, are part `part` of the token range)
+  const unsigned wg = MODE == 1 ? blockIdx.x % a.dw_tiles_grid : blockIdx.x;
+  const int tpart = MODE == 1 ? (int)(blockIdx.x / a.dw_tiles_grid) : 0;
   if (MODE == 1 && n_rt % 2 == 0 && n_ct % 4 == 0) {
     // dw streams a [tokens][TR] panel of G per row tile and a [tokens][256] panel of x per column
     // tile, and each XCD has an L2 of its own: the XCDs (workgroup number mod 8) are laid out 2 x 4
     // over the tile grid, so that each reads half of G and a quarter of x instead of an eighth of
     // G and all of x.
-    const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8, pc = n_ct / 4;
+    const int xcd = wg % 8, slot = wg / 8, pc = n_ct / 4;
     hw.head = (xcd / 4) * (n_rt / 2) + slot / pc;
     hw.item = (xcd % 4) * pc + slot % pc;
     if (hw.head >= ((xcd / 4) + 1) * (n_rt / 2)) return;
-  } else if (!xcd_decode(blockIdx.x, n_rt, n_ct, &hw)) {   // the column tiles of a row tile share an XCD
+  } else if (!xcd_decode(wg, n_rt, n_ct, &hw)) {   // the column tiles of a row tile share an XCD
     return;
   }
   const long r0 = (long)hw.head * TR;                // first token (MODE 0) / first column n (MODE 1)
@@ -96,7 +113,10 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, l31 = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;           // this wave's 128 rows / 128 columns of the tile
-  const int nk = MODE == 0 ? a.N / BK : (int)((a.M + BK - 1) / BK);
+  // tile pairs: all of them (dx), or this part's share of the token range (dw): k0 .. k0 + nk - 1
+  const int nk_all = MODE == 0 ? a.N / BK : (int)((a.M + BK - 1) / BK);
+  const int k0 = MODE == 1 ? (int)((long)tpart * nk_all / a.dw_parts) : 0;
+  const int nk = MODE == 1 ? (int)((long)(tpart + 1) * nk_all / a.dw_parts) - k0 : nk_all;
   const int HD = a.H * a.D;
   const float inv_S = 1.0f / (float)a.S;
   const long head_b = (long)a.S * a.D * 2;           // bytes of one head of one batch in g
@@ -163,7 +183,7 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
         const char* base = (const char*)a.w + ((long)(kt * BK + 16 * wave + 2 * j) * a.E + e0) * 2;
         dma16u(base, (unsigned)lh * wrow_b + kr_chunk[j & 1], dst);
       } else {
-        const long m_first = (long)kt * BK;
+        const long m_first = (long)(k0 + kt) * BK;
         const int last = (int)(a.M - 1 - m_first);   // rows past it re-read it, and are cleared in LDS
         const int r = 16 * wave + 2 * j + lh;
         const char* base = (const char*)a.x + (m_first * a.ldx + e0) * 2;
@@ -190,7 +210,7 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
              st + (unsigned)(TILE_B + (64 * wave + 8 * j) * RK_ROWB));
     } else {                                         // B side: G, 64 tokens x TR columns
       const int jb = part - 8;
-      const long m_first = (long)kt * BK;
+      const long m_first = (long)(k0 + kt) * BK;
       const int r = 16 * wave + RPI * jb + b_rin;
       const long m = m_first + r < a.M ? m_first + r : a.M - 1;
       int b, s;
@@ -256,9 +276,9 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
 
   // dw: the rows of the last tile pair that lie past the last token are cleared, in both tiles,
   // once the pair has landed (every thread calls this behind the barrier that says so)
-  const int tail_rows = (int)(a.M - (long)(nk - 1) * BK);      // rows of the last pair that exist
+  const int tail_rows = (int)(a.M - (long)(nk_all - 1) * BK);  // rows of the last pair that exist
   auto settle = [&](int kt) __attribute__((always_inline)) {
-    if (MODE == 1 && kt == nk - 1 && tail_rows < BK) {
+    if (MODE == 1 && k0 + kt == nk_all - 1 && tail_rows < BK) {
       char* const st = smem + (kt % NSLOT) * SLOT_B;
       const u32x4 z = {0u, 0u, 0u, 0u};
       for (int c = tid; c < (BK - tail_rows) * (KR_ROWB / 16); c += 256)
@@ -311,7 +331,7 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
     if (STEADY || more) {
       __builtin_amdgcn_s_waitcnt(0x0070);              // vmcnt(0) and lgkmcnt(0)
       wg_barrier();
-      settle(P + 1);
+      if constexpr (!STEADY) settle(P + 1);          // (a steady pair is never followed by the last one)
     }
     mma16(bb, ab, [&](int u) __attribute__((always_inline)) {
       if (STEADY || more) fetch(sn, 0, u, ba, aa);
@@ -353,20 +373,58 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
       if (m < a.M) *(u32x4*)(out + m * a.ldx + 8 * ch) = y;
     }
   } else {
-    // this workgroup alone owns its tile of dw: add in place, 16 bytes per lane and register group
-    float* const out = a.dw + (r0 + wm * (32 * RB) + l31) * (long)a.E + e0 + wn * 128 + 4 * g;
+    if (a.dw_parts == 1) {
+      // this workgroup alone owns its tile of dw: add in place, 16 bytes per lane and register group
+      float* const out = a.dw + (r0 + wm * (32 * RB) + l31) * (long)a.E + e0 + wn * 128 + 4 * g;
 #pragma unroll
-    for (int i = 0; i < RB; ++i)
+      for (int i = 0; i < RB; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          f32x4* const p = (f32x4*)(out + (long)(32 * i) * a.E + 32 * j + 8 * q);
-          f32x4 v = *p;
+          for (int q = 0; q < 4; ++q) {
+            f32x4* const p = (f32x4*)(out + (long)(32 * i) * a.E + 32 * j + 8 * q);
+            f32x4 v = *p;
 #pragma unroll
-          for (int t = 0; t < 4; ++t) v[t] += acc[j][i][4 * q + t];
-          *p = v;
+            for (int t = 0; t < 4; ++t) v[t] += acc[j][i][4 * q + t];
+            *p = v;
+          }
+    } else {
+      // the parts of a tile take turns, in the order of their numbers
+      int* const turn = dw_turn + hw.head * n_ct + hw.item;
+      if (tid == 0) {
+        int tries = 0;
+        while (__hip_atomic_load((gint*)turn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != tpart) {
+          if (++tries > SPIN_LIMIT) break;
+          __builtin_amdgcn_s_sleep(8);
         }
+      }
+      __syncthreads();
+      // agent-scope accesses through a buffer descriptor of the tile's rows (uniform offsets per
+      // register group, the lane's part in the vector offset)
+      constexpr int AGENT = 16;                      // cache policy sc1
+      const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+          (char*)(a.dw + r0 * (long)a.E + e0), 0, (int)(((long)TR * a.E - e0) * 4), 0x00020000);
+      const int voff = ((wm * (32 * RB) + l31) * a.E + wn * 128 + 4 * g) * 4;
+      const int row32 = __builtin_amdgcn_readfirstlane(32 * a.E * 4);
+#pragma unroll
+      for (int i = 0; i < RB; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int soff = i * row32 + (32 * j + 8 * q) * 4;
+            const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, AGENT);
+            const u32x4 y = {__float_as_uint(__uint_as_float(x[0]) + acc[j][i][4 * q]),
+                             __float_as_uint(__uint_as_float(x[1]) + acc[j][i][4 * q + 1]),
+                             __float_as_uint(__uint_as_float(x[2]) + acc[j][i][4 * q + 2]),
+                             __float_as_uint(__uint_as_float(x[3]) + acc[j][i][4 * q + 3])};
+            __builtin_amdgcn_raw_buffer_store_b128(y, rs, voff, soff, AGENT);
+          }
+      wait_vmcnt<0>();                               // this wave's stores have been acknowledged ...
+      __syncthreads();                               // ... and so have every wave's: the next part may come
+      if (tid == 0)
+        __hip_atomic_store((gint*)turn, tpart + 1 == a.dw_parts ? 0 : tpart + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
   }
 }
 
@@ -441,16 +499,29 @@ hipError_t launch_project_bwd(const ProjBwdArgs& a, int is_f32, hipStream_t s) {
       }
     }
     if (a.dw) {
-      // tiles of 128 rows when tiles of 256 would leave a quarter of the compute units idle
+      // Fewer 256 x 256 tiles than three quarters of the compute units: the token range is cut
+      // into parts (at least 8 tile pairs each) until the grid covers the chip; where that cannot
+      // be (very few tokens, more tiles than turn words), tiles of 128 rows instead.
       const long tiles = (long)(a.N / T) * (a.E / T);
-      if (tiles * 4 > (long)a.n_cu * 3) {
+      const long pairs = (a.M + BK - 1) / BK;
+      ProjBwdArgs w = a;
+      w.dw_parts = 1;
+      if (tiles * 4 <= (long)a.n_cu * 3 && tiles <= MAX_TURNS) {
+        long parts = a.n_cu / tiles;
+        if (parts > 32) parts = 32;
+        if (parts > pairs / 8) parts = pairs / 8;
+        if (parts >= 2) w.dw_parts = (int)parts;
+      }
+      if (tiles * 4 > (long)a.n_cu * 3 || w.dw_parts > 1) {
         const hipError_t e = ensure_dynamic_lds((const void*)project_bwd_bf16_kernel<1, 4>, SMEM_B, &once_w);
         if (e != hipSuccess) return e;
-        project_bwd_bf16_kernel<1, 4><<<(unsigned)xcd_grid(a.N / T, a.E / T), 256, SMEM_B, s>>>(a);
+        w.dw_tiles_grid = (unsigned)xcd_grid(a.N / T, a.E / T);
+        project_bwd_bf16_kernel<1, 4><<<w.dw_tiles_grid * (unsigned)w.dw_parts, 256, SMEM_B, s>>>(w);
       } else {
         const hipError_t e = ensure_dynamic_lds((const void*)project_bwd_bf16_kernel<1, 2>, SMEM_B, &once_w2);
         if (e != hipSuccess) return e;
-        project_bwd_bf16_kernel<1, 2><<<(unsigned)xcd_grid(a.N / 128, a.E / T), 256, SMEM_B, s>>>(a);
+        w.dw_tiles_grid = (unsigned)xcd_grid(a.N / 128, a.E / T);
+        project_bwd_bf16_kernel<1, 2><<<w.dw_tiles_grid, 256, SMEM_B, s>>>(w);
       }
     }
     const hipError_t e = hipGetLastError();

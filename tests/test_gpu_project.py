@@ -175,6 +175,10 @@ BWD_CASES = [
     ("llama_like_kv", 1, 1000, 1024, 8, 128, 2, 0),
     ("strided_tokens", 1, 515, 256, 2, 128, 1, 64),
     ("q_like_many_column_tiles", 1, 257, 512, 16, 64, 1, 0),
+    # one tile of dw and 63 tile pairs of tokens (the last with 32 rows): seven parts of the token
+    # range take turns on the tile
+    ("dw_parts_take_turns", 1, 4000, 256, 2, 128, 1, 0),
+    ("dw_parts_two_outputs_batches", 2, 1300, 256, 2, 128, 2, 0),
     # 96-wide heads: a tile pair's 64 columns straddle two heads, eight heads fill three column tiles
     ("d96_heads_straddle_tile_pairs", 2, 150, 256, 8, 96, 2, 0),
     # shapes the matrix-core kernels do not take: the plain kernels
@@ -207,9 +211,10 @@ def test_project_bwd_accumulates_into_dw_and_takes_either_output_alone():
     assert np.array_equal(dw2, dw) and np.isnan(dx2).all()                                     # dx untouched
 
 
-def test_project_bwd_repeats_bit_for_bit():
-    a = run_bwd(2, 700, 512, 4, 128, 2, "bf16", seed=9)
-    b = run_bwd(2, 700, 512, 4, 128, 2, "bf16", seed=9)
+@pytest.mark.parametrize("S", [700, 5000])      # (5000 tokens: the parts of dw's token range take turns)
+def test_project_bwd_repeats_bit_for_bit(S):
+    a = run_bwd(2, S, 512, 4, 128, 2, "bf16", seed=9)
+    b = run_bwd(2, S, 512, 4, 128, 2, "bf16", seed=9)
     assert np.array_equal(a[3], b[3]) and np.array_equal(a[4], b[4])
 
 
