@@ -660,6 +660,11 @@ hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t s) {
     const long grid = (long)d.B * d.Hq * a.n_split * ((d.Sq + QM - 1) / QM);
     return d.D == 64 ? launch<64, 2>(a, grid, s) : d.D == 96 ? launch<96, 2>(a, grid, s) : launch<128, 2>(a, grid, s);
   }
+#ifdef LVX_FWD_TWO_WAVES
+  // Measurement builds only (python -m paper_2502_02406_amd.build --define LVX_FWD_TWO_WAVES=1): dense
+  // problems too run the general kernel, whose eight waves of 32 rows put two waves on every SIMD.
+  return launch_fwd_general_bf16(a, s);
+#endif
   if (a.mask.allow != nullptr || d.Skv % TN != 0) return launch_fwd_general_bf16(a, s);
   const int n_qt = (int)(((long)(d.Hq / d.Hkv) * d.Sq + QM - 1) / QM);
   const long grid = xcd_grid(d.B * d.Hkv, a.n_split * n_qt);
