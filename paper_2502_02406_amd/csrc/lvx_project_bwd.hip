@@ -53,7 +53,7 @@ constexpr int TILE_B = BK * KR_ROWB;   // either kind: 32 KB
 static_assert(TILE_B == T * RK_ROWB, "both tile kinds take the same room");
 constexpr int SLOT_B = 2 * TILE_B;     // A-side tile ([k][256 columns e]), then B-side tile (up to as large)
 constexpr int RING_B = NSLOT * SLOT_B;
-constexpr int MAX_TURNS = 4096;        // tiles of dw that can take turns
+constexpr int MAX_TURNS = 512;         // tiles of dw that can take turns (8 turn words each)
 constexpr int SPIN_LIMIT = 1 << 22;    // tries (with a short sleep each) before a part stops waiting for its turn
 constexpr int TB_PITCH = 128 * 2 + 16; // dx epilogue: a wave's 128 tokens x 128 columns of bf16, padded rows
 constexpr int TB_WAVE = 128 * TB_PITCH;
@@ -62,7 +62,7 @@ constexpr int SMEM_B = RING_B > 4 * TB_WAVE ? RING_B : 4 * TB_WAVE;
 __device__ __forceinline__ int perm_of(int r) { return (r & 7) ^ ((r >> 3) & 1); }
 
 // whose turn it is to add to tile t of dw (0 between launches)
-__device__ int dw_turn[MAX_TURNS];
+__device__ int dw_turn[MAX_TURNS * 8];
 typedef int __attribute__((address_space(1))) gint;
 
 // floor(m / S) and the remainder for 0 <= m < 2^24 (exact: the float quotient is off by at most one)
@@ -388,42 +388,62 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
             for (int t = 0; t < 4; ++t) v[t] += acc[j][i][4 * q + t];
             *p = v;
           }
-    } else {
-      // the parts of a tile take turns, in the order of their numbers
-      int* const turn = dw_turn + hw.head * n_ct + hw.item;
-      if (tid == 0) {
+    } else if constexpr (RB == 4) {
+      // The parts of a tile take turns, in the order of their numbers; every wave owns a quarter
+      // of the tile and passes it on in two halves of 64 rows, each with a turn word of its own,
+      // so a part starts on a half as soon as the part before it has left that half.  A half is
+      // turned through LDS (64 rows x 128 floats per wave, 16-byte chunks permuted by the row)
+      // so that every load and store covers two whole 512-byte row segments, and the old values
+      // come in sixteen rows at a time: a turn costs a few trips to memory, not one per register.
+      int* const turn = dw_turn + ((hw.head * n_ct + hw.item) * 4 + wave) * 2;
+      float* const tb = (float*)(smem + wave * 32768);
+      constexpr int AGENT = 16;                      // cache policy sc1: the L2s of different XCDs do not see each other's lines
+      const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+          (char*)(a.dw + r0 * (long)a.E + e0), 0, (int)(((long)TR * a.E - e0) * 4), 0x00020000);
+      const int rrow = lane >> 5, rch = lane & 31;
+      const int two_rows = __builtin_amdgcn_readfirstlane(2 * a.E * 4);
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+#pragma unroll
+        for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const f32x4 v = {acc[j][2 * h + ii][4 * q], acc[j][2 * h + ii][4 * q + 1],
+                               acc[j][2 * h + ii][4 * q + 2], acc[j][2 * h + ii][4 * q + 3]};
+              *(f32x4*)(tb + (32 * ii + l31) * 128 + (((8 * j + 2 * q + g) ^ l31) * 4)) = v;
+            }
         int tries = 0;
-        while (__hip_atomic_load((gint*)turn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != tpart) {
+        while (__builtin_amdgcn_readfirstlane(__hip_atomic_load((gint*)(turn + h), __ATOMIC_RELAXED,
+                                                                __HIP_MEMORY_SCOPE_AGENT)) != tpart) {
           if (++tries > SPIN_LIMIT) break;
           __builtin_amdgcn_s_sleep(8);
         }
-      }
-      __syncthreads();
-      // agent-scope accesses through a buffer descriptor of the tile's rows (uniform offsets per
-      // register group, the lane's part in the vector offset)
-      constexpr int AGENT = 16;                      // cache policy sc1
-      const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
-          (char*)(a.dw + r0 * (long)a.E + e0), 0, (int)(((long)TR * a.E - e0) * 4), 0x00020000);
-      const int voff = ((wm * (32 * RB) + l31) * a.E + wn * 128 + 4 * g) * 4;
-      const int row32 = __builtin_amdgcn_readfirstlane(32 * a.E * 4);
+        asm volatile("" ::: "memory");               // the old values are read after the turn has come
+        const int voff = ((wm * 128 + 64 * h + rrow) * a.E + wn * 128 + 4 * rch) * 4;
 #pragma unroll
-      for (int i = 0; i < RB; ++i)
+        for (int b0 = 0; b0 < 32; b0 += 16) {
+          u32x4 old[16];
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+          for (int t = 0; t < 16; ++t)
+            old[t] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, (b0 + t) * two_rows, AGENT);
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int soff = i * row32 + (32 * j + 8 * q) * 4;
-            const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, AGENT);
-            const u32x4 y = {__float_as_uint(__uint_as_float(x[0]) + acc[j][i][4 * q]),
-                             __float_as_uint(__uint_as_float(x[1]) + acc[j][i][4 * q + 1]),
-                             __float_as_uint(__uint_as_float(x[2]) + acc[j][i][4 * q + 2]),
-                             __float_as_uint(__uint_as_float(x[3]) + acc[j][i][4 * q + 3])};
-            __builtin_amdgcn_raw_buffer_store_b128(y, rs, voff, soff, AGENT);
+          for (int t = 0; t < 16; ++t) {
+            const int row = 2 * (b0 + t) + rrow;
+            const f32x4 v = *(const f32x4*)(tb + row * 128 + ((rch ^ (row & 31)) * 4));
+            const u32x4 y = {__float_as_uint(__uint_as_float(old[t][0]) + v[0]),
+                             __float_as_uint(__uint_as_float(old[t][1]) + v[1]),
+                             __float_as_uint(__uint_as_float(old[t][2]) + v[2]),
+                             __float_as_uint(__uint_as_float(old[t][3]) + v[3])};
+            __builtin_amdgcn_raw_buffer_store_b128(y, rs, voff, (b0 + t) * two_rows, AGENT);
           }
-      wait_vmcnt<0>();                               // this wave's stores have been acknowledged ...
-      __syncthreads();                               // ... and so have every wave's: the next part may come
-      if (tid == 0)
-        __hip_atomic_store((gint*)turn, tpart + 1 == a.dw_parts ? 0 : tpart + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        wait_vmcnt<0>();                             // this wave's stores have been acknowledged: the next part may come
+        asm volatile("" ::: "memory");
+        __hip_atomic_store((gint*)(turn + h), tpart + 1 == a.dw_parts ? 0 : tpart + 1, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+      }
     }
   }
 }
