@@ -187,7 +187,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
                        SM::WIN_BYTES, tid, 256);
       have_bits = true;
       share(build_bits(bits, n_tiles, tid, 256, [&](int t) {
-        return mask_rect(mk, b, i_wg0, i_wg1, t * TN, min(d.Skv, t * TN + TN) - 1) != 0;
+        return mask_rect_tall(mk, b, i_wg0, i_wg1, t * TN, min(d.Skv, t * TN + TN) - 1) != 0;
       }));
     } else if (t_begin < t_end) {
       mk = mask_to_lds(a.mask, b, i_wg0 / mk.q_chunk, i_wg1 / mk.q_chunk, (t_begin * TN) / mk.kv_block,
@@ -410,7 +410,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
     int cls = 1;
     if (mk.allow && i_wave0 < d.Sq)
       cls = have_cls ? class_of(cls_any, cls_all, t)      // (of the whole tile: fine for either half)
-                     : mask_rect(mk, b, i_wave0, min(d.Sq, i_wave0 + 32 * QB) - 1, min(j0, d.Skv - 1),
+                     : mask_rect_tall(mk, b, i_wave0, min(d.Sq, i_wave0 + 32 * QB) - 1, min(j0, d.Skv - 1),
                                  min(d.Skv, j0 + 32) - 1);
     if (cls == 1 && j0 + 32 <= d.Skv) return;
     asm volatile("" ::: "memory");

@@ -159,7 +159,7 @@ fwd_general_bf16_kernel(FwdArgs a) {
       have_bits = true;
       const int nn = build_bits(bits, n_tiles, tid, 64 * NW, [&](int t) {
         // (pass 2 leaves the tiles that every row of the workgroup sees to the other launch)
-        const int c = mask_rect(mk, b, i_wg0, i_wg1, t * BN, min(d.Skv, t * BN + BN) - 1);
+        const int c = mask_rect_tall(mk, b, i_wg0, i_wg1, t * BN, min(d.Skv, t * BN + BN) - 1);
         return c != 0 && !(a.pass == 2 && c == 1);
       });
       const int k0 = (int)((long)split * nn / a.n_split), k1 = (int)((long)(split + 1) * nn / a.n_split);
@@ -184,7 +184,7 @@ fwd_general_bf16_kernel(FwdArgs a) {
   auto wave_class = [&](int t) -> int {               // 0 skip, 1 dense, 2 per-element mask
     if (t >= t_end || i_wave0 >= d.Sq) return 0;
     if (!mk.allow) return 1;
-    return mask_rect(mk, b, i_wave0, min(d.Sq - 1, i_wave0 + 31), t * BN, min(d.Skv, t * BN + BN) - 1);
+    return mask_rect_tall(mk, b, i_wave0, min(d.Sq - 1, i_wave0 + 31), t * BN, min(d.Skv, t * BN + BN) - 1);
   };
 
   f32x16 oacc[DB];

@@ -188,6 +188,31 @@ __device__ __forceinline__ int mask_rect(const MaskDev& m, int b, int i0, int i1
   return all ? 1 : (any ? 2 : 0);
 }
 
+// mask_rect for rectangles that may span many chunks (planning: a workgroup's rows against one key
+// tile, a different tile in every lane; the loops: a wave's rows when chunks are a few rows): the
+// same probes and the same answer, the bitmap's rows taken eight at a time so that their round
+// trips overlap when the bitmap is in global memory (the rows past the last chunk repeat the last
+// one).
+__device__ inline int mask_rect_tall(const MaskDev& m, int b, int i0, int i1, int j0, int j1) {
+  if (!m.allow) return 1;
+  const uint8_t* base = m.allow + b * m.stride_b;
+  const int ca = i0 / m.q_chunk, cb = i1 / m.q_chunk;
+  if (cb - ca < 4) return mask_rect(m, b, i0, i1, j0, j1);
+  unsigned any = 0, all = 1;
+  for (int f = j0 / m.kv_block; f <= j1 / m.kv_block; ++f)
+    for (int c = ca; c <= cb; c += 8) {
+      uint8_t v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = base[(long)min(c + u, cb) * m.stride_q + f];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        any |= v[u];
+        all &= v[u] != 0 ? 1u : 0u;
+      }
+    }
+  return all ? 1 : (any ? 2 : 0);
+}
+
 __device__ __forceinline__ bool mask_elem(const MaskDev& m, int b, int i, int j) {
   return m.allow[b * m.stride_b + (long)(i / m.q_chunk) * m.stride_q + (j / m.kv_block)] != 0;
 }

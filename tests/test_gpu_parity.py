@@ -252,6 +252,21 @@ def test_step_aligned_media_masks(name, kw, per_batch, p_on):
     run_case(w, do_bwd=True, allow=(rng.random(shape) < p_on))
 
 
+@pytest.mark.parametrize("kind", ["recent", "random"])
+def test_masks_whose_window_stays_in_global_memory(kind):
+    # chunks of 2 rows against 320 frames of 16 keys: the 128 chunks of a workgroup's rows times
+    # all frames are more bytes than the window areas in LDS hold, so the kernels plan their tiles
+    # from the bitmap where it lies (the one-frame mask of the short-frame models at a small size,
+    # and a random bitmap with rows and frames that pair with nothing)
+    w = small(f"bf16_{kind}_tiny_chunks", D=64, Hq=4, Hkv=2, Sq=512, Skv=5120, q_chunk=2, kv_block=16)
+    nq, nk = w.Sq // w.q_chunk, w.Skv // w.kv_block
+    if kind == "recent":
+        allow = np.arange(nk)[None, :] == np.minimum(np.arange(nq)[:, None] + 40, nk - 1)
+    else:
+        allow = np.random.Generator(np.random.Philox(77)).random((nq, nk)) < 0.02
+    run_case(w, do_bwd=True, allow=allow)
+
+
 def _random_case(it, rng, wide=False):
     """A small random problem: head dims, group sizes, query lengths around the tile sizes, key
     blocks that are and are not tile multiples, block loops, and media masks of three kinds
