@@ -125,7 +125,7 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
     if (spH <= (SM::BITS_BYTES - 16) * 8) {
       have_bits = true;
       per_head = build_bits(bits, spH, tid, 256, [&](int t) {
-        return mask_rect(mk, b, t * KM, min(d.Sq, t * KM + KM) - 1, j_wg0, j_wg1) != 0;
+        return mask_rect_tall(mk, b, t * KM, min(d.Sq, t * KM + KM) - 1, j_wg0, j_wg1) != 0;
       });
     }
   }
@@ -160,7 +160,7 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   constexpr bool RUNNING = !GENERAL && !STEPS;
   auto step_needed = [&](const Cursor& c) __attribute__((always_inline)) -> bool {
     if (!GENERAL || !mk.allow) return true;
-    return mask_rect(mk, b, c.i0, min(d.Sq, c.i0 + KM) - 1, j_wg0, j_wg1) != 0;
+    return mask_rect_tall(mk, b, c.i0, min(d.Sq, c.i0 + KM) - 1, j_wg0, j_wg1) != 0;
   };
   auto advance = [&](Cursor& c) __attribute__((always_inline)) {      // to the next needed step (or the end)
     if (STEPS) {
@@ -457,7 +457,7 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   auto mask_scores = [&](int st, f32x16 (&s)[KVB]) __attribute__((always_inline)) {
     if (!GENERAL || !mk.allow) return;
     const int i0 = (st % spH) * KM;
-    const int cls = mask_rect(mk, b, i0, min(d.Sq, i0 + KM) - 1, min(j_wave0, d.Skv - 1),
+    const int cls = mask_rect_tall(mk, b, i0, min(d.Sq, i0 + KM) - 1, min(j_wave0, d.Skv - 1),
                               min(d.Skv - 1, j_wave0 + 32 * KVB - 1));
     if (cls == 1) return;
     asm volatile("" ::: "memory");
