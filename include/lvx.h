@@ -218,7 +218,12 @@ lvx_status lvx_xattn_project(const lvx_projection* p, lvx_dtype dtype, const voi
  * LVX_BF16 runs on the matrix cores when E % 256 == 0, (H * D) % 256 == 0, D % 8 == 0,
  * B * S < 2^24 and B * S * H * D < 2^30; other shapes, and LVX_F32, take a plain kernel (one
  * float32 sum per element in the order of the definition: correctness-grade, slow).
- * LVX_BF16: pointers and x's row stride must be 16-byte aligned.  No workspace. */
+ * LVX_BF16: pointers and x's row stride must be 16-byte aligned.  No workspace.
+ * When dw has fewer tiles of 256 x 256 than the GPU has compute units, the tokens are divided
+ * among several workgroups per tile, which add their sums to dw one after the other in a fixed
+ * order (so results still repeat bit for bit); whose turn it is stands in a small table inside the
+ * library, one per GPU, that every call leaves as it found it.  Two such calls running at the same
+ * time on one GPU (different streams) would share that table: do not overlap them. */
 lvx_status lvx_xattn_project_bwd(const lvx_projection* p, lvx_dtype dtype, const void* x, const void* w,
                                  int n_out, const void* const* d_out, void* dx, float* dw,
                                  void* hip_stream);

@@ -53,6 +53,14 @@ constexpr int TILE_B = BK * KR_ROWB;   // either kind: 32 KB
 static_assert(TILE_B == T * RK_ROWB, "both tile kinds take the same room");
 constexpr int SLOT_B = 2 * TILE_B;     // A-side tile ([k][256 columns e]), then B-side tile (up to as large)
 constexpr int RING_B = NSLOT * SLOT_B;
+// Measurement builds only (python -m paper_2502_02406_amd.build --define LVX_PROJ_PROBE=1; results
+// are wrong): the dw kernel copies the first four tile pairs of its tokens over and over, so every
+// copy after the first finds its lines in the nearest cache -- what is left is the kernel's own pace.
+#ifdef LVX_PROJ_PROBE
+#define PROBE_PAIR(p) ((p) & 3)
+#else
+#define PROBE_PAIR(p) (p)
+#endif
 constexpr int MAX_TURNS = 512;         // tiles of dw that can take turns (8 turn words each)
 constexpr int SPIN_LIMIT = 1 << 22;    // tries (with a short sleep each) before a part stops waiting for its turn
 constexpr int TB_PITCH = 128 * 2 + 16; // dx epilogue: a wave's 128 tokens x 128 columns of bf16, padded rows
@@ -183,7 +191,7 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
         const char* base = (const char*)a.w + ((long)(kt * BK + 16 * wave + 2 * j) * a.E + e0) * 2;
         dma16u(base, (unsigned)lh * wrow_b + kr_chunk[j & 1], dst);
       } else {
-        const long m_first = (long)(k0 + kt) * BK;
+        const long m_first = (long)PROBE_PAIR(k0 + kt) * BK;
         const int last = (int)(a.M - 1 - m_first);   // rows past it re-read it, and are cleared in LDS
         const int r = 16 * wave + 2 * j + lh;
         const char* base = (const char*)a.x + (m_first * a.ldx + e0) * 2;
@@ -210,7 +218,7 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
              st + (unsigned)(TILE_B + (64 * wave + 8 * j) * RK_ROWB));
     } else {                                         // B side: G, 64 tokens x TR columns
       const int jb = part - 8;
-      const long m_first = (long)(k0 + kt) * BK;
+      const long m_first = (long)PROBE_PAIR(k0 + kt) * BK;
       const int r = 16 * wave + RPI * jb + b_rin;
       const long m = m_first + r < a.M ? m_first + r : a.M - 1;
       int b, s;
