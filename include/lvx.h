@@ -223,7 +223,8 @@ lvx_status lvx_xattn_project(const lvx_projection* p, lvx_dtype dtype, const voi
  * among several workgroups per tile, which add their sums to dw one after the other in a fixed
  * order (so results still repeat bit for bit); whose turn it is stands in a small table inside the
  * library, one per GPU, that every call leaves as it found it.  Two such calls running at the same
- * time on one GPU (different streams) would share that table: do not overlap them. */
+ * time on one GPU (different streams) would share that table: do not overlap them.  Waits are
+ * bounded; a workgroup whose turn never came writes NaN over its part of dw instead of a sum. */
 lvx_status lvx_xattn_project_bwd(const lvx_projection* p, lvx_dtype dtype, const void* x, const void* w,
                                  int n_out, const void* const* d_out, void* dx, float* dw,
                                  void* hip_stream);

@@ -429,6 +429,9 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
           __builtin_amdgcn_s_sleep(8);
         }
         asm volatile("" ::: "memory");               // the old values are read after the turn has come
+        // (a wait that gave up -- the part before never came, which takes a fault elsewhere -- must
+        // not pass for a result: this half of the tile becomes NaN)
+        const float poison = tries > SPIN_LIMIT ? __builtin_nanf("") : 0.f;
         const int voff = ((wm * 128 + 64 * h + rrow) * a.E + wn * 128 + 4 * rch) * 4;
 #pragma unroll
         for (int b0 = 0; b0 < 32; b0 += 16) {
@@ -440,10 +443,10 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
           for (int t = 0; t < 16; ++t) {
             const int row = 2 * (b0 + t) + rrow;
             const f32x4 v = *(const f32x4*)(tb + row * 128 + ((rch ^ (row & 31)) * 4));
-            const u32x4 y = {__float_as_uint(__uint_as_float(old[t][0]) + v[0]),
-                             __float_as_uint(__uint_as_float(old[t][1]) + v[1]),
-                             __float_as_uint(__uint_as_float(old[t][2]) + v[2]),
-                             __float_as_uint(__uint_as_float(old[t][3]) + v[3])};
+            const u32x4 y = {__float_as_uint(__uint_as_float(old[t][0]) + (v[0] + poison)),
+                             __float_as_uint(__uint_as_float(old[t][1]) + (v[1] + poison)),
+                             __float_as_uint(__uint_as_float(old[t][2]) + (v[2] + poison)),
+                             __float_as_uint(__uint_as_float(old[t][3]) + (v[3] + poison))};
             __builtin_amdgcn_raw_buffer_store_b128(y, rs, voff, (b0 + t) * two_rows, AGENT);
           }
         }
