@@ -28,80 +28,113 @@ __host__ __device__ inline int merge_lanes_per_row(int n) {   // smallest power 
   return p;
 }
 
+constexpr int MERGE_UNITS = 1;        // 16-byte pieces of rows that one thread merges (2: measured, no faster)
+
 template <bool PART_F32, bool OUT_F32>
 __global__ void __launch_bounds__(256) merge_kernel(MergeArgs a) {
   constexpr int VEC_IN = PART_F32 ? 4 : 8;
   constexpr int VEC_OUT = OUT_F32 ? 4 : 8;
-  constexpr int VEC = VEC_IN < VEC_OUT ? VEC_IN : VEC_OUT;   // elements per thread
-  const int vpr = merge_lanes_per_row(a.D / VEC);             // threads per row
-  const long t = (long)blockIdx.x * 256 + threadIdx.x;
-  const long row = t / vpr;
-  if (row >= a.rows) return;
-  const int c = (int)(t % vpr) * VEC;
-  if (c >= a.D) return;
+  constexpr int VEC = VEC_IN < VEC_OUT ? VEC_IN : VEC_OUT;   // elements per piece
+  constexpr int U = MERGE_UNITS, GRP = 4;
+  const int vpr = merge_lanes_per_row(a.D / VEC);             // lanes per row
+  // Piece u of a thread lies a whole grid further on (a multiple of 64 lanes, so rows still sit in
+  // one wavefront).  The parts' elements are fetched four parts at a time, the first four of
+  // every piece before anything else: they are on their way while the rows' statistics are read
+  // and turned into weights, so a thread waits for memory once, not twice.  (A part without keys
+  // still has a buffer; what it holds is fetched and dropped.)
+  const long t0 = (long)blockIdx.x * 256 + threadIdx.x, stride = (long)gridDim.x * 256;
+  long row[U];
+  int c[U];
+  bool on[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const long t = t0 + u * stride;
+    row[u] = t / vpr;
+    c[u] = (int)(t % vpr) * VEC;
+    on[u] = row[u] < a.rows && c[u] < a.D;
+  }
+  auto load_part = [&](int u, int k) __attribute__((always_inline)) -> u32x4 {
+    if (PART_F32) return *(const u32x4*)((const float*)a.o_parts[k] + row[u] * a.D + c[u]);
+    const uint16_t* src = (const uint16_t*)a.o_parts[k] + row[u] * a.D + c[u];
+    if (VEC == 8) return *(const u32x4*)src;
+    const unsigned x0 = ((const unsigned*)src)[0], x1 = ((const unsigned*)src)[1];
+    return u32x4{x0, x1, 0u, 0u};
+  };
+  const int n = a.n_parts;
+  u32x4 buf[U][GRP];
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+#pragma unroll
+    for (int g = 0; g < GRP; ++g)
+      if (on[u] && g < n) buf[u][g] = load_part(u, g);
 
-  float M = -INFINITY;
-  for (int k = 0; k < a.n_parts; ++k) M = fmaxf(M, a.lse_parts[k][row]);
-  float acc[VEC];
+  float acc[U][VEC], Lout[U];
 #pragma unroll
-  for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
-  float Lout = -INFINITY;
-  if (M != -INFINITY) {
-    float z = 0.f;
-    for (int k = 0; k < a.n_parts; ++k) z += expf(a.lse_parts[k][row] - M);
-    Lout = M + logf(z);
-    for (int k = 0; k < a.n_parts; ++k) {
-      const float lk = a.lse_parts[k][row];
-      if (lk == -INFINITY) continue;
-      const float w = expf(lk - Lout);
+  for (int u = 0; u < U; ++u) {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[u][e] = 0.f;
+    Lout[u] = -INFINITY;
+    if (!on[u]) continue;
+    auto add_part = [&](const u32x4& x, float w) __attribute__((always_inline)) {
       if (PART_F32) {
-        const float* src = (const float*)a.o_parts[k] + row * a.D + c;
 #pragma unroll
-        for (int e = 0; e < VEC; e += 4) {
-          f32x4 x = *(const f32x4*)(src + e);
-          acc[e] += w * x[0]; acc[e + 1] += w * x[1]; acc[e + 2] += w * x[2]; acc[e + 3] += w * x[3];
-        }
+        for (int e = 0; e < 4; ++e) acc[u][e] += w * __uint_as_float(x[e]);
       } else {
-        const unsigned* src = (const unsigned*)((const uint16_t*)a.o_parts[k] + row * a.D + c);
-        if (VEC == 8) {
-          u32x4 x = *(const u32x4*)src;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) { acc[2 * e] += w * bf16_lo(x[e]); acc[2 * e + 1] += w * bf16_hi(x[e]); }
-        } else {
-          unsigned x0 = src[0], x1 = src[1];
-          acc[0] += w * bf16_lo(x0); acc[1] += w * bf16_hi(x0);
-          acc[2] += w * bf16_lo(x1); acc[3] += w * bf16_hi(x1);
+        for (int e = 0; e < VEC / 2; ++e) {
+          acc[u][2 * e] += w * bf16_lo(x[e]);
+          acc[u][2 * e + 1] += w * bf16_hi(x[e]);
         }
       }
-    }
-  }
-  const long i = row % a.Sq, h = (row / a.Sq) % a.Hq, b = row / ((long)a.Sq * a.Hq);
-  const long off = b * a.o_sb + h * a.o_sh + i * a.o_ss + c;
-  if (OUT_F32) {
-    float* dst = (float*)a.o_out + off;
+    };
+    float M = -INFINITY;
+    for (int k = 0; k < n; ++k) M = fmaxf(M, a.lse_parts[k][row[u]]);
+    if (M == -INFINITY) continue;
+    float z = 0.f;
+    for (int k = 0; k < n; ++k) z += expf(a.lse_parts[k][row[u]] - M);
+    Lout[u] = M + logf(z);
+    for (int k0 = 0; k0 < n; k0 += GRP) {
+      if (k0 > 0) {
 #pragma unroll
-    for (int e = 0; e < VEC; e += 4) {
-      f32x4 y = {acc[e], acc[e + 1], acc[e + 2], acc[e + 3]};
-      *(f32x4*)(dst + e) = y;
-    }
-  } else {
-    unsigned* dst = (unsigned*)((uint16_t*)a.o_out + off);
-    if (VEC == 8) {
-      u32x4 y = {pack_bf16(acc[0], acc[1]), pack_bf16(acc[2], acc[3]), pack_bf16(acc[4], acc[5]),
-                 pack_bf16(acc[6], acc[7])};
-      *(u32x4*)dst = y;
-    } else {
-      dst[0] = pack_bf16(acc[0], acc[1]);
-      dst[1] = pack_bf16(acc[2], acc[3]);
+        for (int g = 0; g < GRP; ++g)
+          if (k0 + g < n) buf[u][g] = load_part(u, k0 + g);
+      }
+#pragma unroll
+      for (int g = 0; g < GRP; ++g)
+        if (k0 + g < n) {
+          const float lk = a.lse_parts[k0 + g][row[u]];
+          if (lk != -INFINITY) add_part(buf[u][g], expf(lk - Lout[u]));
+        }
     }
   }
-  if (c == 0) a.lse_out[row] = Lout;
+  // (every load of the statistics above precedes every store below: lse_out may be lse_parts[0])
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    if (!on[u]) continue;
+    const long i = row[u] % a.Sq, h = (row[u] / a.Sq) % a.Hq, b = row[u] / ((long)a.Sq * a.Hq);
+    const long off = b * a.o_sb + h * a.o_sh + i * a.o_ss + c[u];
+    if (OUT_F32) {
+      const f32x4 y = {acc[u][0], acc[u][1], acc[u][2], acc[u][3]};
+      *(f32x4*)((float*)a.o_out + off) = y;
+    } else {
+      unsigned* dst = (unsigned*)((uint16_t*)a.o_out + off);
+      if (VEC == 8) {
+        const u32x4 y = {pack_bf16(acc[u][0], acc[u][1]), pack_bf16(acc[u][2], acc[u][3]),
+                         pack_bf16(acc[u][4], acc[u][5]), pack_bf16(acc[u][6], acc[u][7])};
+        *(u32x4*)dst = y;
+      } else {
+        dst[0] = pack_bf16(acc[u][0], acc[u][1]);
+        dst[1] = pack_bf16(acc[u][2], acc[u][3]);
+      }
+    }
+    if (c[u] == 0) a.lse_out[row[u]] = Lout[u];
+  }
 }
 
 hipError_t launch_merge(const MergeArgs& a, int part_is_f32, int out_is_f32, hipStream_t s) {
   const int vec = (part_is_f32 || out_is_f32) ? 4 : 8;
   const long threads = a.rows * merge_lanes_per_row(a.D / vec);
-  const unsigned blocks = (unsigned)((threads + 255) / 256);
+  const unsigned blocks = (unsigned)((threads + 256 * MERGE_UNITS - 1) / (256 * MERGE_UNITS));
   if (part_is_f32 && out_is_f32) merge_kernel<true, true><<<blocks, 256, 0, s>>>(a);
   else if (part_is_f32) merge_kernel<true, false><<<blocks, 256, 0, s>>>(a);
   else if (out_is_f32) merge_kernel<false, true><<<blocks, 256, 0, s>>>(a);
