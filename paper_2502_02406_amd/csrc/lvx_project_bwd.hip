@@ -19,9 +19,10 @@
 //               operands come from transposing reads.
 // A [k][256] tile has rows of 512 bytes; chunk c (16 bytes) of row r sits at position
 // c ^ 4 (r % 4): the four rows that a transposing read of 16 lanes touches then lie in four
-// different 64-byte bank groups.  The transposing read delivers the 16 contraction steps of a
-// matrix instruction in the order 0-3, 8-11 (lanes 0-31) / 4-7, 12-15 (lanes 32-63); the G
-// operand of dx, read with plain 8-byte reads, takes the same order.
+// different 64-byte bank groups.  A transposing read hands a lane four contraction steps, the
+// four rows its group of 16 lanes points at; a lane's two reads per operand take rows 4 g .. 4 g + 3
+// and 8 + 4 g .. in dw (g = lane / 32), and rows 8 g .. 8 g + 7 in dx, whose G operand then is one
+// plain 16-byte read of the same eight steps.
 // Rows past the last token are never stored (dx) and are cleared in LDS before they are
 // multiplied (dw, where they would otherwise enter every sum).
 // dw of a narrow projection (K and V of a model with few K/V heads) has fewer 256 x 256 tiles
@@ -229,38 +230,39 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
   };
 
   // ---- operands.  From a [k][256] tile: block jj of the wave's 128 columns, k-step q (16 rows);
-  // lane l supplies the address of 8 bytes of row 4 g + (l % 16) / 4 (+ 16 q, + 8 for the second
+  // lane l supplies the address of 8 bytes of row KG g + (l % 16) / 4 (+ 16 q, + KH for the second
   // read), byte column 64 jj' + 32 ((l / 16) % 2) + 8 (l % 4), where jj' is the block's position
-  // after the permutation: (4 wcol + jj) ^ (row % 4).
+  // after the permutation: (4 wcol + jj) ^ (row % 4).  Which rows a lane asks for decides which
+  // contraction steps it holds, and both operands must agree: dw (both from such tiles) takes steps
+  // 4 g .. 4 g + 3 and 8 + 4 g .. 8 + 4 g + 3; dx takes 8 g .. 8 g + 7, the order in which its other
+  // operand lies in ONE 16-byte chunk of a [256][64] tile (two 8-byte reads of half chunks, which
+  // the other order needs, use half the banks and cost 9 % of the kernel's cycles in conflicts).
   const int j16 = lane & 15, jr = j16 >> 2;
   const int tr_col = 32 * ((lane >> 4) & 1) + 8 * (j16 & 3);
   int ka[4], kb[RB];
+  constexpr int KG = MODE == 0 ? 8 : 4, KH = MODE == 0 ? 4 : 8;
 #pragma unroll
-  for (int jj = 0; jj < 4; ++jj) ka[jj] = (4 * g + jr) * KR_ROWB + tr_col + 64 * ((4 * wn + jj) ^ jr);
+  for (int jj = 0; jj < 4; ++jj) ka[jj] = (KG * g + jr) * KR_ROWB + tr_col + 64 * ((4 * wn + jj) ^ jr);
 #pragma unroll
   for (int i = 0; i < RB; ++i) kb[i] = TILE_B + (4 * g + jr) * BROWB + tr_col + 64 * ((RB * wm + i) ^ jr);
   auto tr_op = [&](const char* p, auto pitch) __attribute__((always_inline)) -> bf16x8 {
-    const s16x4 lo = lds_read_tr(p), hi = lds_read_tr(p + 8 * decltype(pitch)::value);
+    const s16x4 lo = lds_read_tr(p), hi = lds_read_tr(p + KH * decltype(pitch)::value);
     typedef __attribute__((ext_vector_type(8))) short s16x8;
     const s16x8 r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     return __builtin_bit_cast(bf16x8, r);
   };
-  // From the [256][64] tile (MODE 0): row 32 i + l % 32 of the wave's tokens, k-step q: bytes
-  // 8 g .. 8 g + 7 of chunks 2 q and 2 q + 1 (steps 4 g .. 4 g + 3 and 8 + 4 g .. 8 + 4 g + 3)
+  // From the [256][64] tile (MODE 0): row 32 i + l % 32 of the wave's tokens, k-step q: chunk
+  // 2 q + g (steps 8 g .. 8 g + 7), which lies at position (2 q + g) ^ perm_of(row)
   int rk[4];
 #pragma unroll
   for (int q = 0; q < 4; ++q)
-    rk[q] = TILE_B + (wm * 128 + l31) * RK_ROWB + 16 * ((2 * q) ^ perm_of(l31)) + 8 * g;
+    rk[q] = TILE_B + (wm * 128 + l31) * RK_ROWB + 16 * ((2 * q + g) ^ perm_of(l31));
   auto a_op = [&](const char* st, int q, int jj) __attribute__((always_inline)) -> bf16x8 {
     return tr_op(st + ka[jj] + 16 * q * KR_ROWB, std::integral_constant<int, KR_ROWB>{});
   };
   auto b_op = [&](const char* st, int q, int i) __attribute__((always_inline)) -> bf16x8 {
     if (MODE == 1) return tr_op(st + kb[i] + 16 * q * BROWB, std::integral_constant<int, BROWB>{});
-    const char* p = st + rk[q] + 32 * i * RK_ROWB;
-    const u32x2 lo = *(const u32x2*)p;
-    const u32x2 hi = *(const u32x2*)(st + (rk[q] ^ 16) + 32 * i * RK_ROWB);
-    const u32x4 r = {lo[0], lo[1], hi[0], hi[1]};
-    return __builtin_bit_cast(bf16x8, r);
+    return __builtin_bit_cast(bf16x8, *(const u32x4*)(st + rk[q] + 32 * i * RK_ROWB));
   };
 
   f32x16 acc[4][RB];                                 // [column block jj][row block i]: lane = row, registers = columns
