@@ -85,6 +85,17 @@ template <int D> constexpr int dkdv_step_list_cap() {
 // visible to all of a workgroup's keys or to none, so the mask only selects WHICH steps a
 // workgroup performs: the dense kernel runs over a list of them and nothing inside a step
 // changes.
+// Measurement builds only (python -m paper_2502_02406_amd.build --define LVX_DKDV_PROBE=1): every
+// workgroup with steps to run adds the clocks of its three phases (set-up until the first tiles and
+// K, V are in place; the loop; the epilogue until its stores have been acknowledged), a count and
+// its number of steps to dkdv_probe, which lvx_debug_dkdv_probe copies out and clears.
+#ifdef LVX_DKDV_PROBE
+__device__ unsigned long long dkdv_probe[8];
+#define DKDV_STAMP(x) const unsigned long long x = __builtin_readcyclecounter()
+#else
+#define DKDV_STAMP(x)
+#endif
+
 template <int D, bool GENERAL, bool STEPS = false>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 bwd_dkdv_bf16_kernel(BwdArgs a) {
@@ -102,6 +113,7 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   const int n_kt = (d.Skv + KN - 1) / KN;
   HeadWork hw;
   if (!xcd_decode(blockIdx.x, d.B * d.Hkv, n_kt, &hw)) return;
+  DKDV_STAMP(stamp0);
   const int b = hw.head / d.Hkv, hk = hw.head % d.Hkv;
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, kl = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -254,25 +266,38 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
     // wave fetches its rows whole instead (16 lanes per 256-byte row), parks them in the part of
     // the V area that its own rows will occupy, and reads its operands back from there; the V
     // rows, fetched meanwhile, are stored once every wave has its K operands.
+    // All of these loads are issued before the first of them is waited for (rows past the last
+    // key re-read it and are zeroed afterwards: a branch around a load would make every load
+    // wait for the one before it).
     constexpr int WR = 32 * KVB;                   // key rows of a wave
+    constexpr int KIT = WR * CPR / 64;
     char* const kst = vres + wave * WR * SM::P;
+    const uint16_t* const k_head = (const uint16_t*)a.k + b * d.kv_sb + hk * d.kv_sh;
+    const uint16_t* const v_head = (const uint16_t*)a.v + b * d.kv_sb + hk * d.kv_sh;
+    u32x4 xk[KIT];
 #pragma unroll
-    for (int it = 0; it < WR * CPR / 64; ++it) {
-      const int c = it * 64 + lane, r = c / CPR, col = (c % CPR) * 8, j = j_wave0 + r;
-      u32x4 x = {0, 0, 0, 0};
-      if (j < d.Skv)
-        x = *(const u32x4*)((const uint16_t*)a.k + b * d.kv_sb + hk * d.kv_sh + (long)j * d.kv_ss + col);
-      *(u32x4*)(kst + r * SM::P + col * 2) = x;
+    for (int it = 0; it < KIT; ++it) {
+      const int c = it * 64 + lane, r = c / CPR, col = (c % CPR) * 8, j = min(j_wave0 + r, d.Skv - 1);
+      xk[it] = *(const u32x4*)(k_head + (long)j * d.kv_ss + col);
     }
     // ---- V rows of the workgroup -> LDS (plain row-major: only read as whole rows)
     constexpr int VIT = KN * CPR / 256;
     u32x4 vy[VIT];
 #pragma unroll
     for (int it = 0; it < VIT; ++it) {
-      const int c = it * 256 + tid, r = c / CPR, col = (c % CPR) * 8, j = j_wg0 + r;
-      vy[it] = u32x4{0, 0, 0, 0};
-      if (j < d.Skv)
-        vy[it] = *(const u32x4*)((const uint16_t*)a.v + b * d.kv_sb + hk * d.kv_sh + (long)j * d.kv_ss + col);
+      const int c = it * 256 + tid, r = c / CPR, col = (c % CPR) * 8, j = min(j_wg0 + r, d.Skv - 1);
+      vy[it] = *(const u32x4*)(v_head + (long)j * d.kv_ss + col);
+    }
+    const u32x4 zero4 = {0, 0, 0, 0};
+#pragma unroll
+    for (int it = 0; it < KIT; ++it) {
+      const int c = it * 64 + lane, r = c / CPR, col = (c % CPR) * 8;
+      *(u32x4*)(kst + r * SM::P + col * 2) = j_wave0 + r < d.Skv ? xk[it] : zero4;
+    }
+#pragma unroll
+    for (int it = 0; it < VIT; ++it) {
+      const int c = it * 256 + tid, r = c / CPR;
+      if (j_wg0 + r >= d.Skv) vy[it] = zero4;
     }
 #pragma unroll
     for (int kb = 0; kb < KVB; ++kb)
@@ -583,6 +608,7 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   load_kv();
   wait_vmcnt<0>();
   __syncthreads();                                 // V rows and the first tiles are in LDS
+  DKDV_STAMP(stamp1);
   const char* const vw = vres + (wave * 32 * KVB + kl) * SM::P + g * 16;
 
   f32x16 s[KVB], p[KVB];
@@ -658,6 +684,7 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
     e[0] = e[1]; e[1] = e[2]; e[2] = e[3]; e[3] = e[4];
   }
 
+  DKDV_STAMP(stamp2);
   // ---- write dK = scale * acc, dV = acc (transposed accumulators: lane = key row).  The last
   // matrix instructions must have retired before their registers are read.
   // (the accumulators are operands of the statement, so that the compiler cannot read them before it)
@@ -711,6 +738,17 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
     *(u32x4*)((char*)a.dk + off) = yk;
     *(u32x4*)((char*)a.dv + off) = yv;
   }
+#ifdef LVX_DKDV_PROBE
+  wait_vmcnt<0>();
+  const unsigned long long stamp3 = __builtin_readcyclecounter();
+  if (tid == 0) {
+    atomicAdd(&dkdv_probe[0], stamp1 - stamp0);
+    atomicAdd(&dkdv_probe[1], stamp2 - stamp1);
+    atomicAdd(&dkdv_probe[2], stamp3 - stamp2);
+    atomicAdd(&dkdv_probe[3], 1ull);
+    atomicAdd(&dkdv_probe[4], (unsigned long long)n);
+  }
+#endif
 }
 
 template <int D, bool GENERAL, bool STEPS = false>
@@ -743,3 +781,12 @@ hipError_t launch_bwd_dkdv_bf16(const BwdArgs& a, hipStream_t s) {
 }
 
 }  // namespace lvx
+
+#ifdef LVX_DKDV_PROBE
+extern "C" int lvx_debug_dkdv_probe(unsigned long long* out8) {
+  if (hipDeviceSynchronize() != hipSuccess) return 1;
+  if (hipMemcpyFromSymbol(out8, HIP_SYMBOL(lvx::dkdv_probe), 8 * sizeof(unsigned long long)) != hipSuccess) return 1;
+  const unsigned long long z[8] = {};
+  return hipMemcpyToSymbol(HIP_SYMBOL(lvx::dkdv_probe), z, sizeof(z)) == hipSuccess ? 0 : 1;
+}
+#endif
