@@ -105,17 +105,19 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   float nl2[QB], nd[QB];               // -L log2(e) (-inf: no probability mass) and -delta
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
-    const int r = i_wave0 + 32 * qb + ql;
+    // (rows past the last one re-read it and become zero: no branch stands between the loads, so
+    // all of them are on their way before the first is waited for)
+    const int r = i_wave0 + 32 * qb + ql, rc = min(r, rows_lim - 1);
     const bool ok = r < rows_lim;
-    const int hq_l = PACK ? hq + r / d.Sq : hq, i = PACK ? r % d.Sq : r;
+    const int hq_l = PACK ? hq + rc / d.Sq : hq, i = PACK ? rc % d.Sq : rc;
     const long off = b * d.q_sb + hq_l * d.q_sh + (long)i * d.q_ss;
+    const u32x4 zero4 = {0, 0, 0, 0};
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      u32x4 x = {0, 0, 0, 0}, y = {0, 0, 0, 0};
-      if (ok) {
-        x = *(const u32x4*)((const uint16_t*)a.q + off + 16 * ks + 8 * g);
-        y = *(const u32x4*)((const uint16_t*)a.d_o + off + 16 * ks + 8 * g);
-      }
+      u32x4 x = *(const u32x4*)((const uint16_t*)a.q + off + 16 * ks + 8 * g);
+      u32x4 y = *(const u32x4*)((const uint16_t*)a.d_o + off + 16 * ks + 8 * g);
+      x = ok ? x : zero4;
+      y = ok ? y : zero4;
       if (FOLD) {
 #pragma unroll
         for (int w = 0; w < 4; ++w)
@@ -124,13 +126,10 @@ bwd_dq_bf16_kernel(BwdArgs a) {
       qf[qb][ks] = __builtin_bit_cast(bf16x8, x);
       gf[qb][ks] = __builtin_bit_cast(bf16x8, y);
     }
-    nl2[qb] = -INFINITY;
-    nd[qb] = 0.f;
-    if (ok) {
-      const long slot = (((long)b * d.Hq + hq_l) * a.sq_pad + (i & ~31)) * 2 + (i & 31);
-      nl2[qb] = a.stats[slot];
-      nd[qb] = a.stats[slot + 32];
-    }
+    const long slot = (((long)b * d.Hq + hq_l) * a.sq_pad + (i & ~31)) * 2 + (i & 31);
+    const float st_l = a.stats[slot], st_d = a.stats[slot + 32];
+    nl2[qb] = ok ? st_l : -INFINITY;
+    nd[qb] = ok ? st_d : 0.f;
   }
   // Finish these loads (and move the operands into the accumulation registers) before the tile
   // copies start: the copies are not counted by the compiler, so nothing may wait on memory later.
@@ -211,9 +210,11 @@ bwd_dq_bf16_kernel(BwdArgs a) {
       unsigned ok;
       if (LIST == 2) {
         ok = 0;
-        for (int k = 0; k < QM / 32; ++k) {
-          const int i = i_wg0 + 32 * k;
-          if (i < d.Sq && a.mask.allow[b * a.mask.stride_b + (long)(i / a.mask.q_chunk) * a.mask.stride_q + f] != 0) ok |= 1u << k;
+#pragma unroll
+        for (int k = 0; k < QM / 32; ++k) {          // (all probes on their way at once: rows past the last re-read it)
+          const int i = i_wg0 + 32 * k, ic = min(i, d.Sq - 1);
+          const uint8_t on = a.mask.allow[b * a.mask.stride_b + (long)(ic / a.mask.q_chunk) * a.mask.stride_q + f];
+          ok |= (i < d.Sq && on != 0 ? 1u : 0u) << k;
         }
       } else {
         ok = 1;

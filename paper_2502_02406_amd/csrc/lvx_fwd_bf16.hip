@@ -116,22 +116,20 @@ fwd_bf16_kernel(FwdArgs a) {
   bf16x8 qf[QB][KS];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
-    const int r = r_wave0 + 32 * qb + ql;
-    const int hq = PACK ? hq0 + r / d.Sq : hq0, i = PACK ? r % d.Sq : r;
+    // (rows past the last one re-read it and become zero: a branch around the loads would make
+    // each of them wait for the one before)
+    const int r = r_wave0 + 32 * qb + ql, rc = min(r, rows_kv - 1);
+    const int hq = PACK ? hq0 + rc / d.Sq : hq0, i = PACK ? rc % d.Sq : rc;
     const long off = b * d.q_sb + hq * d.q_sh + (long)i * d.q_ss;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      u32x4 x = {0, 0, 0, 0};
-      if (r < rows_kv) x = *(const u32x4*)((const uint16_t*)a.q + off + 16 * ks + 8 * g);
-      qf[qb][ks] = __builtin_bit_cast(bf16x8, x);
+      const u32x4 x = *(const u32x4*)((const uint16_t*)a.q + off + 16 * ks + 8 * g);
+      qf[qb][ks] = __builtin_bit_cast(bf16x8, r < rows_kv ? x : u32x4{0, 0, 0, 0});
     }
   }
-  // Finish these loads (and move the operands into the accumulation registers) before the tile
-  // copies start: the copies are not counted by the compiler, so nothing may wait on memory later.
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[qb][ks]));
+  // These loads are finished (and the operands moved into the accumulation registers) below, once
+  // the tile list has been built -- its probes of the bitmap travel with them -- and before the
+  // tile copies start: the copies are not counted by the compiler, so nothing may wait on memory later.
 
   // LIST: the tiles every row of the workgroup sees, compacted into a list (in the area of the
   // mask window; its length in the last word), shared evenly by the splits.  From here on
@@ -151,9 +149,11 @@ fwd_bf16_kernel(FwdArgs a) {
       unsigned ok;
       if (LIST == 2) {
         ok = 0;
-        for (int k = 0; k < QM / 32; ++k) {
-          const int i = i_wg0 + 32 * k;
-          if (i < d.Sq && a.mask.allow[b * a.mask.stride_b + (long)(i / a.mask.q_chunk) * a.mask.stride_q + f] != 0) ok |= 1u << k;
+#pragma unroll
+        for (int k = 0; k < QM / 32; ++k) {          // (all probes on their way at once: rows past the last re-read it)
+          const int i = i_wg0 + 32 * k, ic = min(i, d.Sq - 1);
+          const uint8_t on = a.mask.allow[b * a.mask.stride_b + (long)(ic / a.mask.q_chunk) * a.mask.stride_q + f];
+          ok |= (i < d.Sq && on != 0 ? 1u : 0u) << k;
         }
       } else {
         ok = 1;
@@ -191,6 +191,10 @@ fwd_bf16_kernel(FwdArgs a) {
     t_begin = (int)((long)split * nn / a.n_split);
     t_end = (int)((long)(split + 1) * nn / a.n_split);
   }
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[qb][ks]));
   auto tile_of = [&](int entry) __attribute__((always_inline)) -> int {
     return LIST == 2 ? entry & ((1 << VIS_SHIFT) - 1) : entry;
   };
