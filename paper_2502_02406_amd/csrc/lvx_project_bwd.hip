@@ -383,29 +383,36 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
       if (m < a.M) *(u32x4*)(out + m * a.ldx + 8 * ch) = y;
     }
   } else {
-    if (a.dw_parts == 1) {
-      // this workgroup alone owns its tile of dw: add in place, 16 bytes per lane and register group
+    if constexpr (RB != 4) {
+      // (128-row tiles: never divided) this workgroup alone owns its tile of dw: add in place, 16
+      // bytes per lane and register group, the sixteen old values of a row block read before the
+      // first sum is stored (a store between two loads would make the second wait for the first)
       float* const out = a.dw + (r0 + wm * (32 * RB) + l31) * (long)a.E + e0 + wn * 128 + 4 * g;
 #pragma unroll
-      for (int i = 0; i < RB; ++i)
+      for (int i = 0; i < RB; ++i) {
+        f32x4 v[4][4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) v[j][q] = *(const f32x4*)(out + (long)(32 * i) * a.E + 32 * j + 8 * q);
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
-            f32x4* const p = (f32x4*)(out + (long)(32 * i) * a.E + 32 * j + 8 * q);
-            f32x4 v = *p;
 #pragma unroll
-            for (int t = 0; t < 4; ++t) v[t] += acc[j][i][4 * q + t];
-            *p = v;
+            for (int t = 0; t < 4; ++t) v[j][q][t] += acc[j][i][4 * q + t];
+            *(f32x4*)(out + (long)(32 * i) * a.E + 32 * j + 8 * q) = v[j][q];
           }
-    } else if constexpr (RB == 4) {
-      // The parts of a tile take turns, in the order of their numbers; every wave owns a quarter
+      }
+    } else {
+      // A tile whose tokens are divided (dw_parts > 1): the parts take turns, in the order of their
+      // numbers; an undivided tile goes the same way without the waiting.  Every wave owns a quarter
       // of the tile and passes it on in two halves of 64 rows, each with a turn word of its own,
       // so a part starts on a half as soon as the part before it has left that half.  A half is
       // turned through LDS (64 rows x 128 floats per wave, 16-byte chunks permuted by the row)
       // so that every load and store covers two whole 512-byte row segments, and the old values
       // come in sixteen rows at a time: a turn costs a few trips to memory, not one per register.
-      int* const turn = dw_turn + ((hw.head * n_ct + hw.item) * 4 + wave) * 2;
+      int* const turn = dw_turn + (a.dw_parts > 1 ? ((hw.head * n_ct + hw.item) * 4 + wave) * 2 : 0);
       float* const tb = (float*)(smem + wave * 32768);
       constexpr int AGENT = 16;                      // cache policy sc1: the L2s of different XCDs do not see each other's lines
       const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
@@ -425,8 +432,8 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
               *(f32x4*)(tb + (32 * ii + l31) * 128 + (((8 * j + 2 * q + g) ^ l31) * 4)) = v;
             }
         int tries = 0;
-        while (__builtin_amdgcn_readfirstlane(__hip_atomic_load((gint*)(turn + h), __ATOMIC_RELAXED,
-                                                                __HIP_MEMORY_SCOPE_AGENT)) != tpart) {
+        while (a.dw_parts > 1 && __builtin_amdgcn_readfirstlane(__hip_atomic_load(
+                                     (gint*)(turn + h), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) != tpart) {
           if (++tries > SPIN_LIMIT) break;
           __builtin_amdgcn_s_sleep(8);
         }
@@ -452,10 +459,12 @@ project_bwd_bf16_kernel(ProjBwdArgs a) {
             __builtin_amdgcn_raw_buffer_store_b128(y, rs, voff, (b0 + t) * two_rows, AGENT);
           }
         }
-        wait_vmcnt<0>();                             // this wave's stores have been acknowledged: the next part may come
-        asm volatile("" ::: "memory");
-        __hip_atomic_store((gint*)(turn + h), tpart + 1 == a.dw_parts ? 0 : tpart + 1, __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_AGENT);
+        if (a.dw_parts > 1) {
+          wait_vmcnt<0>();                           // this wave's stores have been acknowledged: the next part may come
+          asm volatile("" ::: "memory");
+          __hip_atomic_store((gint*)(turn + h), tpart + 1 == a.dw_parts ? 0 : tpart + 1, __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+        }
       }
     }
   }
