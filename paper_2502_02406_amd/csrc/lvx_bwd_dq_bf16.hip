@@ -632,14 +632,29 @@ bwd_dq_bf16_kernel(BwdArgs a) {
                       (((long)b * d.Hq + hq) * d.Sq) * D;
   // (dq_accum and the partial sums are contiguous [B,Hq,Sq,D]: row i of the group's list is row i
   // past the first row of the group's first head)
-  for (int r0 = 0; r0 < 32 * QB; r0 += RPI) {
-    const int r = r0 + rsub, i = i_wave0 + r;
-    if (i >= rows_lim) continue;
-    if (!EVEN && (rsub >= RPI || r >= 32 * QB)) continue;
-    f32x4 y = *(const f32x4*)(tbuf + r * RP + col * 4);
-    float* const out = out0 + (long)i * D + col;
-    if (whole) y += *(const f32x4*)out;
-    *(f32x4*)out = y;
+  // Eight instructions' worth of rows at a time: their old values are all requested before the
+  // first sum is stored (a store, or a branch, between two loads would make the second wait for
+  // the first: one round trip per instruction instead of one per eight).  Rows past the last one
+  // re-read it and store nothing.
+  constexpr int NB = 8;
+  for (int r00 = 0; r00 < 32 * QB; r00 += NB * RPI) {
+    f32x4 old[NB];
+    if (whole) {
+#pragma unroll
+      for (int u = 0; u < NB; ++u) {
+        const int i = min(i_wave0 + r00 + u * RPI + rsub, rows_lim - 1);
+        old[u] = *(const f32x4*)(out0 + (long)i * D + col);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+      const int r = r00 + u * RPI + rsub, i = i_wave0 + r;
+      const bool ok = i < rows_lim && r < 32 * QB && (EVEN || rsub < RPI);
+      if (!ok) continue;
+      f32x4 y = *(const f32x4*)(tbuf + r * RP + col * 4);
+      if (whole) y += old[u];
+      *(f32x4*)(out0 + (long)i * D + col) = y;
+    }
   }
 }
 
