@@ -87,13 +87,28 @@ __global__ void __launch_bounds__(256) merge_kernel(MergeArgs a) {
         }
       }
     };
+    // The statistics of the first LG parts (all of them, as a rule) are read once, together, and
+    // kept: read part by part inside the loops below, each would wait for the one before it.
+    constexpr int LG = 8;
+    float lk[LG];
+#pragma unroll
+    for (int k = 0; k < LG; ++k) {
+      const float x = a.lse_parts[k < n ? k : n - 1][row[u]];
+      lk[k] = k < n ? x : -INFINITY;
+    }
     float M = -INFINITY;
-    for (int k = 0; k < n; ++k) M = fmaxf(M, a.lse_parts[k][row[u]]);
+#pragma unroll
+    for (int k = 0; k < LG; ++k) M = fmaxf(M, lk[k]);
+    for (int k = LG; k < n; ++k) M = fmaxf(M, a.lse_parts[k][row[u]]);
     if (M == -INFINITY) continue;
     float z = 0.f;
-    for (int k = 0; k < n; ++k) z += expf(a.lse_parts[k][row[u]] - M);
+#pragma unroll
+    for (int k = 0; k < LG; ++k) z += expf(lk[k] - M);               // (exp(-inf) = 0: parts that are not there)
+    for (int k = LG; k < n; ++k) z += expf(a.lse_parts[k][row[u]] - M);
     Lout[u] = M + logf(z);
-    for (int k0 = 0; k0 < n; k0 += GRP) {
+#pragma unroll
+    for (int k0 = 0; k0 < LG; k0 += GRP) {
+      if (k0 >= n) break;
       if (k0 > 0) {
 #pragma unroll
         for (int g = 0; g < GRP; ++g)
@@ -101,9 +116,17 @@ __global__ void __launch_bounds__(256) merge_kernel(MergeArgs a) {
       }
 #pragma unroll
       for (int g = 0; g < GRP; ++g)
+        if (k0 + g < n && lk[k0 + g] != -INFINITY) add_part(buf[u][g], expf(lk[k0 + g] - Lout[u]));
+    }
+    for (int k0 = LG; k0 < n; k0 += GRP) {
+#pragma unroll
+      for (int g = 0; g < GRP; ++g)
+        if (k0 + g < n) buf[u][g] = load_part(u, k0 + g);
+#pragma unroll
+      for (int g = 0; g < GRP; ++g)
         if (k0 + g < n) {
-          const float lk = a.lse_parts[k0 + g][row[u]];
-          if (lk != -INFINITY) add_part(buf[u][g], expf(lk - Lout[u]));
+          const float l = a.lse_parts[k0 + g][row[u]];
+          if (l != -INFINITY) add_part(buf[u][g], expf(l - Lout[u]));
         }
     }
   }
