@@ -594,6 +594,7 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
   // Iteration i contracts step i while converting step i + 1 (already scored); then, at the one
   // barrier of the iteration, every wave is done with step i, whose stage takes step i + 4, and
   // step i + 2 -- issued two iterations ago -- has landed; then step i + 2 is scored.
+  DKDV_STAMP(stamp_a);
   int e[NSTG + 1];                                 // step ids of steps i .. i + 4 (static indexing only)
 #pragma unroll
   for (int q = 0; q <= NSTG; ++q) e[q] = n_all;
@@ -605,7 +606,9 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
       advance(cursor);
     }
   }
+  DKDV_STAMP(stamp_b);
   load_kv();
+  DKDV_STAMP(stamp_c);
   wait_vmcnt<0>();
   __syncthreads();                                 // V rows and the first tiles are in LDS
   DKDV_STAMP(stamp1);
@@ -747,6 +750,9 @@ bwd_dkdv_bf16_kernel(BwdArgs a) {
     atomicAdd(&dkdv_probe[2], stamp3 - stamp2);
     atomicAdd(&dkdv_probe[3], 1ull);
     atomicAdd(&dkdv_probe[4], (unsigned long long)n);
+    atomicAdd(&dkdv_probe[5], stamp_a - stamp0);     // of the set-up: until the first tile copy goes out,
+    atomicAdd(&dkdv_probe[6], stamp_b - stamp_a);    // issuing the first four steps' copies,
+    atomicAdd(&dkdv_probe[7], stamp_c - stamp_b);    // K and V from memory into registers and LDS (the rest: the last wait)
   }
 #endif
 }
