@@ -324,12 +324,14 @@ def test_masked_rows_without_keys():
     run_case(w, do_bwd=True)
 
 
-@pytest.mark.parametrize("D", [128, 96])
+@pytest.mark.parametrize("D,n", [(128, 5), (96, 5), (128, 11), (64, 19)])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_merge_matches_oracle(dtype, D):
+def test_merge_matches_oracle(dtype, D, n):
+    # (the kernel keeps the statistics of eight parts in registers and fetches the parts' elements
+    # four parts at a time: 5, 11 and 19 parts end inside a group of four, of eight, and past both)
     from paper_2502_02406_amd import binding as B
     rng = np.random.default_rng(5)
-    n, shape = 5, (2, 3, 50, D)
+    shape = (2, 3, 50, D)
     O = rng.standard_normal((n,) + shape)
     L = rng.standard_normal((n,) + shape[:3]) * 4
     L[1, :, :, :7] = -np.inf
