@@ -33,6 +33,17 @@ constexpr int PF = 1;                  // LDS operand prefetch distance, in k-st
 constexpr int XE = 8;                  // elements of a half converted during the contraction (of 32)
 template <int D> using DqSmem = KvSmem<D>;
 
+// Measurement builds only (python -m paper_2502_02406_amd.build --define LVX_DQ_PROBE=1): every
+// workgroup adds the clocks of its three phases (set-up until the first tiles are in place; the
+// loop; the epilogue until its stores have been acknowledged), a count and its number of tiles to
+// dq_probe, which lvx_debug_dq_probe copies out and clears.
+#ifdef LVX_DQ_PROBE
+__device__ unsigned long long dq_probe[8];
+#define DQ_STAMP(x) const unsigned long long x = __builtin_readcyclecounter()
+#else
+#define DQ_STAMP(x)
+#endif
+
 // GENERAL = false: dense attention and Skv a multiple of 64 (no mask code, no ragged tile, so that
 // the steady-state loop is one basic block); GENERAL = true: everything else.
 // LIST (with GENERAL = false): the dense kernel over a list of key tiles -- those that EVERY row
@@ -84,6 +95,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
     qt = hw.item % n_qt;
   }
 
+  DQ_STAMP(stamp0);
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ql = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int i_wave0 = qt * QM + wave * 32 * QB;     // first row (of the head, or of the group's list) of this wave
@@ -235,15 +247,27 @@ bwd_dq_bf16_kernel(BwdArgs a) {
     }
     __syncthreads();
     if (wave == 0) {
+      // (the words of 64 tiles each are fetched 64 at a time, one per lane, and handed round from
+      // the registers: read one by one from LDS, each would wait for the one before it; words
+      // without a visible tile -- most of them under a sparse mask -- cost nothing more)
       int count = 0;
-      for (int base = 0; base < n_tiles; base += 64) {         // wave-uniform trip count
-        const unsigned long long m = *(const unsigned long long*)(plane + base / 32);
-        if ((m >> lane) & 1ull) {
-          int entry = base + lane;
-          if (LIST == 2) entry |= (int)(bits[((base + lane) * TN) / a.mask.kv_block] << VIS_SHIFT);
-          tlist[count + __popcll(m & ((1ull << lane) - 1ull))] = entry;
+      const int n_words = (n_tiles + 63) / 64;
+      for (int w0 = 0; w0 < n_words; w0 += 64) {               // wave-uniform trip counts
+        const int nw = min(64, n_words - w0);
+        const unsigned long long mine = lane < nw ? *(const unsigned long long*)(plane + 2 * (w0 + lane)) : 0ull;
+        for (int k = 0; k < nw; ++k) {
+          const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)mine, k);
+          const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(mine >> 32), k);
+          const unsigned long long m = ((unsigned long long)hi << 32) | lo;
+          if (m == 0ull) continue;
+          const int base = (w0 + k) * 64;
+          if ((m >> lane) & 1ull) {
+            int entry = base + lane;
+            if (LIST == 2) entry |= (int)(bits[((base + lane) * TN) / a.mask.kv_block] << VIS_SHIFT);
+            tlist[count + __popcll(m & ((1ull << lane) - 1ull))] = entry;
+          }
+          count += (int)__popcll(m);
         }
-        count += (int)__popcll(m);
       }
       if (lane == 0) tlist[LIST_CAP] = count;
     }
@@ -512,6 +536,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   }
   wait_vmcnt<0>();
   __syncthreads();
+  DQ_STAMP(stamp1);
   auto stage = [&](int q) __attribute__((always_inline)) -> char* { return smem + (q % NSTG) * SM::STAGE; };
   auto mid = [&](auto all_in_flight, bool issue, char* st_copy) __attribute__((always_inline)) {
     // (The general variant may spill registers inside the loop; its spill stores are counted with
@@ -599,6 +624,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   // of the workspace and a reduction follows the kernel (float atomics from every split would
   // be bounded by the L2 atomic rate, about 80 G elements per second).
   // The last matrix instructions must have retired before their registers are read.
+  DQ_STAMP(stamp2);
   if constexpr (DB == 4) {
     asm volatile("s_nop 15\n\ts_nop 15" : "+a"(dq[0][0]), "+a"(dq[0][1]), "+a"(dq[0][2]), "+a"(dq[0][3]),
                  "+a"(dq[1][0]), "+a"(dq[1][1]), "+a"(dq[1][2]), "+a"(dq[1][3]));
@@ -656,6 +682,17 @@ bwd_dq_bf16_kernel(BwdArgs a) {
       *(f32x4*)(out0 + (long)i * D + col) = y;
     }
   }
+#ifdef LVX_DQ_PROBE
+  wait_vmcnt<0>();
+  const unsigned long long stamp3 = __builtin_readcyclecounter();
+  if (tid == 0) {
+    atomicAdd(&dq_probe[0], stamp1 - stamp0);
+    atomicAdd(&dq_probe[1], stamp2 - stamp1);
+    atomicAdd(&dq_probe[2], stamp3 - stamp2);
+    atomicAdd(&dq_probe[3], 1ull);
+    atomicAdd(&dq_probe[4], (unsigned long long)nt);
+  }
+#endif
 }
 
 template <int D, bool GENERAL, int LIST = 0>
@@ -787,3 +824,12 @@ hipError_t launch_bwd_bf16(const BwdArgs& a, unsigned stages, hipStream_t s) {
 }
 
 }  // namespace lvx
+
+#ifdef LVX_DQ_PROBE
+extern "C" int lvx_debug_dq_probe(unsigned long long* out8) {
+  if (hipDeviceSynchronize() != hipSuccess) return 1;
+  if (hipMemcpyFromSymbol(out8, HIP_SYMBOL(lvx::dq_probe), 8 * sizeof(unsigned long long)) != hipSuccess) return 1;
+  const unsigned long long z[8] = {};
+  return hipMemcpyToSymbol(HIP_SYMBOL(lvx::dq_probe), z, sizeof(z)) == hipSuccess ? 0 : 1;
+}
+#endif

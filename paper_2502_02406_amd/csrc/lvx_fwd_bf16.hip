@@ -174,15 +174,27 @@ fwd_bf16_kernel(FwdArgs a) {
     }
     __syncthreads();
     if (wave == 0) {
+      // (the words of 64 tiles each are fetched 64 at a time, one per lane, and handed round from
+      // the registers: read one by one from LDS, each would wait for the one before it; words
+      // without a visible tile -- most of them under a sparse mask -- cost nothing more)
       int count = 0;
-      for (int base = 0; base < n_tiles; base += 64) {         // wave-uniform trip count
-        const unsigned long long m = *(const unsigned long long*)(plane + base / 32);
-        if ((m >> lane) & 1ull) {
-          int entry = base + lane;
-          if (LIST == 2) entry |= (int)(full[((base + lane) * TN) / a.mask.kv_block] << VIS_SHIFT);
-          tlist[count + __popcll(m & ((1ull << lane) - 1ull))] = entry;
+      const int n_words = (n_tiles + 63) / 64;
+      for (int w0 = 0; w0 < n_words; w0 += 64) {               // wave-uniform trip counts
+        const int nw = min(64, n_words - w0);
+        const unsigned long long mine = lane < nw ? *(const unsigned long long*)(plane + 2 * (w0 + lane)) : 0ull;
+        for (int k = 0; k < nw; ++k) {
+          const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)mine, k);
+          const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(mine >> 32), k);
+          const unsigned long long m = ((unsigned long long)hi << 32) | lo;
+          if (m == 0ull) continue;
+          const int base = (w0 + k) * 64;
+          if ((m >> lane) & 1ull) {
+            int entry = base + lane;
+            if (LIST == 2) entry |= (int)(full[((base + lane) * TN) / a.mask.kv_block] << VIS_SHIFT);
+            tlist[count + __popcll(m & ((1ull << lane) - 1ull))] = entry;
+          }
+          count += (int)__popcll(m);
         }
-        count += (int)__popcll(m);
       }
       if (lane == 0) tlist[LIST_CAP] = count;
     }
