@@ -460,20 +460,35 @@ bwd_dq_bf16_kernel(BwdArgs a) {
   // qb = x / 16, register v = x % 16): p = exp2(s c2 - L2), dS = p (dP - delta) -- with FOLD both
   // differences were formed by the accumulation already -- packed in pairs as bf16 into word
   // (v % 8) / 2 of operand v / 8 of the query block.
-  struct Carry { float ds; };
-  auto conv_elem = [&](int x, Carry& cy, const f32x16 (&s)[QB], const f32x16 (&p)[QB],
-                       u32x4 (&dsw)[QB][2]) __attribute__((always_inline)) {
+  // An element is started (its exp2) in one place and finished (multiply, packing) in the next, so
+  // that between the matrix instructions of the pipelined loop the exponential's result is never
+  // read by the very next instruction, which costs an idle issue slot: conv_elem(x) finishes
+  // element x - 1 and starts element x; conv_last finishes element 31 of the half.
+  struct Carry { float ds, ex; };
+  auto conv_start = [&](int x, const f32x16 (&s)[QB]) __attribute__((always_inline)) -> float {
     const int qb = x / 16, v = x % 16;
-    const float pr = __builtin_amdgcn_exp2f(FOLD ? s[qb][v] : fmaf(s[qb][v], c2, nl2[qb]));
-    const float ds = pr * (FOLD ? p[qb][v] : p[qb][v] + nd[qb]);
+    return __builtin_amdgcn_exp2f(FOLD ? s[qb][v] : fmaf(s[qb][v], c2, nl2[qb]));
+  };
+  auto conv_finish = [&](int x, Carry& cy, const f32x16 (&p)[QB], u32x4 (&dsw)[QB][2]) __attribute__((always_inline)) {
+    const int qb = x / 16, v = x % 16;
+    const float ds = cy.ex * (FOLD ? p[qb][v] : p[qb][v] + nd[qb]);
     if (v % 2 == 0) { cy.ds = ds; return; }
     const unsigned w2 = pack2_bf16(cy.ds, ds);
     dsw[qb][v / 8][(v % 8) / 2] = (LIST != 2 || ((vcur >> qb) & 1)) ? w2 : 0u;
+  };
+  auto conv_elem = [&](int x, Carry& cy, const f32x16 (&s)[QB], const f32x16 (&p)[QB],
+                       u32x4 (&dsw)[QB][2]) __attribute__((always_inline)) {
+    if (x > 0) conv_finish(x - 1, cy, p, dsw);
+    cy.ex = conv_start(x, s);
+  };
+  auto conv_last = [&](Carry& cy, const f32x16 (&p)[QB], u32x4 (&dsw)[QB][2]) __attribute__((always_inline)) {
+    conv_finish(31, cy, p, dsw);
   };
   auto convert = [&](const f32x16 (&s)[QB], const f32x16 (&p)[QB], u32x4 (&dsw)[QB][2]) __attribute__((always_inline)) {
     Carry cy;
 #pragma unroll
     for (int x = 0; x < 32; ++x) conv_elem(x, cy, s, p, dsw);
+    conv_last(cy, p, dsw);
   };
   // dQ^T += K^T dS^T over the 32 keys of a half (two k-steps of 16 keys)
   auto contract = [&](const char* __restrict__ st, int hb, const u32x4 (&dsw)[QB][2]) __attribute__((always_inline)) {
@@ -517,6 +532,7 @@ bwd_dq_bf16_kernel(BwdArgs a) {
       for (int x = XE + m * (32 - XE) / NU; x < XE + (m + 1) * (32 - XE) / NU; ++x) conv_elem(x, cy, s, p, dso);
       extra(m);
     }, first, tail);
+    conv_last(cy, p, dso);
   };
 
   // ---- pipeline.  Tile number q of the sequence lives in ring stage q % 4.  Per tile T (halves
