@@ -52,6 +52,11 @@ def _blocks(body):
     ("lvx_bwd_dkdv_bf16.hip", "bwd_dkdv_bf16_kernelILi64ELb0ELb1E", 64),
     ("lvx_bwd_dq_bf16.hip", "bwd_dq_bf16_kernelILi64ELb0ELi0E", 48),
     ("lvx_bwd_dq_bf16.hip", "bwd_dq_bf16_kernelILi64ELb0ELi1E", 48),
+    # ... and for 96-wide heads: three quarters of them
+    ("lvx_bwd_dkdv_bf16.hip", "bwd_dkdv_bf16_kernelILi96ELb0ELb0E", 96),
+    ("lvx_bwd_dkdv_bf16.hip", "bwd_dkdv_bf16_kernelILi96ELb0ELb1E", 96),
+    ("lvx_bwd_dq_bf16.hip", "bwd_dq_bf16_kernelILi96ELb0ELi0E", 72),
+    ("lvx_bwd_dq_bf16.hip", "bwd_dq_bf16_kernelILi96ELb0ELi2E", 72),
     # the fused backward: scoring of one step and contraction of the next in one block
     ("lvx_bwd_fused_bf16.hip", "bwd_fused_bf16_kernelILi128E", 80),
 ])
@@ -88,6 +93,10 @@ def test_general_dkdv_leaves_half_the_accumulation_file():
     ("lvx_fwd_bf16.hip", "fwd_bf16_kernelILi64ELi2EE"),
     ("lvx_bwd_dq_bf16.hip", "bwd_dq_bf16_kernelILi64ELb1ELi0E"),
     ("lvx_bwd_dkdv_bf16.hip", "bwd_dkdv_bf16_kernelILi64ELb1ELb0E"),
+    ("lvx_fwd_bf16.hip", "fwd_bf16_kernelILi96ELi0EE"),      # 96-wide heads
+    ("lvx_fwd_bf16.hip", "fwd_bf16_kernelILi96ELi2EE"),
+    ("lvx_bwd_dq_bf16.hip", "bwd_dq_bf16_kernelILi96ELb1ELi0E"),
+    ("lvx_bwd_dkdv_bf16.hip", "bwd_dkdv_bf16_kernelILi96ELb1ELb0E"),
 ])
 def test_blocks_with_matrix_instructions_move_no_accumulator(src, kernel):
     """The dense forward's loop has (rare) branches and the general dQ kernel has mask code, so
