@@ -232,12 +232,18 @@ def test_project_bwd_wide_projection_takes_tall_tiles_sampled():
     assert np.isfinite(dw).all() and np.isfinite(dx).all()
 
 
-def test_project_bwd_full_size_block_sampled():
-    """The gradients of one K/V block of the long-video workload: 32768 tokens of width 4096, 8 K
-    heads and 8 V heads of 128 -- the launch bench.py times -- on sampled tokens (dx) and sampled
-    columns of the projection (dw)."""
-    B, S, E, H, D = 1, 32768, 4096, 8, 128
-    print("[project_bwd] full size: GPU", flush=True)
+@pytest.mark.parametrize("tag,S,E,H,D", [
+    # the long-video workload's K/V block: 128 tiles of dw, the tokens of each in two parts
+    ("long_video_block", 32768, 4096, 8, 128),
+    # a block of the 64-token-frame model (embedding width 512, 8 heads of 64): 8 tiles of dw, the
+    # tokens of each in 32 parts that take turns
+    ("short_frame_block", 131072, 512, 8, 64),
+])
+def test_project_bwd_full_size_block_sampled(tag, S, E, H, D):
+    """The gradients of one K/V block at full size -- the launches bench.py times -- on sampled
+    tokens (dx) and sampled columns of the projection (dw)."""
+    B = 1
+    print(f"[project_bwd] full size {tag}: GPU", flush=True)
     x, w, gs, dx, dw = run_bwd(B, S, E, H, D, 2, "bf16", seed=W.BASE_SEED)
     rng = np.random.default_rng(5)
     rows = np.stack([np.zeros(24, dtype=np.int64), np.sort(rng.choice(S, 24, replace=False))], axis=1)
